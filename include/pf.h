@@ -1,0 +1,217 @@
+/*
+ * pf.h - C ABI of the fused-subgraph engine for AMD MI355X (gfx950).
+ *
+ * The library takes a computational subgraph in the sense of the paper's
+ * Definition 3.1 (a DAG of operator nodes, each with an operator type and an
+ * output shape), partitions it into fusible groups, lowers every group to one
+ * hand-written HIP kernel skeleton with a generated straight-line body,
+ * compiles it once, and executes it on caller-owned device buffers.  The
+ * outputs of a candidate execution can then be scored against a reference
+ * under the tolerance test of Definition 3.2 / Eq. 1 with the atol/rtol pair
+ * of Appendix F.
+ *
+ * Conventions
+ *   - Every function returns a pf_status (0 = PF_OK, < 0 = error).  Nothing
+ *     throws across this boundary.  pf_last_error() gives the message of the
+ *     last failing call on the calling thread.
+ *   - "h_" arguments are host pointers, "d_" arguments are device pointers.
+ *   - Tensors are dense, row-major, in the dtype declared in the graph.
+ *     Device pointers must be 16-byte aligned.
+ *   - The caller owns all device buffers and the stream.  The library owns
+ *     pf_graph / pf_exec handles and the code objects behind them.
+ *   - pf_execute and pf_score only enqueue work on the given stream; they
+ *     never synchronise and never allocate device memory.
+ *   - The paper's failure classes (Sec. 3.4: accuracy = 1, compilation = 2,
+ *     runtime = 3) map to: PF_E_COMPILE (class 2), PF_E_RUNTIME (class 3); an
+ *     accuracy failure is not an error code but allclose == 0 in a
+ *     pf_score_result.
+ */
+#ifndef PF_H
+#define PF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PF_OK = 0,
+    PF_E_INVALID = -1, /* bad argument, null handle, misaligned pointer            */
+    PF_E_COMPILE = -2, /* ill-formed graph, unsupported op/dtype/shape, JIT failed */
+    PF_E_RUNTIME = -3, /* wrong buffer count, short workspace, launch failed       */
+    PF_E_NOMEM = -4
+} pf_status;
+
+/* Storage dtypes.  PF_F64 is accepted only as the reference side of pf_score. */
+typedef enum { PF_F32 = 0, PF_BF16 = 1, PF_F64 = 2 } pf_dtype;
+
+/*
+ * Operator types (the set tau ranges over).  Binary operators broadcast
+ * right-aligned, NumPy style.  Reductions act on the last dim and keep it as
+ * size 1 unless keepdim=0.  All arithmetic is carried out in fp32 (sums in a
+ * wider accumulator for fp32 graphs); a value is rounded to its node dtype
+ * only where it is written to memory.
+ */
+typedef enum {
+    PF_OP_INPUT = 0,
+    PF_OP_CONST,     /* attr value=<float>; rank-0 scalar                        */
+    PF_OP_ADD, PF_OP_SUB, PF_OP_MUL, PF_OP_DIV,
+    PF_OP_EXP, PF_OP_TANH,
+    PF_OP_SIGMOID,   /* 1 / (1 + exp(-x))                                        */
+    PF_OP_GELU,      /* attr approx=tanh (default) | erf                         */
+    PF_OP_RSQRT,     /* 1 / sqrt(x)                                              */
+    PF_OP_SUM, PF_OP_MAX, PF_OP_MEAN,   /* attr keepdim=1|0; max propagates NaN  */
+    PF_OP_VAR,       /* mean((x-mean)^2) * n/(n-correction); attr correction=0   */
+    PF_OP_TRANSPOSE, /* swaps the last two dims                                  */
+    PF_OP_ROT_PAIRS, /* out[2i] = -x[2i+1], out[2i+1] = x[2i] on the last dim    */
+    PF_OP_COUNT_
+} pf_op;
+
+#define PF_MAX_RANK 4
+
+typedef struct pf_graph pf_graph;
+typedef struct pf_exec pf_exec;
+
+typedef struct { const char* key; const char* value; } pf_attr;
+
+/* ---- graph construction (Def. 3.1: nodes, edges, operator types, shapes) ---- */
+
+pf_status pf_graph_create(pf_graph** g);
+void      pf_graph_destroy(pf_graph* g);
+
+/* Declares an external input tensor; rank in [0, PF_MAX_RANK], dims > 0.
+ * Returns the new node id through node_out.  Ids are consecutive from 0. */
+pf_status pf_graph_input(pf_graph* g, pf_dtype dtype, int rank, const int64_t* h_shape, int* node_out);
+
+/* Adds an operator node reading earlier nodes.  The output shape is inferred
+ * (broadcast / reduction / transposition rules) and never supplied.
+ * out_dtype is the dtype the value has whenever it is stored to memory. */
+pf_status pf_graph_node(pf_graph* g, pf_op op, const int* h_in_nodes, int n_in,
+                        const pf_attr* h_attrs, int n_attr, pf_dtype out_dtype, int* node_out);
+
+/* Marks a node as a graph output (order of calls = order of output buffers). */
+pf_status pf_graph_output(pf_graph* g, int node);
+
+/* Text form (one statement per line):
+ *     in %0 : bf16[8192,11008]
+ *     %2 = add(%0, %1) {key=value} : bf16
+ *     out %2
+ * pf_graph_print writes a form that pf_graph_parse reads back into an equal
+ * graph.  print: buf may be NULL / cap 0 to query *needed (bytes incl. NUL). */
+pf_status pf_graph_parse(const char* h_text, size_t len, pf_graph** g);
+pf_status pf_graph_print(const pf_graph* g, char* h_buf, size_t cap, size_t* needed);
+
+typedef struct {
+    pf_op    op;
+    pf_dtype dtype;
+    int      rank;
+    int64_t  shape[PF_MAX_RANK];
+    int      n_in;
+    int      in_nodes[2];
+    int      is_output;
+} pf_node_info;
+
+pf_status pf_graph_size(const pf_graph* g, int* n_nodes, int* n_inputs, int* n_outputs);
+pf_status pf_graph_node_info(const pf_graph* g, int node, pf_node_info* h_info);
+
+/* ---- compilation: fusion planning + kernel specialisation ---- */
+
+typedef struct {
+    int fuse;              /* 1: group nodes into fused kernels (default); 0: one kernel per node */
+    int intermediates_f32; /* 1: values crossing a kernel boundary are kept in fp32 (default for
+                              fuse=1); 0: stored in their node dtype, as op-by-op execution would */
+    int reserved[6];       /* must be zero */
+} pf_options;
+
+void pf_options_default(pf_options* h_opt);
+
+/* Plans and JIT-compiles for gfx950.  Needs no GPU: code objects are loaded
+ * onto the device at the first pf_execute. */
+pf_status pf_compile(const pf_graph* g, const pf_options* h_opt, pf_exec** e);
+void      pf_exec_destroy(pf_exec* e);
+
+typedef enum { PF_T_EW_FLAT = 0, PF_T_ROW_RESIDENT = 1, PF_T_TILE = 2, PF_T_ROW_LOOP = 3 } pf_template;
+
+typedef struct {
+    int      n_kernels;          /* number of kernel launches per pf_execute              */
+    int      n_inputs, n_outputs;
+    uint64_t algorithmic_bytes;  /* external inputs once + outputs once                   */
+    uint64_t workspace_bytes;    /* device scratch pf_execute needs (may be 0)            */
+    uint64_t planned_bytes;      /* bytes the planned kernels read + write, incl. scratch */
+} pf_plan_info;
+
+typedef struct {
+    pf_template tmpl;
+    int      n_nodes;            /* operator nodes computed by this kernel                */
+    int      nodes[64];
+    int64_t  rows, cols;         /* iteration domain: product of leading dims, last dim   */
+    int      block_threads;
+    int64_t  grid_blocks;
+    int      lanes_per_row;      /* row templates: lanes cooperating on one row           */
+    uint64_t bytes_read, bytes_written;
+} pf_group_info;
+
+pf_status pf_exec_info(const pf_exec* e, pf_plan_info* h_info);
+pf_status pf_exec_group_info(const pf_exec* e, int group, pf_group_info* h_info);
+/* Generated HIP source of one kernel, for inspection (same buffer protocol as print). */
+pf_status pf_exec_source(const pf_exec* e, int group, char* h_buf, size_t cap, size_t* needed);
+
+/* Runs the compiled subgraph once.  d_inputs / d_outputs follow the order of
+ * the graph's `in` declarations and pf_graph_output calls.  d_workspace must
+ * hold workspace_bytes (256-byte aligned) and is private to this call while it
+ * is in flight.  Enqueues n_kernels launches on `stream` (a hipStream_t; NULL
+ * is the default stream). */
+pf_status pf_execute(pf_exec* e, const void* const* d_inputs, int n_in, void* const* d_outputs, int n_out,
+                     void* d_workspace, size_t workspace_bytes, void* stream);
+
+/* ---- error scoring (Def. 3.2 / Eq. 1 with atol, rtol of Appendix F) ---- */
+
+typedef struct {
+    const void* d_cand;   /* candidate output                      */
+    const void* d_ref;    /* reference output                      */
+    uint64_t    n;        /* elements                              */
+    int32_t     cand_dtype, ref_dtype;   /* pf_dtype               */
+    double      rtol, atol;
+    int32_t     equal_nan; /* 1: NaN vs NaN at the same index passes */
+    int32_t     reserved;
+} pf_pair;
+
+/* One element passes when a == b, or |a-b| is finite and <= atol + rtol*|b|
+ * (b = reference); NaN on either side fails unless equal_nan and both are NaN.
+ * max_abs / max_rel range over elements where neither side is NaN; relative
+ * error is 0 when a == b, +inf when b == 0 or |a-b| is infinite, else
+ * |a-b|/|b|.  All comparisons are made in fp64 on exactly widened values. */
+typedef struct {
+    double   max_abs, max_rel;
+    uint64_t n, n_viol;
+    uint64_t nan_cand, nan_ref, inf_cand, inf_ref;
+    uint32_t allclose;       /* n_viol == 0                                   */
+    uint32_t bit_identical;  /* same dtype and every element has the same bits */
+    uint64_t reserved_;      /* internal progress counter; ignore              */
+} pf_score_result;
+
+/* Bytes of device scratch pf_score needs for n_pairs pairs. */
+size_t pf_score_workspace_bytes(int n_pairs);
+
+/* Scores n_pairs pairs in one pass over their elements.  h_pairs is read
+ * before the call returns.  d_results receives n_pairs structs once the
+ * stream has run. */
+pf_status pf_score(const pf_pair* h_pairs, int n_pairs, pf_score_result* d_results,
+                   void* d_workspace, size_t workspace_bytes, void* stream);
+
+/* ---- misc ---- */
+
+/* Plain device copy of `bytes` bytes (multiple of 16) with the library's
+ * streaming load/store path; the practical bandwidth ceiling to quote beside
+ * the fused kernels. */
+pf_status pf_copy_bytes(void* d_dst, const void* d_src, size_t bytes, void* stream);
+
+const char* pf_last_error(void);
+const char* pf_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PF_H */

@@ -1,0 +1,145 @@
+"""The four named synthetic workloads (fused subgraphs of known structure).
+
+Each function returns a Workload: the DAG in text form, the input tensors as
+stored bits, the comparison tolerances and the bytes that must cross HBM
+(every external input once + every output once).  `rows` arguments shrink a
+workload along its leading dims for quick tests; the defaults are the full
+sizes.  "N(m, s)" means mean m and standard deviation s throughout.
+"""
+from dataclasses import dataclass, field
+import numpy as np
+
+from . import rng
+from .irtext import Builder
+
+ITEMSIZE = {"f32": 4, "bf16": 2}
+# comparison tolerances against the fp64 oracle, by dtype of the graph output
+RTOL = {"f32": 1e-5, "bf16": 2e-2}
+ATOL = {"f32": 1e-5, "bf16": 1e-5}
+
+
+@dataclass
+class Workload:
+    name: str
+    text: str
+    inputs: list                      # numpy arrays: float32, or uint16 for bf16
+    input_dtypes: list                # 'f32' | 'bf16'
+    input_shapes: list
+    output_dtypes: list
+    output_shapes: list
+    algorithmic_bytes: int = 0
+    meta: dict = field(default_factory=dict)
+
+    def finish(self):
+        b = 0
+        for d, s in zip(self.input_dtypes, self.input_shapes):
+            b += ITEMSIZE[d] * int(np.prod(s, dtype=np.int64))
+        for d, s in zip(self.output_dtypes, self.output_shapes):
+            b += ITEMSIZE[d] * int(np.prod(s, dtype=np.int64))
+        self.algorithmic_bytes = b
+        return self
+
+
+def _tensor(seed, idx, shape, dtype, mean=0.0, std=1.0):
+    n = int(np.prod(shape, dtype=np.int64))
+    return rng.normal_stored(seed, idx, n, dtype, mean, std).reshape(shape)
+
+
+def cfg1_add_layernorm(rows=64, cols=768, seed=0, use_var_op=False):
+    """Residual add + LayerNorm over the last dim, fp32, eps = 1e-5."""
+    g = Builder()
+    x = g.input("f32", (rows, cols))
+    r = g.input("f32", (rows, cols))
+    gamma = g.input("f32", (cols,))
+    beta = g.input("f32", (cols,))
+    h = g.op("add", [x, r], "f32")
+    mu = g.op("mean", [h], "f32")
+    d = g.op("sub", [h, mu], "f32")
+    if use_var_op:
+        v = g.op("var", [h], "f32", correction=0)
+    else:
+        v = g.op("mean", [g.op("mul", [d, d], "f32")], "f32")
+    eps = g.const(1e-5, "f32")
+    inv = g.op("rsqrt", [g.op("add", [v, eps], "f32")], "f32")
+    y = g.op("add", [g.op("mul", [g.op("mul", [d, inv], "f32"), gamma], "f32"), beta], "f32")
+    g.output(y)
+    ins = [_tensor(seed, 0, (rows, cols), "f32"), _tensor(seed, 1, (rows, cols), "f32"),
+           _tensor(seed, 2, (cols,), "f32", 1.0, 0.1), _tensor(seed, 3, (cols,), "f32", 0.0, 0.1)]
+    return Workload("cfg1_add_layernorm_f32_%dx%d" % (rows, cols), g.text(), ins,
+                    ["f32"] * 4, [(rows, cols), (rows, cols), (cols,), (cols,)],
+                    ["f32"], [(rows, cols)], meta={"eps": 1e-5}).finish()
+
+
+def causal_mask_bits(n):
+    """Additive causal mask [n, n] in bf16 bits: 0 on and below the diagonal, -inf above."""
+    m = np.zeros((n, n), dtype=np.uint16)
+    m[np.triu_indices(n, k=1)] = np.uint16(0xFF80)
+    return m
+
+
+def cfg2_masked_softmax(heads=32, seq=512, seed=1):
+    """Scaled, causally masked softmax over the last dim, bf16; scale = 1/sqrt(64)."""
+    g = Builder()
+    z = g.input("bf16", (heads, seq, seq))
+    m = g.input("bf16", (seq, seq))
+    s = g.const(0.125, "bf16")
+    t = g.op("add", [g.op("mul", [z, s], "bf16"), m], "bf16")
+    mx = g.op("max", [t], "bf16")
+    e = g.op("exp", [g.op("sub", [t, mx], "bf16")], "bf16")
+    y = g.op("div", [e, g.op("sum", [e], "bf16")], "bf16")
+    g.output(y)
+    ins = [_tensor(seed, 0, (heads, seq, seq), "bf16", 0.0, 2.0), causal_mask_bits(seq)]
+    return Workload("cfg2_masked_softmax_bf16_%dx%dx%d" % (heads, seq, seq), g.text(), ins,
+                    ["bf16", "bf16"], [(heads, seq, seq), (seq, seq)],
+                    ["bf16"], [(heads, seq, seq)], meta={"scale": 0.125}).finish()
+
+
+def cfg3_bias_gelu_gate(rows=8192, cols=11008, seed=2):
+    """out = gelu_tanh(a + bias) * b, bf16, bias broadcast over rows."""
+    g = Builder()
+    a = g.input("bf16", (rows, cols))
+    bias = g.input("bf16", (cols,))
+    b = g.input("bf16", (rows, cols))
+    y = g.op("mul", [g.op("gelu", [g.op("add", [a, bias], "bf16")], "bf16", approx="tanh"), b], "bf16")
+    g.output(y)
+    ins = [_tensor(seed, 0, (rows, cols), "bf16"), _tensor(seed, 1, (cols,), "bf16", 0.0, 0.02),
+           _tensor(seed, 2, (rows, cols), "bf16")]
+    return Workload("cfg3_bias_gelu_gate_bf16_%dx%d" % (rows, cols), g.text(), ins,
+                    ["bf16"] * 3, [(rows, cols), (cols,), (rows, cols)],
+                    ["bf16"], [(rows, cols)]).finish()
+
+
+def rotary_tables(positions, dim, base=10000.0):
+    """cos/sin tables [positions, 1, dim] in fp32 for interleaved pairs.
+
+    Pair i of the last dim (elements 2i, 2i+1) at position p turns by
+    theta = p * base**(-2i/dim); both elements of a pair hold the same entry.
+    """
+    i = np.arange(dim // 2, dtype=np.float64)
+    inv_freq = base ** (-2.0 * i / dim)
+    theta = np.arange(positions, dtype=np.float64)[:, None] * inv_freq[None, :]
+    cos = np.repeat(np.cos(theta), 2, axis=1).reshape(positions, 1, dim)
+    sin = np.repeat(np.sin(theta), 2, axis=1).reshape(positions, 1, dim)
+    return cos.astype(np.float32), sin.astype(np.float32)
+
+
+def cfg4_rmsnorm_rope(batch=4, positions=2048, heads=32, dim=128, seed=3):
+    """Weighted RMSNorm over the last dim (eps = 1e-6) then rotary embedding, bf16."""
+    g = Builder()
+    shape = (batch, positions, heads, dim)
+    x = g.input("bf16", shape)
+    w = g.input("bf16", (dim,))
+    cos = g.input("f32", (positions, 1, dim))
+    sin = g.input("f32", (positions, 1, dim))
+    ms = g.op("mean", [g.op("mul", [x, x], "bf16")], "bf16")
+    eps = g.const(1e-6, "f32")
+    inv = g.op("rsqrt", [g.op("add", [ms, eps], "bf16")], "bf16")
+    n = g.op("mul", [g.op("mul", [x, inv], "bf16"), w], "bf16")
+    y = g.op("add", [g.op("mul", [n, cos], "bf16"),
+                     g.op("mul", [g.op("rot_pairs", [n], "bf16"), sin], "bf16")], "bf16")
+    g.output(y)
+    c, s = rotary_tables(positions, dim)
+    ins = [_tensor(seed, 0, shape, "bf16"), _tensor(seed, 1, (dim,), "bf16", 1.0, 0.1), c, s]
+    return Workload("cfg4_rmsnorm_rope_bf16_%dx%dx%dx%d" % shape, g.text(), ins,
+                    ["bf16", "bf16", "f32", "f32"], [shape, (dim,), (positions, 1, dim), (positions, 1, dim)],
+                    ["bf16"], [shape], meta={"eps": 1e-6, "base": 10000.0}).finish()
