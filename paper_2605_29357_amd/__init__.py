@@ -1,0 +1,242 @@
+"""Python binding of libpf.so, the fused-subgraph engine for MI355X (gfx950).
+
+Argument marshalling only: every step of the hot path (planning, kernel
+specialisation, fused execution, error scoring) runs inside the library.  The
+names mirror include/pf.h.  There is no fallback: if the library has not been
+built (python -m paper_2605_29357_amd.build, or __graft_entry__.build())
+every call raises.
+"""
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpf.so")
+
+PF_OK, PF_E_INVALID, PF_E_COMPILE, PF_E_RUNTIME, PF_E_NOMEM = 0, -1, -2, -3, -4
+F32, BF16, F64 = 0, 1, 2
+DTYPES = {"f32": F32, "bf16": BF16, "f64": F64}
+DTYPE_NAMES = {v: k for k, v in DTYPES.items()}
+OPS = ["input", "const", "add", "sub", "mul", "div", "exp", "tanh", "sigmoid", "gelu", "rsqrt",
+       "sum", "max", "mean", "var", "transpose", "rot_pairs"]
+TEMPLATES = ["ew_flat", "row_resident", "tile", "row_loop"]
+
+
+class PfError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__("pf status %d: %s" % (status, message))
+        self.status = status
+
+
+class _Attr(C.Structure):
+    _fields_ = [("key", C.c_char_p), ("value", C.c_char_p)]
+
+
+class _Options(C.Structure):
+    _fields_ = [("fuse", C.c_int), ("intermediates_f32", C.c_int), ("reserved", C.c_int * 6)]
+
+
+class _NodeInfo(C.Structure):
+    _fields_ = [("op", C.c_int), ("dtype", C.c_int), ("rank", C.c_int), ("shape", C.c_int64 * 4),
+                ("n_in", C.c_int), ("in_nodes", C.c_int * 2), ("is_output", C.c_int)]
+
+
+class _PlanInfo(C.Structure):
+    _fields_ = [("n_kernels", C.c_int), ("n_inputs", C.c_int), ("n_outputs", C.c_int),
+                ("algorithmic_bytes", C.c_uint64), ("workspace_bytes", C.c_uint64), ("planned_bytes", C.c_uint64)]
+
+
+class _GroupInfo(C.Structure):
+    _fields_ = [("tmpl", C.c_int), ("n_nodes", C.c_int), ("nodes", C.c_int * 64), ("rows", C.c_int64),
+                ("cols", C.c_int64), ("block_threads", C.c_int), ("grid_blocks", C.c_int64),
+                ("lanes_per_row", C.c_int), ("bytes_read", C.c_uint64), ("bytes_written", C.c_uint64)]
+
+
+class Pair(C.Structure):
+    _fields_ = [("d_cand", C.c_void_p), ("d_ref", C.c_void_p), ("n", C.c_uint64), ("cand_dtype", C.c_int32),
+                ("ref_dtype", C.c_int32), ("rtol", C.c_double), ("atol", C.c_double), ("equal_nan", C.c_int32),
+                ("reserved", C.c_int32)]
+
+
+class ScoreResult(C.Structure):
+    _fields_ = [("max_abs", C.c_double), ("max_rel", C.c_double), ("n", C.c_uint64), ("n_viol", C.c_uint64),
+                ("nan_cand", C.c_uint64), ("nan_ref", C.c_uint64), ("inf_cand", C.c_uint64), ("inf_ref", C.c_uint64),
+                ("allclose", C.c_uint32), ("bit_identical", C.c_uint32), ("reserved_", C.c_uint64)]
+
+    def as_dict(self):
+        return {k: getattr(self, k) for k, _ in self._fields_ if k != "reserved_"}
+
+
+_lib_handle = None
+
+
+def lib():
+    """The loaded library; raises if it has not been built."""
+    global _lib_handle
+    if _lib_handle is not None:
+        return _lib_handle
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("libpf.so is not built (%s); run `python -m paper_2605_29357_amd.build`" % LIB_PATH)
+    L = C.CDLL(LIB_PATH)
+    vp, ip, sz = C.c_void_p, C.POINTER(C.c_int), C.c_size_t
+    sigs = {
+        "pf_graph_create": [C.POINTER(vp)],
+        "pf_graph_input": [vp, C.c_int, C.c_int, C.POINTER(C.c_int64), ip],
+        "pf_graph_node": [vp, C.c_int, ip, C.c_int, C.POINTER(_Attr), C.c_int, C.c_int, ip],
+        "pf_graph_output": [vp, C.c_int],
+        "pf_graph_parse": [C.c_char_p, sz, C.POINTER(vp)],
+        "pf_graph_print": [vp, C.c_char_p, sz, C.POINTER(sz)],
+        "pf_graph_size": [vp, ip, ip, ip],
+        "pf_graph_node_info": [vp, C.c_int, C.POINTER(_NodeInfo)],
+        "pf_compile": [vp, C.POINTER(_Options), C.POINTER(vp)],
+        "pf_exec_info": [vp, C.POINTER(_PlanInfo)],
+        "pf_exec_group_info": [vp, C.c_int, C.POINTER(_GroupInfo)],
+        "pf_exec_source": [vp, C.c_int, C.c_char_p, sz, C.POINTER(sz)],
+        "pf_execute": [vp, C.POINTER(vp), C.c_int, C.POINTER(vp), C.c_int, vp, sz, vp],
+        "pf_score": [C.POINTER(Pair), C.c_int, vp, vp, sz, vp],
+        "pf_copy_bytes": [vp, vp, sz, vp],
+    }
+    for name, args in sigs.items():
+        fn = getattr(L, name)
+        fn.argtypes = args
+        fn.restype = C.c_int
+    L.pf_graph_destroy.argtypes = [vp]
+    L.pf_graph_destroy.restype = None
+    L.pf_exec_destroy.argtypes = [vp]
+    L.pf_exec_destroy.restype = None
+    L.pf_options_default.argtypes = [C.POINTER(_Options)]
+    L.pf_options_default.restype = None
+    L.pf_score_workspace_bytes.argtypes = [C.c_int]
+    L.pf_score_workspace_bytes.restype = sz
+    L.pf_last_error.restype = C.c_char_p
+    L.pf_version.restype = C.c_char_p
+    _lib_handle = L
+    return L
+
+
+def _check(status):
+    if status != PF_OK:
+        raise PfError(status, lib().pf_last_error().decode("utf-8", "replace"))
+
+
+def version():
+    return lib().pf_version().decode()
+
+
+class Graph:
+    """pf_graph handle."""
+
+    def __init__(self, text=None):
+        self._h = C.c_void_p()
+        if text is None:
+            _check(lib().pf_graph_create(C.byref(self._h)))
+        else:
+            b = text.encode()
+            _check(lib().pf_graph_parse(b, len(b), C.byref(self._h)))
+
+    def __del__(self):
+        if getattr(self, "_h", None) and _lib_handle is not None:
+            _lib_handle.pf_graph_destroy(self._h)
+            self._h = None
+
+    def input(self, dtype, shape):
+        out = C.c_int()
+        arr = (C.c_int64 * max(len(shape), 1))(*shape)
+        _check(lib().pf_graph_input(self._h, DTYPES[dtype], len(shape), arr, C.byref(out)))
+        return out.value
+
+    def node(self, op, operands, dtype, **attrs):
+        out = C.c_int()
+        ins = (C.c_int * max(len(operands), 1))(*operands)
+        at = (_Attr * max(len(attrs), 1))()
+        for i, (k, v) in enumerate(attrs.items()):
+            at[i].key = k.encode()
+            at[i].value = (repr(v) if isinstance(v, float) else str(v)).encode()
+        _check(lib().pf_graph_node(self._h, OPS.index(op), ins, len(operands), at, len(attrs), DTYPES[dtype], C.byref(out)))
+        return out.value
+
+    def output(self, node):
+        _check(lib().pf_graph_output(self._h, node))
+
+    def text(self):
+        need = C.c_size_t()
+        _check(lib().pf_graph_print(self._h, None, 0, C.byref(need)))
+        buf = C.create_string_buffer(need.value)
+        _check(lib().pf_graph_print(self._h, buf, need.value, C.byref(need)))
+        return buf.value.decode()
+
+    def size(self):
+        a, b, c = C.c_int(), C.c_int(), C.c_int()
+        _check(lib().pf_graph_size(self._h, C.byref(a), C.byref(b), C.byref(c)))
+        return a.value, b.value, c.value
+
+    def node_info(self, node):
+        ni = _NodeInfo()
+        _check(lib().pf_graph_node_info(self._h, node, C.byref(ni)))
+        return {"op": OPS[ni.op], "dtype": DTYPE_NAMES[ni.dtype], "shape": tuple(ni.shape[:ni.rank]),
+                "inputs": list(ni.in_nodes[:ni.n_in]), "is_output": bool(ni.is_output)}
+
+
+class Exec:
+    """pf_exec handle: a planned and compiled subgraph."""
+
+    def __init__(self, graph, fuse=True, intermediates_f32=None):
+        self._h = C.c_void_p()
+        opt = _Options()
+        lib().pf_options_default(C.byref(opt))
+        opt.fuse = 1 if fuse else 0
+        if intermediates_f32 is not None:
+            opt.intermediates_f32 = 1 if intermediates_f32 else 0
+        if isinstance(graph, str):
+            graph = Graph(graph)
+        self.graph = graph
+        _check(lib().pf_compile(graph._h, C.byref(opt), C.byref(self._h)))
+
+    def __del__(self):
+        if getattr(self, "_h", None) and _lib_handle is not None:
+            _lib_handle.pf_exec_destroy(self._h)
+            self._h = None
+
+    def info(self):
+        pi = _PlanInfo()
+        _check(lib().pf_exec_info(self._h, C.byref(pi)))
+        return {k: getattr(pi, k) for k, _ in pi._fields_}
+
+    def group_info(self, i):
+        gi = _GroupInfo()
+        _check(lib().pf_exec_group_info(self._h, i, C.byref(gi)))
+        d = {k: getattr(gi, k) for k, _ in gi._fields_ if k not in ("nodes", "tmpl")}
+        d["template"] = TEMPLATES[gi.tmpl]
+        d["nodes"] = list(gi.nodes[:gi.n_nodes])
+        return d
+
+    def groups(self):
+        return [self.group_info(i) for i in range(self.info()["n_kernels"])]
+
+    def source(self, i):
+        need = C.c_size_t()
+        _check(lib().pf_exec_source(self._h, i, None, 0, C.byref(need)))
+        buf = C.create_string_buffer(need.value)
+        _check(lib().pf_exec_source(self._h, i, buf, need.value, C.byref(need)))
+        return buf.value.decode()
+
+    def execute(self, input_ptrs, output_ptrs, workspace_ptr=0, workspace_bytes=0, stream=0):
+        """Device pointers as ints; enqueues the kernels on `stream` (a hipStream_t as int)."""
+        ins = (C.c_void_p * max(len(input_ptrs), 1))(*input_ptrs)
+        outs = (C.c_void_p * max(len(output_ptrs), 1))(*output_ptrs)
+        _check(lib().pf_execute(self._h, ins, len(input_ptrs), outs, len(output_ptrs),
+                                C.c_void_p(workspace_ptr), workspace_bytes, C.c_void_p(stream)))
+
+
+def score_workspace_bytes(n_pairs):
+    return lib().pf_score_workspace_bytes(n_pairs)
+
+
+def score(pairs, results_ptr, workspace_ptr, workspace_bytes, stream=0):
+    """pairs: list of Pair; results_ptr: device pointer to len(pairs) ScoreResult structs."""
+    arr = (Pair * max(len(pairs), 1))(*pairs)
+    _check(lib().pf_score(arr, len(pairs), C.c_void_p(results_ptr), C.c_void_p(workspace_ptr), workspace_bytes,
+                          C.c_void_p(stream)))
+
+
+def copy_bytes(dst_ptr, src_ptr, nbytes, stream=0):
+    _check(lib().pf_copy_bytes(C.c_void_p(dst_ptr), C.c_void_p(src_ptr), nbytes, C.c_void_p(stream)))

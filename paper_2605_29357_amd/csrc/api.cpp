@@ -1,0 +1,334 @@
+// The C boundary.  Every entry point catches, records the message in a
+// thread-local string and returns a pf_status.
+#include <hip/hip_runtime_api.h>
+
+#include <cstring>
+#include <memory>
+#include <new>
+
+#include "exec.h"
+#include "pf_internal.h"
+#include "score_dev.h"
+
+namespace {
+
+thread_local std::string g_last_error;
+
+template <typename F>
+pf_status guarded(F&& f) {
+    try {
+        f();
+        return PF_OK;
+    } catch (const pf::Error& e) {
+        g_last_error = e.what();
+        return e.status;
+    } catch (const std::bad_alloc&) {
+        g_last_error = "out of host memory";
+        return PF_E_NOMEM;
+    } catch (const std::exception& e) {
+        g_last_error = e.what();
+        return PF_E_INVALID;
+    }
+}
+
+void need(const void* p, const char* what) {
+    if (!p) pf::fail(PF_E_INVALID, "%s is NULL", what);
+}
+
+pf_status copy_out(const std::string& s, char* buf, size_t cap, size_t* needed) {
+    if (needed) *needed = s.size() + 1;
+    if (buf && cap) {
+        size_t n = s.size() < cap - 1 ? s.size() : cap - 1;
+        memcpy(buf, s.data(), n);
+        buf[n] = '\0';
+        if (n < s.size()) {
+            g_last_error = "buffer too small";
+            return PF_E_INVALID;
+        }
+    }
+    return PF_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* pf_last_error(void) { return g_last_error.c_str(); }
+const char* pf_version(void) { return "pf 0.1 (gfx950)"; }
+
+pf_status pf_graph_create(pf_graph** g) {
+    return guarded([&] {
+        need(g, "g");
+        *g = new pf_graph();
+    });
+}
+
+void pf_graph_destroy(pf_graph* g) { delete g; }
+
+pf_status pf_graph_input(pf_graph* g, pf_dtype dtype, int rank, const int64_t* h_shape, int* node_out) {
+    return guarded([&] {
+        need(g, "g");
+        if (rank < 0 || rank > PF_MAX_RANK) pf::fail(PF_E_COMPILE, "rank %d out of range", rank);
+        if (rank) need(h_shape, "h_shape");
+        int id = pf::graph_add_input(*g, dtype, pf::Shape(h_shape, h_shape + rank));
+        if (node_out) *node_out = id;
+    });
+}
+
+pf_status pf_graph_node(pf_graph* g, pf_op op, const int* h_in_nodes, int n_in, const pf_attr* h_attrs, int n_attr,
+                        pf_dtype out_dtype, int* node_out) {
+    return guarded([&] {
+        need(g, "g");
+        if (n_in < 0 || n_in > 2) pf::fail(PF_E_COMPILE, "operators take at most two operands");
+        if (n_in) need(h_in_nodes, "h_in_nodes");
+        if (n_attr < 0) pf::fail(PF_E_INVALID, "n_attr < 0");
+        if (n_attr) need(h_attrs, "h_attrs");
+        std::vector<std::pair<std::string, std::string>> attrs;
+        for (int i = 0; i < n_attr; ++i) {
+            need(h_attrs[i].key, "attr key");
+            need(h_attrs[i].value, "attr value");
+            attrs.emplace_back(h_attrs[i].key, h_attrs[i].value);
+        }
+        int id = pf::graph_add_node(*g, op, std::vector<int>(h_in_nodes, h_in_nodes + n_in), attrs, out_dtype);
+        if (node_out) *node_out = id;
+    });
+}
+
+pf_status pf_graph_output(pf_graph* g, int node) {
+    return guarded([&] {
+        need(g, "g");
+        pf::graph_add_output(*g, node);
+    });
+}
+
+pf_status pf_graph_parse(const char* h_text, size_t len, pf_graph** g) {
+    return guarded([&] {
+        need(h_text, "h_text");
+        need(g, "g");
+        *g = nullptr;
+        pf_graph* ng = new pf_graph();
+        try {
+            pf::graph_parse(std::string(h_text, len), *ng);
+        } catch (...) {
+            delete ng;
+            throw;
+        }
+        *g = ng;
+    });
+}
+
+pf_status pf_graph_print(const pf_graph* g, char* h_buf, size_t cap, size_t* needed) {
+    pf_status st = PF_OK;
+    pf_status outer = guarded([&] {
+        need(g, "g");
+        st = copy_out(pf::graph_print(*g), h_buf, cap, needed);
+    });
+    return outer != PF_OK ? outer : st;
+}
+
+pf_status pf_graph_size(const pf_graph* g, int* n_nodes, int* n_inputs, int* n_outputs) {
+    return guarded([&] {
+        need(g, "g");
+        if (n_nodes) *n_nodes = (int)g->nodes.size();
+        if (n_inputs) *n_inputs = (int)g->inputs.size();
+        if (n_outputs) *n_outputs = (int)g->outputs.size();
+    });
+}
+
+pf_status pf_graph_node_info(const pf_graph* g, int node, pf_node_info* h_info) {
+    return guarded([&] {
+        need(g, "g");
+        need(h_info, "h_info");
+        if (node < 0 || node >= (int)g->nodes.size()) pf::fail(PF_E_INVALID, "node %d out of range", node);
+        const pf::Node& n = g->nodes[node];
+        memset(h_info, 0, sizeof *h_info);
+        h_info->op = n.op;
+        h_info->dtype = n.dtype;
+        h_info->rank = (int)n.shape.size();
+        for (size_t i = 0; i < n.shape.size(); ++i) h_info->shape[i] = n.shape[i];
+        h_info->n_in = (int)n.in.size();
+        for (size_t i = 0; i < n.in.size() && i < 2; ++i) h_info->in_nodes[i] = n.in[i];
+        h_info->is_output = n.is_output ? 1 : 0;
+    });
+}
+
+void pf_options_default(pf_options* h_opt) {
+    if (!h_opt) return;
+    memset(h_opt, 0, sizeof *h_opt);
+    h_opt->fuse = 1;
+    h_opt->intermediates_f32 = 1;
+}
+
+pf_status pf_compile(const pf_graph* g, const pf_options* h_opt, pf_exec** e) {
+    return guarded([&] {
+        need(g, "g");
+        need(e, "e");
+        *e = nullptr;
+        pf_options opt;
+        pf_options_default(&opt);
+        if (h_opt) opt = *h_opt;
+        for (int r : opt.reserved)
+            if (r) pf::fail(PF_E_INVALID, "pf_options.reserved must be zero");
+        std::unique_ptr<pf_exec> ex(new pf_exec());
+        ex->opt = opt;
+        pf::make_plan(*g, opt, ex->plan);
+        int idx = 0;
+        for (auto& grp : ex->plan.groups) {
+            pf::generate_source(*g, opt, grp, idx++);
+            pf::jit_compile(grp);
+        }
+        ex->n_inputs = (int)g->inputs.size();
+        ex->n_outputs = (int)g->outputs.size();
+        for (int i : g->inputs) ex->input_bytes.push_back((uint64_t)pf::numel(g->nodes[i].shape) * pf::itemsize(g->nodes[i].dtype));
+        for (int o : g->outputs) ex->output_bytes.push_back((uint64_t)pf::numel(g->nodes[o].shape) * pf::itemsize(g->nodes[o].dtype));
+        *e = ex.release();
+    });
+}
+
+void pf_exec_destroy(pf_exec* e) {
+    if (!e) return;
+    pf::exec_unload(*e);
+    delete e;
+}
+
+pf_status pf_exec_info(const pf_exec* e, pf_plan_info* h_info) {
+    return guarded([&] {
+        need(e, "e");
+        need(h_info, "h_info");
+        memset(h_info, 0, sizeof *h_info);
+        h_info->n_kernels = (int)e->plan.groups.size();
+        h_info->n_inputs = e->n_inputs;
+        h_info->n_outputs = e->n_outputs;
+        h_info->algorithmic_bytes = e->plan.algorithmic_bytes;
+        h_info->workspace_bytes = e->plan.workspace_bytes;
+        for (auto& grp : e->plan.groups) h_info->planned_bytes += grp.bytes_read + grp.bytes_written;
+    });
+}
+
+pf_status pf_exec_group_info(const pf_exec* e, int group, pf_group_info* h_info) {
+    return guarded([&] {
+        need(e, "e");
+        need(h_info, "h_info");
+        if (group < 0 || group >= (int)e->plan.groups.size()) pf::fail(PF_E_INVALID, "group %d out of range", group);
+        const pf::Group& grp = e->plan.groups[group];
+        memset(h_info, 0, sizeof *h_info);
+        h_info->tmpl = grp.tmpl;
+        h_info->n_nodes = (int)grp.nodes.size();
+        for (size_t i = 0; i < grp.nodes.size() && i < 64; ++i) h_info->nodes[i] = grp.nodes[i];
+        h_info->rows = grp.rows;
+        h_info->cols = grp.cols;
+        h_info->block_threads = grp.block;
+        h_info->grid_blocks = grp.grid;
+        h_info->lanes_per_row = grp.lanes_per_row;
+        h_info->bytes_read = grp.bytes_read;
+        h_info->bytes_written = grp.bytes_written;
+    });
+}
+
+pf_status pf_exec_source(const pf_exec* e, int group, char* h_buf, size_t cap, size_t* needed) {
+    pf_status st = PF_OK;
+    pf_status outer = guarded([&] {
+        need(e, "e");
+        if (group < 0 || group >= (int)e->plan.groups.size()) pf::fail(PF_E_INVALID, "group %d out of range", group);
+        st = copy_out(e->plan.groups[group].source, h_buf, cap, needed);
+    });
+    return outer != PF_OK ? outer : st;
+}
+
+pf_status pf_execute(pf_exec* e, const void* const* d_inputs, int n_in, void* const* d_outputs, int n_out, void* d_workspace,
+                     size_t workspace_bytes, void* stream) {
+    return guarded([&] {
+        need(e, "e");
+        if (n_in != e->n_inputs) pf::fail(PF_E_RUNTIME, "expected %d input buffers, got %d", e->n_inputs, n_in);
+        if (n_out != e->n_outputs) pf::fail(PF_E_RUNTIME, "expected %d output buffers, got %d", e->n_outputs, n_out);
+        if (n_in) need(d_inputs, "d_inputs");
+        need(d_outputs, "d_outputs");
+        for (int i = 0; i < n_in; ++i) {
+            if (!d_inputs[i]) pf::fail(PF_E_RUNTIME, "input buffer %d is NULL", i);
+            if ((uintptr_t)d_inputs[i] & 15) pf::fail(PF_E_INVALID, "input buffer %d is not 16-byte aligned", i);
+        }
+        for (int i = 0; i < n_out; ++i) {
+            if (!d_outputs[i]) pf::fail(PF_E_RUNTIME, "output buffer %d is NULL", i);
+            if ((uintptr_t)d_outputs[i] & 15) pf::fail(PF_E_INVALID, "output buffer %d is not 16-byte aligned", i);
+        }
+        if (e->plan.workspace_bytes) {
+            if (!d_workspace || workspace_bytes < e->plan.workspace_bytes)
+                pf::fail(PF_E_RUNTIME, "workspace of %llu bytes needed, %zu given", (unsigned long long)e->plan.workspace_bytes,
+                         workspace_bytes);
+            if ((uintptr_t)d_workspace & 255) pf::fail(PF_E_INVALID, "workspace is not 256-byte aligned");
+        }
+        pf::exec_run(*e, d_inputs, d_outputs, d_workspace, stream);
+    });
+}
+
+size_t pf_score_workspace_bytes(int n_pairs) {
+    if (n_pairs < 0) n_pairs = 0;
+    size_t b = (size_t)n_pairs * sizeof(pf::PairDev);
+    b = (b + 255) / 256 * 256;
+    return b + ((size_t)n_pairs + 1) * sizeof(unsigned long long);
+}
+
+pf_status pf_score(const pf_pair* h_pairs, int n_pairs, pf_score_result* d_results, void* d_workspace, size_t workspace_bytes,
+                   void* stream) {
+    return guarded([&] {
+        if (n_pairs < 0) pf::fail(PF_E_INVALID, "n_pairs < 0");
+        if (n_pairs == 0) return;
+        need(h_pairs, "h_pairs");
+        need(d_results, "d_results");
+        need(d_workspace, "d_workspace");
+        if (workspace_bytes < pf_score_workspace_bytes(n_pairs)) pf::fail(PF_E_RUNTIME, "score workspace too small");
+        if ((uintptr_t)d_workspace & 255) pf::fail(PF_E_INVALID, "workspace is not 256-byte aligned");
+        const size_t pairs_bytes = ((size_t)n_pairs * sizeof(pf::PairDev) + 255) / 256 * 256;
+        pf::PairDev* d_pairs = (pf::PairDev*)d_workspace;
+        unsigned long long* d_start = (unsigned long long*)((char*)d_workspace + pairs_bytes);
+        const unsigned long long chunk = pf::score_chunk_elems();
+        for (int i = 0; i < n_pairs; ++i) {
+            const pf_pair& p = h_pairs[i];
+            if (p.cand_dtype != PF_F32 && p.cand_dtype != PF_BF16) pf::fail(PF_E_INVALID, "pair %d: candidate dtype must be f32 or bf16", i);
+            if (p.ref_dtype != PF_F32 && p.ref_dtype != PF_BF16 && p.ref_dtype != PF_F64) pf::fail(PF_E_INVALID, "pair %d: bad reference dtype", i);
+            if (p.n && (!p.d_cand || !p.d_ref)) pf::fail(PF_E_INVALID, "pair %d: NULL buffer", i);
+            if (((uintptr_t)p.d_cand | (uintptr_t)p.d_ref) & 15) pf::fail(PF_E_INVALID, "pair %d: buffers must be 16-byte aligned", i);
+            if (!(p.rtol >= 0.0) || !(p.atol >= 0.0)) pf::fail(PF_E_INVALID, "pair %d: tolerances must be >= 0", i);
+        }
+        unsigned long long total = 0;
+        hipError_t err = hipSuccess;
+        for (int first = 0; first < n_pairs; first += pf::kPairBatch) {
+            pf::PairBatch b;
+            memset(&b, 0, sizeof b);
+            b.first = first;
+            b.count = n_pairs - first < pf::kPairBatch ? n_pairs - first : pf::kPairBatch;
+            b.last = first + b.count == n_pairs;
+            for (int k = 0; k < b.count; ++k) {
+                const pf_pair& p = h_pairs[first + k];
+                b.pairs[k].cand = p.d_cand;
+                b.pairs[k].ref = p.d_ref;
+                b.pairs[k].n = p.n;
+                b.pairs[k].cand_dtype = p.cand_dtype;
+                b.pairs[k].ref_dtype = p.ref_dtype;
+                b.pairs[k].rtol = p.rtol;
+                b.pairs[k].atol = p.atol;
+                b.pairs[k].equal_nan = p.equal_nan;
+                b.start[k] = total;
+                total += (p.n + chunk - 1) / chunk;
+            }
+            b.start[b.count] = total;
+            if (total >= (1ull << 31)) pf::fail(PF_E_INVALID, "too many elements for one scoring call");
+            err = pf::launch_score_upload(b, d_pairs, d_start, (hipStream_t)stream);
+            if (err != hipSuccess) pf::fail(PF_E_RUNTIME, "descriptor upload failed: %s", hipGetErrorString(err));
+        }
+        err = pf::launch_score(d_pairs, d_start, n_pairs, total, d_results, (hipStream_t)stream);
+        if (err != hipSuccess) pf::fail(PF_E_RUNTIME, "score launch failed: %s", hipGetErrorString(err));
+    });
+}
+
+pf_status pf_copy_bytes(void* d_dst, const void* d_src, size_t bytes, void* stream) {
+    return guarded([&] {
+        need(d_dst, "d_dst");
+        need(d_src, "d_src");
+        if ((bytes & 15) || (((uintptr_t)d_dst | (uintptr_t)d_src) & 15)) pf::fail(PF_E_INVALID, "copy needs 16-byte granularity");
+        hipError_t err = pf::launch_copy(d_dst, d_src, bytes, (hipStream_t)stream);
+        if (err != hipSuccess) pf::fail(PF_E_RUNTIME, "copy launch failed: %s", hipGetErrorString(err));
+    });
+}
+
+}  // extern "C"

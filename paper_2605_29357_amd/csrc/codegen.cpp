@@ -1,0 +1,633 @@
+// Kernel specialisation: emits the HIP source of one fused group.
+//
+// Each template is a hand-written skeleton (how elements map to lanes, how
+// they are loaded, reduced and stored); the operators of the group become a
+// straight-line body over per-lane register arrays.  All shapes are static, so
+// every extent, stride and divisor is a literal in the emitted source.
+//
+//   EW_FLAT       elementwise chains, broadcast operands; flat 16-byte vectors
+//   ROW_RESIDENT  last-dim reductions + epilogue; a team of T lanes holds one
+//                 row in registers: one HBM read, one write (the paper's Case 1
+//                 kernel makes three passes over the row instead)
+//   TILE          groups that read a tensor through a swap of its last two
+//                 dims; 64x64 tiles staged through LDS
+#include <cmath>
+#include <cstring>
+#include <set>
+
+#include "device_prelude.h"
+#include "pf_internal.h"
+
+namespace pf {
+
+namespace {
+
+struct Emit {
+    const pf_graph& g;
+    const pf_options& opt;
+    Group& grp;
+    std::string s;                       // source being built
+    std::map<int, int> operand_of;       // node -> operand index (plain reads)
+    std::map<int, int> toperand_of;      // node -> operand index (transposed reads)
+    std::set<int> members;
+    std::map<int, int> kind;             // member/operand node -> 2 full, 1 row-uniform
+    bool precise = false;
+    bool wide = false;                   // 64-bit indexing
+    int rd = 0;                          // domain rank
+
+    Emit(const pf_graph& gr, const pf_options& o, Group& gp) : g(gr), opt(o), grp(gp) {}
+
+    void line(const std::string& t) { s += t; s += '\n'; }
+
+    static std::string lit(double v) {
+        if (std::isnan(v)) return "__builtin_nanf(\"\")";
+        if (std::isinf(v)) return v > 0 ? "__builtin_inff()" : "(-__builtin_inff())";
+        return strf("((float)%a)", v);
+    }
+    const char* ctype(pf_dtype d) const { return d == PF_BF16 ? "u16" : "float"; }
+    const char* idx_t() const { return wide ? "long long" : "unsigned"; }
+
+    bool in_kernel(int p) const {
+        if (!members.count(p)) return false;
+        const Node& n = g.nodes[p];
+        return !(is_reduction(n.op) && !n.keepdim);
+    }
+
+    // expression for the value of node p at register slot j (a string like "j" or "3")
+    std::string ref(int consumer, int p, const std::string& j) const {
+        const Node& n = g.nodes[p];
+        if (n.op == PF_OP_CONST) return lit(n.value);
+        (void)consumer;
+        if (in_kernel(p)) return kind.at(p) == 2 ? strf("v%d[%s]", p, j.c_str()) : strf("s%d", p);
+        int oi = operand_of.at(p);
+        return operand_kind(oi) == 2 ? strf("x%d[%s]", oi, j.c_str()) : strf("x%d", oi);
+    }
+
+    // 2: varies along the last dim (array per lane); 1: uniform along it (scalar per row)
+    int operand_kind(int oi) const {
+        const Operand& o = grp.operands[oi];
+        if (grp.tmpl == PF_T_TILE) return 2;
+        if (grp.tmpl == PF_T_EW_FLAT && straddle) return 2;
+        if (rd == 0) return 1;
+        if (grp.cols == 1) return 2;          // last dim of size 1: "full" and "row-uniform" coincide
+        return o.stride[rd - 1] != 0 ? 2 : 1;
+    }
+
+    bool straddle = false;
+
+    int node_kind(int id) const {
+        const Node& n = g.nodes[id];
+        if (is_reduction(n.op)) return 1;
+        if (grp.tmpl != PF_T_ROW_RESIDENT) return 2;
+        if (grp.cols == 1) return 2;
+        // row-uniform iff every operand is
+        for (int p : n.in) {
+            if (g.nodes[p].op == PF_OP_CONST) continue;
+            int k = in_kernel(p) ? kind.at(p) : operand_kind(operand_of.at(p));
+            if (k == 2) return 2;
+        }
+        return 1;
+    }
+
+    // ---- body: one statement (or loop) per member node over N register slots ----
+    void emit_elementwise(int id, int N) {
+        const Node& n = g.nodes[id];
+        const int k = kind.at(id);
+        auto expr = [&](const std::string& j) -> std::string {
+            auto a = [&](int i) { return ref(id, n.in[i], j); };
+            switch (n.op) {
+                case PF_OP_ADD: return a(0) + " + " + a(1);
+                case PF_OP_SUB: return a(0) + " - " + a(1);
+                case PF_OP_MUL: return a(0) + " * " + a(1);
+                case PF_OP_DIV: return "pf_div(" + a(0) + ", " + a(1) + ")";
+                case PF_OP_EXP: return "pf_exp(" + a(0) + ")";
+                case PF_OP_TANH: return "pf_tanh(" + a(0) + ")";
+                case PF_OP_SIGMOID: return "pf_sigmoid(" + a(0) + ")";
+                case PF_OP_GELU: return std::string(n.gelu_erf ? "pf_gelu_erf(" : "pf_gelu_tanh(") + a(0) + ")";
+                case PF_OP_RSQRT: return "pf_rsqrt(" + a(0) + ")";
+                default: fail(PF_E_COMPILE, "internal: %s is not elementwise", op_name(n.op));
+            }
+        };
+        if (n.op == PF_OP_TRANSPOSE) {
+            // value arrives through the transposed operand
+            int oi = toperand_of.at(n.in[0]);
+            line(strf("    float v%d[%d];", id, N));
+            line(strf("    _Pragma(\"unroll\") for (int j = 0; j < %d; ++j) v%d[j] = x%d[j];", N, id, oi));
+            return;
+        }
+        if (n.op == PF_OP_ROT_PAIRS) {
+            if (k != 2) fail(PF_E_COMPILE, "rot_pairs of a row-uniform value");
+            std::string a0 = ref(id, n.in[0], "j + 1"), a1 = ref(id, n.in[0], "j");
+            line(strf("    float v%d[%d];", id, N));
+            line(strf("    _Pragma(\"unroll\") for (int j = 0; j < %d; j += 2) { v%d[j] = -(%s); v%d[j + 1] = %s; }", N, id,
+                      a0.c_str(), id, a1.c_str()));
+            return;
+        }
+        if (k == 2) {
+            line(strf("    float v%d[%d];", id, N));
+            line(strf("    _Pragma(\"unroll\") for (int j = 0; j < %d; ++j) v%d[j] = %s;", N, id, expr("j").c_str()));
+        } else {
+            line(strf("    const float s%d = %s;", id, expr("0").c_str()));
+        }
+    }
+
+    // ================================================================ ROW_RESIDENT
+    void gen_row() {
+        const int64_t C = grp.cols, R = grp.rows;
+        int min_item = 4;
+        for (auto& o : grp.operands)
+            if (operand_kind_pre(o) == 2) min_item = std::min(min_item, itemsize(o.dtype));
+        for (auto& st : grp.stores)
+            if (!st.row_scalar) min_item = std::min(min_item, itemsize(st.dtype));
+        int vec = 16 / min_item;
+        while (vec > 1 && C % vec) vec >>= 1;
+        const int64_t chunks = (C + vec - 1) / vec;
+        const int per_lane_max = 32 / vec > 0 ? 32 / vec : 1;      // keep <= 32 floats per value per lane
+        int T = 1;
+        while (T < 16 && T < chunks) T <<= 1;       // a team's load should cover whole cache lines
+        while (T < 1024 && (chunks + T - 1) / T > std::min<int64_t>(per_lane_max, 4)) T <<= 1;
+        while ((chunks + T - 1) / T > per_lane_max && T < 1024) T <<= 1;
+        int64_t K = (chunks + T - 1) / T;
+        if (K * vec > 64) fail(PF_E_COMPILE, "row of %lld elements does not fit on chip for the resident row template", (long long)C);
+        // few rows: spread each row over more lanes to cut latency
+        while (K > 1 && T < 1024 && R * T < 256 * 256) {
+            T <<= 1;
+            K = (chunks + T - 1) / T;
+        }
+        const int block = T > 256 ? T : 256;
+        const int teams = block / T;
+        const int N = (int)K * vec;
+        const bool mask = (int64_t)K * T * vec != C;
+        grp.block = block;
+        grp.grid = (R + teams - 1) / teams;
+        grp.lanes_per_row = T;
+        grp.vec = vec;
+        grp.chunks_per_lane = (int)K;
+        const char* acc = precise ? "double" : "float";
+
+        int n_red = 0;
+        for (int id : grp.nodes)
+            if (is_reduction(g.nodes[id].op)) n_red += g.nodes[id].op == PF_OP_VAR ? 2 : 1;
+
+        signature();
+        line(strf("    constexpr int T = %d, K = %d, VEC = %d, TEAMS = %d;", T, (int)K, vec, teams));
+        line(strf("    constexpr %s C = %lld, ROWS = %lld;", idx_t(), (long long)C, (long long)R));
+        if (T > 64) line(strf("    __shared__ %s red_lds[%d][%d];", acc, std::max(n_red, 1), block / 64));
+        if (T > 64 && precise) line(strf("    __shared__ float redf_lds[%d][%d];", std::max(n_red, 1), block / 64));
+        line("    const int team = threadIdx.x / T, lane = threadIdx.x % T;");
+        line(strf("    const %s row_raw = (%s)blockIdx.x * TEAMS + team;", idx_t(), idx_t()));
+        line("    const bool row_ok = row_raw < ROWS;");
+        line(strf("    const %s row = row_ok ? row_raw : ROWS - 1;", idx_t()));
+        emit_row_decomposition("row");
+        // loads
+        for (size_t oi = 0; oi < grp.operands.size(); ++oi) {
+            const Operand& o = grp.operands[oi];
+            std::string base = lead_offset(o, "row");
+            if (operand_kind((int)oi) == 1) {
+                line(strf("    const float x%zu = pf_ld1(p%zu + %s);", oi, oi, base.c_str()));
+                continue;
+            }
+            const bool nt = numel(o.shape) * itemsize(o.dtype) >= (int64_t(1) << 22);
+            line(strf("    float x%zu[%d];", oi, N));
+            line(strf("    _Pragma(\"unroll\") for (int k = 0; k < K; ++k) {"));
+            line(strf("        const %s c0 = (%s)(k * T + lane) * VEC;", idx_t(), idx_t()));
+            if (mask) {
+                line(strf("        if (c0 < C) pf_ld<VEC, %s>(p%zu + %s + c0, &x%zu[k * VEC]);", nt ? "true" : "false", oi,
+                          base.c_str(), oi));
+                line(strf("        else { _Pragma(\"unroll\") for (int j = 0; j < VEC; ++j) x%zu[k * VEC + j] = 0.0f; }", oi));
+            } else {
+                line(strf("        pf_ld<VEC, %s>(p%zu + %s + c0, &x%zu[k * VEC]);", nt ? "true" : "false", oi, base.c_str(), oi));
+            }
+            line("    }");
+        }
+        // body
+        int red_slot = 0;
+        for (int id : grp.nodes) {
+            const Node& n = g.nodes[id];
+            if (!is_reduction(n.op)) {
+                emit_elementwise(id, N);
+                continue;
+            }
+            const int src = n.in[0];
+            auto valid_open = [&]() {
+                line("    _Pragma(\"unroll\") for (int k = 0; k < K; ++k) {");
+                if (mask) line(strf("        if ((%s)(k * T + lane) * VEC < C) {", idx_t()));
+                else line("        {");
+                line("            _Pragma(\"unroll\") for (int jj = 0; jj < VEC; ++jj) {");
+                line("                const int j = k * VEC + jj;");
+            };
+            auto valid_close = [&]() { line("            }"); line("        }"); line("    }"); };
+            std::string xj = ref(id, src, "j");
+            if (n.op == PF_OP_MAX) {
+                line(strf("    float m%d = -__builtin_inff(); bool nan%d = false;", id, id));
+                valid_open();
+                line(strf("                const float t = %s; m%d = fmaxf(m%d, t); nan%d |= (t != t);", xj.c_str(), id, id, id));
+                valid_close();
+                line(strf("    m%d = nan%d ? __builtin_nanf(\"\") : m%d;", id, id, id));
+                line(strf("    const float s%d = pf_team_max<T>(m%d, %s);", id, id,
+                          T > 64 ? strf(precise ? "redf_lds[%d]" : "red_lds[%d]", red_slot).c_str() : "nullptr"));
+                ++red_slot;
+                continue;
+            }
+            // sum, mean, var
+            line(strf("    %s a%d = 0;", acc, id));
+            valid_open();
+            line(strf("                a%d += (%s)(%s);", id, acc, xj.c_str()));
+            valid_close();
+            line(strf("    a%d = pf_team_sum<T, %s>(a%d, %s);", id, acc, id,
+                      T > 64 ? strf("red_lds[%d]", red_slot).c_str() : "nullptr"));
+            ++red_slot;
+            if (n.op == PF_OP_SUM) {
+                line(strf("    const float s%d = (float)a%d;", id, id));
+            } else if (n.op == PF_OP_MEAN) {
+                line(strf("    const float s%d = (float)(a%d / (%s)%lld);", id, id, acc, (long long)C));
+            } else {
+                line(strf("    const %s mu%d = a%d / (%s)%lld;", acc, id, id, acc, (long long)C));
+                line(strf("    %s q%d = 0;", acc, id));
+                valid_open();
+                line(strf("                const %s d = (%s)(%s) - mu%d; q%d += d * d;", acc, acc, xj.c_str(), id, id));
+                valid_close();
+                line(strf("    q%d = pf_team_sum<T, %s>(q%d, %s);", id, acc, id,
+                          T > 64 ? strf("red_lds[%d]", red_slot).c_str() : "nullptr"));
+                ++red_slot;
+                line(strf("    const float s%d = (float)(q%d / (%s)%lld);", id, id, acc, (long long)(C - n.correction)));
+            }
+        }
+        // stores
+        int sp = 0;
+        for (auto& st : grp.stores) {
+            std::vector<int> ptrs;
+            ptrs.push_back(sp++);
+            for (size_t k = 0; k < st.also_outputs.size(); ++k) ptrs.push_back(sp++);
+            for (int q : ptrs) {
+                if (st.row_scalar) {
+                    line(strf("    if (row_ok && lane == 0) pf_st1(q%d + row, s%d);", q, st.node));
+                } else if (kind.at(st.node) == 1) {
+                    // a row-uniform value stored at full shape cannot occur: its shape has last dim 1
+                    fail(PF_E_COMPILE, "internal: full store of a row-uniform value");
+                } else {
+                    const bool nt = numel(st.shape) * itemsize(st.dtype) >= (int64_t(1) << 22);
+                    line("    _Pragma(\"unroll\") for (int k = 0; k < K; ++k) {");
+                    line(strf("        const %s c0 = (%s)(k * T + lane) * VEC;", idx_t(), idx_t()));
+                    line(strf("        if (row_ok%s) pf_st<VEC, %s>(q%d + row * C + c0, &v%d[k * VEC]);", mask ? " && c0 < C" : "",
+                              nt ? "true" : "false", q, st.node));
+                    line("    }");
+                }
+            }
+        }
+        line("}");
+    }
+
+    int operand_kind_pre(const Operand& o) const { return rd > 0 && (o.stride[rd - 1] != 0 || grp.cols == 1) ? 2 : 1; }
+
+    // ================================================================ EW_FLAT
+    void gen_flat() {
+        const int64_t C = grp.cols, R = grp.rows, N = C * R;
+        int min_item = 4;
+        for (auto& o : grp.operands) min_item = std::min(min_item, itemsize(o.dtype));
+        for (auto& st : grp.stores) min_item = std::min(min_item, itemsize(st.dtype));
+        const int vec = 16 / min_item;
+        // aligned: a vector never crosses a row, so broadcast operands are uniform or
+        // contiguous inside it; otherwise vectors run over the flat index and
+        // operands that are not plain contiguous are gathered per element
+        bool all_flat = true;
+        for (auto& o : grp.operands)
+            if (!is_contiguous_full(o) && numel(o.shape) != 1) all_flat = false;
+        straddle = (C % vec) != 0;
+        const bool tail = straddle && (N % vec) != 0;
+        const int U = N >= (int64_t(1) << 22) ? 4 : 1;
+        const int block = 256;
+        const int64_t nvec = (N + vec - 1) / vec;
+        grp.block = block;
+        grp.grid = (nvec + (int64_t)block * U - 1) / ((int64_t)block * U);
+        grp.vec = vec;
+        grp.chunks_per_lane = U;
+        grp.lanes_per_row = 0;
+        (void)all_flat;
+
+        // re-evaluate kinds now that straddle is known
+        recompute_kinds();
+
+        // body as a device function of the vector index
+        line(strf("template <bool TAIL> PF_DEV void body(%s, %s v) {", param_list().c_str(), idx_t()));
+        line(strf("    constexpr int VEC = %d;", vec));
+        line(strf("    constexpr %s C = %lld, NEL = %lld;", idx_t(), (long long)C, (long long)N));
+        line(strf("    const %s e0 = v * VEC;", idx_t()));
+        if (!straddle) {
+            line(strf("    const %s row = e0 / C, col0 = e0 %% C;", idx_t()));
+            emit_row_decomposition("row");
+        }
+        for (size_t oi = 0; oi < grp.operands.size(); ++oi) {
+            const Operand& o = grp.operands[oi];
+            const bool nt = numel(o.shape) * itemsize(o.dtype) >= (int64_t(1) << 22);
+            if (!straddle) {
+                std::string base = lead_offset(o, "row");
+                if (operand_kind((int)oi) == 1) line(strf("    const float x%zu = pf_ld1(p%zu + %s);", oi, oi, base.c_str()));
+                else {
+                    line(strf("    float x%zu[VEC];", oi));
+                    line(strf("    pf_ld<VEC, %s>(p%zu + %s + col0, x%zu);", nt ? "true" : "false", oi, base.c_str(), oi));
+                }
+                continue;
+            }
+            line(strf("    float x%zu[VEC];", oi));
+            if (is_contiguous_full(o)) {
+                line(strf("    if (!TAIL) pf_ld<VEC, %s>(p%zu + e0, x%zu);", nt ? "true" : "false", oi, oi));
+                line(strf("    else { _Pragma(\"unroll\") for (int j = 0; j < VEC; ++j) x%zu[j] = (e0 + j < NEL) ? pf_ld1(p%zu + e0 + j) : 0.0f; }",
+                          oi, oi));
+            } else {
+                line("    _Pragma(\"unroll\") for (int j = 0; j < VEC; ++j) {");
+                line(strf("        const %s e = (TAIL && e0 + j >= NEL) ? NEL - 1 : e0 + j;", idx_t()));
+                line(strf("        const %s row = e / C, col = e %% C;", idx_t()));
+                std::string off = element_offset(o, "row", "col");
+                line(strf("        x%zu[j] = pf_ld1(p%zu + %s);", oi, oi, off.c_str()));
+                line("    }");
+            }
+        }
+        for (int id : grp.nodes) emit_elementwise(id, vec);
+        int sp = 0;
+        for (auto& st : grp.stores) {
+            const bool nt = numel(st.shape) * itemsize(st.dtype) >= (int64_t(1) << 22);
+            int cnt = 1 + (int)st.also_outputs.size();
+            for (int c = 0; c < cnt; ++c, ++sp) {
+                line(strf("    if (!TAIL) pf_st<VEC, %s>(q%d + e0, v%d);", nt ? "true" : "false", sp, st.node));
+                line(strf("    else { _Pragma(\"unroll\") for (int j = 0; j < VEC; ++j) if (e0 + j < NEL) pf_st1(q%d + e0 + j, v%d[j]); }",
+                          sp, st.node));
+            }
+        }
+        line("}");
+        signature();
+        line(strf("    constexpr int U = %d, BLOCK = %d;", U, block));
+        line(strf("    constexpr %s NVEC = %lld;", idx_t(), (long long)nvec));
+        line(strf("    const %s v0 = (%s)blockIdx.x * (BLOCK * U) + threadIdx.x;", idx_t(), idx_t()));
+        std::string args = arg_list();
+        if (tail) {
+            line("    _Pragma(\"unroll\") for (int u = 0; u < U; ++u) {");
+            line(strf("        const %s v = v0 + (%s)u * BLOCK;", idx_t(), idx_t()));
+            line(strf("        if (v + 1 < NVEC) body<false>(%s, v); else if (v < NVEC) body<true>(%s, v);", args.c_str(), args.c_str()));
+            line("    }");
+        } else {
+            line(strf("    if (v0 + (%s)(U - 1) * BLOCK < NVEC) {", idx_t()));
+            line(strf("        _Pragma(\"unroll\") for (int u = 0; u < U; ++u) body<false>(%s, v0 + (%s)u * BLOCK);", args.c_str(), idx_t()));
+            line("    } else {");
+            line("        _Pragma(\"unroll\") for (int u = 0; u < U; ++u) {");
+            line(strf("            const %s v = v0 + (%s)u * BLOCK;", idx_t(), idx_t()));
+            line(strf("            if (v < NVEC) body<false>(%s, v);", args.c_str()));
+            line("        }");
+            line("    }");
+        }
+        line("}");
+    }
+
+    // ================================================================ TILE
+    void gen_tile() {
+        if (rd < 2) fail(PF_E_COMPILE, "internal: tiled group of rank < 2");
+        const int64_t C = grp.domain[rd - 1], R = grp.domain[rd - 2];
+        int64_t L = 1;
+        for (int k = 0; k < rd - 2; ++k) L *= grp.domain[k];
+        const int64_t tr = (R + 63) / 64, tc = (C + 63) / 64;
+        grp.block = 256;
+        grp.grid = L * tr * tc;
+        grp.vec = 4;
+        grp.chunks_per_lane = 4;
+        grp.lanes_per_row = 0;
+        int n_t = 0;
+        for (auto& o : grp.operands) n_t += o.transposed ? 1 : 0;
+
+        signature();
+        line(strf("    constexpr %s C = %lld, R = %lld, TR = %lld, TC = %lld;", idx_t(), (long long)C, (long long)R, (long long)tr,
+                  (long long)tc));
+        line(strf("    __shared__ float tile[%d][64][65];", std::max(n_t, 1)));
+        line(strf("    const %s b = blockIdx.x;", idx_t()));
+        line(strf("    const %s tcol = b %% TC, trow = (b / TC) %% TR, lead = b / (TC * TR);", idx_t()));
+        line(strf("    const %s r0 = trow * 64, c0 = tcol * 64;", idx_t()));
+        line("    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;");
+        emit_lead_decomposition("lead", rd - 2);
+        // stage transposed operands through LDS: memory is [.., C, R] with R contiguous
+        int ti = 0;
+        for (size_t oi = 0; oi < grp.operands.size(); ++oi) {
+            const Operand& o = grp.operands[oi];
+            if (!o.transposed) continue;
+            std::string base = lead_offset_n(o, rd - 2);
+            const bool vec_ok = (R % 4 == 0) && lead_strides_multiple_of(o, 4, rd - 2);
+            line("    _Pragma(\"unroll\") for (int i = 0; i < 4; ++i) {");
+            line(strf("        const %s cc = c0 + ty + 16 * i, rr = r0 + tx * 4;", idx_t()));
+            line("        float t4[4] = {0.0f, 0.0f, 0.0f, 0.0f};");
+            if (vec_ok) {
+                line(strf("        if (cc < C && rr < R) pf_ld<4, false>(p%zu + %s + cc * R + rr, t4);", oi, base.c_str()));
+            } else {
+                line(strf("        if (cc < C) { _Pragma(\"unroll\") for (int j = 0; j < 4; ++j) if (rr + j < R) t4[j] = pf_ld1(p%zu + %s + cc * R + rr + j); }",
+                          oi, base.c_str()));
+            }
+            line(strf("        _Pragma(\"unroll\") for (int j = 0; j < 4; ++j) tile[%d][ty + 16 * i][tx * 4 + j] = t4[j];", ti));
+            line("    }");
+            ++ti;
+        }
+        if (n_t) line("    __syncthreads();");
+        ti = 0;
+        for (size_t oi = 0; oi < grp.operands.size(); ++oi) {
+            const Operand& o = grp.operands[oi];
+            line(strf("    float x%zu[16];", oi));
+            if (o.transposed) {
+                line("    _Pragma(\"unroll\") for (int i = 0; i < 4; ++i)");
+                line(strf("        _Pragma(\"unroll\") for (int j = 0; j < 4; ++j) x%zu[i * 4 + j] = tile[%d][tx * 4 + j][ty + 16 * i];", oi, ti));
+                ++ti;
+                continue;
+            }
+            std::string base = lead_offset_n(o, rd - 2);
+            const int64_t sr = o.stride[rd - 2], sc = o.stride[rd - 1];
+            const bool vec_ok = sc == 1 && (C % 4 == 0) && (sr % 4 == 0) && lead_strides_multiple_of(o, 4, rd - 2);
+            line("    _Pragma(\"unroll\") for (int i = 0; i < 4; ++i) {");
+            line(strf("        const %s rr = r0 + ty + 16 * i, cc = c0 + tx * 4;", idx_t()));
+            line(strf("        const %s rc = rr < R ? rr : R - 1;", idx_t()));
+            if (vec_ok) {
+                line(strf("        if (cc < C) pf_ld<4, false>(p%zu + %s + rc * %lld + cc, &x%zu[i * 4]);", oi, base.c_str(), (long long)sr, oi));
+                line(strf("        else { _Pragma(\"unroll\") for (int j = 0; j < 4; ++j) x%zu[i * 4 + j] = 0.0f; }", oi));
+            } else {
+                line("        _Pragma(\"unroll\") for (int j = 0; j < 4; ++j) {");
+                line(strf("            const %s cj = cc + j < C ? cc + j : C - 1;", idx_t()));
+                line(strf("            x%zu[i * 4 + j] = pf_ld1(p%zu + %s + rc * %lld + cj * %lld);", oi, oi, base.c_str(), (long long)sr,
+                          (long long)sc));
+                line("        }");
+            }
+            line("    }");
+        }
+        for (int id : grp.nodes) emit_elementwise(id, 16);
+        int sp = 0;
+        const bool st_vec = C % 4 == 0;
+        for (auto& st : grp.stores) {
+            int cnt = 1 + (int)st.also_outputs.size();
+            for (int c = 0; c < cnt; ++c, ++sp) {
+                line("    _Pragma(\"unroll\") for (int i = 0; i < 4; ++i) {");
+                line(strf("        const %s rr = r0 + ty + 16 * i, cc = c0 + tx * 4;", idx_t()));
+                line(strf("        const %s o = (lead * R + rr) * C + cc;", idx_t()));
+                if (st_vec) line(strf("        if (rr < R && cc < C) pf_st<4, false>(q%d + o, &v%d[i * 4]);", sp, st.node));
+                else
+                    line(strf("        if (rr < R) { _Pragma(\"unroll\") for (int j = 0; j < 4; ++j) if (cc + j < C) pf_st1(q%d + o + j, v%d[i * 4 + j]); }",
+                              sp, st.node));
+                line("    }");
+            }
+        }
+        line("}");
+    }
+
+    // ---------------------------------------------------------------- addressing
+    bool is_contiguous_full(const Operand& o) const {
+        if (o.transposed) return false;
+        int64_t st = 1;
+        for (int k = rd - 1; k >= 0; --k) {
+            if (grp.domain[k] != 1 && o.stride[k] != st) return false;
+            st *= grp.domain[k];
+        }
+        return true;
+    }
+    bool lead_strides_multiple_of(const Operand& o, int m, int nlead) const {
+        for (int k = 0; k < nlead; ++k)
+            if (o.stride[k] % m) return false;
+        return true;
+    }
+    bool need_decomp = false;
+    int decomp_dims = 0;
+
+    // can the leading offset be written as row * stride? (strides nest like the domain)
+    bool lead_mergeable(const Operand& o, int nlead) const {
+        for (int k = 0; k + 1 < nlead; ++k)
+            if (o.stride[k] != o.stride[k + 1] * grp.domain[k + 1]) return false;
+        return true;
+    }
+    bool lead_zero(const Operand& o, int nlead) const {
+        for (int k = 0; k < nlead; ++k)
+            if (o.stride[k] != 0) return false;
+        return true;
+    }
+    void scan_decomp(int nlead) {
+        need_decomp = false;
+        for (auto& o : grp.operands)
+            if (!lead_zero(o, nlead) && !lead_mergeable(o, nlead)) need_decomp = true;
+        decomp_dims = nlead;
+    }
+    // emits i0..i{n-1} from a flat index over the leading dims
+    void emit_lead_decomposition(const std::string& var, int nlead) {
+        scan_decomp(nlead);
+        if (!need_decomp) return;
+        std::string cur = var;
+        for (int k = nlead - 1; k >= 0; --k) {
+            if (k == 0) {
+                line(strf("    const %s i0 = %s;", idx_t(), cur.c_str()));
+            } else {
+                line(strf("    const %s i%d = %s %% %lld; const %s t%d = %s / %lld;", idx_t(), k, cur.c_str(), (long long)grp.domain[k],
+                          idx_t(), k, cur.c_str(), (long long)grp.domain[k]));
+                cur = strf("t%d", k);
+            }
+        }
+    }
+    void emit_row_decomposition(const std::string& var) { emit_lead_decomposition(var, rd > 0 ? rd - 1 : 0); }
+
+    std::string lead_offset_n(const Operand& o, int nlead) const {
+        if (lead_zero(o, nlead)) return strf("(%s)0", idx_t());
+        if (lead_mergeable(o, nlead)) return strf("%s * %lld", nlead == rd - 1 ? row_var.c_str() : "lead", (long long)o.stride[nlead - 1]);
+        std::string e;
+        for (int k = 0; k < nlead; ++k) {
+            if (!o.stride[k]) continue;
+            if (!e.empty()) e += " + ";
+            e += strf("i%d * %lld", k, (long long)o.stride[k]);
+        }
+        return "(" + e + ")";
+    }
+    std::string row_var = "row";
+    std::string lead_offset(const Operand& o, const std::string& rv) {
+        row_var = rv;
+        return lead_offset_n(o, rd > 0 ? rd - 1 : 0);
+    }
+    // offset of one element from (row, col) without pre-computed indices (gather path)
+    std::string element_offset(const Operand& o, const std::string& rv, const std::string& cv) const {
+        const int nlead = rd > 0 ? rd - 1 : 0;
+        std::string e = strf("%s * %lld", cv.c_str(), rd > 0 ? (long long)o.stride[rd - 1] : 0LL);
+        if (lead_zero(o, nlead)) return e;
+        if (lead_mergeable(o, nlead)) return e + strf(" + %s * %lld", rv.c_str(), (long long)o.stride[nlead - 1]);
+        // decompose inline
+        std::string cur = rv;
+        for (int k = nlead - 1; k >= 0; --k) {
+            if (k == 0) e += strf(" + (%s) * %lld", cur.c_str(), (long long)o.stride[0]);
+            else {
+                e += strf(" + ((%s) %% %lld) * %lld", cur.c_str(), (long long)grp.domain[k], (long long)o.stride[k]);
+                cur = strf("((%s) / %lld)", cur.c_str(), (long long)grp.domain[k]);
+            }
+        }
+        return e;
+    }
+
+    // ---------------------------------------------------------------- signature
+    std::string param_list() const {
+        std::string p;
+        for (size_t oi = 0; oi < grp.operands.size(); ++oi)
+            p += strf("%sconst %s* __restrict__ p%zu", oi ? ", " : "", ctype(grp.operands[oi].dtype), oi);
+        int sp = 0;
+        for (auto& st : grp.stores)
+            for (size_t c = 0; c < 1 + st.also_outputs.size(); ++c, ++sp)
+                p += strf("%s%s* __restrict__ q%d", p.empty() ? "" : ", ", ctype(st.dtype), sp);
+        return p;
+    }
+    std::string arg_list() const {
+        std::string p;
+        for (size_t oi = 0; oi < grp.operands.size(); ++oi) p += strf("%sp%zu", oi ? ", " : "", oi);
+        int sp = 0;
+        for (auto& st : grp.stores)
+            for (size_t c = 0; c < 1 + st.also_outputs.size(); ++c, ++sp) p += strf("%sq%d", p.empty() ? "" : ", ", sp);
+        return p;
+    }
+    void signature() {
+        line(strf("extern \"C\" __global__ void __launch_bounds__(%d) %s(%s) {", grp.block, grp.kernel_name.c_str(), param_list().c_str()));
+    }
+
+    void recompute_kinds() {
+        kind.clear();
+        for (int id : grp.nodes) kind[id] = node_kind(id);
+    }
+
+    void run(int index) {
+        rd = (int)grp.domain.size();
+        for (int id : grp.nodes) members.insert(id);
+        for (size_t oi = 0; oi < grp.operands.size(); ++oi) {
+            if (grp.operands[oi].via_transpose) toperand_of[grp.operands[oi].node] = (int)oi;
+            else operand_of[grp.operands[oi].node] = (int)oi;
+        }
+        // a transpose that moves no data is planned as a plain operand
+        int64_t maxel = numel(grp.domain);
+        for (auto& o : grp.operands) maxel = std::max(maxel, numel(o.shape));
+        wide = maxel >= (int64_t(1) << 30);
+        for (int o : g.outputs)
+            if (g.nodes[o].dtype == PF_F32) precise = true;
+        if (grp.tmpl == PF_T_TILE) {
+            bool any_t = false;
+            for (auto& o : grp.operands) any_t |= o.transposed;
+            if (!any_t) grp.tmpl = PF_T_EW_FLAT;
+        }
+        grp.kernel_name = strf("pf_k%d_%s", index,
+                               grp.tmpl == PF_T_EW_FLAT ? "ew" : grp.tmpl == PF_T_ROW_RESIDENT ? "row" : grp.tmpl == PF_T_TILE ? "tile" : "loop");
+        recompute_kinds();
+        s.clear();
+        s += strf("// group %d: %s over domain [", index, grp.kernel_name.c_str());
+        for (size_t k = 0; k < grp.domain.size(); ++k) s += strf(k ? ",%lld" : "%lld", (long long)grp.domain[k]);
+        s += "], nodes";
+        for (int id : grp.nodes) s += strf(" %%%d=%s", id, op_name(g.nodes[id].op));
+        s += "\n";
+        s += strf("#define PF_PRECISE %d\n", precise ? 1 : 0);
+        s += kDevicePrelude;
+        switch (grp.tmpl) {
+            case PF_T_EW_FLAT: gen_flat(); break;
+            case PF_T_ROW_RESIDENT: gen_row(); break;
+            case PF_T_TILE: gen_tile(); break;
+            default: fail(PF_E_COMPILE, "template not implemented");
+        }
+        grp.source = s;
+    }
+};
+
+}  // namespace
+
+void generate_source(const pf_graph& g, const pf_options& opt, Group& grp, int index) {
+    Emit e(g, opt, grp);
+    e.run(index);
+}
+
+}  // namespace pf

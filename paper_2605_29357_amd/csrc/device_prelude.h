@@ -1,0 +1,207 @@
+// Device-side helpers prepended to every generated kernel (as source text).
+//
+// Everything is written for gfx950 wave64: 16-byte global accesses, bf16
+// conversion through the hardware pack instruction, cross-lane reductions by
+// xor shuffles inside a wave and one LDS exchange across waves.
+#pragma once
+
+namespace pf {
+
+static const char* kDevicePrelude = R"PF(
+typedef unsigned short u16;
+typedef unsigned int u32;
+typedef u32 u32x2 __attribute__((ext_vector_type(2)));
+typedef u32 u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+#define PF_DEV __device__ __forceinline__
+
+PF_DEV float pf_bits2f(u32 u) { return __builtin_bit_cast(float, u); }
+PF_DEV u32 pf_f2bits(float f) { return __builtin_bit_cast(u32, f); }
+PF_DEV u32 pf_pack_bf16(float lo, float hi) {
+    f32x2 v = {lo, hi};
+    return __builtin_bit_cast(u32, __builtin_convertvector(v, bf16x2));   // round to nearest even
+}
+PF_DEV u16 pf_f2bf(float f) { return __builtin_bit_cast(u16, (__bf16)f); }
+
+// ---- loads of N contiguous elements into fp32 registers (p aligned to the access) ----
+template <int N, bool NT> struct LdBf16;
+template <bool NT> struct LdBf16<1, NT> {
+    static PF_DEV void run(const u16* p, float* o) { o[0] = pf_bits2f((u32)(NT ? __builtin_nontemporal_load(p) : *p) << 16); }
+};
+template <bool NT> struct LdBf16<2, NT> {
+    static PF_DEV void run(const u16* p, float* o) {
+        u32 r = NT ? __builtin_nontemporal_load((const u32*)p) : *(const u32*)p;
+        o[0] = pf_bits2f(r << 16); o[1] = pf_bits2f(r & 0xffff0000u);
+    }
+};
+template <bool NT> struct LdBf16<4, NT> {
+    static PF_DEV void run(const u16* p, float* o) {
+        u32x2 r = NT ? __builtin_nontemporal_load((const u32x2*)p) : *(const u32x2*)p;
+        o[0] = pf_bits2f(r.x << 16); o[1] = pf_bits2f(r.x & 0xffff0000u);
+        o[2] = pf_bits2f(r.y << 16); o[3] = pf_bits2f(r.y & 0xffff0000u);
+    }
+};
+template <bool NT> struct LdBf16<8, NT> {
+    static PF_DEV void run(const u16* p, float* o) {
+        u32x4 r = NT ? __builtin_nontemporal_load((const u32x4*)p) : *(const u32x4*)p;
+        o[0] = pf_bits2f(r.x << 16); o[1] = pf_bits2f(r.x & 0xffff0000u);
+        o[2] = pf_bits2f(r.y << 16); o[3] = pf_bits2f(r.y & 0xffff0000u);
+        o[4] = pf_bits2f(r.z << 16); o[5] = pf_bits2f(r.z & 0xffff0000u);
+        o[6] = pf_bits2f(r.w << 16); o[7] = pf_bits2f(r.w & 0xffff0000u);
+    }
+};
+template <int N, bool NT> struct LdF32;
+template <bool NT> struct LdF32<1, NT> {
+    static PF_DEV void run(const float* p, float* o) { o[0] = NT ? __builtin_nontemporal_load(p) : *p; }
+};
+template <bool NT> struct LdF32<2, NT> {
+    static PF_DEV void run(const float* p, float* o) {
+        f32x2 r = NT ? __builtin_nontemporal_load((const f32x2*)p) : *(const f32x2*)p;
+        o[0] = r.x; o[1] = r.y;
+    }
+};
+template <bool NT> struct LdF32<4, NT> {
+    static PF_DEV void run(const float* p, float* o) {
+        f32x4 r = NT ? __builtin_nontemporal_load((const f32x4*)p) : *(const f32x4*)p;
+        o[0] = r.x; o[1] = r.y; o[2] = r.z; o[3] = r.w;
+    }
+};
+template <bool NT> struct LdF32<8, NT> {
+    static PF_DEV void run(const float* p, float* o) {
+        LdF32<4, NT>::run(p, o); LdF32<4, NT>::run(p + 4, o + 4);
+    }
+};
+template <int N, bool NT> PF_DEV void pf_ld(const u16* p, float* o) { LdBf16<N, NT>::run(p, o); }
+template <int N, bool NT> PF_DEV void pf_ld(const float* p, float* o) { LdF32<N, NT>::run(p, o); }
+PF_DEV float pf_ld1(const u16* p) { return pf_bits2f((u32)*p << 16); }
+PF_DEV float pf_ld1(const float* p) { return *p; }
+
+// ---- stores of N contiguous fp32 registers, rounded once to the stored dtype ----
+template <int N, bool NT> struct StBf16;
+template <bool NT> struct StBf16<1, NT> {
+    static PF_DEV void run(u16* p, const float* v) { u16 r = pf_f2bf(v[0]); if (NT) __builtin_nontemporal_store(r, p); else *p = r; }
+};
+template <bool NT> struct StBf16<2, NT> {
+    static PF_DEV void run(u16* p, const float* v) {
+        u32 r = pf_pack_bf16(v[0], v[1]);
+        if (NT) __builtin_nontemporal_store(r, (u32*)p); else *(u32*)p = r;
+    }
+};
+template <bool NT> struct StBf16<4, NT> {
+    static PF_DEV void run(u16* p, const float* v) {
+        u32x2 r = {pf_pack_bf16(v[0], v[1]), pf_pack_bf16(v[2], v[3])};
+        if (NT) __builtin_nontemporal_store(r, (u32x2*)p); else *(u32x2*)p = r;
+    }
+};
+template <bool NT> struct StBf16<8, NT> {
+    static PF_DEV void run(u16* p, const float* v) {
+        u32x4 r = {pf_pack_bf16(v[0], v[1]), pf_pack_bf16(v[2], v[3]), pf_pack_bf16(v[4], v[5]), pf_pack_bf16(v[6], v[7])};
+        if (NT) __builtin_nontemporal_store(r, (u32x4*)p); else *(u32x4*)p = r;
+    }
+};
+template <int N, bool NT> struct StF32;
+template <bool NT> struct StF32<1, NT> {
+    static PF_DEV void run(float* p, const float* v) { if (NT) __builtin_nontemporal_store(v[0], p); else *p = v[0]; }
+};
+template <bool NT> struct StF32<2, NT> {
+    static PF_DEV void run(float* p, const float* v) {
+        f32x2 r = {v[0], v[1]};
+        if (NT) __builtin_nontemporal_store(r, (f32x2*)p); else *(f32x2*)p = r;
+    }
+};
+template <bool NT> struct StF32<4, NT> {
+    static PF_DEV void run(float* p, const float* v) {
+        f32x4 r = {v[0], v[1], v[2], v[3]};
+        if (NT) __builtin_nontemporal_store(r, (f32x4*)p); else *(f32x4*)p = r;
+    }
+};
+template <bool NT> struct StF32<8, NT> {
+    static PF_DEV void run(float* p, const float* v) { StF32<4, NT>::run(p, v); StF32<4, NT>::run(p + 4, v + 4); }
+};
+template <int N, bool NT> PF_DEV void pf_st(u16* p, const float* v) { StBf16<N, NT>::run(p, v); }
+template <int N, bool NT> PF_DEV void pf_st(float* p, const float* v) { StF32<N, NT>::run(p, v); }
+PF_DEV void pf_st1(u16* p, float v) { *p = pf_f2bf(v); }
+PF_DEV void pf_st1(float* p, float v) { *p = v; }
+
+// ---- scalar math ----
+#if PF_PRECISE
+PF_DEV float pf_div(float a, float b) { return a / b; }
+PF_DEV float pf_exp(float x) { return expf(x); }
+PF_DEV float pf_tanh(float x) { return tanhf(x); }
+PF_DEV float pf_sigmoid(float x) { return 1.0f / (1.0f + expf(-x)); }
+PF_DEV float pf_gelu_tanh(float x) {
+    // 0.5 x (1 + tanh u) = x / (1 + exp(-2u)), u = sqrt(2/pi) (x + 0.044715 x^3)
+    float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
+    return x / (1.0f + expf(-2.0f * u));
+}
+#else
+PF_DEV float pf_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
+PF_DEV float pf_div(float a, float b) { return a * pf_rcp(b); }
+PF_DEV float pf_exp(float x) { return __builtin_amdgcn_exp2f(x * 1.4426950408889634f); }
+PF_DEV float pf_tanh(float x) { return 1.0f - 2.0f * pf_rcp(1.0f + __builtin_amdgcn_exp2f(x * 2.8853900817779268f)); }
+PF_DEV float pf_sigmoid(float x) { return pf_rcp(1.0f + __builtin_amdgcn_exp2f(x * -1.4426950408889634f)); }
+PF_DEV float pf_gelu_tanh(float x) {
+    // x / (1 + exp(-2u)), with -2 * log2(e) * sqrt(2/pi) folded into the polynomial
+    float t = x * x;
+    float p = __builtin_fmaf(t, -0.10294324f, -2.3022082f);
+    return x * pf_rcp(1.0f + __builtin_amdgcn_exp2f(x * p));
+}
+#endif
+PF_DEV float pf_rsqrt(float x) { return __builtin_amdgcn_rsqf(x); }
+PF_DEV float pf_gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.7071067811865476f)); }
+PF_DEV float pf_max_nan(float a, float b) {       // max that propagates NaN
+    float m = fmaxf(a, b);
+    return (a != a) ? a : ((b != b) ? b : m);
+}
+
+// ---- reductions across the T lanes that share a row ----
+// T <= 64: the lanes are consecutive lanes of one wave.  T > 64: whole waves;
+// wave results meet in LDS (one slot set per call site, so one barrier each).
+template <int T> PF_DEV float pf_wave_sum(float v) {
+#pragma unroll
+    for (int o = (T < 64 ? T : 64) / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+template <int T> PF_DEV double pf_wave_sum(double v) {
+#pragma unroll
+    for (int o = (T < 64 ? T : 64) / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+template <int T> PF_DEV float pf_wave_max(float v) {
+#pragma unroll
+    for (int o = (T < 64 ? T : 64) / 2; o > 0; o >>= 1) v = pf_max_nan(v, __shfl_xor(v, o, 64));
+    return v;
+}
+template <int T, typename A> PF_DEV A pf_team_sum(A v, A* lds /* [BLOCK/64] */) {
+    v = pf_wave_sum<T>(v);
+    if (T > 64) {
+        const int wave = threadIdx.x >> 6;
+        if ((threadIdx.x & 63) == 0) lds[wave] = v;
+        __syncthreads();
+        const int first = (wave / (T / 64)) * (T / 64);
+        A s = lds[first];
+#pragma unroll
+        for (int w = 1; w < T / 64; ++w) s += lds[first + w];
+        v = s;
+    }
+    return v;
+}
+template <int T> PF_DEV float pf_team_max(float v, float* lds) {
+    v = pf_wave_max<T>(v);
+    if (T > 64) {
+        const int wave = threadIdx.x >> 6;
+        if ((threadIdx.x & 63) == 0) lds[wave] = v;
+        __syncthreads();
+        const int first = (wave / (T / 64)) * (T / 64);
+        float s = lds[first];
+#pragma unroll
+        for (int w = 1; w < T / 64; ++w) s = pf_max_nan(s, lds[first + w]);
+        v = s;
+    }
+    return v;
+}
+)PF";
+
+}  // namespace pf

@@ -1,0 +1,20 @@
+// A compiled subgraph: the plan, its code objects and (once loaded) the
+// device modules.
+#pragma once
+#include "pf_internal.h"
+
+struct pf_exec {
+    pf::Plan plan;
+    pf_options opt;
+    int n_inputs = 0, n_outputs = 0;
+    std::vector<uint64_t> input_bytes, output_bytes;
+    bool loaded = false;
+    std::vector<void*> modules;     // hipModule_t
+    std::vector<void*> functions;   // hipFunction_t
+};
+
+namespace pf {
+void exec_load(pf_exec& e);
+void exec_unload(pf_exec& e);
+void exec_run(pf_exec& e, const void* const* d_inputs, void* const* d_outputs, void* d_ws, void* stream);
+}  // namespace pf

@@ -1,0 +1,131 @@
+// Internal data structures of the fused-subgraph engine (host side).
+#pragma once
+
+#include <cstdint>
+#include <map>
+#include <stdexcept>
+#include <string>
+#include <vector>
+
+#include "pf.h"
+
+namespace pf {
+
+// Error carrying a pf_status; caught at the C boundary.
+struct Error : std::runtime_error {
+    pf_status status;
+    Error(pf_status s, const std::string& m) : std::runtime_error(m), status(s) {}
+};
+
+[[noreturn]] void fail(pf_status s, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+std::string strf(const char* fmt, ...) __attribute__((format(printf, 1, 2)));
+
+using Shape = std::vector<int64_t>;
+
+inline int64_t numel(const Shape& s) {
+    int64_t n = 1;
+    for (int64_t d : s) n *= d;
+    return n;
+}
+inline int itemsize(pf_dtype d) { return d == PF_BF16 ? 2 : d == PF_F32 ? 4 : 8; }
+const char* dtype_name(pf_dtype d);
+const char* op_name(pf_op op);
+bool op_from_name(const std::string& name, pf_op* op);
+bool is_reduction(pf_op op);
+bool is_unary(pf_op op);
+bool is_binary(pf_op op);
+
+// A node of the computational graph (Def. 3.1): operator type, operands,
+// inferred output shape, and the dtype it has when stored.
+struct Node {
+    pf_op op = PF_OP_INPUT;
+    pf_dtype dtype = PF_F32;
+    std::vector<int> in;
+    Shape shape;
+    // attributes
+    double value = 0.0;   // const
+    int keepdim = 1;      // reductions
+    int correction = 0;   // var
+    int gelu_erf = 0;     // gelu: 0 tanh form, 1 erf form
+    bool is_output = false;
+};
+
+}  // namespace pf
+
+struct pf_graph {
+    std::vector<pf::Node> nodes;
+    std::vector<int> inputs;    // node ids of inputs, in declaration order
+    std::vector<int> outputs;   // node ids of outputs, in declaration order
+};
+
+namespace pf {
+
+// ---- ir.cpp ----
+int graph_add_input(pf_graph& g, pf_dtype dt, const Shape& shape);
+int graph_add_node(pf_graph& g, pf_op op, const std::vector<int>& in,
+                   const std::vector<std::pair<std::string, std::string>>& attrs, pf_dtype dt);
+void graph_add_output(pf_graph& g, int node);
+void graph_parse(const std::string& text, pf_graph& g);
+std::string graph_print(const pf_graph& g);
+Shape broadcast_shapes(const Shape& a, const Shape& b);
+
+// ---- plan.cpp ----
+
+// How a kernel reads one external tensor inside its iteration domain.
+struct Operand {
+    int node = -1;            // producing node (graph input or earlier group's member)
+    pf_dtype dtype = PF_F32;  // dtype in memory
+    Shape shape;              // its own shape
+    // element strides per domain dim (domain rank-aligned; 0 where broadcast)
+    int64_t stride[PF_MAX_RANK] = {0, 0, 0, 0};
+    bool transposed = false;  // read through a swap of the last two dims (data really moves)
+    bool via_transpose = false;  // requested by a transpose node (even when it moves no data)
+    // where the bytes live
+    int graph_input = -1;     // index into d_inputs, or
+    int64_t ws_offset = -1;   // byte offset into the workspace, or
+    int graph_output = -1;    // an earlier group's graph output buffer
+};
+
+struct Store {
+    int node = -1;
+    pf_dtype dtype = PF_F32;
+    Shape shape;
+    bool row_scalar = false;   // one value per row of the domain
+    int graph_output = -1;     // index into d_outputs, or
+    int64_t ws_offset = -1;    // byte offset into the workspace
+    std::vector<int> also_outputs;  // further graph-output slots receiving the same values
+};
+
+struct Group {
+    pf_template tmpl = PF_T_EW_FLAT;
+    std::vector<int> nodes;        // members in topological order (const nodes folded in)
+    Shape domain;                  // iteration domain, rank-aligned full shape
+    int64_t rows = 1, cols = 1;    // product of leading dims, last dim
+    std::vector<Operand> operands; // external reads
+    std::vector<Store> stores;     // writes
+    // launch configuration (filled by codegen)
+    int block = 256;
+    int64_t grid = 1;
+    int lanes_per_row = 0;
+    int vec = 1, chunks_per_lane = 1;
+    std::string source;            // generated HIP
+    std::string kernel_name;
+    std::vector<char> code;        // code object
+    uint64_t bytes_read = 0, bytes_written = 0;
+};
+
+struct Plan {
+    std::vector<Group> groups;
+    uint64_t workspace_bytes = 0;
+    uint64_t algorithmic_bytes = 0;
+};
+
+void make_plan(const pf_graph& g, const pf_options& opt, Plan& plan);
+
+// ---- codegen.cpp ----
+void generate_source(const pf_graph& g, const pf_options& opt, Group& grp, int index);
+
+// ---- runtime.cpp ----
+void jit_compile(Group& grp);
+
+}  // namespace pf

@@ -1,0 +1,295 @@
+// Fusion planner: partitions the op-DAG into kernel groups.
+//
+// A fusible subgraph is a run of operators that one execution unit can absorb
+// (paper Sec. 3.2, prefix analysis: an operator is fusible with its prefix when
+// adding it does not add a kernel).  Here a group is a set of nodes that share
+// one iteration domain D = [leading..., C]:
+//   - elementwise nodes whose shape is D ("full") or D with the last dim 1
+//     ("row-uniform", only inside row groups),
+//   - reductions over the last dim of a full value (their result is
+//     row-uniform and may be consumed inside the same kernel),
+//   - transposes of tensors that already sit in memory (read through a swap of
+//     the last two dims; the group then iterates in tiles).
+// Boundaries fall where the domain changes (a transpose of a value computed in
+// the same kernel, a broadcast that grows the shape) and where a reduction
+// would have to join a tiled group.  Groups are numbered in execution order;
+// a node only ever joins a group at or after the groups of all its producers,
+// so the group graph is acyclic by construction.
+#include <algorithm>
+#include <cstring>
+
+#include "pf_internal.h"
+
+namespace pf {
+
+namespace {
+
+Shape canon(const Shape& s) {
+    size_t i = 0;
+    while (i < s.size() && s[i] == 1) ++i;
+    return Shape(s.begin() + i, s.end());
+}
+
+Shape row_scalar_of(const Shape& d) {
+    if (d.empty()) return d;
+    Shape r = d;
+    r.back() = 1;
+    return canon(r);
+}
+
+struct Builder {
+    const pf_graph& g;
+    const pf_options& opt;
+    std::vector<int> group_of;                  // per node, -1 = none (inputs, consts)
+    std::vector<std::vector<int>> consumers;
+    struct G {
+        pf_template tmpl;
+        Shape domain;
+        std::vector<int> nodes;
+        bool has_rowuni = false;
+    };
+    std::vector<G> groups;
+
+    Builder(const pf_graph& gr, const pf_options& o) : g(gr), opt(o) {
+        group_of.assign(g.nodes.size(), -1);
+        consumers.resize(g.nodes.size());
+        for (size_t i = 0; i < g.nodes.size(); ++i)
+            for (int p : g.nodes[i].in) consumers[p].push_back((int)i);
+    }
+
+    bool grouped(int n) const { return group_of[n] >= 0; }
+
+    // kind of node n if it were a member of a group with domain d: 2 full, 1 row-uniform, 0 neither
+    int kind_in(const Node& n, const Shape& d) const {
+        Shape c = canon(n.shape);
+        if (c == d) return 2;
+        if (!d.empty() && d.back() > 1 && c == row_scalar_of(d) && (n.keepdim || !is_reduction(n.op))) return 1;
+        return 0;
+    }
+
+    // May a member of the group be read in-kernel by a consumer?  A reduction
+    // with keepdim=0 has a shape that aligns differently under broadcasting,
+    // so its consumers always read it back from memory.
+    bool usable_in_kernel(int p) const {
+        const Node& n = g.nodes[p];
+        return !(is_reduction(n.op) && !n.keepdim);
+    }
+
+    bool can_join(int id, int gi) const {
+        const Node& n = g.nodes[id];
+        const G& grp = groups[gi];
+        if (grp.nodes.size() >= 60) return false;
+        for (int p : n.in)
+            if (group_of[p] == gi && !usable_in_kernel(p)) return false;
+        if (n.op == PF_OP_TRANSPOSE) {
+            if (group_of[n.in[0]] == gi) return false;          // operand must already be in memory
+            if (grp.tmpl != PF_T_EW_FLAT && grp.tmpl != PF_T_TILE) return false;
+            if (grp.has_rowuni) return false;
+            return canon(n.shape) == grp.domain && grp.domain.size() >= 2;
+        }
+        if (is_reduction(n.op)) {
+            if (grp.tmpl == PF_T_TILE) return false;
+            const Node& x = g.nodes[n.in[0]];
+            return canon(x.shape) == grp.domain && !grp.domain.empty();
+        }
+        int k = kind_in(n, grp.domain);
+        if (k == 2) {
+            // every operand must broadcast *into* the domain, which holds since
+            // the node's own shape is the domain
+            return true;
+        }
+        if (k == 1) return grp.tmpl == PF_T_ROW_RESIDENT || grp.tmpl == PF_T_ROW_LOOP;
+        return false;
+    }
+
+    void join(int id, int gi) {
+        const Node& n = g.nodes[id];
+        G& grp = groups[gi];
+        grp.nodes.push_back(id);
+        group_of[id] = gi;
+        if (n.op == PF_OP_TRANSPOSE) grp.tmpl = PF_T_TILE;
+        if (is_reduction(n.op)) grp.tmpl = PF_T_ROW_RESIDENT;
+        if (kind_in(n, grp.domain) == 1 || is_reduction(n.op)) grp.has_rowuni = true;
+    }
+
+    void seed(int id) {
+        const Node& n = g.nodes[id];
+        G grp;
+        grp.tmpl = PF_T_EW_FLAT;
+        if (is_reduction(n.op)) grp.domain = canon(g.nodes[n.in[0]].shape);
+        else grp.domain = canon(n.shape);
+        groups.push_back(grp);
+        join(id, (int)groups.size() - 1);
+    }
+
+    void run() {
+        for (size_t i = 0; i < g.nodes.size(); ++i) {
+            const Node& n = g.nodes[i];
+            if (n.op == PF_OP_INPUT || n.op == PF_OP_CONST) continue;
+            if (!opt.fuse) {
+                seed((int)i);
+                continue;
+            }
+            int cand = -1;
+            for (int p : n.in) cand = std::max(cand, group_of[p]);
+            int last = (int)groups.size() - 1;
+            if (cand >= 0 && can_join((int)i, cand)) join((int)i, cand);
+            else if (last > cand && last >= 0 && can_join((int)i, last)) join((int)i, last);
+            else seed((int)i);
+        }
+    }
+};
+
+uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
+
+}  // namespace
+
+void make_plan(const pf_graph& g, const pf_options& opt, Plan& plan) {
+    if (g.outputs.empty()) fail(PF_E_COMPILE, "graph has no outputs");
+    for (int o : g.outputs)
+        if (g.nodes[o].op == PF_OP_INPUT) fail(PF_E_COMPILE, "output %%%d is a graph input; nothing to compute", o);
+    Builder b(g, opt);
+    b.run();
+
+    const size_t nn = g.nodes.size();
+    // where each node's bytes live once its group has run
+    std::vector<int64_t> ws_off(nn, -1);
+    std::vector<pf_dtype> mem_dtype(nn, PF_F32);
+    std::vector<int> input_slot(nn, -1), output_slot(nn, -1);
+    for (size_t k = 0; k < g.inputs.size(); ++k) {
+        input_slot[g.inputs[k]] = (int)k;
+        mem_dtype[g.inputs[k]] = g.nodes[g.inputs[k]].dtype;
+    }
+    for (size_t k = 0; k < g.outputs.size(); ++k)
+        if (output_slot[g.outputs[k]] < 0) output_slot[g.outputs[k]] = (int)k;
+
+    uint64_t ws = 0;
+    plan.groups.clear();
+    plan.algorithmic_bytes = 0;
+    for (int i : g.inputs) plan.algorithmic_bytes += (uint64_t)numel(g.nodes[i].shape) * itemsize(g.nodes[i].dtype);
+    for (int o : g.outputs) plan.algorithmic_bytes += (uint64_t)numel(g.nodes[o].shape) * itemsize(g.nodes[o].dtype);
+
+    for (size_t gi = 0; gi < b.groups.size(); ++gi) {
+        const auto& bg = b.groups[gi];
+        Group grp;
+        grp.tmpl = bg.tmpl;
+        grp.nodes = bg.nodes;
+        grp.domain = bg.domain;
+        grp.cols = bg.domain.empty() ? 1 : bg.domain.back();
+        grp.rows = 1;
+        for (size_t d = 0; d + 1 < bg.domain.size(); ++d) grp.rows *= bg.domain[d];
+        const int rd = (int)bg.domain.size();
+
+        // external reads
+        auto add_operand = [&](int p, bool transposed) {
+            for (auto& o : grp.operands)
+                if (o.node == p && o.via_transpose == transposed) return;
+            Operand o;
+            o.node = p;
+            o.transposed = transposed;
+            o.via_transpose = transposed;
+            o.shape = g.nodes[p].shape;
+            if (input_slot[p] >= 0) {
+                o.graph_input = input_slot[p];
+                o.dtype = g.nodes[p].dtype;
+            } else if (ws_off[p] >= 0) {
+                o.ws_offset = ws_off[p];
+                o.dtype = mem_dtype[p];
+            } else if (output_slot[p] >= 0) {
+                o.graph_output = output_slot[p];
+                o.dtype = g.nodes[p].dtype;
+            } else {
+                fail(PF_E_COMPILE, "internal: node %%%d read before it is materialised", p);
+            }
+            Shape s = canon(o.shape);
+            if (transposed) {
+                // the operand as seen after swapping its last two dims
+                const Shape& full = g.nodes[p].shape;
+                Shape t = full;
+                std::swap(t[t.size() - 1], t[t.size() - 2]);
+                Shape tc = canon(t);
+                const int64_t r_o = t[t.size() - 2], c_o = t[t.size() - 1];
+                if (r_o == 1 || c_o == 1 || (int)tc.size() < 2) {
+                    // no data movement: same linear order
+                    s = tc;
+                    o.transposed = false;
+                } else {
+                    if ((int)tc.size() != rd) fail(PF_E_COMPILE, "internal: transposed operand rank");
+                    int64_t st = r_o * c_o;
+                    for (int k = rd - 3; k >= 0; --k) {
+                        o.stride[k] = tc[k] == 1 ? 0 : st;
+                        st *= tc[k];
+                    }
+                    o.stride[rd - 2] = 1;
+                    o.stride[rd - 1] = r_o;
+                    grp.operands.push_back(o);
+                    return;
+                }
+            }
+            if ((int)s.size() > rd) fail(PF_E_COMPILE, "internal: operand %%%d rank exceeds domain", p);
+            int64_t st = 1;
+            for (int j = (int)s.size() - 1; j >= 0; --j) {
+                int k = rd - ((int)s.size() - j);
+                if (s[j] != 1 && s[j] != bg.domain[k])
+                    fail(PF_E_COMPILE, "internal: operand %%%d does not broadcast into the domain", p);
+                o.stride[k] = s[j] == 1 ? 0 : st;
+                st *= s[j];
+            }
+            grp.operands.push_back(o);
+        };
+        for (int id : bg.nodes) {
+            const Node& n = g.nodes[id];
+            for (int p : n.in) {
+                if (g.nodes[p].op == PF_OP_CONST) continue;
+                bool inside = b.group_of[p] == (int)gi && b.usable_in_kernel(p);
+                if (n.op == PF_OP_TRANSPOSE) add_operand(p, true);
+                else if (!inside) add_operand(p, false);
+            }
+        }
+
+        // writes: members that are graph outputs or read by another kernel
+        for (int id : bg.nodes) {
+            const Node& n = g.nodes[id];
+            bool outside_use = false;
+            for (int c : b.consumers[id])
+                if (b.group_of[c] != (int)gi || !b.usable_in_kernel(id) || g.nodes[c].op == PF_OP_TRANSPOSE) outside_use = true;
+            if (!n.is_output && !outside_use) continue;
+            const bool row_scalar = is_reduction(n.op) || (b.kind_in(n, bg.domain) == 1);
+            if (n.is_output) {
+                Store s;
+                s.node = id;
+                s.dtype = n.dtype;
+                s.shape = n.shape;
+                s.row_scalar = row_scalar;
+                s.graph_output = output_slot[id];
+                for (size_t k = 0; k < g.outputs.size(); ++k)
+                    if (g.outputs[k] == id && (int)k != output_slot[id]) s.also_outputs.push_back((int)k);
+                grp.stores.push_back(s);
+                mem_dtype[id] = n.dtype;
+            }
+            // a second, full-precision copy when later kernels need the value and
+            // the output buffer would round it
+            const bool need_ws = outside_use && (!n.is_output || (opt.intermediates_f32 && n.dtype != PF_F32));
+            if (need_ws) {
+                Store s;
+                s.node = id;
+                s.dtype = opt.intermediates_f32 ? PF_F32 : n.dtype;
+                s.shape = n.shape;
+                s.row_scalar = row_scalar;
+                s.ws_offset = (int64_t)ws;
+                ws_off[id] = (int64_t)ws;
+                mem_dtype[id] = s.dtype;
+                ws = align_up(ws + (uint64_t)numel(n.shape) * itemsize(s.dtype), 256);
+                grp.stores.push_back(s);
+            }
+        }
+        if (grp.stores.empty()) continue;   // dead code: nothing observes this group
+        for (auto& o : grp.operands) grp.bytes_read += (uint64_t)numel(o.shape) * itemsize(o.dtype);
+        for (auto& s : grp.stores)
+            grp.bytes_written += (uint64_t)numel(s.shape) * itemsize(s.dtype) * (1 + s.also_outputs.size());
+        plan.groups.push_back(std::move(grp));
+    }
+    plan.workspace_bytes = ws;
+}
+
+}  // namespace pf

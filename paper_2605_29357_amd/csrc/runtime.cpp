@@ -1,0 +1,142 @@
+// Runtime: JIT compilation of generated kernels (hipRTC), code-object cache,
+// lazy module loading and launches.
+#include <hip/hip_runtime_api.h>
+#include <hip/hiprtc.h>
+
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <fstream>
+#include <mutex>
+#include <unordered_map>
+
+#include "exec.h"
+#include "pf_internal.h"
+
+namespace pf {
+
+namespace {
+
+std::mutex g_cache_mu;
+std::unordered_map<std::string, std::vector<char>> g_code_cache;   // source text -> code object
+
+uint64_t fnv1a(const std::string& s) {
+    uint64_t h = 1469598103934665603ull;
+    for (unsigned char c : s) {
+        h ^= c;
+        h *= 1099511628211ull;
+    }
+    return h;
+}
+
+std::string disk_path(const std::string& source) {
+    const char* dir = getenv("PF_CACHE_DIR");
+    if (!dir || !*dir) return "";
+    return strf("%s/pf_%016llx_%zu.hsaco", dir, (unsigned long long)fnv1a(source), source.size());
+}
+
+}  // namespace
+
+void jit_compile(Group& grp) {
+    {
+        std::lock_guard<std::mutex> lk(g_cache_mu);
+        auto it = g_code_cache.find(grp.source);
+        if (it != g_code_cache.end()) {
+            grp.code = it->second;
+            return;
+        }
+    }
+    const std::string path = disk_path(grp.source);
+    if (!path.empty()) {
+        std::ifstream f(path, std::ios::binary);
+        if (f) {
+            std::vector<char> code((std::istreambuf_iterator<char>(f)), std::istreambuf_iterator<char>());
+            if (!code.empty()) {
+                grp.code = code;
+                std::lock_guard<std::mutex> lk(g_cache_mu);
+                g_code_cache[grp.source] = code;
+                return;
+            }
+        }
+    }
+    hiprtcProgram prog;
+    if (hiprtcCreateProgram(&prog, grp.source.c_str(), (grp.kernel_name + ".hip").c_str(), 0, nullptr, nullptr) != HIPRTC_SUCCESS)
+        fail(PF_E_COMPILE, "hiprtcCreateProgram failed");
+    // packed fp32 instructions are kept out of generated code on purpose
+    const char* opts[] = {"--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"};
+    hiprtcResult r = hiprtcCompileProgram(prog, (int)(sizeof opts / sizeof opts[0]), opts);
+    if (r != HIPRTC_SUCCESS) {
+        size_t n = 0;
+        hiprtcGetProgramLogSize(prog, &n);
+        std::string log(n, '\0');
+        if (n) hiprtcGetProgramLog(prog, log.data());
+        hiprtcDestroyProgram(&prog);
+        if (getenv("PF_DUMP_FAILED")) fprintf(stderr, "%s\n", grp.source.c_str());
+        fail(PF_E_COMPILE, "JIT compilation of %s failed: %s\n%.1500s", grp.kernel_name.c_str(), hiprtcGetErrorString(r), log.c_str());
+    }
+    size_t sz = 0;
+    hiprtcGetCodeSize(prog, &sz);
+    grp.code.resize(sz);
+    hiprtcGetCode(prog, grp.code.data());
+    hiprtcDestroyProgram(&prog);
+    if (!path.empty()) {
+        std::ofstream f(path + ".tmp", std::ios::binary);
+        f.write(grp.code.data(), (std::streamsize)grp.code.size());
+        f.close();
+        rename((path + ".tmp").c_str(), path.c_str());
+    }
+    std::lock_guard<std::mutex> lk(g_cache_mu);
+    g_code_cache[grp.source] = grp.code;
+}
+
+void exec_load(pf_exec& e) {
+    if (e.loaded) return;
+    e.modules.assign(e.plan.groups.size(), nullptr);
+    e.functions.assign(e.plan.groups.size(), nullptr);
+    for (size_t i = 0; i < e.plan.groups.size(); ++i) {
+        Group& grp = e.plan.groups[i];
+        hipModule_t mod = nullptr;
+        hipError_t err = hipModuleLoadData(&mod, grp.code.data());
+        if (err != hipSuccess) fail(PF_E_RUNTIME, "hipModuleLoadData(%s): %s", grp.kernel_name.c_str(), hipGetErrorString(err));
+        e.modules[i] = mod;
+        hipFunction_t fn = nullptr;
+        err = hipModuleGetFunction(&fn, mod, grp.kernel_name.c_str());
+        if (err != hipSuccess) fail(PF_E_RUNTIME, "hipModuleGetFunction(%s): %s", grp.kernel_name.c_str(), hipGetErrorString(err));
+        e.functions[i] = fn;
+    }
+    e.loaded = true;
+}
+
+void exec_unload(pf_exec& e) {
+    for (void* m : e.modules)
+        if (m) (void)hipModuleUnload((hipModule_t)m);
+    e.modules.clear();
+    e.functions.clear();
+    e.loaded = false;
+}
+
+void exec_run(pf_exec& e, const void* const* d_inputs, void* const* d_outputs, void* d_ws, void* stream) {
+    exec_load(e);
+    for (size_t i = 0; i < e.plan.groups.size(); ++i) {
+        Group& grp = e.plan.groups[i];
+        void* ptrs[160];
+        void* args[160];
+        int n = 0;
+        for (auto& o : grp.operands) {
+            const void* p = o.graph_input >= 0    ? d_inputs[o.graph_input]
+                            : o.ws_offset >= 0    ? (const void*)((const char*)d_ws + o.ws_offset)
+                                                  : (const void*)d_outputs[o.graph_output];
+            ptrs[n++] = (void*)p;
+        }
+        for (auto& s : grp.stores) {
+            ptrs[n++] = s.graph_output >= 0 ? d_outputs[s.graph_output] : (void*)((char*)d_ws + s.ws_offset);
+            for (int k : s.also_outputs) ptrs[n++] = d_outputs[k];
+        }
+        for (int k = 0; k < n; ++k) args[k] = &ptrs[k];
+        hipError_t err = hipModuleLaunchKernel((hipFunction_t)e.functions[i], (unsigned)grp.grid, 1, 1, (unsigned)grp.block, 1, 1, 0,
+                                               (hipStream_t)stream, args, nullptr);
+        if (err != hipSuccess) fail(PF_E_RUNTIME, "launch of %s failed: %s", grp.kernel_name.c_str(), hipGetErrorString(err));
+    }
+}
+
+}  // namespace pf

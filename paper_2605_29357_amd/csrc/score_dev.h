@@ -1,0 +1,34 @@
+// Device-visible descriptor of one (candidate, reference) pair and the launch
+// entry points of the ahead-of-time compiled kernels.
+#pragma once
+#include <hip/hip_runtime_api.h>
+
+#include "pf.h"
+
+namespace pf {
+
+struct PairDev {
+    const void* cand;
+    const void* ref;
+    unsigned long long n;
+    int cand_dtype, ref_dtype;
+    double rtol, atol;
+    int equal_nan;
+    int pad_;
+};
+
+// up to kBatch descriptors passed by value to the upload kernel
+constexpr int kPairBatch = 24;
+struct PairBatch {
+    PairDev pairs[kPairBatch];
+    unsigned long long start[kPairBatch + 1];   // first block of each pair (+ total when last)
+    int first, count, last, pad_;
+};
+
+unsigned long long score_chunk_elems();
+hipError_t launch_score_upload(const PairBatch& batch, PairDev* d_pairs, unsigned long long* d_block_start, hipStream_t stream);
+hipError_t launch_score(const PairDev* d_pairs, const unsigned long long* d_block_start, int n_pairs,
+                        unsigned long long total_blocks, pf_score_result* d_results, hipStream_t stream);
+hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
+
+}  // namespace pf

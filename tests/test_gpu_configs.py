@@ -1,0 +1,171 @@
+"""GPU parity of the four named fused subgraphs against the fp64 oracle.
+
+Tolerances (stated by the benchmark spec): |gpu - oracle| <= atol + rtol*|oracle| with
+rtol 1e-5 (fp32 outputs) or 2e-2 (bf16 outputs) and atol 1e-5.  Reduced sizes
+are compared element by element; the full sizes are compared on whole sampled
+rows (every row of these subgraphs is independent of the others, so the oracle
+evaluates the sampled rows as a smaller instance of the same DAG).
+"""
+import numpy as np
+import pytest
+import torch
+
+from tests.harness import Runner, alloc_outputs, check_against_oracle, to_host_bits
+from oracle import dag as oracle_dag
+from workloads import configs
+from workloads.irtext import Builder
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_and_check(w, fuse=True, **kw):
+    r = Runner(w, fuse=fuse, **kw)
+    outs = r.run()
+    torch.cuda.synchronize()
+    worst = check_against_oracle(w, outs, what=w.name + (" fused" if fuse else " unfused"))
+    return r, worst
+
+
+@pytest.mark.parametrize("rows,cols", [(64, 768), (3, 768), (7, 96), (5, 100), (2, 4096), (3, 133), (1, 4), (300, 20)])
+@pytest.mark.parametrize("use_var_op", [False, True])
+def test_cfg1_add_layernorm(rows, cols, use_var_op):
+    print("case cfg1", rows, cols, use_var_op, flush=True)
+    w = configs.cfg1_add_layernorm(rows=rows, cols=cols, use_var_op=use_var_op)
+    r, _ = _run_and_check(w)
+    assert r.info["n_kernels"] == 1
+    assert r.exe.group_info(0)["template"] == "row_resident"
+
+
+@pytest.mark.parametrize("heads,seq", [(2, 512), (1, 64), (3, 40), (1, 1024)])
+def test_cfg2_masked_softmax(heads, seq):
+    print("case cfg2", heads, seq, flush=True)
+    w = configs.cfg2_masked_softmax(heads=heads, seq=seq)
+    r, _ = _run_and_check(w)
+    assert r.info["n_kernels"] == 1
+    out = r.run()[0]
+    torch.cuda.synchronize()
+    got = oracle_dag.upconvert(to_host_bits(out, "bf16"), "bf16")
+    iu = np.triu_indices(seq, k=1)
+    assert (got[:, iu[0], iu[1]] == 0).all()          # masked entries exactly zero
+
+
+def test_cfg2_fully_masked_rows_give_nan_like_the_definition():
+    w = configs.cfg2_masked_softmax(heads=1, seq=64)
+    w.inputs[1][5, :] = 0xFF80
+    _run_and_check(w)
+
+
+@pytest.mark.parametrize("rows,cols", [(16, 11008), (5, 8), (3, 1000), (7, 133), (1, 1)])
+def test_cfg3_bias_gelu_gate(rows, cols):
+    print("case cfg3", rows, cols, flush=True)
+    w = configs.cfg3_bias_gelu_gate(rows=rows, cols=cols)
+    r, _ = _run_and_check(w)
+    assert r.info["n_kernels"] == 1
+    assert r.exe.group_info(0)["template"] == "ew_flat"
+
+
+@pytest.mark.parametrize("batch,positions,heads,dim", [(1, 16, 4, 128), (2, 33, 3, 64), (1, 5, 1, 6), (2, 8, 32, 128)])
+def test_cfg4_rmsnorm_rope(batch, positions, heads, dim):
+    print("case cfg4", batch, positions, heads, dim, flush=True)
+    w = configs.cfg4_rmsnorm_rope(batch=batch, positions=positions, heads=heads, dim=dim)
+    r, _ = _run_and_check(w)
+    assert r.info["n_kernels"] == 1
+
+
+def test_unfused_execution_matches_and_counts_one_kernel_per_node():
+    w = configs.cfg1_add_layernorm(rows=9, cols=768)
+    r, _ = _run_and_check(w, fuse=False, intermediates_f32=True)
+    assert r.info["n_kernels"] == 10
+    w = configs.cfg3_bias_gelu_gate(rows=9, cols=1000)
+    r, _ = _run_and_check(w, fuse=False, intermediates_f32=True)
+    assert r.info["n_kernels"] == 3
+    w = configs.cfg2_masked_softmax(heads=1, seq=128)
+    r, _ = _run_and_check(w, fuse=False, intermediates_f32=True)
+    assert r.info["n_kernels"] == 7
+    w = configs.cfg4_rmsnorm_rope(batch=1, positions=9, heads=2, dim=128)
+    _run_and_check(w, fuse=False, intermediates_f32=True)
+
+
+def test_bf16_store_rounds_to_nearest_even_bit_exactly():
+    # x + 0 with fp32 input and bf16 output is a pure rounding step
+    vals = np.array([1.0, 1.00390625, 1.01171875, 1.005, -2.5, 3.0e38, 1e-40, 0.0, -0.0, np.inf, -np.inf,
+                     3.3895313892515355e38], dtype=np.float32)
+    rng = np.random.default_rng(0)
+    vals = np.concatenate([vals, rng.normal(size=4084).astype(np.float32),
+                           rng.integers(0, 2 ** 32, size=4096, dtype=np.uint64).astype(np.uint32).view(np.float32)])
+    vals = vals[~np.isnan(vals)][:8000]
+    g = Builder()
+    i = g.input("f32", (vals.size,))
+    g.output(g.op("add", [i, g.const(0.0, "f32")], "bf16"))
+    w = configs.Workload("round", g.text(), [vals], ["f32"], [(vals.size,)], ["bf16"], [(vals.size,)]).finish()
+    r = Runner(w)
+    out = r.run()[0]
+    torch.cuda.synchronize()
+    from workloads import rng as wrng
+    want = wrng.round_to_bf16_bits((vals.astype(np.float64) + 0.0))
+    got = to_host_bits(out, "bf16")
+    # -0.0 + 0.0 = +0.0 in round-to-nearest
+    np.testing.assert_array_equal(got, want)
+
+
+# ----------------------------------------------------------------- full sizes
+def _sampled_rows_check(w_full, make_small, row_ids, out, row_shape):
+    """Oracle on the sampled rows only, compared with the same rows of the full GPU output."""
+    got_full = to_host_bits(out, w_full.output_dtypes[0]).reshape((-1,) + row_shape)
+    w_small = make_small(row_ids)
+    refs = oracle_dag.run(w_small.text, w_small.inputs)
+    got = oracle_dag.upconvert(got_full[row_ids], w_full.output_dtypes[0]).reshape(refs[0].shape)
+    dt = w_full.output_dtypes[0]
+    err = np.abs(got - refs[0])
+    bound = configs.ATOL[dt] + configs.RTOL[dt] * np.abs(refs[0])
+    assert np.array_equal(np.isnan(got), np.isnan(refs[0]))
+    assert (err <= bound).all(), "worst %g" % float((err / bound).max())
+
+
+def test_cfg3_full_size_sampled_rows():
+    w = configs.cfg3_bias_gelu_gate()
+    r = Runner(w)
+    out = r.run()[0]
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([[0, 1, 8191, 8190, 4095, 4096], np.random.default_rng(2).integers(0, 8192, 58)]))
+
+    def small(ids):
+        s = configs.cfg3_bias_gelu_gate(rows=len(ids))
+        s.inputs = [w.inputs[0][ids], w.inputs[1], w.inputs[2][ids]]
+        return s
+    _sampled_rows_check(w, small, rows, out, (11008,))
+    # nothing left unwritten (outputs start as NaN)
+    assert not torch.isnan(out).any()
+
+
+def test_cfg4_full_size_sampled_rows():
+    w = configs.cfg4_rmsnorm_rope()
+    r = Runner(w)
+    out = r.run()[0]
+    torch.cuda.synchronize()
+    assert not torch.isnan(out).any()
+    # sample whole positions: a position p of batch b is a [32,128] slab that uses table row p
+    rng = np.random.default_rng(3)
+    got = to_host_bits(out, "bf16")
+    x = w.inputs[0]
+    for b, p in [(0, 0), (3, 2047), (1, 1), (2, 1024)] + [(int(rng.integers(4)), int(rng.integers(2048))) for _ in range(12)]:
+        s = configs.cfg4_rmsnorm_rope(batch=1, positions=1, heads=32, dim=128)
+        s.inputs = [x[b:b + 1, p:p + 1], w.inputs[1], w.inputs[2][p:p + 1], w.inputs[3][p:p + 1]]
+        ref = oracle_dag.run(s.text, s.inputs)[0]
+        g64 = oracle_dag.upconvert(got[b:b + 1, p:p + 1], "bf16")
+        err = np.abs(g64 - ref)
+        assert (err <= 1e-5 + 2e-2 * np.abs(ref)).all(), (b, p)
+
+
+def test_cfg2_full_size():
+    w = configs.cfg2_masked_softmax()
+    _run_and_check(w)
+
+
+def test_cfg1_full_size_is_one_kernel_and_repeatable():
+    w = configs.cfg1_add_layernorm()
+    r, _ = _run_and_check(w)
+    a = r.run()[0]
+    b = r.run()[0]
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
