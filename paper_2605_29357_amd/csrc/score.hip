@@ -59,11 +59,26 @@ template <> struct Elem<PF_F64> {
     static __device__ __forceinline__ raw load1(const void* base, unsigned long long i) { return ((const unsigned long long*)base)[i]; }
 };
 
+// Per-lane accumulators.  The largest relative error needs a correctly rounded
+// fp64 division, which is far too slow to run on every element.  Instead each
+// lane tracks the running maximum of a cheap fp32 estimate q ~ d/|b| (relative
+// error < 1e-6) and keeps the (d, |b|) of that element; only elements whose
+// estimate lies within 2e-6 of the running maximum, or whose operands leave
+// the range where the estimate is trustworthy, are divided exactly on the
+// spot.  An element that is neither kept nor divided is smaller than the kept
+// one by more than both estimates can be wrong, so the exact maximum is
+// max(exact divisions, kept_d / kept_b), evaluated once per lane at the end.
 struct Acc {
-    double max_abs = 0.0, max_rel = 0.0;
+    double max_abs = 0.0, max_rel = 0.0;     // max_rel: exact divisions so far
+    double keep_d = 0.0, keep_b = 1.0;       // element with the largest estimate (0/1: none yet)
+    float keep_q = 0.0f;
     unsigned long long n_viol = 0, bitdiff = 0;
     unsigned int nan_c = 0, nan_r = 0, inf_c = 0, inf_r = 0;
 };
+
+__device__ __forceinline__ bool est_range_ok(float x) {   // 1e-18 <= x <= 1e18, false for 0/inf/nan
+    return x >= 1e-18f && x <= 1e18f;
+}
 
 template <int CD, int RD>
 __device__ __forceinline__ void score_one(typename Elem<CD>::raw ra, typename Elem<RD>::raw rb, const pf::PairDev& pr, Acc& acc) {
@@ -83,10 +98,24 @@ __device__ __forceinline__ void score_one(typename Elem<CD>::raw ra, typename El
     const double d = fabs(__dsub_rn(a, b));           // +inf when exactly one side is infinite or signs differ
     const double ab = fabs(b);
     acc.max_abs = fmax(acc.max_abs, d);
-    const double rel = (ab == 0.0 || d == inf) ? inf : __ddiv_rn(d, ab);
-    acc.max_rel = fmax(acc.max_rel, rel);
     const double allowed = __dadd_rn(pr.atol, __dmul_rn(pr.rtol, ab));
     acc.n_viol += !(d != inf && d <= allowed);
+    if (ab == 0.0 || d == inf) {
+        acc.max_rel = inf;
+        return;
+    }
+    const float d32 = (float)d, b32 = (float)ab;
+    if (est_range_ok(d32) && est_range_ok(b32)) {
+        const float q = d32 * __builtin_amdgcn_rcpf(b32);
+        if (q > acc.keep_q * 1.000002f) {             // certainly larger than the kept element
+            acc.keep_q = q;
+            acc.keep_d = d;
+            acc.keep_b = ab;
+            return;
+        }
+        if (q < acc.keep_q * 0.999998f) return;       // certainly smaller
+    }
+    acc.max_rel = fmax(acc.max_rel, __ddiv_rn(d, ab));
 }
 
 template <int CD, int RD>
@@ -162,6 +191,7 @@ __global__ void __launch_bounds__(kBlock) score_kernel(const pf::PairDev* pairs,
         case PF_BF16 * 3 + PF_F64: score_chunk<PF_BF16, PF_F64>(pr, begin, end, acc); break;
         default: break;
     }
+    acc.max_rel = fmax(acc.max_rel, __ddiv_rn(acc.keep_d, acc.keep_b));
     // block reduction: waves by shuffle, then LDS
     __shared__ double s_abs[kBlock / 64], s_rel[kBlock / 64];
     __shared__ unsigned long long s_cnt[kBlock / 64][6];

@@ -1,0 +1,80 @@
+"""torch plumbing around the C ABI: device memory and streams only.
+
+torch allocates the buffers and owns the stream; every computation is done by
+libpf.so through the binding in this package.
+"""
+import ctypes
+
+import numpy as np
+import torch
+
+import paper_2605_29357_amd as pf
+
+TORCH_DT = {"f32": torch.float32, "bf16": torch.bfloat16, "f64": torch.float64}
+
+
+def to_device(arr, dtype):
+    """Stored numpy bits -> device tensor of the matching torch dtype."""
+    if dtype == "bf16":
+        return torch.from_numpy(np.ascontiguousarray(arr).view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(arr)).cuda()
+
+
+def to_host_bits(t, dtype):
+    """Device tensor -> stored numpy bits (uint16 for bf16, float32/float64 otherwise)."""
+    if dtype == "bf16":
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+def alloc_outputs(w, poison=True):
+    """Output buffers pre-filled with NaN so that an element a kernel skips cannot pass
+    (the paper's reverse-evaluation rule: never score against stale pool memory)."""
+    outs = []
+    for dt, shape in zip(w.output_dtypes, w.output_shapes):
+        t = torch.empty(tuple(shape) if len(shape) else (), dtype=TORCH_DT[dt], device="cuda")
+        if poison:
+            t.fill_(float("nan"))
+        outs.append(t)
+    return outs
+
+
+class Runner:
+    """Compiles a workload's DAG once and runs it on device tensors."""
+
+    def __init__(self, w, fuse=True, intermediates_f32=None, upload=True):
+        self.w = w
+        self.exe = pf.Exec(w.text, fuse=fuse, intermediates_f32=intermediates_f32)
+        self.info = self.exe.info()
+        ws = self.info["workspace_bytes"]
+        self.ws = torch.empty(max(ws, 256), dtype=torch.uint8, device="cuda") if ws else None
+        self.d_in = [to_device(a, dt) for a, dt in zip(w.inputs, w.input_dtypes)] if upload else None
+
+    def run(self, outs=None, stream=None):
+        outs = outs if outs is not None else alloc_outputs(self.w)
+        s = stream if stream is not None else torch.cuda.current_stream()
+        self.exe.execute([t.data_ptr() for t in self.d_in], [t.data_ptr() for t in outs],
+                         self.ws.data_ptr() if self.ws is not None else 0,
+                         self.ws.numel() if self.ws is not None else 0, s.cuda_stream)
+        return outs
+
+
+def score_on_gpu(pairs_spec, stream=None):
+    """pairs_spec: list of (cand_tensor, cand_dtype, ref_tensor, ref_dtype, rtol, atol, equal_nan).
+    Returns a list of dicts read back from the device result structs."""
+    n = len(pairs_spec)
+    pairs = []
+    for c, cd, r, rd, rtol, atol, en in pairs_spec:
+        p = pf.Pair()
+        p.d_cand, p.d_ref, p.n = c.data_ptr(), r.data_ptr(), c.numel()
+        p.cand_dtype, p.ref_dtype = pf.DTYPES[cd], pf.DTYPES[rd]
+        p.rtol, p.atol, p.equal_nan = rtol, atol, int(en)
+        pairs.append(p)
+    res = torch.zeros(max(n, 1) * ctypes.sizeof(pf.ScoreResult), dtype=torch.uint8, device="cuda")
+    wsb = pf.score_workspace_bytes(n)
+    ws = torch.empty(max(wsb, 256), dtype=torch.uint8, device="cuda")
+    s = stream if stream is not None else torch.cuda.current_stream()
+    pf.score(pairs, res.data_ptr(), ws.data_ptr(), ws.numel(), s.cuda_stream)
+    s.synchronize()
+    raw = res.cpu().numpy().tobytes()
+    return [pf.ScoreResult.from_buffer_copy(raw, i * ctypes.sizeof(pf.ScoreResult)).as_dict() for i in range(n)]

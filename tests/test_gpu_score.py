@@ -1,0 +1,129 @@
+"""GPU parity of the error-scoring kernel against the oracle scorer.
+
+Every reported quantity is order-independent (maxima, integer counts) and is
+computed in fp64 with correctly rounded subtract / multiply / add / divide on
+exactly widened inputs, so the device result must equal the oracle's bit for
+bit: dictionaries are compared with ==.
+"""
+import numpy as np
+import pytest
+import torch
+
+from tests.harness import oracle_score_dict, score_on_gpu, to_device
+from workloads import rng
+
+pytestmark = pytest.mark.gpu
+
+
+def _pair(n, cd, rd, seed, rtol, atol, plant=True):
+    base = rng.normal(seed, 0, n)
+    noise = rng.normal(seed, 1, n)
+    ref64 = base
+    cand64 = base * (1 + noise * rtol) + noise * atol * 0.5
+    if plant and n >= 64:
+        r = np.random.default_rng(seed)
+        idx = r.choice(n, size=min(40, n), replace=False)
+        cand64[idx[0:5]] = np.nan
+        ref64 = ref64.copy()
+        ref64[idx[3:9]] = np.nan                 # two overlap with the candidate's NaNs
+        cand64[idx[9:12]] = np.inf
+        ref64[idx[11:14]] = np.inf               # one equal +inf
+        ref64[idx[14]] = -np.inf
+        cand64[idx[14]] = np.inf                 # opposite infinities
+        ref64[idx[15:20]] = 0.0                  # zero reference, non-zero candidate
+        cand64[idx[20:23]] = 0.0
+        ref64[idx[20:23]] = 0.0                  # both zero
+        cand64[idx[23]] = 1e30                   # a large outlier
+    store = {"f32": lambda x: x.astype(np.float32), "bf16": rng.round_to_bf16_bits, "f64": lambda x: x.astype(np.float64)}
+    return store[cd](cand64), store[rd](ref64)
+
+
+CASES = [(0, "f32", "f32"), (1, "f32", "f32"), (7, "bf16", "bf16"), (8, "f32", "f64"), (63, "bf16", "f64"),
+         (64, "bf16", "f32"), (1000, "f32", "bf16"), (8191, "f32", "f32"), (8192, "bf16", "bf16"), (8193, "f32", "f64"),
+         (100003, "bf16", "f64"), (1 << 20, "f32", "f32"), (3000017, "bf16", "bf16"), (1234567, "f32", "f64")]
+
+
+def test_batched_pairs_match_the_oracle_bit_for_bit():
+    specs, wants = [], []
+    for k, (n, cd, rd) in enumerate(CASES):
+        rtol, atol = (2e-2, 1e-5) if "bf16" in (cd, rd) else (1e-5, 1e-5)
+        for equal_nan in (False, True):
+            c, r = _pair(n, cd, rd, 100 + k, rtol, atol)
+            # 16-byte aligned device buffers: torch allocations are
+            dc = to_device(c, cd) if n else torch.empty(0, dtype=torch.float32, device="cuda")
+            dr = to_device(r, rd) if n else torch.empty(0, dtype=torch.float32, device="cuda")
+            specs.append((dc, cd, dr, rd, rtol, atol, equal_nan))
+            wants.append(oracle_score_dict(c, cd, r, rd, rtol, atol, equal_nan))
+    got = score_on_gpu(specs)
+    for (n, cd, rd), g, w in zip([c for c in CASES for _ in (0, 1)], got, wants):
+        assert g == w, (n, cd, rd, g, w)
+
+
+def test_identical_buffers_and_single_outlier():
+    x = rng.normal_stored(5, 0, 500000, "bf16")
+    d = to_device(x, "bf16")
+    y = x.copy()
+    y[123457] ^= 0x0001                            # one ulp in one element
+    dy = to_device(y, "bf16")
+    got = score_on_gpu([(d, "bf16", d.clone(), "bf16", 0.0, 0.0, False), (dy, "bf16", d, "bf16", 0.0, 0.0, False)])
+    assert got[0] == oracle_score_dict(x, "bf16", x, "bf16", 0.0, 0.0)
+    assert got[0]["allclose"] == 1 and got[0]["bit_identical"] == 1 and got[0]["max_abs"] == 0
+    assert got[1] == oracle_score_dict(y, "bf16", x, "bf16", 0.0, 0.0)
+    assert got[1]["n_viol"] == 1 and got[1]["bit_identical"] == 0
+
+
+def test_near_ties_in_relative_error_pick_the_exact_maximum():
+    # many elements whose relative errors differ only in the last bits
+    n = 200000
+    r = np.random.default_rng(9)
+    b = r.uniform(1.0, 2.0, n).astype(np.float32)
+    a = (b.astype(np.float64) * (1 + 1e-3 * (1 + 1e-7 * r.standard_normal(n)))).astype(np.float32)
+    got = score_on_gpu([(to_device(a, "f32"), "f32", to_device(b, "f32"), "f32", 1e-3, 0.0, False)])[0]
+    assert got == oracle_score_dict(a, "f32", b, "f32", 1e-3, 0.0)
+    # equal ratios at different magnitudes, extreme magnitudes, subnormal differences
+    b2 = np.array([1.0, 2.0, 4.0, 1e-30, 1e30, 3.0, 1e-38, 1.0], np.float32)
+    a2 = np.array([1.5, 3.0, 6.0, 1.5e-30, 1.5e30, 4.5, 1.5e-38, 1.0 + 2 ** -23], np.float32)
+    b2 = np.tile(b2, 1000)
+    a2 = np.tile(a2, 1000)
+    got = score_on_gpu([(to_device(a2, "f32"), "f32", to_device(b2, "f32"), "f32", 0.5, 0.0, False)])[0]
+    assert got == oracle_score_dict(a2, "f32", b2, "f32", 0.5, 0.0)
+
+
+def test_f64_reference_with_values_outside_float_range():
+    b = np.array([1e300, -1e300, 1e-300, 5e-324, 0.0, 1.0, 1e39, -1e-46] * 64, np.float64)
+    a = np.array([np.inf, -3e38, 0.0, 1e-45, 1e-45, 1.0, 3e38, -1e-45] * 64, np.float32)
+    got = score_on_gpu([(to_device(a, "f32"), "f32", to_device(b, "f64"), "f64", 1e-2, 1e-2, False)])[0]
+    assert got == oracle_score_dict(a, "f32", b, "f64", 1e-2, 1e-2)
+
+
+def test_many_pairs_in_one_call():
+    specs, wants = [], []
+    r = np.random.default_rng(4)
+    for k in range(70):                            # more than one descriptor batch
+        n = int(r.integers(1, 40000))
+        c, rf = _pair(n, "f32", "f32", 300 + k, 1e-5, 1e-5, plant=k % 3 == 0)
+        specs.append((to_device(c, "f32"), "f32", to_device(rf, "f32"), "f32", 1e-5, 1e-5, False))
+        wants.append(oracle_score_dict(c, "f32", rf, "f32", 1e-5, 1e-5))
+    got = score_on_gpu(specs)
+    for k, (g, w) in enumerate(zip(got, wants)):
+        assert g == w, (k, g, w)
+
+
+def test_bad_arguments_are_refused():
+    import paper_2605_29357_amd as pf
+    x = torch.zeros(64, device="cuda")
+    ws = torch.empty(4096, dtype=torch.uint8, device="cuda")
+    p = pf.Pair()
+    p.d_cand, p.d_ref, p.n = x.data_ptr() + 4, x.data_ptr(), 8      # misaligned
+    p.cand_dtype = p.ref_dtype = pf.F32
+    with pytest.raises(pf.PfError) as e:
+        pf.score([p], ws.data_ptr(), ws.data_ptr(), 4096)
+    assert e.value.status == pf.PF_E_INVALID
+    p.d_cand = x.data_ptr()
+    p.cand_dtype = pf.F64
+    with pytest.raises(pf.PfError):
+        pf.score([p], ws.data_ptr(), ws.data_ptr(), 4096)
+    p.cand_dtype = pf.F32
+    with pytest.raises(pf.PfError) as e:
+        pf.score([p], ws.data_ptr(), ws.data_ptr(), 8)              # workspace too small
+    assert e.value.status == pf.PF_E_RUNTIME

@@ -1,0 +1,179 @@
+"""Host-only tests of the library: IR, shape inference, text round trip, planner,
+kernel specialisation (JIT for gfx950 needs no GPU) and the exported symbols."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2605_29357_amd as pf
+from oracle import dag as oracle_dag
+from workloads import configs, dags
+from workloads.irtext import Builder
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "pf.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(pf_[a-z0-9_]+)\s*\(", hdr))
+    assert {"pf_compile", "pf_execute", "pf_score", "pf_graph_parse", "pf_exec_info", "pf_copy_bytes"} <= names
+    L = ctypes.CDLL(pf.LIB_PATH)
+    for n in sorted(names):
+        assert hasattr(L, n), n
+    assert pf.version().startswith("pf ")
+
+
+def test_struct_layouts_match_the_header():
+    assert ctypes.sizeof(pf.ScoreResult) == 80
+    assert ctypes.sizeof(pf.Pair) == 56
+
+
+def test_text_round_trip_and_shape_inference_agree_with_the_oracle_reader():
+    for w in [configs.cfg1_add_layernorm(rows=4, cols=8), configs.cfg2_masked_softmax(heads=2, seq=8),
+              configs.cfg3_bias_gelu_gate(rows=4, cols=8), configs.cfg4_rmsnorm_rope(1, 4, 2, 8)] + \
+             [dags.cfg5(k, max_rows=4) for k in range(0, 256, 17)]:
+        g = pf.Graph(w.text)
+        t1 = g.text()
+        g2 = pf.Graph(t1)
+        assert g2.text() == t1                                   # print -> parse -> print is a fixed point
+        og = oracle_dag.parse(w.text)
+        oracle_dag.run(og, w.inputs)                             # fills the oracle's shapes
+        n_nodes, n_in, n_out = g.size()
+        assert n_nodes == len(og.nodes) and n_in == len(og.inputs) and n_out == len(og.outputs)
+        for i, on in enumerate(og.nodes):
+            ni = g.node_info(i)
+            assert ni["op"] == on.op and ni["shape"] == tuple(on.shape), (i, ni, on.op, on.shape)
+            assert ni["inputs"] == list(on.args)
+            assert ni["is_output"] == (i in og.outputs)
+
+
+def test_node_by_node_construction_equals_parsing():
+    g = pf.Graph()
+    a = g.input("bf16", (6, 10))
+    b = g.input("bf16", (10,))
+    c = g.node("add", [a, b], "bf16")
+    d = g.node("gelu", [c], "bf16", approx="erf")
+    e = g.node("var", [d], "f32", correction=1, keepdim=0)
+    k = g.node("const", [], "f32", value=0.5)
+    f = g.node("mul", [e, k], "f32")
+    g.output(f)
+    assert g.node_info(e)["shape"] == (6,)
+    assert pf.Graph(g.text()).text() == g.text()
+    assert "approx=erf" in g.text() and "correction=1" in g.text()
+
+
+@pytest.mark.parametrize("text,frag", [
+    ("in %0 : f32[4]\n%1 = add(%0) : f32\nout %1\n", "takes 2"),
+    ("in %0 : f32[4]\nin %1 : f32[5]\n%2 = add(%0, %1) : f32\nout %2\n", "broadcast"),
+    ("in %0 : f32[4]\n%1 = frob(%0) : f32\nout %1\n", "unknown operator"),
+    ("in %0 : f16[4]\n%1 = exp(%0) : f32\nout %1\n", "dtype"),
+    ("in %0 : f32[4]\n%2 = exp(%0) : f32\nout %2\n", "consecutive"),
+    ("in %0 : f32[4]\n%1 = exp(%1) : f32\nout %1\n", "earlier"),
+    ("in %0 : f32[4]\n%1 = transpose(%0) : f32\nout %1\n", "rank"),
+    ("in %0 : f32[4,3]\n%1 = rot_pairs(%0) : f32\nout %1\n", "even"),
+    ("in %0 : f32[4,0]\n", "positive"),
+    ("in %0 : f32[2,2,2,2,2]\n", "rank"),
+    ("in %0 : f32[4]\n%1 = exp(%0) {keepdim=1} : f32\nout %1\n", "not valid"),
+    ("in %0 : f32[4]\n%1 = const() : f32\n", "value"),
+    ("in %0 : f32[4]\n%1 = exp(%0) : f32\n", "no outputs"),
+    ("in %0 : f32[4]\nout %0\n", "graph input"),
+])
+def test_ill_formed_graphs_are_compile_errors(text, frag):
+    with pytest.raises(pf.PfError) as e:
+        pf.Exec(text)
+    assert e.value.status == pf.PF_E_COMPILE
+    assert frag in str(e.value), str(e.value)
+
+
+def test_runtime_argument_errors_need_no_gpu():
+    e = pf.Exec(configs.cfg3_bias_gelu_gate(rows=4, cols=8).text)
+    with pytest.raises(pf.PfError) as err:
+        e.execute([16, 32], [64])                                # wrong buffer count
+    assert err.value.status == pf.PF_E_RUNTIME
+    with pytest.raises(pf.PfError) as err:
+        e.execute([16, 32, 0], [64])                             # NULL buffer
+    assert err.value.status == pf.PF_E_RUNTIME
+    with pytest.raises(pf.PfError) as err:
+        e.execute([16, 32, 52], [64])                            # misaligned
+    assert err.value.status == pf.PF_E_INVALID
+    u = pf.Exec(configs.cfg3_bias_gelu_gate(rows=4, cols=8).text, fuse=False)
+    assert u.info()["workspace_bytes"] > 0
+    with pytest.raises(pf.PfError) as err:
+        u.execute([16, 32, 48], [64], 0, 0)                      # workspace missing
+    assert err.value.status == pf.PF_E_RUNTIME
+
+
+def test_named_subgraphs_fuse_into_one_kernel_and_unfuse_into_one_per_node():
+    expect = [(configs.cfg1_add_layernorm(), "row_resident", 10), (configs.cfg2_masked_softmax(heads=1), "row_resident", 7),
+              (configs.cfg3_bias_gelu_gate(rows=8), "ew_flat", 3), (configs.cfg4_rmsnorm_rope(1, 8), "row_resident", 10)]
+    for w, tmpl, n_ops in expect:
+        e = pf.Exec(w.text)
+        info = e.info()
+        assert info["n_kernels"] == 1 and info["workspace_bytes"] == 0
+        assert info["algorithmic_bytes"] == w.algorithmic_bytes == info["planned_bytes"]
+        gi = e.group_info(0)
+        assert gi["template"] == tmpl and len(gi["nodes"]) == n_ops
+        u = pf.Exec(w.text, fuse=False)
+        assert u.info()["n_kernels"] == n_ops
+        assert u.info()["planned_bytes"] > info["planned_bytes"]
+
+
+def test_prefix_kernel_count_is_monotone_with_plateaus_inside_groups():
+    # K(P): kernels needed for the first P operator nodes.  Inside a fusible run
+    # adding an operator adds no kernel (the paper's prefix analysis).
+    w = configs.cfg1_add_layernorm()
+    lines = w.text.splitlines()
+    op_lines = [i for i, l in enumerate(lines) if l.startswith("%") and "const" not in l]
+    counts = []
+    for p in range(1, len(op_lines) + 1):
+        upto = op_lines[p - 1]
+        nid = int(lines[upto].split("=")[0].strip()[1:])
+        text = "\n".join(l for l in lines[:upto + 1]) + "\nout %%%d\n" % nid
+        counts.append(pf.Exec(text).info()["n_kernels"])
+    assert counts == [1] * len(counts)
+    # a transpose of a computed value ends the run; what follows fuses behind the transpose
+    g = Builder()
+    x = g.input("f32", (64, 96))
+    e = g.op("exp", [x], "f32")
+    t = g.op("transpose", [e], "f32")
+    h = g.op("tanh", [t], "f32")
+    s = g.op("sum", [h], "f32")
+    y = g.op("div", [h, s], "f32")
+    g.output(y)
+    ex = pf.Exec(g.text())
+    tm = [gi["template"] for gi in ex.groups()]
+    assert tm == ["ew_flat", "tile", "row_resident"], tm
+    assert [len(gi["nodes"]) for gi in ex.groups()] == [1, 2, 2]
+
+
+def test_every_random_dag_plans_and_compiles():
+    fused_k = unfused_k = ops = 0
+    for k in range(0, dags.N_DAGS, 8):
+        w = dags.cfg5(k, with_inputs=False)
+        f = pf.Exec(w.text)
+        fused_k += f.info()["n_kernels"]
+        ops += w.meta["n_ops"]
+        nodes = sorted(n for gi in f.groups() for n in gi["nodes"])
+        assert len(nodes) == len(set(nodes))                     # each node is computed once
+        assert f.info()["algorithmic_bytes"] == w.algorithmic_bytes
+    assert fused_k < ops
+
+
+def test_generated_source_is_inspectable_and_specialised():
+    e = pf.Exec(configs.cfg2_masked_softmax(heads=2, seq=512).text)
+    src = e.source(0)
+    assert 'extern "C" __global__' in src and "pf_team_max" in src and "C = 512" in src
+    assert e.group_info(0)["lanes_per_row"] in (16, 32, 64)
+
+
+def test_keepdim0_reduction_is_read_back_from_memory_by_its_consumers():
+    g = Builder()
+    x = g.input("f32", (8, 8))
+    s = g.op("sum", [x], "f32", keepdim=0)                       # shape [8]: aligns with columns
+    y = g.op("add", [x, s], "f32")
+    g.output(y)
+    e = pf.Exec(g.text())
+    assert e.info()["n_kernels"] == 2
