@@ -122,7 +122,11 @@ typedef struct {
     int fuse;              /* 1: group nodes into fused kernels (default); 0: one kernel per node */
     int intermediates_f32; /* 1: values crossing a kernel boundary are kept in fp32 (default for
                               fuse=1); 0: stored in their node dtype, as op-by-op execution would */
-    int reserved[6];       /* must be zero */
+    /* tiling overrides for experiments; 0 = let the planner choose from the shape */
+    int tune_row_lanes;    /* row templates: lanes per row (power of two)                         */
+    int tune_row_unroll;   /* row templates: rows in flight per team of lanes                     */
+    int tune_flat_unroll;  /* ew_flat: 16-byte vectors per lane                                   */
+    int reserved[3];       /* must be zero */
 } pf_options;
 
 void pf_options_default(pf_options* h_opt);
@@ -165,6 +169,15 @@ pf_status pf_exec_source(const pf_exec* e, int group, char* h_buf, size_t cap, s
  * is the default stream). */
 pf_status pf_execute(pf_exec* e, const void* const* d_inputs, int n_in, void* const* d_outputs, int n_out,
                      void* d_workspace, size_t workspace_bytes, void* stream);
+
+/* As pf_execute, with two caller-owned hipEvent_t handles (either may be NULL):
+ * start_event is recorded when the first kernel begins executing and
+ * stop_event when the last kernel has finished, so that
+ * hipEventElapsedTime(start, stop) is the device time of the kernels without
+ * the launch overhead around them.  Used by the benchmark (paper Sec. 4.1
+ * protocol: warm-up runs, then timed trials). */
+pf_status pf_execute_timed(pf_exec* e, const void* const* d_inputs, int n_in, void* const* d_outputs, int n_out,
+                           void* d_workspace, size_t workspace_bytes, void* stream, void* start_event, void* stop_event);
 
 /* ---- error scoring (Def. 3.2 / Eq. 1 with atol, rtol of Appendix F) ---- */
 

@@ -32,7 +32,8 @@ class _Attr(C.Structure):
 
 
 class _Options(C.Structure):
-    _fields_ = [("fuse", C.c_int), ("intermediates_f32", C.c_int), ("reserved", C.c_int * 6)]
+    _fields_ = [("fuse", C.c_int), ("intermediates_f32", C.c_int), ("tune_row_lanes", C.c_int),
+                ("tune_row_unroll", C.c_int), ("tune_flat_unroll", C.c_int), ("reserved", C.c_int * 3)]
 
 
 class _NodeInfo(C.Structure):
@@ -76,6 +77,12 @@ def lib():
         return _lib_handle
     if not os.path.exists(LIB_PATH):
         raise RuntimeError("libpf.so is not built (%s); run `python -m paper_2605_29357_amd.build`" % LIB_PATH)
+    # code objects of kernels that were specialised before are kept beside the library
+    cache = os.environ.setdefault("PF_CACHE_DIR", os.path.join(_HERE, "_kcache"))
+    try:
+        os.makedirs(cache, exist_ok=True)
+    except OSError:
+        os.environ["PF_CACHE_DIR"] = ""
     L = C.CDLL(LIB_PATH)
     vp, ip, sz = C.c_void_p, C.POINTER(C.c_int), C.c_size_t
     sigs = {
@@ -92,6 +99,7 @@ def lib():
         "pf_exec_group_info": [vp, C.c_int, C.POINTER(_GroupInfo)],
         "pf_exec_source": [vp, C.c_int, C.c_char_p, sz, C.POINTER(sz)],
         "pf_execute": [vp, C.POINTER(vp), C.c_int, C.POINTER(vp), C.c_int, vp, sz, vp],
+        "pf_execute_timed": [vp, C.POINTER(vp), C.c_int, C.POINTER(vp), C.c_int, vp, sz, vp, vp, vp],
         "pf_score": [C.POINTER(Pair), C.c_int, vp, vp, sz, vp],
         "pf_copy_bytes": [vp, vp, sz, vp],
     }
@@ -179,11 +187,13 @@ class Graph:
 class Exec:
     """pf_exec handle: a planned and compiled subgraph."""
 
-    def __init__(self, graph, fuse=True, intermediates_f32=None):
+    def __init__(self, graph, fuse=True, intermediates_f32=None, **tune):
         self._h = C.c_void_p()
         opt = _Options()
         lib().pf_options_default(C.byref(opt))
         opt.fuse = 1 if fuse else 0
+        for k, v in tune.items():            # tune_row_lanes, tune_row_unroll, tune_flat_unroll
+            setattr(opt, k, int(v))
         if intermediates_f32 is not None:
             opt.intermediates_f32 = 1 if intermediates_f32 else 0
         if isinstance(graph, str):
@@ -219,12 +229,17 @@ class Exec:
         _check(lib().pf_exec_source(self._h, i, buf, need.value, C.byref(need)))
         return buf.value.decode()
 
-    def execute(self, input_ptrs, output_ptrs, workspace_ptr=0, workspace_bytes=0, stream=0):
-        """Device pointers as ints; enqueues the kernels on `stream` (a hipStream_t as int)."""
+    def execute(self, input_ptrs, output_ptrs, workspace_ptr=0, workspace_bytes=0, stream=0, start_event=0, stop_event=0):
+        """Device pointers as ints; enqueues the kernels on `stream` (a hipStream_t as int).
+        start_event / stop_event: optional hipEvent_t handles bracketing the kernels themselves."""
         ins = (C.c_void_p * max(len(input_ptrs), 1))(*input_ptrs)
         outs = (C.c_void_p * max(len(output_ptrs), 1))(*output_ptrs)
-        _check(lib().pf_execute(self._h, ins, len(input_ptrs), outs, len(output_ptrs),
-                                C.c_void_p(workspace_ptr), workspace_bytes, C.c_void_p(stream)))
+        if start_event or stop_event:
+            _check(lib().pf_execute_timed(self._h, ins, len(input_ptrs), outs, len(output_ptrs), C.c_void_p(workspace_ptr),
+                                          workspace_bytes, C.c_void_p(stream), C.c_void_p(start_event), C.c_void_p(stop_event)))
+        else:
+            _check(lib().pf_execute(self._h, ins, len(input_ptrs), outs, len(output_ptrs),
+                                    C.c_void_p(workspace_ptr), workspace_bytes, C.c_void_p(stream)))
 
 
 def score_workspace_bytes(n_pairs):

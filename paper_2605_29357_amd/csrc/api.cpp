@@ -235,29 +235,42 @@ pf_status pf_exec_source(const pf_exec* e, int group, char* h_buf, size_t cap, s
     return outer != PF_OK ? outer : st;
 }
 
+static void check_execute_args(pf_exec* e, const void* const* d_inputs, int n_in, void* const* d_outputs, int n_out,
+                               void* d_workspace, size_t workspace_bytes) {
+    need(e, "e");
+    if (n_in != e->n_inputs) pf::fail(PF_E_RUNTIME, "expected %d input buffers, got %d", e->n_inputs, n_in);
+    if (n_out != e->n_outputs) pf::fail(PF_E_RUNTIME, "expected %d output buffers, got %d", e->n_outputs, n_out);
+    if (n_in) need(d_inputs, "d_inputs");
+    need(d_outputs, "d_outputs");
+    for (int i = 0; i < n_in; ++i) {
+        if (!d_inputs[i]) pf::fail(PF_E_RUNTIME, "input buffer %d is NULL", i);
+        if ((uintptr_t)d_inputs[i] & 15) pf::fail(PF_E_INVALID, "input buffer %d is not 16-byte aligned", i);
+    }
+    for (int i = 0; i < n_out; ++i) {
+        if (!d_outputs[i]) pf::fail(PF_E_RUNTIME, "output buffer %d is NULL", i);
+        if ((uintptr_t)d_outputs[i] & 15) pf::fail(PF_E_INVALID, "output buffer %d is not 16-byte aligned", i);
+    }
+    if (e->plan.workspace_bytes) {
+        if (!d_workspace || workspace_bytes < e->plan.workspace_bytes)
+            pf::fail(PF_E_RUNTIME, "workspace of %llu bytes needed, %zu given", (unsigned long long)e->plan.workspace_bytes,
+                     workspace_bytes);
+        if ((uintptr_t)d_workspace & 255) pf::fail(PF_E_INVALID, "workspace is not 256-byte aligned");
+    }
+}
+
 pf_status pf_execute(pf_exec* e, const void* const* d_inputs, int n_in, void* const* d_outputs, int n_out, void* d_workspace,
                      size_t workspace_bytes, void* stream) {
     return guarded([&] {
-        need(e, "e");
-        if (n_in != e->n_inputs) pf::fail(PF_E_RUNTIME, "expected %d input buffers, got %d", e->n_inputs, n_in);
-        if (n_out != e->n_outputs) pf::fail(PF_E_RUNTIME, "expected %d output buffers, got %d", e->n_outputs, n_out);
-        if (n_in) need(d_inputs, "d_inputs");
-        need(d_outputs, "d_outputs");
-        for (int i = 0; i < n_in; ++i) {
-            if (!d_inputs[i]) pf::fail(PF_E_RUNTIME, "input buffer %d is NULL", i);
-            if ((uintptr_t)d_inputs[i] & 15) pf::fail(PF_E_INVALID, "input buffer %d is not 16-byte aligned", i);
-        }
-        for (int i = 0; i < n_out; ++i) {
-            if (!d_outputs[i]) pf::fail(PF_E_RUNTIME, "output buffer %d is NULL", i);
-            if ((uintptr_t)d_outputs[i] & 15) pf::fail(PF_E_INVALID, "output buffer %d is not 16-byte aligned", i);
-        }
-        if (e->plan.workspace_bytes) {
-            if (!d_workspace || workspace_bytes < e->plan.workspace_bytes)
-                pf::fail(PF_E_RUNTIME, "workspace of %llu bytes needed, %zu given", (unsigned long long)e->plan.workspace_bytes,
-                         workspace_bytes);
-            if ((uintptr_t)d_workspace & 255) pf::fail(PF_E_INVALID, "workspace is not 256-byte aligned");
-        }
-        pf::exec_run(*e, d_inputs, d_outputs, d_workspace, stream);
+        check_execute_args(e, d_inputs, n_in, d_outputs, n_out, d_workspace, workspace_bytes);
+        pf::exec_run(*e, d_inputs, d_outputs, d_workspace, stream, nullptr, nullptr);
+    });
+}
+
+pf_status pf_execute_timed(pf_exec* e, const void* const* d_inputs, int n_in, void* const* d_outputs, int n_out,
+                           void* d_workspace, size_t workspace_bytes, void* stream, void* start_event, void* stop_event) {
+    return guarded([&] {
+        check_execute_args(e, d_inputs, n_in, d_outputs, n_out, d_workspace, workspace_bytes);
+        pf::exec_run(*e, d_inputs, d_outputs, d_workspace, stream, start_event, stop_event);
     });
 }
 
@@ -265,7 +278,9 @@ size_t pf_score_workspace_bytes(int n_pairs) {
     if (n_pairs < 0) n_pairs = 0;
     size_t b = (size_t)n_pairs * sizeof(pf::PairDev);
     b = (b + 255) / 256 * 256;
-    return b + ((size_t)n_pairs + 1) * sizeof(unsigned long long);
+    b += ((size_t)n_pairs + 1) * sizeof(unsigned long long);
+    b = (b + 255) / 256 * 256;
+    return b + (size_t)n_pairs * pf::kScoreSlots * sizeof(pf_score_result);
 }
 
 pf_status pf_score(const pf_pair* h_pairs, int n_pairs, pf_score_result* d_results, void* d_workspace, size_t workspace_bytes,
@@ -281,6 +296,8 @@ pf_status pf_score(const pf_pair* h_pairs, int n_pairs, pf_score_result* d_resul
         const size_t pairs_bytes = ((size_t)n_pairs * sizeof(pf::PairDev) + 255) / 256 * 256;
         pf::PairDev* d_pairs = (pf::PairDev*)d_workspace;
         unsigned long long* d_start = (unsigned long long*)((char*)d_workspace + pairs_bytes);
+        const size_t start_bytes = (((size_t)n_pairs + 1) * sizeof(unsigned long long) + 255) / 256 * 256;
+        pf_score_result* d_slots = (pf_score_result*)((char*)d_workspace + pairs_bytes + start_bytes);
         const unsigned long long chunk = pf::score_chunk_elems();
         for (int i = 0; i < n_pairs; ++i) {
             const pf_pair& p = h_pairs[i];
@@ -316,7 +333,7 @@ pf_status pf_score(const pf_pair* h_pairs, int n_pairs, pf_score_result* d_resul
             err = pf::launch_score_upload(b, d_pairs, d_start, (hipStream_t)stream);
             if (err != hipSuccess) pf::fail(PF_E_RUNTIME, "descriptor upload failed: %s", hipGetErrorString(err));
         }
-        err = pf::launch_score(d_pairs, d_start, n_pairs, total, d_results, (hipStream_t)stream);
+        err = pf::launch_score(d_pairs, d_start, n_pairs, total, d_results, d_slots, (hipStream_t)stream);
         if (err != hipSuccess) pf::fail(PF_E_RUNTIME, "score launch failed: %s", hipGetErrorString(err));
     });
 }

@@ -16,5 +16,6 @@ struct pf_exec {
 namespace pf {
 void exec_load(pf_exec& e);
 void exec_unload(pf_exec& e);
-void exec_run(pf_exec& e, const void* const* d_inputs, void* const* d_outputs, void* d_ws, void* stream);
+void exec_run(pf_exec& e, const void* const* d_inputs, void* const* d_outputs, void* d_ws, void* stream, void* start_event,
+              void* stop_event);
 }  // namespace pf

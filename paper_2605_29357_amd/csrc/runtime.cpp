@@ -1,6 +1,7 @@
 // Runtime: JIT compilation of generated kernels (hipRTC), code-object cache,
 // lazy module loading and launches.
 #include <hip/hip_runtime_api.h>
+#include <hip/hip_ext.h>
 #include <hip/hiprtc.h>
 
 #include <cstdio>
@@ -9,6 +10,7 @@
 #include <fstream>
 #include <mutex>
 #include <unordered_map>
+#include <unistd.h>
 
 #include "exec.h"
 #include "pf_internal.h"
@@ -32,7 +34,7 @@ uint64_t fnv1a(const std::string& s) {
 std::string disk_path(const std::string& source) {
     const char* dir = getenv("PF_CACHE_DIR");
     if (!dir || !*dir) return "";
-    return strf("%s/pf_%016llx_%zu.hsaco", dir, (unsigned long long)fnv1a(source), source.size());
+    return strf("%s/pf_%016llx_%zu.pfk", dir, (unsigned long long)fnv1a(source), source.size());
 }
 
 }  // namespace
@@ -46,16 +48,23 @@ void jit_compile(Group& grp) {
             return;
         }
     }
+    // on-disk cache: a file holds the full source text followed by the code
+    // object, and is used only if the text matches byte for byte
     const std::string path = disk_path(grp.source);
     if (!path.empty()) {
         std::ifstream f(path, std::ios::binary);
         if (f) {
-            std::vector<char> code((std::istreambuf_iterator<char>(f)), std::istreambuf_iterator<char>());
-            if (!code.empty()) {
-                grp.code = code;
-                std::lock_guard<std::mutex> lk(g_cache_mu);
-                g_code_cache[grp.source] = code;
-                return;
+            std::vector<char> blob((std::istreambuf_iterator<char>(f)), std::istreambuf_iterator<char>());
+            uint64_t len = 0;
+            if (blob.size() > 16 && memcmp(blob.data(), "PFCACHE1", 8) == 0) {
+                memcpy(&len, blob.data() + 8, 8);
+                if (len == grp.source.size() && blob.size() > 16 + len &&
+                    memcmp(blob.data() + 16, grp.source.data(), len) == 0) {
+                    grp.code.assign(blob.begin() + 16 + len, blob.end());
+                    std::lock_guard<std::mutex> lk(g_cache_mu);
+                    g_code_cache[grp.source] = grp.code;
+                    return;
+                }
             }
         }
     }
@@ -80,10 +89,18 @@ void jit_compile(Group& grp) {
     hiprtcGetCode(prog, grp.code.data());
     hiprtcDestroyProgram(&prog);
     if (!path.empty()) {
-        std::ofstream f(path + ".tmp", std::ios::binary);
-        f.write(grp.code.data(), (std::streamsize)grp.code.size());
-        f.close();
-        rename((path + ".tmp").c_str(), path.c_str());
+        const std::string tmp = strf("%s.%d.tmp", path.c_str(), (int)getpid());
+        std::ofstream f(tmp, std::ios::binary);
+        if (f) {
+            const uint64_t len = grp.source.size();
+            f.write("PFCACHE1", 8);
+            f.write((const char*)&len, 8);
+            f.write(grp.source.data(), (std::streamsize)len);
+            f.write(grp.code.data(), (std::streamsize)grp.code.size());
+            f.close();
+            if (f.good()) rename(tmp.c_str(), path.c_str());
+            else remove(tmp.c_str());
+        }
     }
     std::lock_guard<std::mutex> lk(g_cache_mu);
     g_code_cache[grp.source] = grp.code;
@@ -115,7 +132,8 @@ void exec_unload(pf_exec& e) {
     e.loaded = false;
 }
 
-void exec_run(pf_exec& e, const void* const* d_inputs, void* const* d_outputs, void* d_ws, void* stream) {
+void exec_run(pf_exec& e, const void* const* d_inputs, void* const* d_outputs, void* d_ws, void* stream, void* start_event,
+              void* stop_event) {
     exec_load(e);
     for (size_t i = 0; i < e.plan.groups.size(); ++i) {
         Group& grp = e.plan.groups[i];
@@ -133,8 +151,20 @@ void exec_run(pf_exec& e, const void* const* d_inputs, void* const* d_outputs, v
             for (int k : s.also_outputs) ptrs[n++] = d_outputs[k];
         }
         for (int k = 0; k < n; ++k) args[k] = &ptrs[k];
-        hipError_t err = hipModuleLaunchKernel((hipFunction_t)e.functions[i], (unsigned)grp.grid, 1, 1, (unsigned)grp.block, 1, 1, 0,
-                                               (hipStream_t)stream, args, nullptr);
+        // events, when given, bracket the kernels themselves (dispatch timestamps), not the
+        // launch calls: the first kernel carries the start event, the last one the stop event
+        hipEvent_t ev0 = i == 0 ? (hipEvent_t)start_event : nullptr;
+        hipEvent_t ev1 = i + 1 == e.plan.groups.size() ? (hipEvent_t)stop_event : nullptr;
+        hipError_t err;
+        if ((ev0 || ev1) && (uint64_t)grp.grid * (uint64_t)grp.block < (1ull << 32))
+            err = hipExtModuleLaunchKernel((hipFunction_t)e.functions[i], (uint32_t)(grp.grid * grp.block), 1, 1, (uint32_t)grp.block, 1, 1,
+                                           0, (hipStream_t)stream, args, nullptr, ev0, ev1, 0);
+        else {
+            if (ev0) (void)hipEventRecord(ev0, (hipStream_t)stream);
+            err = hipModuleLaunchKernel((hipFunction_t)e.functions[i], (unsigned)grp.grid, 1, 1, (unsigned)grp.block, 1, 1, 0,
+                                        (hipStream_t)stream, args, nullptr);
+            if (ev1 && err == hipSuccess) (void)hipEventRecord(ev1, (hipStream_t)stream);
+        }
         if (err != hipSuccess) fail(PF_E_RUNTIME, "launch of %s failed: %s", grp.kernel_name.c_str(), hipGetErrorString(err));
     }
 }

@@ -19,7 +19,8 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kBlock = 256;
-constexpr int kPerThread = 32;                       // elements per thread per block-chunk
+constexpr int kPerThread = 64;                       // elements per thread per block-chunk
+constexpr int kSlots = pf::kScoreSlots;              // partial results per pair (spreads the atomics)
 constexpr unsigned long long kChunk = (unsigned long long)kBlock * kPerThread;
 
 template <int DT> struct Elem;                        // DT: pf_dtype
@@ -157,8 +158,16 @@ __global__ void __launch_bounds__(64) score_upload_kernel(pf::PairBatch batch, p
     if (i == 0 && batch.last) block_start[batch.first + batch.count] = batch.start[batch.count];
 }
 
-__global__ void __launch_bounds__(kBlock) score_init_kernel(const pf::PairDev* pairs, int n_pairs, pf_score_result* res) {
+__global__ void __launch_bounds__(kBlock) score_init_kernel(const pf::PairDev* pairs, int n_pairs, pf_score_result* res,
+                                                            pf_score_result* slots) {
     const int p = blockIdx.x * blockDim.x + threadIdx.x;
+    if (p < n_pairs * kSlots) {
+        pf_score_result z;
+        z.max_abs = 0.0; z.max_rel = 0.0; z.n = 0; z.n_viol = 0;
+        z.nan_cand = z.nan_ref = z.inf_cand = z.inf_ref = 0;
+        z.allclose = 0; z.bit_identical = 0; z.reserved_ = 0;
+        slots[p] = z;
+    }
     if (p >= n_pairs) return;
     pf_score_result r;
     r.max_abs = 0.0; r.max_rel = 0.0;
@@ -168,8 +177,14 @@ __global__ void __launch_bounds__(kBlock) score_init_kernel(const pf::PairDev* p
     res[p] = r;
 }
 
+__device__ __forceinline__ void raise_max(double* slot, double v) {
+    // values only grow, so a stale read can at worst cause a redundant atomic
+    const unsigned long long bits = (unsigned long long)__double_as_longlong(v);
+    if (bits > __atomic_load_n((unsigned long long*)slot, __ATOMIC_RELAXED)) atomicMax((unsigned long long*)slot, bits);
+}
+
 __global__ void __launch_bounds__(kBlock) score_kernel(const pf::PairDev* pairs, const unsigned long long* block_start,
-                                                       int n_pairs, pf_score_result* res) {
+                                                       int n_pairs, pf_score_result* slots) {
     // which pair does this block belong to: largest p with block_start[p] <= blockIdx.x
     int lo = 0, hi = n_pairs;
     const unsigned long long bid = blockIdx.x;
@@ -216,10 +231,11 @@ __global__ void __launch_bounds__(kBlock) score_kernel(const pf::PairDev* pairs,
 #pragma unroll
             for (int k = 0; k < 6; ++k) t[k] += s_cnt[w][k];
         }
-        pf_score_result* r = res + lo;
+        // one of kSlots partial results of this pair; the final kernel folds them
+        pf_score_result* r = slots + (size_t)lo * kSlots + (bid - block_start[lo]) % kSlots;
         // errors are >= 0 and never NaN, so their bit patterns order like the values
-        if (ma > 0.0) atomicMax((unsigned long long*)&r->max_abs, (unsigned long long)__double_as_longlong(ma));
-        if (mr > 0.0) atomicMax((unsigned long long*)&r->max_rel, (unsigned long long)__double_as_longlong(mr));
+        if (ma > 0.0) raise_max(&r->max_abs, ma);
+        if (mr > 0.0) raise_max(&r->max_rel, mr);
         if (t[0]) atomicAdd((unsigned long long*)&r->n_viol, t[0]);
         if (t[1]) atomicAdd((unsigned long long*)&r->reserved_, t[1]);
         if (t[2]) atomicAdd((unsigned long long*)&r->nan_cand, t[2]);
@@ -229,11 +245,23 @@ __global__ void __launch_bounds__(kBlock) score_kernel(const pf::PairDev* pairs,
     }
 }
 
-__global__ void __launch_bounds__(kBlock) score_final_kernel(const pf::PairDev* pairs, int n_pairs, pf_score_result* res) {
+__global__ void __launch_bounds__(kBlock) score_final_kernel(const pf::PairDev* pairs, int n_pairs, pf_score_result* res,
+                                                             const pf_score_result* slots) {
     const int p = blockIdx.x * blockDim.x + threadIdx.x;
     if (p >= n_pairs) return;
-    res[p].allclose = res[p].n_viol == 0 ? 1u : 0u;
-    res[p].bit_identical = (pairs[p].cand_dtype == pairs[p].ref_dtype && res[p].reserved_ == 0) ? 1u : 0u;
+    pf_score_result r = res[p];
+    for (int k = 0; k < kSlots; ++k) {
+        const pf_score_result& s = slots[(size_t)p * kSlots + k];
+        r.max_abs = fmax(r.max_abs, s.max_abs);
+        r.max_rel = fmax(r.max_rel, s.max_rel);
+        r.n_viol += s.n_viol;
+        r.reserved_ += s.reserved_;
+        r.nan_cand += s.nan_cand; r.nan_ref += s.nan_ref;
+        r.inf_cand += s.inf_cand; r.inf_ref += s.inf_ref;
+    }
+    r.allclose = r.n_viol == 0 ? 1u : 0u;
+    r.bit_identical = (pairs[p].cand_dtype == pairs[p].ref_dtype && r.reserved_ == 0) ? 1u : 0u;
+    res[p] = r;
 }
 
 __global__ void __launch_bounds__(256) copy_kernel(u32x4* __restrict__ dst, const u32x4* __restrict__ src, unsigned long long n16) {
@@ -263,13 +291,14 @@ hipError_t launch_score_upload(const PairBatch& batch, PairDev* d_pairs, unsigne
 }
 
 hipError_t launch_score(const PairDev* d_pairs, const unsigned long long* d_block_start, int n_pairs,
-                        unsigned long long total_blocks, pf_score_result* d_results, hipStream_t stream) {
+                        unsigned long long total_blocks, pf_score_result* d_results, pf_score_result* d_slots, hipStream_t stream) {
     const int nb = (n_pairs + kBlock - 1) / kBlock;
-    hipLaunchKernelGGL(score_init_kernel, dim3(nb), dim3(kBlock), 0, stream, d_pairs, n_pairs, d_results);
+    const int nbs = (n_pairs * kSlots + kBlock - 1) / kBlock;
+    hipLaunchKernelGGL(score_init_kernel, dim3(nbs), dim3(kBlock), 0, stream, d_pairs, n_pairs, d_results, d_slots);
     if (total_blocks)
         hipLaunchKernelGGL(score_kernel, dim3((unsigned)total_blocks), dim3(kBlock), 0, stream, d_pairs, d_block_start, n_pairs,
-                           d_results);
-    hipLaunchKernelGGL(score_final_kernel, dim3(nb), dim3(kBlock), 0, stream, d_pairs, n_pairs, d_results);
+                           d_slots);
+    hipLaunchKernelGGL(score_final_kernel, dim3(nb), dim3(kBlock), 0, stream, d_pairs, n_pairs, d_results, d_slots);
     return hipGetLastError();
 }
 

@@ -17,6 +17,8 @@ struct PairDev {
     int pad_;
 };
 
+constexpr int kScoreSlots = 64;   // partial result slots per pair
+
 // up to kBatch descriptors passed by value to the upload kernel
 constexpr int kPairBatch = 24;
 struct PairBatch {
@@ -28,7 +30,7 @@ struct PairBatch {
 unsigned long long score_chunk_elems();
 hipError_t launch_score_upload(const PairBatch& batch, PairDev* d_pairs, unsigned long long* d_block_start, hipStream_t stream);
 hipError_t launch_score(const PairDev* d_pairs, const unsigned long long* d_block_start, int n_pairs,
-                        unsigned long long total_blocks, pf_score_result* d_results, hipStream_t stream);
+                        unsigned long long total_blocks, pf_score_result* d_results, pf_score_result* d_slots, hipStream_t stream);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
 
 }  // namespace pf

@@ -42,21 +42,63 @@ def alloc_outputs(w, poison=True):
 class Runner:
     """Compiles a workload's DAG once and runs it on device tensors."""
 
-    def __init__(self, w, fuse=True, intermediates_f32=None, upload=True):
+    def __init__(self, w, fuse=True, intermediates_f32=None, upload=True, **tune):
         self.w = w
-        self.exe = pf.Exec(w.text, fuse=fuse, intermediates_f32=intermediates_f32)
+        self.exe = pf.Exec(w.text, fuse=fuse, intermediates_f32=intermediates_f32, **tune)
         self.info = self.exe.info()
         ws = self.info["workspace_bytes"]
         self.ws = torch.empty(max(ws, 256), dtype=torch.uint8, device="cuda") if ws else None
         self.d_in = [to_device(a, dt) for a, dt in zip(w.inputs, w.input_dtypes)] if upload else None
 
-    def run(self, outs=None, stream=None):
+    def run(self, outs=None, stream=None, events=None):
+        """events: optional (start, stop) HipEvent pair bracketing the kernels themselves."""
         outs = outs if outs is not None else alloc_outputs(self.w)
         s = stream if stream is not None else torch.cuda.current_stream()
         self.exe.execute([t.data_ptr() for t in self.d_in], [t.data_ptr() for t in outs],
                          self.ws.data_ptr() if self.ws is not None else 0,
-                         self.ws.numel() if self.ws is not None else 0, s.cuda_stream)
+                         self.ws.numel() if self.ws is not None else 0, s.cuda_stream,
+                         events[0].handle if events else 0, events[1].handle if events else 0)
         return outs
+
+
+_hip = None
+
+
+def _hiprt():
+    global _hip
+    if _hip is None:
+        _hip = ctypes.CDLL("libamdhip64.so")
+        _hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        _hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        _hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        _hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+        _hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+    return _hip
+
+
+class HipEvent:
+    """A raw hipEvent_t (torch's Event hides its handle until it has been recorded)."""
+
+    def __init__(self):
+        self._h = ctypes.c_void_p()
+        if _hiprt().hipEventCreate(ctypes.byref(self._h)) != 0:
+            raise RuntimeError("hipEventCreate failed")
+        self.handle = self._h.value
+
+    def record(self, stream):
+        if _hiprt().hipEventRecord(self._h, ctypes.c_void_p(stream.cuda_stream)) != 0:
+            raise RuntimeError("hipEventRecord failed")
+
+    def elapsed_us(self, stop):
+        ms = ctypes.c_float()
+        if _hiprt().hipEventElapsedTime(ctypes.byref(ms), self._h, stop._h) != 0:
+            raise RuntimeError("hipEventElapsedTime failed")
+        return ms.value * 1e3
+
+    def __del__(self):
+        if _hip is not None and self._h:
+            _hip.hipEventDestroy(self._h)
+            self._h = None
 
 
 def score_on_gpu(pairs_spec, stream=None):

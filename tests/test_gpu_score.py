@@ -112,17 +112,17 @@ def test_many_pairs_in_one_call():
 def test_bad_arguments_are_refused():
     import paper_2605_29357_amd as pf
     x = torch.zeros(64, device="cuda")
-    ws = torch.empty(4096, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(16384, dtype=torch.uint8, device="cuda")
     p = pf.Pair()
     p.d_cand, p.d_ref, p.n = x.data_ptr() + 4, x.data_ptr(), 8      # misaligned
     p.cand_dtype = p.ref_dtype = pf.F32
     with pytest.raises(pf.PfError) as e:
-        pf.score([p], ws.data_ptr(), ws.data_ptr(), 4096)
+        pf.score([p], ws.data_ptr(), ws.data_ptr(), 16384)
     assert e.value.status == pf.PF_E_INVALID
     p.d_cand = x.data_ptr()
     p.cand_dtype = pf.F64
     with pytest.raises(pf.PfError):
-        pf.score([p], ws.data_ptr(), ws.data_ptr(), 4096)
+        pf.score([p], ws.data_ptr(), ws.data_ptr(), 16384)
     p.cand_dtype = pf.F32
     with pytest.raises(pf.PfError) as e:
         pf.score([p], ws.data_ptr(), ws.data_ptr(), 8)              # workspace too small
