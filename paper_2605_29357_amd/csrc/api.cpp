@@ -2,6 +2,7 @@
 // thread-local string and returns a pf_status.
 #include <hip/hip_runtime_api.h>
 
+#include <algorithm>
 #include <cstring>
 #include <memory>
 #include <new>
@@ -307,6 +308,13 @@ pf_status pf_score(const pf_pair* h_pairs, int n_pairs, pf_score_result* d_resul
             if (((uintptr_t)p.d_cand | (uintptr_t)p.d_ref) & 15) pf::fail(PF_E_INVALID, "pair %d: buffers must be 16-byte aligned", i);
             if (!(p.rtol >= 0.0) || !(p.atol >= 0.0)) pf::fail(PF_E_INVALID, "pair %d: tolerances must be >= 0", i);
         }
+        // order the pairs by dtype combination: each combination then owns a contiguous block range
+        std::vector<int> order(n_pairs);
+        for (int i = 0; i < n_pairs; ++i) order[i] = i;
+        auto combo = [&](int i) { return h_pairs[i].cand_dtype * 3 + h_pairs[i].ref_dtype; };
+        std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return combo(a) < combo(b); });
+        pf::ScoreRanges ranges;
+        memset(&ranges, 0, sizeof ranges);
         unsigned long long total = 0;
         hipError_t err = hipSuccess;
         for (int first = 0; first < n_pairs; first += pf::kPairBatch) {
@@ -316,7 +324,7 @@ pf_status pf_score(const pf_pair* h_pairs, int n_pairs, pf_score_result* d_resul
             b.count = n_pairs - first < pf::kPairBatch ? n_pairs - first : pf::kPairBatch;
             b.last = first + b.count == n_pairs;
             for (int k = 0; k < b.count; ++k) {
-                const pf_pair& p = h_pairs[first + k];
+                const pf_pair& p = h_pairs[order[first + k]];
                 b.pairs[k].cand = p.d_cand;
                 b.pairs[k].ref = p.d_ref;
                 b.pairs[k].n = p.n;
@@ -325,15 +333,19 @@ pf_status pf_score(const pf_pair* h_pairs, int n_pairs, pf_score_result* d_resul
                 b.pairs[k].rtol = p.rtol;
                 b.pairs[k].atol = p.atol;
                 b.pairs[k].equal_nan = p.equal_nan;
+                b.pairs[k].orig = order[first + k];
                 b.start[k] = total;
-                total += (p.n + chunk - 1) / chunk;
+                const unsigned long long nb = (p.n + chunk - 1) / chunk;
+                if (ranges.count[p.cand_dtype][p.ref_dtype] == 0) ranges.first[p.cand_dtype][p.ref_dtype] = total;
+                ranges.count[p.cand_dtype][p.ref_dtype] += nb;
+                total += nb;
             }
             b.start[b.count] = total;
             if (total >= (1ull << 31)) pf::fail(PF_E_INVALID, "too many elements for one scoring call");
             err = pf::launch_score_upload(b, d_pairs, d_start, (hipStream_t)stream);
             if (err != hipSuccess) pf::fail(PF_E_RUNTIME, "descriptor upload failed: %s", hipGetErrorString(err));
         }
-        err = pf::launch_score(d_pairs, d_start, n_pairs, total, d_results, d_slots, (hipStream_t)stream);
+        err = pf::launch_score(d_pairs, d_start, n_pairs, ranges, d_results, d_slots, (hipStream_t)stream);
         if (err != hipSuccess) pf::fail(PF_E_RUNTIME, "score launch failed: %s", hipGetErrorString(err));
     });
 }

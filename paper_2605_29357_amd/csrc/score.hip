@@ -119,6 +119,32 @@ __device__ __forceinline__ void score_one(typename Elem<CD>::raw ra, typename El
     acc.max_rel = fmax(acc.max_rel, __ddiv_rn(d, ab));
 }
 
+// One element, entirely in fp64, every quantity exact (the definition itself).
+template <int CD, int RD>
+__device__ __forceinline__ void score_exact(typename Elem<CD>::raw ra, typename Elem<RD>::raw rb, const pf::PairDev& pr, Acc& acc) {
+    const double a = Elem<CD>::widen(ra), b = Elem<RD>::widen(rb);
+    const bool na = a != a, nb = b != b;
+    acc.nan_c += na;
+    acc.nan_r += nb;
+    const double inf = __builtin_inf();
+    acc.inf_c += (fabs(a) == inf);
+    acc.inf_r += (fabs(b) == inf);
+    if (na || nb) {
+        acc.n_viol += !(pr.equal_nan && na && nb);
+        return;
+    }
+    if (a == b) return;
+    const double d = fabs(__dsub_rn(a, b));
+    const double ab = fabs(b);
+    acc.max_abs = fmax(acc.max_abs, d);
+    const double allowed = __dadd_rn(pr.atol, __dmul_rn(pr.rtol, ab));
+    acc.n_viol += !(d != inf && d <= allowed);
+    // a division only where the quotient can exceed the running maximum:
+    // d <= max_rel * |b| * (1 - 2^-50) implies RN(d / |b|) <= max_rel
+    if (ab == 0.0 || d == inf) acc.max_rel = inf;
+    else if (d > acc.max_rel * ab * 0.999999999999999) acc.max_rel = fmax(acc.max_rel, __ddiv_rn(d, ab));
+}
+
 template <int CD, int RD>
 __device__ __forceinline__ void score_chunk(const pf::PairDev& pr, unsigned long long begin, unsigned long long end, Acc& acc) {
     // vectors of 8 elements, lanes interleaved so that a wave reads contiguous memory
@@ -133,6 +159,143 @@ __device__ __forceinline__ void score_chunk(const pf::PairDev& pr, unsigned long
     }
     for (unsigned long long i = begin + nvec * 8 + threadIdx.x; i < end; i += kBlock)
         score_one<CD, RD>(Elem<CD>::load1(pr.cand, i), Elem<RD>::load1(pr.ref, i), pr, acc);
+}
+
+__device__ __forceinline__ double wave_max(double v);
+
+// ---- fp32 screening path (both sides f32 or bf16) --------------------------
+// Almost every element can be classified without fp64: with a, b widened to
+// fp32, d32 = |a - b| carries a relative error of 2^-24 (and is exact when it
+// is subnormal), so comparing it against thresholds that are pulled 2e-6 to
+// the safe side decides "certainly inside the tolerance", "certainly outside",
+// "certainly not a new maximum of |a-b| or of |a-b|/|b|".  A vector of eight
+// elements in which any element is not decided this way (or is NaN/Inf) is
+// re-evaluated exactly in fp64, element by element, by score_one; the fast
+// counts of that vector are then discarded.  The maxima thresholds are shared
+// by the wave and follow the exact maxima found so far, so the exact path
+// runs only O(log n) times per wave plus once per genuine near-tie.
+struct Screen {
+    float rtol_lo, atol_lo, rtol_hi, atol_hi;   // tolerance pulled 2e-6 inwards / outwards
+    bool viol_decidable;                         // false: tolerances too small for fp32 screening
+};
+
+__device__ __forceinline__ Screen make_screen(const pf::PairDev& pr) {
+    Screen sc;
+    sc.rtol_lo = (float)(pr.rtol * (1.0 - 2e-6));
+    sc.atol_lo = (float)(pr.atol * (1.0 - 2e-6));
+    sc.rtol_hi = (float)(pr.rtol * (1.0 + 2e-6));
+    sc.atol_hi = (float)(pr.atol * (1.0 + 2e-6));
+    const bool r_ok = pr.rtol == 0.0 || pr.rtol >= 1e-30, a_ok = pr.atol == 0.0 || pr.atol >= 1e-30;
+    sc.viol_decidable = r_ok && a_ok;
+    return sc;
+}
+
+// Eight consecutive elements as loaded: packed 32-bit words (4 for bf16, 8 for f32).
+template <int DT> struct Vec8 {
+    static constexpr int NW = DT == PF_BF16 ? 4 : 8;
+    unsigned int w[NW];
+    __device__ __forceinline__ void load(const void* base, unsigned long long i) {
+        const u32x4* p = (const u32x4*)((const char*)base + i * (DT == PF_BF16 ? 2 : 4));
+#pragma unroll
+        for (int k = 0; k < NW / 4; ++k) {
+            const u32x4 r = __builtin_nontemporal_load(p + k);
+            w[4 * k] = r.x; w[4 * k + 1] = r.y; w[4 * k + 2] = r.z; w[4 * k + 3] = r.w;
+        }
+    }
+    // element j widened to fp32 (exact)
+    __device__ __forceinline__ float f32(int j) const {
+        if (DT == PF_BF16) return __uint_as_float((j & 1) ? (w[j >> 1] & 0xffff0000u) : (w[j >> 1] << 16));
+        return __uint_as_float(w[j]);
+    }
+    // element j as Elem<DT>::raw
+    __device__ __forceinline__ unsigned int raw(int j) const {
+        if (DT == PF_BF16) return (j & 1) ? (w[j >> 1] >> 16) : (w[j >> 1] & 0xffffu);
+        return w[j];
+    }
+};
+
+template <int CD, int RD>
+__device__ __forceinline__ void score_chunk_fast(const pf::PairDev& pr, unsigned long long begin, unsigned long long end, Acc& acc,
+                                                 double seed_abs, double seed_rel) {
+    const Screen sc = make_screen(pr);
+    const int zero_tol = (pr.rtol == 0.0) & (pr.atol == 0.0);
+    const int force_exact = !sc.viol_decidable;
+    // wave-shared lower bounds of the exact maxima (rounded to fp32 and pulled down)
+    double wave_abs = seed_abs, wave_rel = seed_rel;
+    float thr_abs = wave_abs >= 1e-30 ? (float)wave_abs * 0.999998f : 0.0f;
+    float thr_rel = wave_rel >= 1e-30 ? (float)wave_rel * 0.999998f : 0.0f;
+    unsigned int xor_acc = 0;
+    const unsigned long long nvec = (end - begin) / 8;
+    const unsigned long long iters = (nvec + kBlock - 1) / kBlock;
+    // the next vector is already on its way while the current one is screened
+    Vec8<CD> na;
+    Vec8<RD> nb;
+    if (threadIdx.x < nvec) {
+        na.load(pr.cand, begin + (unsigned long long)threadIdx.x * 8);
+        nb.load(pr.ref, begin + (unsigned long long)threadIdx.x * 8);
+    }
+    for (unsigned long long it = 0; it < iters; ++it) {
+        const unsigned long long v = it * kBlock + threadIdx.x;
+        const bool live = v < nvec;
+        const Vec8<CD> va = na;
+        const Vec8<RD> vb = nb;
+        if (v + kBlock < nvec) {
+            na.load(pr.cand, begin + (v + kBlock) * 8);
+            nb.load(pr.ref, begin + (v + kBlock) * 8);
+        }
+        unsigned int fmask = 0;          // bit j: element j needs the exact path
+        unsigned int nv = 0;
+        if (live) {
+            if (CD == RD) {
+#pragma unroll
+                for (int k = 0; k < Vec8<CD>::NW; ++k) xor_acc |= va.w[k] ^ vb.w[k];
+            }
+            // branch-free on purpose (bitwise | and &): short-circuit forms turn into
+            // exec-mask juggling that costs more than the arithmetic
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const float a = va.f32(j), b = vb.f32(j);
+                const float d = fabsf(a - b), ab = fabsf(b);
+                const float lo = __builtin_fmaf(sc.rtol_lo, ab, sc.atol_lo);
+                const float hi = __builtin_fmaf(sc.rtol_hi, ab, sc.atol_hi);
+                // thresholds below 1e-30 are too close to the fp32 subnormal range to be trusted
+                const int ok = (d == 0.0f) | ((d <= lo) & (lo >= 1e-30f));
+                const int out = (d > hi) & ((hi >= 1e-30f) | zero_tol);
+                const float pr_rel = thr_rel * ab;
+                // undecided tolerance test, NaN/Inf (d is then NaN or inf), or a possible new maximum
+                const int f = (!(ok | out)) | (!(d < __builtin_inff())) | (d > thr_abs) | (d > pr_rel) | ((pr_rel < 1e-30f) & (d != 0.0f)) |
+                              force_exact;
+                nv += out & !f;
+                fmask |= (unsigned)f << j;
+            }
+        }
+        acc.n_viol += nv;
+        if (__any(fmask != 0)) {
+            // exact fp64 evaluation of the flagged elements only; the trip count is the
+            // largest number of flagged elements in any lane of the wave
+            while (fmask) {
+                const int j = __builtin_ctz(fmask);
+                fmask &= fmask - 1;
+                unsigned int ea = va.raw(0), eb = vb.raw(0);
+#pragma unroll
+                for (int t = 1; t < 8; ++t) { ea = j == t ? va.raw(t) : ea; eb = j == t ? vb.raw(t) : eb; }
+                score_exact<CD, RD>(ea, eb, pr, acc);
+            }
+            if (__any((acc.max_abs > wave_abs) | (acc.max_rel > wave_rel))) {
+                wave_abs = fmax(wave_abs, wave_max(acc.max_abs));
+                wave_rel = fmax(wave_rel, wave_max(acc.max_rel));
+                thr_abs = wave_abs >= 1e-30 ? (float)wave_abs * 0.999998f : 0.0f;
+                thr_rel = wave_rel >= 1e-30 ? (float)wave_rel * 0.999998f : 0.0f;
+            }
+        }
+    }
+    if (CD == RD) acc.bitdiff += xor_acc ? 1u : 0u;
+    for (unsigned long long i = begin + nvec * 8 + threadIdx.x; i < end; i += kBlock) {
+        const typename Elem<CD>::raw ea = Elem<CD>::load1(pr.cand, i);
+        const typename Elem<RD>::raw eb = Elem<RD>::load1(pr.ref, i);
+        if (CD == RD) acc.bitdiff += ea != eb;
+        score_exact<CD, RD>(ea, eb, pr, acc);
+    }
 }
 
 __device__ __forceinline__ unsigned long long wave_sum(unsigned long long v) {
@@ -158,8 +321,7 @@ __global__ void __launch_bounds__(64) score_upload_kernel(pf::PairBatch batch, p
     if (i == 0 && batch.last) block_start[batch.first + batch.count] = batch.start[batch.count];
 }
 
-__global__ void __launch_bounds__(kBlock) score_init_kernel(const pf::PairDev* pairs, int n_pairs, pf_score_result* res,
-                                                            pf_score_result* slots) {
+__global__ void __launch_bounds__(kBlock) score_init_kernel(int n_pairs, pf_score_result* slots) {
     const int p = blockIdx.x * blockDim.x + threadIdx.x;
     if (p < n_pairs * kSlots) {
         pf_score_result z;
@@ -168,13 +330,6 @@ __global__ void __launch_bounds__(kBlock) score_init_kernel(const pf::PairDev* p
         z.allclose = 0; z.bit_identical = 0; z.reserved_ = 0;
         slots[p] = z;
     }
-    if (p >= n_pairs) return;
-    pf_score_result r;
-    r.max_abs = 0.0; r.max_rel = 0.0;
-    r.n = pairs[p].n; r.n_viol = 0;
-    r.nan_cand = r.nan_ref = r.inf_cand = r.inf_ref = 0;
-    r.allclose = 0; r.bit_identical = 0; r.reserved_ = 0;
-    res[p] = r;
 }
 
 __device__ __forceinline__ void raise_max(double* slot, double v) {
@@ -183,11 +338,15 @@ __device__ __forceinline__ void raise_max(double* slot, double v) {
     if (bits > __atomic_load_n((unsigned long long*)slot, __ATOMIC_RELAXED)) atomicMax((unsigned long long*)slot, bits);
 }
 
+// One instantiation per (candidate dtype, reference dtype): the host orders the
+// pairs by dtype combination, so each instantiation owns a contiguous range of
+// blocks and is register-allocated for its own path only.
+template <int CD, int RD>
 __global__ void __launch_bounds__(kBlock) score_kernel(const pf::PairDev* pairs, const unsigned long long* block_start,
-                                                       int n_pairs, pf_score_result* slots) {
-    // which pair does this block belong to: largest p with block_start[p] <= blockIdx.x
+                                                       int n_pairs, pf_score_result* slots, unsigned long long block_offset) {
+    // which pair does this block belong to: largest p with block_start[p] <= bid
     int lo = 0, hi = n_pairs;
-    const unsigned long long bid = blockIdx.x;
+    const unsigned long long bid = block_offset + blockIdx.x;
     while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
         if (block_start[mid] <= bid) lo = mid; else hi = mid;
@@ -196,15 +355,14 @@ __global__ void __launch_bounds__(kBlock) score_kernel(const pf::PairDev* pairs,
     const unsigned long long begin = (bid - block_start[lo]) * kChunk;
     const unsigned long long end = begin + kChunk < pr.n ? begin + kChunk : pr.n;
     Acc acc;
-    const int key = pr.cand_dtype * 3 + pr.ref_dtype;
-    switch (key) {
-        case PF_F32 * 3 + PF_F32: score_chunk<PF_F32, PF_F32>(pr, begin, end, acc); break;
-        case PF_F32 * 3 + PF_BF16: score_chunk<PF_F32, PF_BF16>(pr, begin, end, acc); break;
-        case PF_F32 * 3 + PF_F64: score_chunk<PF_F32, PF_F64>(pr, begin, end, acc); break;
-        case PF_BF16 * 3 + PF_F32: score_chunk<PF_BF16, PF_F32>(pr, begin, end, acc); break;
-        case PF_BF16 * 3 + PF_BF16: score_chunk<PF_BF16, PF_BF16>(pr, begin, end, acc); break;
-        case PF_BF16 * 3 + PF_F64: score_chunk<PF_BF16, PF_F64>(pr, begin, end, acc); break;
-        default: break;
+    // maxima other blocks of this pair have already published: a head start for the screening thresholds
+    pf_score_result* my_slot = slots + (size_t)lo * kSlots + (bid - block_start[lo]) % kSlots;
+    if (RD == PF_F64) {
+        score_chunk<CD, RD>(pr, begin, end, acc);
+    } else {
+        const double seed_abs = __longlong_as_double((long long)__atomic_load_n((unsigned long long*)&my_slot->max_abs, __ATOMIC_RELAXED));
+        const double seed_rel = __longlong_as_double((long long)__atomic_load_n((unsigned long long*)&my_slot->max_rel, __ATOMIC_RELAXED));
+        score_chunk_fast<CD, RD>(pr, begin, end, acc, seed_abs, seed_rel);
     }
     acc.max_rel = fmax(acc.max_rel, __ddiv_rn(acc.keep_d, acc.keep_b));
     // block reduction: waves by shuffle, then LDS
@@ -232,7 +390,7 @@ __global__ void __launch_bounds__(kBlock) score_kernel(const pf::PairDev* pairs,
             for (int k = 0; k < 6; ++k) t[k] += s_cnt[w][k];
         }
         // one of kSlots partial results of this pair; the final kernel folds them
-        pf_score_result* r = slots + (size_t)lo * kSlots + (bid - block_start[lo]) % kSlots;
+        pf_score_result* r = my_slot;
         // errors are >= 0 and never NaN, so their bit patterns order like the values
         if (ma > 0.0) raise_max(&r->max_abs, ma);
         if (mr > 0.0) raise_max(&r->max_rel, mr);
@@ -245,23 +403,25 @@ __global__ void __launch_bounds__(kBlock) score_kernel(const pf::PairDev* pairs,
     }
 }
 
-__global__ void __launch_bounds__(kBlock) score_final_kernel(const pf::PairDev* pairs, int n_pairs, pf_score_result* res,
-                                                             const pf_score_result* slots) {
-    const int p = blockIdx.x * blockDim.x + threadIdx.x;
+// One wave per pair: lane k folds slot k (kSlots == 64), then a wave reduction.
+__global__ void __launch_bounds__(64) score_final_kernel(const pf::PairDev* pairs, int n_pairs, pf_score_result* res,
+                                                         const pf_score_result* slots) {
+    const int p = blockIdx.x;
     if (p >= n_pairs) return;
-    pf_score_result r = res[p];
-    for (int k = 0; k < kSlots; ++k) {
-        const pf_score_result& s = slots[(size_t)p * kSlots + k];
-        r.max_abs = fmax(r.max_abs, s.max_abs);
-        r.max_rel = fmax(r.max_rel, s.max_rel);
-        r.n_viol += s.n_viol;
-        r.reserved_ += s.reserved_;
-        r.nan_cand += s.nan_cand; r.nan_ref += s.nan_ref;
-        r.inf_cand += s.inf_cand; r.inf_ref += s.inf_ref;
+    const pf_score_result s = slots[(size_t)p * kSlots + threadIdx.x];
+    const double ma = wave_max(s.max_abs), mr = wave_max(s.max_rel);
+    const unsigned long long nv = wave_sum(s.n_viol), bd = wave_sum(s.reserved_);
+    const unsigned long long nc = wave_sum(s.nan_cand), nr = wave_sum(s.nan_ref);
+    const unsigned long long ic = wave_sum(s.inf_cand), ir = wave_sum(s.inf_ref);
+    if (threadIdx.x == 0) {
+        pf_score_result r;
+        r.n = pairs[p].n;
+        r.max_abs = ma; r.max_rel = mr; r.n_viol = nv; r.reserved_ = bd;
+        r.nan_cand = nc; r.nan_ref = nr; r.inf_cand = ic; r.inf_ref = ir;
+        r.allclose = nv == 0 ? 1u : 0u;
+        r.bit_identical = (pairs[p].cand_dtype == pairs[p].ref_dtype && bd == 0) ? 1u : 0u;
+        res[pairs[p].orig] = r;                       // pairs were ordered by dtype combination for the launch
     }
-    r.allclose = r.n_viol == 0 ? 1u : 0u;
-    r.bit_identical = (pairs[p].cand_dtype == pairs[p].ref_dtype && r.reserved_ == 0) ? 1u : 0u;
-    res[p] = r;
 }
 
 __global__ void __launch_bounds__(256) copy_kernel(u32x4* __restrict__ dst, const u32x4* __restrict__ src, unsigned long long n16) {
@@ -290,15 +450,22 @@ hipError_t launch_score_upload(const PairBatch& batch, PairDev* d_pairs, unsigne
     return hipGetLastError();
 }
 
-hipError_t launch_score(const PairDev* d_pairs, const unsigned long long* d_block_start, int n_pairs,
-                        unsigned long long total_blocks, pf_score_result* d_results, pf_score_result* d_slots, hipStream_t stream) {
-    const int nb = (n_pairs + kBlock - 1) / kBlock;
+hipError_t launch_score(const PairDev* d_pairs, const unsigned long long* d_block_start, int n_pairs, const ScoreRanges& ranges,
+                        pf_score_result* d_results, pf_score_result* d_slots, hipStream_t stream) {
     const int nbs = (n_pairs * kSlots + kBlock - 1) / kBlock;
-    hipLaunchKernelGGL(score_init_kernel, dim3(nbs), dim3(kBlock), 0, stream, d_pairs, n_pairs, d_results, d_slots);
-    if (total_blocks)
-        hipLaunchKernelGGL(score_kernel, dim3((unsigned)total_blocks), dim3(kBlock), 0, stream, d_pairs, d_block_start, n_pairs,
-                           d_slots);
-    hipLaunchKernelGGL(score_final_kernel, dim3(nb), dim3(kBlock), 0, stream, d_pairs, n_pairs, d_results, d_slots);
+    hipLaunchKernelGGL(score_init_kernel, dim3(nbs), dim3(kBlock), 0, stream, n_pairs, d_slots);
+#define PF_LAUNCH(CD, RD)                                                                                                  \
+    if (ranges.count[CD][RD])                                                                                              \
+        hipLaunchKernelGGL((score_kernel<CD, RD>), dim3((unsigned)ranges.count[CD][RD]), dim3(kBlock), 0, stream, d_pairs,   \
+                           d_block_start, n_pairs, d_slots, ranges.first[CD][RD]);
+    PF_LAUNCH(PF_F32, PF_F32)
+    PF_LAUNCH(PF_F32, PF_BF16)
+    PF_LAUNCH(PF_F32, PF_F64)
+    PF_LAUNCH(PF_BF16, PF_F32)
+    PF_LAUNCH(PF_BF16, PF_BF16)
+    PF_LAUNCH(PF_BF16, PF_F64)
+#undef PF_LAUNCH
+    hipLaunchKernelGGL(score_final_kernel, dim3(n_pairs), dim3(64), 0, stream, d_pairs, n_pairs, d_results, d_slots);
     return hipGetLastError();
 }
 

@@ -14,7 +14,13 @@ struct PairDev {
     int cand_dtype, ref_dtype;
     double rtol, atol;
     int equal_nan;
-    int pad_;
+    int orig;               // index of this pair in the caller's array
+};
+
+// blocks of each (candidate dtype, reference dtype) combination: a contiguous range
+struct ScoreRanges {
+    unsigned long long first[2][3];
+    unsigned long long count[2][3];
 };
 
 constexpr int kScoreSlots = 64;   // partial result slots per pair
@@ -29,8 +35,8 @@ struct PairBatch {
 
 unsigned long long score_chunk_elems();
 hipError_t launch_score_upload(const PairBatch& batch, PairDev* d_pairs, unsigned long long* d_block_start, hipStream_t stream);
-hipError_t launch_score(const PairDev* d_pairs, const unsigned long long* d_block_start, int n_pairs,
-                        unsigned long long total_blocks, pf_score_result* d_results, pf_score_result* d_slots, hipStream_t stream);
+hipError_t launch_score(const PairDev* d_pairs, const unsigned long long* d_block_start, int n_pairs, const ScoreRanges& ranges,
+                        pf_score_result* d_results, pf_score_result* d_slots, hipStream_t stream);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
 
 }  // namespace pf

@@ -127,3 +127,28 @@ def test_bad_arguments_are_refused():
     with pytest.raises(pf.PfError) as e:
         pf.score([p], ws.data_ptr(), ws.data_ptr(), 8)              # workspace too small
     assert e.value.status == pf.PF_E_RUNTIME
+
+
+@pytest.mark.parametrize("cd,rd", [("f32", "f32"), ("bf16", "bf16"), ("bf16", "f32"), ("f32", "bf16")])
+def test_elements_on_the_tolerance_boundary_and_extreme_magnitudes(cd, rd):
+    # the kernel screens in fp32 and must fall back to fp64 wherever fp32 cannot decide
+    r = np.random.default_rng(11)
+    n = 120000
+    store = {"f32": lambda x: x.astype(np.float32), "bf16": rng.round_to_bf16_bits}
+    widen = {"f32": lambda x: x.astype(np.float64), "bf16": lambda x: (x.astype(np.uint32) << 16).view(np.float32).astype(np.float64)}
+    specs, wants = [], []
+    for scale, rtol, atol in [(1.0, 1e-3, 1e-3), (1.0, 0.0, 1e-2), (1.0, 1e-2, 0.0), (1e-38, 1e-3, 1e-41), (1e-40, 1e-3, 0.0),
+                              (1e37, 1e-3, 1e30), (1.0, 0.0, 0.0), (1.0, 1e-35, 1e-35), (1e-20, 1e-6, 1e-26), (1.0, 1e6, 0.0)]:
+        b = store[rd](r.standard_normal(n) * scale)
+        b64 = widen[rd](b)
+        allowed = atol + rtol * np.abs(b64)
+        k = r.integers(-3, 4, n)
+        a64 = b64 + np.where(r.random(n) < 0.5, 1, -1) * allowed * (1.0 + k * 2.0 ** -24)
+        a64[::7] = b64[::7]                              # some exact matches
+        a = store[cd](a64)
+        specs.append((to_device(a, cd), cd, to_device(b, rd), rd, rtol, atol, False))
+        wants.append(oracle_score_dict(a, cd, b, rd, rtol, atol))
+    with np.errstate(all="ignore"):
+        got = score_on_gpu(specs)
+    for i, (g, w) in enumerate(zip(got, wants)):
+        assert g == w, (i, g, w)
