@@ -86,7 +86,7 @@ struct Emit {
     int node_kind(int id) const {
         const Node& n = g.nodes[id];
         if (is_reduction(n.op)) return 1;
-        if (grp.tmpl != PF_T_ROW_RESIDENT) return 2;
+        if (grp.tmpl != PF_T_ROW_RESIDENT && grp.tmpl != PF_T_ROW_LOOP) return 2;
         if (grp.cols == 1) return 2;
         // row-uniform iff every operand is
         for (int p : n.in) {
@@ -164,7 +164,10 @@ struct Emit {
         while (T < 1024 && (chunks + T - 1) / T > std::min<int64_t>(per_lane_max, 4)) T <<= 1;
         while ((chunks + T - 1) / T > per_lane_max && T < 1024) T <<= 1;
         int64_t K = (chunks + T - 1) / T;
-        if (K * vec > 64) fail(PF_E_COMPILE, "row of %lld elements does not fit on chip for the resident row template", (long long)C);
+        if (K * vec > 64) {          // the row does not fit in the registers of 1024 lanes: stream it
+            gen_loop(vec);
+            return;
+        }
         // few rows: spread each row over more lanes to cut latency
         while (K > 1 && T < 1024 && R * T < 256 * 256) {
             T <<= 1;
@@ -336,6 +339,166 @@ struct Emit {
                     line("    }");
                 }
             }
+        }
+        line("}");
+    }
+
+    // ================================================================ ROW_LOOP
+    // Rows too long to hold on chip.  One workgroup of T lanes walks its row in
+    // steps of T*VEC elements, once per "pass": pass p recomputes every value whose
+    // inputs are available by then and accumulates the reductions that read them,
+    // so a chain of k dependent reductions costs k+1 passes over the inputs (the
+    // repeats are served by L2 when the row fits there).  The paper's Case 1
+    // kernel has this same structure (mean pass, variance pass, write pass).
+    void gen_loop(int vec) {
+        grp.tmpl = PF_T_ROW_LOOP;
+        const int64_t C = grp.cols, R = grp.rows;
+        const int T = 1024;
+        const int nlead = rd > 0 ? rd - 1 : 0;
+        RU = 1;
+        NN = vec;
+        hoisted.clear();
+        grp.block = T;
+        grp.grid = R;
+        grp.lanes_per_row = T;
+        grp.vec = vec;
+        grp.chunks_per_lane = (int)((C / vec + T - 1) / T);
+        const char* acc = precise ? "double" : "float";
+        // stage of every value: the first pass in which it can be computed
+        std::map<int, int> stage, rpass;     // node -> stage; reduction -> pass in which it accumulates
+        auto avail = [&](int p) -> int {
+            const Node& n = g.nodes[p];
+            if (n.op == PF_OP_CONST || !in_kernel(p)) return 0;
+            if (is_reduction(n.op)) return rpass.at(p) + (n.op == PF_OP_VAR ? 2 : 1);
+            return stage.at(p);
+        };
+        int last_pass = 0;
+        for (int id : grp.nodes) {
+            const Node& n = g.nodes[id];
+            int st = 0;
+            for (int p : n.in) st = std::max(st, avail(p));
+            if (is_reduction(n.op)) {
+                rpass[id] = st;
+                last_pass = std::max(last_pass, st + (n.op == PF_OP_VAR ? 1 : 0));
+            } else {
+                stage[id] = st;
+            }
+        }
+        for (auto& st : grp.stores)
+            if (!st.row_scalar) last_pass = std::max(last_pass, stage.at(st.node));
+        int n_red = 0;
+        for (int id : grp.nodes)
+            if (is_reduction(g.nodes[id].op)) n_red += g.nodes[id].op == PF_OP_VAR ? 2 : 1;
+
+        signature();
+        line(strf("    constexpr int T = %d, VEC = %d;", T, vec));
+        line(strf("    constexpr %s C = %lld, CHUNKS = %lld;", idx_t(), (long long)C, (long long)(C / vec)));
+        line(strf("    __shared__ %s red_lds[%d][%d];", acc, std::max(n_red, 1), T / 64));
+        if (precise) line(strf("    __shared__ float redf_lds[%d][%d];", std::max(n_red, 1), T / 64));
+        line("    const int lane = threadIdx.x;");
+        line(strf("    %s row[1]; row[0] = blockIdx.x;", idx_t()));
+        line("    constexpr int u = 0;");
+        emit_lead_decomposition("row[0]", nlead);
+        // row-uniform operands are loaded once
+        for (size_t oi = 0; oi < grp.operands.size(); ++oi) {
+            if (operand_kind((int)oi) != 1) continue;
+            const Operand& o = grp.operands[oi];
+            std::string base = lead_zero(o, nlead) ? strf("(%s)0", idx_t())
+                               : lead_mergeable(o, nlead) ? strf("row[0] * %lld", (long long)o.stride[nlead - 1])
+                                                          : lead_offset(o, "row[0]");
+            line(strf("    float x%zu[1]; x%zu[0] = pf_ld1(p%zu + %s);", oi, oi, oi, base.c_str()));
+        }
+        auto emit_uniform_nodes = [&](int st) {
+            for (int id : grp.nodes) {
+                const Node& n = g.nodes[id];
+                if (is_reduction(n.op) || kind.at(id) != 1 || stage.at(id) != st) continue;
+                emit_elementwise(id, vec);
+            }
+        };
+        emit_uniform_nodes(0);
+        int red_slot = 0;
+        std::map<int, int> slot_of;
+        for (int id : grp.nodes)
+            if (is_reduction(g.nodes[id].op)) {
+                slot_of[id] = red_slot;
+                red_slot += g.nodes[id].op == PF_OP_VAR ? 2 : 1;
+            }
+        for (int pass = 0; pass <= last_pass; ++pass) {
+            // accumulators of this pass
+            for (int id : grp.nodes) {
+                const Node& n = g.nodes[id];
+                if (!is_reduction(n.op)) continue;
+                if (rpass.at(id) == pass) {
+                    if (n.op == PF_OP_MAX) line(strf("    float m%d = -__builtin_inff(); bool nan%d = false;", id, id));
+                    else line(strf("    %s a%d = 0;", acc, id));
+                }
+                if (n.op == PF_OP_VAR && rpass.at(id) + 1 == pass) line(strf("    %s q%d = 0;", acc, id));
+            }
+            line(strf("    for (%s k = lane; k < CHUNKS; k += T) {   // pass %d", idx_t(), pass));
+            line(strf("        const %s c0 = k * VEC;", idx_t()));
+            for (size_t oi = 0; oi < grp.operands.size(); ++oi) {
+                if (operand_kind((int)oi) != 2) continue;
+                const Operand& o = grp.operands[oi];
+                std::string base = lead_zero(o, nlead) ? strf("(%s)0", idx_t())
+                                   : lead_mergeable(o, nlead) ? strf("row[0] * %lld", (long long)o.stride[nlead - 1])
+                                                              : lead_offset(o, "row[0]");
+                line(strf("        float x%zu[VEC]; pf_ld<VEC, false>(p%zu + %s + c0, x%zu);", oi, oi, base.c_str(), oi));
+            }
+            for (int id : grp.nodes) {
+                const Node& n = g.nodes[id];
+                if (is_reduction(n.op)) {
+                    std::string xj = ref(id, n.in[0], "j");
+                    if (rpass.at(id) == pass) {
+                        if (n.op == PF_OP_MAX)
+                            line(strf("        _Pragma(\"unroll\") for (int j = 0; j < VEC; ++j) { const float t = %s; m%d = fmaxf(m%d, t); nan%d |= (t != t); }",
+                                      xj.c_str(), id, id, id));
+                        else
+                            line(strf("        _Pragma(\"unroll\") for (int j = 0; j < VEC; ++j) a%d += (%s)(%s);", id, acc, xj.c_str()));
+                    }
+                    if (n.op == PF_OP_VAR && rpass.at(id) + 1 == pass)
+                        line(strf("        _Pragma(\"unroll\") for (int j = 0; j < VEC; ++j) { const %s d = (%s)(%s) - a%d; q%d += d * d; }", acc, acc,
+                                  xj.c_str(), id, id));
+                    continue;
+                }
+                if (kind.at(id) == 2 && stage.at(id) <= pass) emit_elementwise(id, vec);
+            }
+            int sp = 0;
+            for (auto& st : grp.stores) {
+                const int cnt = 1 + (int)st.also_outputs.size();
+                if (!st.row_scalar && stage.at(st.node) == pass)
+                    for (int c = 0; c < cnt; ++c)
+                        line(strf("        pf_st<VEC, false>(q%d + row[0] * C + c0, v%d);", sp + c, st.node));
+                sp += cnt;
+            }
+            line("    }");
+            // finish the reductions of this pass
+            for (int id : grp.nodes) {
+                const Node& n = g.nodes[id];
+                if (!is_reduction(n.op)) continue;
+                const int sl = slot_of.at(id);
+                if (rpass.at(id) == pass) {
+                    if (n.op == PF_OP_MAX) {
+                        line(strf("    float s%d[1]; s%d[0] = pf_team_max<T>(nan%d ? __builtin_nanf(\"\") : m%d, %s[%d]);", id, id, id, id,
+                                  precise ? "redf_lds" : "red_lds", sl));
+                    } else {
+                        line(strf("    a%d = pf_team_sum<T, %s>(a%d, red_lds[%d]);", id, acc, id, sl));
+                        if (n.op == PF_OP_SUM) line(strf("    float s%d[1]; s%d[0] = (float)a%d;", id, id, id));
+                        else if (n.op == PF_OP_MEAN) line(strf("    float s%d[1]; s%d[0] = (float)(a%d / (%s)%lld);", id, id, id, acc, (long long)C));
+                        else line(strf("    a%d = a%d / (%s)%lld;", id, id, acc, (long long)C));
+                    }
+                }
+                if (n.op == PF_OP_VAR && rpass.at(id) + 1 == pass)
+                    line(strf("    float s%d[1]; s%d[0] = (float)(pf_team_sum<T, %s>(q%d, red_lds[%d]) / (%s)%lld);", id, id, acc, id, sl + 1, acc,
+                              (long long)(C - n.correction)));
+            }
+            emit_uniform_nodes(pass + 1);
+        }
+        int sp = 0;
+        for (auto& st : grp.stores) {
+            const int cnt = 1 + (int)st.also_outputs.size();
+            if (st.row_scalar)
+                for (int c = 0; c < cnt; ++c) line(strf("    if (lane == 0) pf_st1(q%d + row[0], s%d[0]);", sp + c, st.node));
+            sp += cnt;
         }
         line("}");
     }

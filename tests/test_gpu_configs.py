@@ -169,3 +169,38 @@ def test_cfg1_full_size_is_one_kernel_and_repeatable():
     b = r.run()[0]
     torch.cuda.synchronize()
     assert torch.equal(a, b)
+
+
+# ------------------------------------------------------------- rows too long to stay on chip
+def _softmax_workload(rows, cols, dtype, seed=31):
+    from workloads import rng as wrng
+    g = Builder()
+    x = g.input(dtype, (rows, cols))
+    m = g.op("max", [x], dtype)
+    e = g.op("exp", [g.op("sub", [x, m], dtype)], dtype)
+    s = g.op("sum", [e], dtype)
+    g.output(g.op("div", [e, s], dtype))
+    g.output(s)
+    xs = wrng.normal_stored(seed, 0, rows * cols, dtype).reshape(rows, cols)
+    return configs.Workload("softmax_%s_%dx%d" % (dtype, rows, cols), g.text(), [xs], [dtype], [(rows, cols)],
+                            [dtype, dtype], [(rows, cols), (rows, 1)]).finish()
+
+
+@pytest.mark.parametrize("rows,cols,dtype", [(3, 70000, "f32"), (2, 100003, "bf16"), (5, 65540, "f32"), (2, 262144, "bf16")])
+def test_long_rows_use_the_streaming_row_template(rows, cols, dtype):
+    w = _softmax_workload(rows, cols, dtype)
+    r, _ = _run_and_check(w)
+    assert [gi["template"] for gi in r.exe.groups()] == ["row_loop"]
+
+
+@pytest.mark.parametrize("use_var_op", [False, True])
+def test_long_row_layernorm(use_var_op):
+    w = configs.cfg1_add_layernorm(rows=3, cols=70000, use_var_op=use_var_op)
+    r, _ = _run_and_check(w)
+    assert r.exe.group_info(0)["template"] == "row_loop"
+
+
+def test_long_row_max_propagates_nan():
+    w = _softmax_workload(2, 70000, "f32")
+    w.inputs[0][1, 12345] = np.nan
+    _run_and_check(w)
