@@ -214,6 +214,49 @@ size_t pf_score_workspace_bytes(int n_pairs);
 pf_status pf_score(const pf_pair* h_pairs, int n_pairs, pf_score_result* d_results,
                    void* d_workspace, size_t workspace_bytes, void* stream);
 
+/* ---- tolerance ladder and error-aware speedup scores (Sec. 3.4, App. D-F) ---- */
+
+#define PF_LADDER_LEVELS 11   /* tolerance indices t = -10 .. 0 */
+#define PF_ES_LEVELS 15       /* t = -10 .. 4 (|E| = 3 error categories, t up to |E|+1) */
+
+/* rtol(t), atol(t) = 10^(k t) with the per-dtype slopes of Appendix F (bf16, f32, f64);
+ * t > 0 gives the values of t = 0. */
+pf_status pf_tolerance(pf_dtype dtype, int t, double* h_rtol, double* h_atol);
+
+typedef struct {
+    uint64_t n;
+    uint64_t n_viol[PF_LADDER_LEVELS];   /* [k]: elements failing at t = k - 10, tolerances of the candidate's dtype */
+} pf_ladder_result;
+
+/* As pf_score, but counts the violations at all 11 numerical tolerance levels
+ * in one pass over the data.  The rtol / atol fields of the pairs are ignored;
+ * equal_nan is honoured. */
+size_t    pf_score_ladder_workspace_bytes(int n_pairs);
+pf_status pf_score_ladder(const pf_pair* h_pairs, int n_pairs, pf_ladder_result* d_results,
+                          void* d_workspace, size_t workspace_bytes, void* stream);
+
+/* One evaluated subgraph: measured speedup over the reference execution, how it
+ * failed if it did (0: ran; 2: compilation, 3: runtime failure; an accuracy
+ * failure, class 1, follows from the counts) and the ladder counts summed over
+ * its outputs. */
+typedef struct {
+    double   speedup;
+    int32_t  error_class;
+    int32_t  reserved;
+    uint64_t n_viol[PF_LADDER_LEVELS];
+} pf_case;
+
+typedef struct {
+    double es[PF_ES_LEVELS];   /* ES_t, Eq. 3, [k]: t = k - 10 */
+    double as;                 /* AS, Eq. 4 */
+} pf_metrics;
+
+/* Host-side aggregation: rectified speedups (Eq. 2, base penalty b, slowdown
+ * exponent p), their geometric mean per t and the weighted geometric mean AS. */
+pf_status pf_aggregate(const pf_case* h_cases, int n_cases, double b, double p, pf_metrics* h_out);
+/* Fraction of all cases that are correct at tolerance index t and faster than threshold. */
+pf_status pf_fast_p(const pf_case* h_cases, int n_cases, double threshold, int t, double* h_out);
+
 /* ---- misc ---- */
 
 /* Plain device copy of `bytes` bytes (multiple of 16) with the library's

@@ -67,6 +67,22 @@ class ScoreResult(C.Structure):
         return {k: getattr(self, k) for k, _ in self._fields_ if k != "reserved_"}
 
 
+LADDER_LEVELS, ES_LEVELS = 11, 15
+
+
+class LadderResult(C.Structure):
+    _fields_ = [("n", C.c_uint64), ("n_viol", C.c_uint64 * LADDER_LEVELS)]
+
+
+class Case(C.Structure):
+    _fields_ = [("speedup", C.c_double), ("error_class", C.c_int32), ("reserved", C.c_int32),
+                ("n_viol", C.c_uint64 * LADDER_LEVELS)]
+
+
+class Metrics(C.Structure):
+    _fields_ = [("es", C.c_double * ES_LEVELS), ("as_", C.c_double)]
+
+
 _lib_handle = None
 
 
@@ -102,6 +118,10 @@ def lib():
         "pf_execute_timed": [vp, C.POINTER(vp), C.c_int, C.POINTER(vp), C.c_int, vp, sz, vp, vp, vp],
         "pf_score": [C.POINTER(Pair), C.c_int, vp, vp, sz, vp],
         "pf_copy_bytes": [vp, vp, sz, vp],
+        "pf_score_ladder": [C.POINTER(Pair), C.c_int, vp, vp, sz, vp],
+        "pf_tolerance": [C.c_int, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)],
+        "pf_aggregate": [C.POINTER(Case), C.c_int, C.c_double, C.c_double, C.POINTER(Metrics)],
+        "pf_fast_p": [C.POINTER(Case), C.c_int, C.c_double, C.c_int, C.POINTER(C.c_double)],
     }
     for name, args in sigs.items():
         fn = getattr(L, name)
@@ -115,6 +135,8 @@ def lib():
     L.pf_options_default.restype = None
     L.pf_score_workspace_bytes.argtypes = [C.c_int]
     L.pf_score_workspace_bytes.restype = sz
+    L.pf_score_ladder_workspace_bytes.argtypes = [C.c_int]
+    L.pf_score_ladder_workspace_bytes.restype = sz
     L.pf_last_error.restype = C.c_char_p
     L.pf_version.restype = C.c_char_p
     _lib_handle = L
@@ -255,3 +277,44 @@ def score(pairs, results_ptr, workspace_ptr, workspace_bytes, stream=0):
 
 def copy_bytes(dst_ptr, src_ptr, nbytes, stream=0):
     _check(lib().pf_copy_bytes(C.c_void_p(dst_ptr), C.c_void_p(src_ptr), nbytes, C.c_void_p(stream)))
+
+
+def tolerance(dtype, t):
+    """(rtol, atol) of tolerance index t for a dtype name."""
+    r, a = C.c_double(), C.c_double()
+    _check(lib().pf_tolerance(DTYPES[dtype], t, C.byref(r), C.byref(a)))
+    return r.value, a.value
+
+
+def score_ladder_workspace_bytes(n_pairs):
+    return lib().pf_score_ladder_workspace_bytes(n_pairs)
+
+
+def score_ladder(pairs, results_ptr, workspace_ptr, workspace_bytes, stream=0):
+    """results_ptr: device pointer to len(pairs) LadderResult structs."""
+    arr = (Pair * max(len(pairs), 1))(*pairs)
+    _check(lib().pf_score_ladder(arr, len(pairs), C.c_void_p(results_ptr), C.c_void_p(workspace_ptr), workspace_bytes,
+                                 C.c_void_p(stream)))
+
+
+def _cases(cases):
+    arr = (Case * max(len(cases), 1))()
+    for i, c in enumerate(cases):
+        arr[i].speedup = c["speedup"]
+        arr[i].error_class = c["error_class"]
+        for k, v in enumerate(c["viol"]):
+            arr[i].n_viol[k] = v
+    return arr
+
+
+def aggregate(cases, b=0.1, p=0.0):
+    """cases: dicts(speedup, error_class, viol[11]).  Returns (ES_t for t=-10..4, AS)."""
+    m = Metrics()
+    _check(lib().pf_aggregate(_cases(cases), len(cases), b, p, C.byref(m)))
+    return list(m.es), m.as_
+
+
+def fast_p(cases, threshold, t=0):
+    out = C.c_double()
+    _check(lib().pf_fast_p(_cases(cases), len(cases), threshold, t, C.byref(out)))
+    return out.value

@@ -9,6 +9,7 @@
 
 #include "exec.h"
 #include "pf_internal.h"
+#include "metric.h"
 #include "score_dev.h"
 
 namespace {
@@ -275,78 +276,150 @@ pf_status pf_execute_timed(pf_exec* e, const void* const* d_inputs, int n_in, vo
     });
 }
 
-size_t pf_score_workspace_bytes(int n_pairs) {
-    if (n_pairs < 0) n_pairs = 0;
-    size_t b = (size_t)n_pairs * sizeof(pf::PairDev);
-    b = (b + 255) / 256 * 256;
-    b += ((size_t)n_pairs + 1) * sizeof(unsigned long long);
-    b = (b + 255) / 256 * 256;
-    return b + (size_t)n_pairs * pf::kScoreSlots * sizeof(pf_score_result);
+}  // extern "C"
+
+namespace {
+
+// Validates the pairs, orders them by dtype combination (each combination then
+// owns a contiguous block range) and uploads descriptors + block prefix into the
+// head of the workspace.  Returns where the per-pair scratch after them begins.
+struct StagedPairs {
+    pf::PairDev* d_pairs;
+    unsigned long long* d_start;
+    char* d_rest;
+    pf::ScoreRanges ranges;
+};
+
+size_t staged_head_bytes(int n_pairs) {
+    size_t b = ((size_t)n_pairs * sizeof(pf::PairDev) + 255) / 256 * 256;
+    return b + (((size_t)n_pairs + 1) * sizeof(unsigned long long) + 255) / 256 * 256;
 }
+
+StagedPairs stage_pairs(const pf_pair* h_pairs, int n_pairs, void* d_workspace, void* stream) {
+    StagedPairs sp;
+    const size_t pairs_bytes = ((size_t)n_pairs * sizeof(pf::PairDev) + 255) / 256 * 256;
+    sp.d_pairs = (pf::PairDev*)d_workspace;
+    sp.d_start = (unsigned long long*)((char*)d_workspace + pairs_bytes);
+    sp.d_rest = (char*)d_workspace + staged_head_bytes(n_pairs);
+    const unsigned long long chunk = pf::score_chunk_elems();
+    for (int i = 0; i < n_pairs; ++i) {
+        const pf_pair& p = h_pairs[i];
+        if (p.cand_dtype != PF_F32 && p.cand_dtype != PF_BF16) pf::fail(PF_E_INVALID, "pair %d: candidate dtype must be f32 or bf16", i);
+        if (p.ref_dtype != PF_F32 && p.ref_dtype != PF_BF16 && p.ref_dtype != PF_F64) pf::fail(PF_E_INVALID, "pair %d: bad reference dtype", i);
+        if (p.n && (!p.d_cand || !p.d_ref)) pf::fail(PF_E_INVALID, "pair %d: NULL buffer", i);
+        if (((uintptr_t)p.d_cand | (uintptr_t)p.d_ref) & 15) pf::fail(PF_E_INVALID, "pair %d: buffers must be 16-byte aligned", i);
+        if (!(p.rtol >= 0.0) || !(p.atol >= 0.0)) pf::fail(PF_E_INVALID, "pair %d: tolerances must be >= 0", i);
+    }
+    std::vector<int> order(n_pairs);
+    for (int i = 0; i < n_pairs; ++i) order[i] = i;
+    auto combo = [&](int i) { return h_pairs[i].cand_dtype * 3 + h_pairs[i].ref_dtype; };
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return combo(a) < combo(b); });
+    memset(&sp.ranges, 0, sizeof sp.ranges);
+    unsigned long long total = 0;
+    for (int first = 0; first < n_pairs; first += pf::kPairBatch) {
+        pf::PairBatch b;
+        memset(&b, 0, sizeof b);
+        b.first = first;
+        b.count = n_pairs - first < pf::kPairBatch ? n_pairs - first : pf::kPairBatch;
+        b.last = first + b.count == n_pairs;
+        for (int k = 0; k < b.count; ++k) {
+            const pf_pair& p = h_pairs[order[first + k]];
+            b.pairs[k].cand = p.d_cand;
+            b.pairs[k].ref = p.d_ref;
+            b.pairs[k].n = p.n;
+            b.pairs[k].cand_dtype = p.cand_dtype;
+            b.pairs[k].ref_dtype = p.ref_dtype;
+            b.pairs[k].rtol = p.rtol;
+            b.pairs[k].atol = p.atol;
+            b.pairs[k].equal_nan = p.equal_nan;
+            b.pairs[k].orig = order[first + k];
+            b.start[k] = total;
+            const unsigned long long nb = (p.n + chunk - 1) / chunk;
+            if (sp.ranges.count[p.cand_dtype][p.ref_dtype] == 0) sp.ranges.first[p.cand_dtype][p.ref_dtype] = total;
+            sp.ranges.count[p.cand_dtype][p.ref_dtype] += nb;
+            total += nb;
+        }
+        b.start[b.count] = total;
+        if (total >= (1ull << 31)) pf::fail(PF_E_INVALID, "too many elements for one scoring call");
+        hipError_t err = pf::launch_score_upload(b, sp.d_pairs, sp.d_start, (hipStream_t)stream);
+        if (err != hipSuccess) pf::fail(PF_E_RUNTIME, "descriptor upload failed: %s", hipGetErrorString(err));
+    }
+    return sp;
+}
+
+void check_score_args(const void* h_pairs, int n_pairs, const void* d_results, void* d_workspace, size_t have, size_t want) {
+    if (n_pairs < 0) pf::fail(PF_E_INVALID, "n_pairs < 0");
+    need(h_pairs, "h_pairs");
+    need(d_results, "d_results");
+    need(d_workspace, "d_workspace");
+    if (have < want) pf::fail(PF_E_RUNTIME, "score workspace too small (%zu < %zu bytes)", have, want);
+    if ((uintptr_t)d_workspace & 255) pf::fail(PF_E_INVALID, "workspace is not 256-byte aligned");
+}
+
+}  // namespace
+
+extern "C" {
 
 pf_status pf_score(const pf_pair* h_pairs, int n_pairs, pf_score_result* d_results, void* d_workspace, size_t workspace_bytes,
                    void* stream) {
     return guarded([&] {
-        if (n_pairs < 0) pf::fail(PF_E_INVALID, "n_pairs < 0");
         if (n_pairs == 0) return;
-        need(h_pairs, "h_pairs");
-        need(d_results, "d_results");
-        need(d_workspace, "d_workspace");
-        if (workspace_bytes < pf_score_workspace_bytes(n_pairs)) pf::fail(PF_E_RUNTIME, "score workspace too small");
-        if ((uintptr_t)d_workspace & 255) pf::fail(PF_E_INVALID, "workspace is not 256-byte aligned");
-        const size_t pairs_bytes = ((size_t)n_pairs * sizeof(pf::PairDev) + 255) / 256 * 256;
-        pf::PairDev* d_pairs = (pf::PairDev*)d_workspace;
-        unsigned long long* d_start = (unsigned long long*)((char*)d_workspace + pairs_bytes);
-        const size_t start_bytes = (((size_t)n_pairs + 1) * sizeof(unsigned long long) + 255) / 256 * 256;
-        pf_score_result* d_slots = (pf_score_result*)((char*)d_workspace + pairs_bytes + start_bytes);
-        const unsigned long long chunk = pf::score_chunk_elems();
-        for (int i = 0; i < n_pairs; ++i) {
-            const pf_pair& p = h_pairs[i];
-            if (p.cand_dtype != PF_F32 && p.cand_dtype != PF_BF16) pf::fail(PF_E_INVALID, "pair %d: candidate dtype must be f32 or bf16", i);
-            if (p.ref_dtype != PF_F32 && p.ref_dtype != PF_BF16 && p.ref_dtype != PF_F64) pf::fail(PF_E_INVALID, "pair %d: bad reference dtype", i);
-            if (p.n && (!p.d_cand || !p.d_ref)) pf::fail(PF_E_INVALID, "pair %d: NULL buffer", i);
-            if (((uintptr_t)p.d_cand | (uintptr_t)p.d_ref) & 15) pf::fail(PF_E_INVALID, "pair %d: buffers must be 16-byte aligned", i);
-            if (!(p.rtol >= 0.0) || !(p.atol >= 0.0)) pf::fail(PF_E_INVALID, "pair %d: tolerances must be >= 0", i);
-        }
-        // order the pairs by dtype combination: each combination then owns a contiguous block range
-        std::vector<int> order(n_pairs);
-        for (int i = 0; i < n_pairs; ++i) order[i] = i;
-        auto combo = [&](int i) { return h_pairs[i].cand_dtype * 3 + h_pairs[i].ref_dtype; };
-        std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return combo(a) < combo(b); });
-        pf::ScoreRanges ranges;
-        memset(&ranges, 0, sizeof ranges);
-        unsigned long long total = 0;
-        hipError_t err = hipSuccess;
-        for (int first = 0; first < n_pairs; first += pf::kPairBatch) {
-            pf::PairBatch b;
-            memset(&b, 0, sizeof b);
-            b.first = first;
-            b.count = n_pairs - first < pf::kPairBatch ? n_pairs - first : pf::kPairBatch;
-            b.last = first + b.count == n_pairs;
-            for (int k = 0; k < b.count; ++k) {
-                const pf_pair& p = h_pairs[order[first + k]];
-                b.pairs[k].cand = p.d_cand;
-                b.pairs[k].ref = p.d_ref;
-                b.pairs[k].n = p.n;
-                b.pairs[k].cand_dtype = p.cand_dtype;
-                b.pairs[k].ref_dtype = p.ref_dtype;
-                b.pairs[k].rtol = p.rtol;
-                b.pairs[k].atol = p.atol;
-                b.pairs[k].equal_nan = p.equal_nan;
-                b.pairs[k].orig = order[first + k];
-                b.start[k] = total;
-                const unsigned long long nb = (p.n + chunk - 1) / chunk;
-                if (ranges.count[p.cand_dtype][p.ref_dtype] == 0) ranges.first[p.cand_dtype][p.ref_dtype] = total;
-                ranges.count[p.cand_dtype][p.ref_dtype] += nb;
-                total += nb;
-            }
-            b.start[b.count] = total;
-            if (total >= (1ull << 31)) pf::fail(PF_E_INVALID, "too many elements for one scoring call");
-            err = pf::launch_score_upload(b, d_pairs, d_start, (hipStream_t)stream);
-            if (err != hipSuccess) pf::fail(PF_E_RUNTIME, "descriptor upload failed: %s", hipGetErrorString(err));
-        }
-        err = pf::launch_score(d_pairs, d_start, n_pairs, ranges, d_results, d_slots, (hipStream_t)stream);
+        check_score_args(h_pairs, n_pairs, d_results, d_workspace, workspace_bytes, pf_score_workspace_bytes(n_pairs));
+        StagedPairs sp = stage_pairs(h_pairs, n_pairs, d_workspace, stream);
+        hipError_t err = pf::launch_score(sp.d_pairs, sp.d_start, n_pairs, sp.ranges, d_results, (pf_score_result*)sp.d_rest,
+                                          (hipStream_t)stream);
         if (err != hipSuccess) pf::fail(PF_E_RUNTIME, "score launch failed: %s", hipGetErrorString(err));
+    });
+}
+
+size_t pf_score_workspace_bytes(int n_pairs) {
+    if (n_pairs < 0) n_pairs = 0;
+    return staged_head_bytes(n_pairs) + (size_t)n_pairs * pf::kScoreSlots * sizeof(pf_score_result);
+}
+
+size_t pf_score_ladder_workspace_bytes(int n_pairs) {
+    if (n_pairs < 0) n_pairs = 0;
+    return staged_head_bytes(n_pairs) + (size_t)n_pairs * pf::kScoreSlots * sizeof(pf_ladder_result);
+}
+
+pf_status pf_score_ladder(const pf_pair* h_pairs, int n_pairs, pf_ladder_result* d_results, void* d_workspace,
+                          size_t workspace_bytes, void* stream) {
+    return guarded([&] {
+        if (n_pairs == 0) return;
+        check_score_args(h_pairs, n_pairs, d_results, d_workspace, workspace_bytes, pf_score_ladder_workspace_bytes(n_pairs));
+        StagedPairs sp = stage_pairs(h_pairs, n_pairs, d_workspace, stream);
+        pf::LadderTable table;
+        for (int dt = 0; dt < 2; ++dt)
+            for (int k = 0; k < PF_LADDER_LEVELS; ++k) pf::tolerance_at((pf_dtype)dt, k - (PF_LADDER_LEVELS - 1), &table.rtol[dt][k], &table.atol[dt][k]);
+        hipError_t err = pf::launch_ladder(sp.d_pairs, sp.d_start, n_pairs, sp.ranges, table, d_results, (pf_ladder_result*)sp.d_rest,
+                                           (hipStream_t)stream);
+        if (err != hipSuccess) pf::fail(PF_E_RUNTIME, "ladder launch failed: %s", hipGetErrorString(err));
+    });
+}
+
+pf_status pf_tolerance(pf_dtype dtype, int t, double* h_rtol, double* h_atol) {
+    return guarded([&] {
+        need(h_rtol, "h_rtol");
+        need(h_atol, "h_atol");
+        pf::tolerance_at(dtype, t, h_rtol, h_atol);
+    });
+}
+
+pf_status pf_aggregate(const pf_case* h_cases, int n_cases, double b, double p, pf_metrics* h_out) {
+    return guarded([&] {
+        need(h_cases, "h_cases");
+        need(h_out, "h_out");
+        if (n_cases <= 0) pf::fail(PF_E_INVALID, "need at least one case");
+        pf::aggregate(h_cases, n_cases, b, p, h_out);
+    });
+}
+
+pf_status pf_fast_p(const pf_case* h_cases, int n_cases, double threshold, int t, double* h_out) {
+    return guarded([&] {
+        need(h_cases, "h_cases");
+        need(h_out, "h_out");
+        if (n_cases <= 0) pf::fail(PF_E_INVALID, "need at least one case");
+        *h_out = pf::fast_p(h_cases, n_cases, threshold, t);
     });
 }
 

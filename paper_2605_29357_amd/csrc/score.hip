@@ -424,6 +424,96 @@ __global__ void __launch_bounds__(64) score_final_kernel(const pf::PairDev* pair
     }
 }
 
+// ---- tolerance ladder: violations at all 11 levels in one pass ----------------
+// An element passes level k when a == b or |a-b| is finite and <= atol_k + rtol_k |b|
+// (fp64, same arithmetic as the single-level scorer).  Both tolerances grow with
+// k, so the levels an element fails form a prefix; each level is nevertheless
+// tested on its own, which keeps the kernel free of any assumption on rounding.
+__global__ void __launch_bounds__(kBlock) ladder_init_kernel(int n_pairs, pf_ladder_result* slots) {
+    const int p = blockIdx.x * blockDim.x + threadIdx.x;
+    if (p < n_pairs * kSlots) {
+        pf_ladder_result z;
+        z.n = 0;
+#pragma unroll
+        for (int k = 0; k < PF_LADDER_LEVELS; ++k) z.n_viol[k] = 0;
+        slots[p] = z;
+    }
+}
+
+template <int CD, int RD>
+__device__ __forceinline__ void ladder_one(typename Elem<CD>::raw ra, typename Elem<RD>::raw rb, int equal_nan, const double* rt,
+                                           const double* at, unsigned int* cnt) {
+    const double a = Elem<CD>::widen(ra), b = Elem<RD>::widen(rb);
+    const bool na = a != a, nb = b != b;
+    if (na | nb) {
+        const unsigned int v = !(equal_nan && na && nb);
+#pragma unroll
+        for (int k = 0; k < PF_LADDER_LEVELS; ++k) cnt[k] += v;
+        return;
+    }
+    if (a == b) return;
+    const double d = fabs(__dsub_rn(a, b)), ab = fabs(b);
+    const bool fin = d != __builtin_inf();
+#pragma unroll
+    for (int k = 0; k < PF_LADDER_LEVELS; ++k) cnt[k] += !(fin & (d <= __dadd_rn(at[k], __dmul_rn(rt[k], ab))));
+}
+
+template <int CD, int RD>
+__global__ void __launch_bounds__(kBlock) ladder_kernel(const pf::PairDev* pairs, const unsigned long long* block_start, int n_pairs,
+                                                        pf::LadderTable table, pf_ladder_result* slots, unsigned long long block_offset) {
+    int lo = 0, hi = n_pairs;
+    const unsigned long long bid = block_offset + blockIdx.x;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (block_start[mid] <= bid) lo = mid; else hi = mid;
+    }
+    const pf::PairDev pr = pairs[lo];
+    const unsigned long long begin = (bid - block_start[lo]) * kChunk;
+    const unsigned long long end = begin + kChunk < pr.n ? begin + kChunk : pr.n;
+    const double* rt = table.rtol[CD];
+    const double* at = table.atol[CD];
+    unsigned int cnt[PF_LADDER_LEVELS];
+#pragma unroll
+    for (int k = 0; k < PF_LADDER_LEVELS; ++k) cnt[k] = 0;
+    const unsigned long long nvec = (end - begin) / 8;
+    for (unsigned long long v = threadIdx.x; v < nvec; v += kBlock) {
+        typename Elem<CD>::raw ra[8];
+        typename Elem<RD>::raw rb[8];
+        Elem<CD>::load8(pr.cand, begin + v * 8, ra);
+        Elem<RD>::load8(pr.ref, begin + v * 8, rb);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) ladder_one<CD, RD>(ra[j], rb[j], pr.equal_nan, rt, at, cnt);
+    }
+    for (unsigned long long i = begin + nvec * 8 + threadIdx.x; i < end; i += kBlock)
+        ladder_one<CD, RD>(Elem<CD>::load1(pr.cand, i), Elem<RD>::load1(pr.ref, i), pr.equal_nan, rt, at, cnt);
+    __shared__ unsigned long long s_cnt[kBlock / 64][PF_LADDER_LEVELS];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+#pragma unroll
+    for (int k = 0; k < PF_LADDER_LEVELS; ++k) {
+        const unsigned long long w = wave_sum((unsigned long long)cnt[k]);
+        if (lane == 0) s_cnt[wave][k] = w;
+    }
+    __syncthreads();
+    if (threadIdx.x < PF_LADDER_LEVELS) {
+        unsigned long long t = 0;
+        for (int w = 0; w < kBlock / 64; ++w) t += s_cnt[w][threadIdx.x];
+        pf_ladder_result* r = slots + (size_t)lo * kSlots + (bid - block_start[lo]) % kSlots;
+        if (t) atomicAdd((unsigned long long*)&r->n_viol[threadIdx.x], t);
+    }
+}
+
+__global__ void __launch_bounds__(64) ladder_final_kernel(const pf::PairDev* pairs, int n_pairs, pf_ladder_result* res,
+                                                          const pf_ladder_result* slots) {
+    const int p = blockIdx.x;
+    if (p >= n_pairs) return;
+    const pf_ladder_result s = slots[(size_t)p * kSlots + threadIdx.x];
+    pf_ladder_result r;
+    r.n = pairs[p].n;
+#pragma unroll
+    for (int k = 0; k < PF_LADDER_LEVELS; ++k) r.n_viol[k] = wave_sum(s.n_viol[k]);
+    if (threadIdx.x == 0) res[pairs[p].orig] = r;
+}
+
 __global__ void __launch_bounds__(256) copy_kernel(u32x4* __restrict__ dst, const u32x4* __restrict__ src, unsigned long long n16) {
     const unsigned long long base = (unsigned long long)blockIdx.x * (256 * 4) + threadIdx.x;
     if (base + 3 * 256 < n16) {
@@ -466,6 +556,25 @@ hipError_t launch_score(const PairDev* d_pairs, const unsigned long long* d_bloc
     PF_LAUNCH(PF_BF16, PF_F64)
 #undef PF_LAUNCH
     hipLaunchKernelGGL(score_final_kernel, dim3(n_pairs), dim3(64), 0, stream, d_pairs, n_pairs, d_results, d_slots);
+    return hipGetLastError();
+}
+
+hipError_t launch_ladder(const PairDev* d_pairs, const unsigned long long* d_block_start, int n_pairs, const ScoreRanges& ranges,
+                         const LadderTable& table, pf_ladder_result* d_results, pf_ladder_result* d_slots, hipStream_t stream) {
+    const int nbs = (n_pairs * kSlots + kBlock - 1) / kBlock;
+    hipLaunchKernelGGL(ladder_init_kernel, dim3(nbs), dim3(kBlock), 0, stream, n_pairs, d_slots);
+#define PF_LAUNCH(CD, RD)                                                                                                    \
+    if (ranges.count[CD][RD])                                                                                                \
+        hipLaunchKernelGGL((ladder_kernel<CD, RD>), dim3((unsigned)ranges.count[CD][RD]), dim3(kBlock), 0, stream, d_pairs,    \
+                           d_block_start, n_pairs, table, d_slots, ranges.first[CD][RD]);
+    PF_LAUNCH(PF_F32, PF_F32)
+    PF_LAUNCH(PF_F32, PF_BF16)
+    PF_LAUNCH(PF_F32, PF_F64)
+    PF_LAUNCH(PF_BF16, PF_F32)
+    PF_LAUNCH(PF_BF16, PF_BF16)
+    PF_LAUNCH(PF_BF16, PF_F64)
+#undef PF_LAUNCH
+    hipLaunchKernelGGL(ladder_final_kernel, dim3(n_pairs), dim3(64), 0, stream, d_pairs, n_pairs, d_results, d_slots);
     return hipGetLastError();
 }
 

@@ -33,7 +33,15 @@ struct PairBatch {
     int first, count, last, pad_;
 };
 
+// tolerances of every ladder level, per candidate dtype (f32, bf16)
+struct LadderTable {
+    double rtol[2][PF_LADDER_LEVELS];
+    double atol[2][PF_LADDER_LEVELS];
+};
+
 unsigned long long score_chunk_elems();
+hipError_t launch_ladder(const PairDev* d_pairs, const unsigned long long* d_block_start, int n_pairs, const ScoreRanges& ranges,
+                         const LadderTable& table, pf_ladder_result* d_results, pf_ladder_result* d_slots, hipStream_t stream);
 hipError_t launch_score_upload(const PairBatch& batch, PairDev* d_pairs, unsigned long long* d_block_start, hipStream_t stream);
 hipError_t launch_score(const PairDev* d_pairs, const unsigned long long* d_block_start, int n_pairs, const ScoreRanges& ranges,
                         pf_score_result* d_results, pf_score_result* d_slots, hipStream_t stream);

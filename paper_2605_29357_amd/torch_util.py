@@ -120,3 +120,26 @@ def score_on_gpu(pairs_spec, stream=None):
     s.synchronize()
     raw = res.cpu().numpy().tobytes()
     return [pf.ScoreResult.from_buffer_copy(raw, i * ctypes.sizeof(pf.ScoreResult)).as_dict() for i in range(n)]
+
+
+def ladder_on_gpu(pairs_spec, stream=None):
+    """pairs_spec: list of (cand_tensor, cand_dtype, ref_tensor, ref_dtype, equal_nan).
+    Returns per pair the 11 violation counts for t = -10 .. 0."""
+    n = len(pairs_spec)
+    pairs = []
+    for c, cd, r, rd, en in pairs_spec:
+        p = pf.Pair()
+        p.d_cand, p.d_ref, p.n = c.data_ptr(), r.data_ptr(), c.numel()
+        p.cand_dtype, p.ref_dtype, p.equal_nan = pf.DTYPES[cd], pf.DTYPES[rd], int(en)
+        pairs.append(p)
+    res = torch.zeros(max(n, 1) * ctypes.sizeof(pf.LadderResult), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(max(pf.score_ladder_workspace_bytes(n), 256), dtype=torch.uint8, device="cuda")
+    s = stream if stream is not None else torch.cuda.current_stream()
+    pf.score_ladder(pairs, res.data_ptr(), ws.data_ptr(), ws.numel(), s.cuda_stream)
+    s.synchronize()
+    raw = res.cpu().numpy().tobytes()
+    out = []
+    for i in range(n):
+        lr = pf.LadderResult.from_buffer_copy(raw, i * ctypes.sizeof(pf.LadderResult))
+        out.append((lr.n, list(lr.n_viol)))
+    return out

@@ -1,0 +1,50 @@
+"""GPU parity of the tolerance-ladder scorer: 11 violation counts per pair, exact."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import metric
+from paper_2605_29357_amd.torch_util import ladder_on_gpu, to_device
+from workloads import rng
+
+pytestmark = pytest.mark.gpu
+
+
+def _noisy(n, cd, rd, seed):
+    r = np.random.default_rng(seed)
+    base = rng.normal(seed, 0, n)
+    # relative errors spread over ten decades so that every level separates some elements
+    cand = base * (1 + 10.0 ** r.uniform(-11, 0.5, n) * r.choice([-1, 1], n)) + 10.0 ** r.uniform(-12, -2, n)
+    ref = base.copy()
+    if n > 100:
+        idx = r.choice(n, 12, replace=False)
+        cand[idx[:3]] = np.nan
+        ref[idx[2:5]] = np.nan
+        cand[idx[5]] = np.inf
+        ref[idx[5:7]] = np.inf
+        ref[idx[7:10]] = 0.0
+    store = {"f32": lambda x: x.astype(np.float32), "bf16": rng.round_to_bf16_bits, "f64": lambda x: x.astype(np.float64)}
+    return store[cd](cand), store[rd](ref)
+
+
+def test_ladder_counts_match_the_oracle():
+    cases = [(0, "f32", "f32"), (5, "bf16", "bf16"), (1000, "f32", "f64"), (16384, "f32", "f32"), (16385, "bf16", "f32"),
+             (300007, "f32", "f32"), (1 << 20, "bf16", "bf16"), (77777, "bf16", "f64"), (4099, "f32", "bf16")]
+    specs, wants = [], []
+    for k, (n, cd, rd) in enumerate(cases):
+        for en in (False, True):
+            c, r = _noisy(n, cd, rd, 40 + k)
+            dc = to_device(c, cd) if n else torch.empty(0, device="cuda")
+            dr = to_device(r, rd) if n else torch.empty(0, device="cuda")
+            specs.append((dc, cd, dr, rd, en))
+            want = []
+            for t in metric.LADDER:
+                rt, at = metric.tolerance(cd, t)
+                from oracle.score import score_pair
+                want.append(score_pair(c, cd, r, rd, rt, at, en)["n_viol"])
+            wants.append((n, want))
+    got = ladder_on_gpu(specs)
+    for (n, cd, rd), g, w in zip([c for c in cases for _ in (0, 1)], got, wants):
+        assert g[0] == w[0] and g[1] == w[1], (n, cd, rd, g, w)
+    # the counts really do differ between levels
+    assert len(set(wants[6][1])) > 5
