@@ -161,7 +161,9 @@ struct Emit {
         const int per_lane_max = 32 / vec > 0 ? 32 / vec : 1;      // keep <= 32 floats per value per lane
         int T = 1;
         while (T < 16 && T < chunks) T <<= 1;       // a team's load should cover whole cache lines
-        while (T < 1024 && (chunks + T - 1) / T > std::min<int64_t>(per_lane_max, 4)) T <<= 1;
+        // two 16-byte chunks per lane and row leave room for several rows in flight (measured best
+        // on 512-element bf16 rows: 32 lanes x 2 chunks x 2 rows)
+        while (T < 1024 && (chunks + T - 1) / T > std::min<int64_t>(per_lane_max, 2)) T <<= 1;
         while ((chunks + T - 1) / T > per_lane_max && T < 1024) T <<= 1;
         int64_t K = (chunks + T - 1) / T;
         if (K * vec > 64) {          // the row does not fit in the registers of 1024 lanes: stream it
