@@ -155,8 +155,11 @@ struct Emit {
             if (operand_kind_pre(o) == 2) min_item = std::min(min_item, itemsize(o.dtype));
         for (auto& st : grp.stores)
             if (!st.row_scalar) min_item = std::min(min_item, itemsize(st.dtype));
+        // Rows whose length is not a multiple of the vector still use full 16-byte
+        // accesses (merely element-aligned); only the last chunk of a row is ragged.
         int vec = 16 / min_item;
-        while (vec > 1 && C % vec) vec >>= 1;
+        while (vec > 1 && vec > C) vec >>= 1;
+        const bool ragged = C % vec != 0;
         const int64_t chunks = (C + vec - 1) / vec;
         const int per_lane_max = 32 / vec > 0 ? 32 / vec : 1;      // keep <= 32 floats per value per lane
         int T = 1;
@@ -167,7 +170,7 @@ struct Emit {
         while ((chunks + T - 1) / T > per_lane_max && T < 1024) T <<= 1;
         int64_t K = (chunks + T - 1) / T;
         if (K * vec > 64) {          // the row does not fit in the registers of 1024 lanes: stream it
-            gen_loop(vec);
+            gen_loop(vec, ragged);
             return;
         }
         // few rows: spread each row over more lanes to cut latency
@@ -201,7 +204,7 @@ struct Emit {
         const bool groups_exact = R % RU == 0;
         const int block = T > 256 ? T : 256;
         const int teams = block / T;
-        const bool mask = (int64_t)K * T * vec != C;
+        const bool mask = (int64_t)K * T * vec != C && !ragged;   // whole chunks beyond the row end
         const int64_t row_groups = (R + RU - 1) / RU;
         grp.block = block;
         grp.grid = (row_groups + teams - 1) / teams;
@@ -254,7 +257,12 @@ struct Emit {
             line(strf("    float x%zu[%d];", oi, reps * N));
             line(strf("    _Pragma(\"unroll\") for (int u = 0; u < %d; ++u) _Pragma(\"unroll\") for (int k = 0; k < K; ++k) {", reps));
             line(strf("        const %s c0 = (%s)(k * T + lane) * VEC;", idx_t(), idx_t()));
-            if (mask) {
+            if (ragged) {
+                line(strf("        if (c0 + VEC <= C) pf_ld<VEC, %s, true>(p%zu + %s + c0, &x%zu[u * N + k * VEC]);", nt ? "true" : "false", oi,
+                          base.c_str(), oi));
+                line(strf("        else { _Pragma(\"unroll\") for (int j = 0; j < VEC; ++j) x%zu[u * N + k * VEC + j] = (c0 + j < C) ? pf_ld1(p%zu + %s + c0 + j) : 0.0f; }",
+                          oi, oi, base.c_str()));
+            } else if (mask) {
                 line(strf("        if (c0 < C) pf_ld<VEC, %s>(p%zu + %s + c0, &x%zu[u * N + k * VEC]);", nt ? "true" : "false", oi,
                           base.c_str(), oi));
                 line(strf("        else { _Pragma(\"unroll\") for (int j = 0; j < VEC; ++j) x%zu[u * N + k * VEC + j] = 0.0f; }", oi));
@@ -274,10 +282,10 @@ struct Emit {
             const int src = n.in[0];
             auto valid_open = [&]() {
                 line("    _Pragma(\"unroll\") for (int u = 0; u < RU; ++u) _Pragma(\"unroll\") for (int k = 0; k < K; ++k) {");
-                if (mask) line(strf("        if ((%s)(k * T + lane) * VEC < C) {", idx_t()));
-                else line("        {");
-                line("            _Pragma(\"unroll\") for (int jj = 0; jj < VEC; ++jj) {");
-                line("                const int j = k * VEC + jj;");
+                line(strf("        const %s c0 = (%s)(k * T + lane) * VEC;", idx_t(), idx_t()));
+                line("        _Pragma(\"unroll\") for (int jj = 0; jj < VEC; ++jj) {");
+                line("            const int j = k * VEC + jj;");
+                line(strf("            if (%s) {", ragged ? "c0 + jj < C" : mask ? "c0 < C" : "true"));
             };
             auto valid_close = [&]() { line("            }"); line("        }"); line("    }"); };
             std::string xj = ref(id, src, "j");
@@ -336,6 +344,12 @@ struct Emit {
                     const bool nt = numel(st.shape) * itemsize(st.dtype) >= (int64_t(1) << 22);
                     line("    _Pragma(\"unroll\") for (int u = 0; u < RU; ++u) _Pragma(\"unroll\") for (int k = 0; k < K; ++k) {");
                     line(strf("        const %s c0 = (%s)(k * T + lane) * VEC;", idx_t(), idx_t()));
+                    if (ragged) {
+                        line(strf("        if (row_ok[u] && c0 + VEC <= C) pf_st<VEC, %s, true>(q%d + row[u] * C + c0, &v%d[u * N + k * VEC]);",
+                                  nt ? "true" : "false", q, st.node));
+                        line(strf("        else if (row_ok[u]) { _Pragma(\"unroll\") for (int j = 0; j < VEC; ++j) if (c0 + j < C) pf_st1(q%d + row[u] * C + c0 + j, v%d[u * N + k * VEC + j]); }",
+                                  q, st.node));
+                    } else
                     line(strf("        if (row_ok[u]%s) pf_st<VEC, %s>(q%d + row[u] * C + c0, &v%d[u * N + k * VEC]);", mask ? " && c0 < C" : "",
                               nt ? "true" : "false", q, st.node));
                     line("    }");
@@ -352,7 +366,7 @@ struct Emit {
     // so a chain of k dependent reductions costs k+1 passes over the inputs (the
     // repeats are served by L2 when the row fits there).  The paper's Case 1
     // kernel has this same structure (mean pass, variance pass, write pass).
-    void gen_loop(int vec) {
+    void gen_loop(int vec, bool ragged) {
         grp.tmpl = PF_T_ROW_LOOP;
         const int64_t C = grp.cols, R = grp.rows;
         const int T = 1024;
@@ -364,7 +378,7 @@ struct Emit {
         grp.grid = R;
         grp.lanes_per_row = T;
         grp.vec = vec;
-        grp.chunks_per_lane = (int)((C / vec + T - 1) / T);
+        grp.chunks_per_lane = (int)(((C + vec - 1) / vec + T - 1) / T);
         const char* acc = precise ? "double" : "float";
         // stage of every value: the first pass in which it can be computed
         std::map<int, int> stage, rpass;     // node -> stage; reduction -> pass in which it accumulates
@@ -394,7 +408,7 @@ struct Emit {
 
         signature();
         line(strf("    constexpr int T = %d, VEC = %d;", T, vec));
-        line(strf("    constexpr %s C = %lld, CHUNKS = %lld;", idx_t(), (long long)C, (long long)(C / vec)));
+        line(strf("    constexpr %s C = %lld, CHUNKS = %lld;", idx_t(), (long long)C, (long long)((C + vec - 1) / vec)));
         line(strf("    __shared__ %s red_lds[%d][%d];", acc, std::max(n_red, 1), T / 64));
         if (precise) line(strf("    __shared__ float redf_lds[%d][%d];", std::max(n_red, 1), T / 64));
         line("    const int lane = threadIdx.x;");
@@ -444,6 +458,12 @@ struct Emit {
                 std::string base = lead_zero(o, nlead) ? strf("(%s)0", idx_t())
                                    : lead_mergeable(o, nlead) ? strf("row[0] * %lld", (long long)o.stride[nlead - 1])
                                                               : lead_offset(o, "row[0]");
+                if (ragged) {
+                    line(strf("        float x%zu[VEC];", oi));
+                    line(strf("        if (c0 + VEC <= C) pf_ld<VEC, false, true>(p%zu + %s + c0, x%zu);", oi, base.c_str(), oi));
+                    line(strf("        else { _Pragma(\"unroll\") for (int j = 0; j < VEC; ++j) x%zu[j] = (c0 + j < C) ? pf_ld1(p%zu + %s + c0 + j) : 0.0f; }",
+                              oi, oi, base.c_str()));
+                } else
                 line(strf("        float x%zu[VEC]; pf_ld<VEC, false>(p%zu + %s + c0, x%zu);", oi, oi, base.c_str(), oi));
             }
             for (int id : grp.nodes) {
@@ -452,14 +472,15 @@ struct Emit {
                     std::string xj = ref(id, n.in[0], "j");
                     if (rpass.at(id) == pass) {
                         if (n.op == PF_OP_MAX)
-                            line(strf("        _Pragma(\"unroll\") for (int j = 0; j < VEC; ++j) { const float t = %s; m%d = fmaxf(m%d, t); nan%d |= (t != t); }",
-                                      xj.c_str(), id, id, id));
+                            line(strf("        _Pragma(\"unroll\") for (int j = 0; j < VEC; ++j) if (%s) { const float t = %s; m%d = fmaxf(m%d, t); nan%d |= (t != t); }",
+                                      ragged ? "c0 + j < C" : "true", xj.c_str(), id, id, id));
                         else
-                            line(strf("        _Pragma(\"unroll\") for (int j = 0; j < VEC; ++j) a%d += (%s)(%s);", id, acc, xj.c_str()));
+                            line(strf("        _Pragma(\"unroll\") for (int j = 0; j < VEC; ++j) if (%s) a%d += (%s)(%s);", ragged ? "c0 + j < C" : "true", id,
+                                      acc, xj.c_str()));
                     }
                     if (n.op == PF_OP_VAR && rpass.at(id) + 1 == pass)
-                        line(strf("        _Pragma(\"unroll\") for (int j = 0; j < VEC; ++j) { const %s d = (%s)(%s) - a%d; q%d += d * d; }", acc, acc,
-                                  xj.c_str(), id, id));
+                        line(strf("        _Pragma(\"unroll\") for (int j = 0; j < VEC; ++j) if (%s) { const %s d = (%s)(%s) - a%d; q%d += d * d; }",
+                                  ragged ? "c0 + j < C" : "true", acc, acc, xj.c_str(), id, id));
                     continue;
                 }
                 if (kind.at(id) == 2 && stage.at(id) <= pass) emit_elementwise(id, vec);
@@ -469,6 +490,11 @@ struct Emit {
                 const int cnt = 1 + (int)st.also_outputs.size();
                 if (!st.row_scalar && stage.at(st.node) == pass)
                     for (int c = 0; c < cnt; ++c)
+                        if (ragged) {
+                            line(strf("        if (c0 + VEC <= C) pf_st<VEC, false, true>(q%d + row[0] * C + c0, v%d);", sp + c, st.node));
+                            line(strf("        else { _Pragma(\"unroll\") for (int j = 0; j < VEC; ++j) if (c0 + j < C) pf_st1(q%d + row[0] * C + c0 + j, v%d[j]); }",
+                                      sp + c, st.node));
+                        } else
                         line(strf("        pf_st<VEC, false>(q%d + row[0] * C + c0, v%d);", sp + c, st.node));
                 sp += cnt;
             }

@@ -15,6 +15,16 @@ typedef u32 u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+// Vector types for accesses that are only element-aligned (rows whose byte length is not a
+// multiple of 16): gfx950 under HSA serves unaligned global accesses, and the compiler emits
+// the same wide instructions for them.
+typedef u32 u32_a2 __attribute__((aligned(2)));
+typedef u32x2 u32x2_a2 __attribute__((aligned(2)));
+typedef u32x4 u32x4_a2 __attribute__((aligned(2)));
+typedef f32x2 f32x2_a4 __attribute__((aligned(4)));
+typedef f32x4 f32x4_a4 __attribute__((aligned(4)));
+template <bool UA> struct VT { typedef u32 b1; typedef u32x2 b2; typedef u32x4 b4; typedef f32x2 f2; typedef f32x4 f4; };
+template <> struct VT<true> { typedef u32_a2 b1; typedef u32x2_a2 b2; typedef u32x4_a2 b4; typedef f32x2_a4 f2; typedef f32x4_a4 f4; };
 #define PF_DEV __device__ __forceinline__
 
 PF_DEV float pf_bits2f(u32 u) { return __builtin_bit_cast(float, u); }
@@ -26,102 +36,102 @@ PF_DEV u32 pf_pack_bf16(float lo, float hi) {
 PF_DEV u16 pf_f2bf(float f) { return __builtin_bit_cast(u16, (__bf16)f); }
 
 // ---- loads of N contiguous elements into fp32 registers (p aligned to the access) ----
-template <int N, bool NT> struct LdBf16;
-template <bool NT> struct LdBf16<1, NT> {
+template <int N, bool NT, bool UA> struct LdBf16;
+template <bool NT, bool UA> struct LdBf16<1, NT, UA> {
     static PF_DEV void run(const u16* p, float* o) { o[0] = pf_bits2f((u32)(NT ? __builtin_nontemporal_load(p) : *p) << 16); }
 };
-template <bool NT> struct LdBf16<2, NT> {
+template <bool NT, bool UA> struct LdBf16<2, NT, UA> {
     static PF_DEV void run(const u16* p, float* o) {
-        u32 r = NT ? __builtin_nontemporal_load((const u32*)p) : *(const u32*)p;
+        typedef typename VT<UA>::b1 V; u32 r = NT ? __builtin_nontemporal_load((const V*)p) : *(const V*)p;
         o[0] = pf_bits2f(r << 16); o[1] = pf_bits2f(r & 0xffff0000u);
     }
 };
-template <bool NT> struct LdBf16<4, NT> {
+template <bool NT, bool UA> struct LdBf16<4, NT, UA> {
     static PF_DEV void run(const u16* p, float* o) {
-        u32x2 r = NT ? __builtin_nontemporal_load((const u32x2*)p) : *(const u32x2*)p;
+        typedef typename VT<UA>::b2 V; u32x2 r = NT ? __builtin_nontemporal_load((const V*)p) : *(const V*)p;
         o[0] = pf_bits2f(r.x << 16); o[1] = pf_bits2f(r.x & 0xffff0000u);
         o[2] = pf_bits2f(r.y << 16); o[3] = pf_bits2f(r.y & 0xffff0000u);
     }
 };
-template <bool NT> struct LdBf16<8, NT> {
+template <bool NT, bool UA> struct LdBf16<8, NT, UA> {
     static PF_DEV void run(const u16* p, float* o) {
-        u32x4 r = NT ? __builtin_nontemporal_load((const u32x4*)p) : *(const u32x4*)p;
+        typedef typename VT<UA>::b4 V; u32x4 r = NT ? __builtin_nontemporal_load((const V*)p) : *(const V*)p;
         o[0] = pf_bits2f(r.x << 16); o[1] = pf_bits2f(r.x & 0xffff0000u);
         o[2] = pf_bits2f(r.y << 16); o[3] = pf_bits2f(r.y & 0xffff0000u);
         o[4] = pf_bits2f(r.z << 16); o[5] = pf_bits2f(r.z & 0xffff0000u);
         o[6] = pf_bits2f(r.w << 16); o[7] = pf_bits2f(r.w & 0xffff0000u);
     }
 };
-template <int N, bool NT> struct LdF32;
-template <bool NT> struct LdF32<1, NT> {
+template <int N, bool NT, bool UA> struct LdF32;
+template <bool NT, bool UA> struct LdF32<1, NT, UA> {
     static PF_DEV void run(const float* p, float* o) { o[0] = NT ? __builtin_nontemporal_load(p) : *p; }
 };
-template <bool NT> struct LdF32<2, NT> {
+template <bool NT, bool UA> struct LdF32<2, NT, UA> {
     static PF_DEV void run(const float* p, float* o) {
-        f32x2 r = NT ? __builtin_nontemporal_load((const f32x2*)p) : *(const f32x2*)p;
+        typedef typename VT<UA>::f2 V; f32x2 r = NT ? __builtin_nontemporal_load((const V*)p) : *(const V*)p;
         o[0] = r.x; o[1] = r.y;
     }
 };
-template <bool NT> struct LdF32<4, NT> {
+template <bool NT, bool UA> struct LdF32<4, NT, UA> {
     static PF_DEV void run(const float* p, float* o) {
-        f32x4 r = NT ? __builtin_nontemporal_load((const f32x4*)p) : *(const f32x4*)p;
+        typedef typename VT<UA>::f4 V; f32x4 r = NT ? __builtin_nontemporal_load((const V*)p) : *(const V*)p;
         o[0] = r.x; o[1] = r.y; o[2] = r.z; o[3] = r.w;
     }
 };
-template <bool NT> struct LdF32<8, NT> {
+template <bool NT, bool UA> struct LdF32<8, NT, UA> {
     static PF_DEV void run(const float* p, float* o) {
-        LdF32<4, NT>::run(p, o); LdF32<4, NT>::run(p + 4, o + 4);
+        LdF32<4, NT, UA>::run(p, o); LdF32<4, NT, UA>::run(p + 4, o + 4);
     }
 };
-template <int N, bool NT> PF_DEV void pf_ld(const u16* p, float* o) { LdBf16<N, NT>::run(p, o); }
-template <int N, bool NT> PF_DEV void pf_ld(const float* p, float* o) { LdF32<N, NT>::run(p, o); }
+template <int N, bool NT, bool UA = false> PF_DEV void pf_ld(const u16* p, float* o) { LdBf16<N, NT, UA>::run(p, o); }
+template <int N, bool NT, bool UA = false> PF_DEV void pf_ld(const float* p, float* o) { LdF32<N, NT, UA>::run(p, o); }
 PF_DEV float pf_ld1(const u16* p) { return pf_bits2f((u32)*p << 16); }
 PF_DEV float pf_ld1(const float* p) { return *p; }
 
 // ---- stores of N contiguous fp32 registers, rounded once to the stored dtype ----
-template <int N, bool NT> struct StBf16;
-template <bool NT> struct StBf16<1, NT> {
+template <int N, bool NT, bool UA> struct StBf16;
+template <bool NT, bool UA> struct StBf16<1, NT, UA> {
     static PF_DEV void run(u16* p, const float* v) { u16 r = pf_f2bf(v[0]); if (NT) __builtin_nontemporal_store(r, p); else *p = r; }
 };
-template <bool NT> struct StBf16<2, NT> {
+template <bool NT, bool UA> struct StBf16<2, NT, UA> {
     static PF_DEV void run(u16* p, const float* v) {
         u32 r = pf_pack_bf16(v[0], v[1]);
-        if (NT) __builtin_nontemporal_store(r, (u32*)p); else *(u32*)p = r;
+        typedef typename VT<UA>::b1 V; if (NT) __builtin_nontemporal_store(r, (V*)p); else *(V*)p = r;
     }
 };
-template <bool NT> struct StBf16<4, NT> {
+template <bool NT, bool UA> struct StBf16<4, NT, UA> {
     static PF_DEV void run(u16* p, const float* v) {
         u32x2 r = {pf_pack_bf16(v[0], v[1]), pf_pack_bf16(v[2], v[3])};
-        if (NT) __builtin_nontemporal_store(r, (u32x2*)p); else *(u32x2*)p = r;
+        typedef typename VT<UA>::b2 V; if (NT) __builtin_nontemporal_store(r, (V*)p); else *(V*)p = r;
     }
 };
-template <bool NT> struct StBf16<8, NT> {
+template <bool NT, bool UA> struct StBf16<8, NT, UA> {
     static PF_DEV void run(u16* p, const float* v) {
         u32x4 r = {pf_pack_bf16(v[0], v[1]), pf_pack_bf16(v[2], v[3]), pf_pack_bf16(v[4], v[5]), pf_pack_bf16(v[6], v[7])};
-        if (NT) __builtin_nontemporal_store(r, (u32x4*)p); else *(u32x4*)p = r;
+        typedef typename VT<UA>::b4 V; if (NT) __builtin_nontemporal_store(r, (V*)p); else *(V*)p = r;
     }
 };
-template <int N, bool NT> struct StF32;
-template <bool NT> struct StF32<1, NT> {
+template <int N, bool NT, bool UA> struct StF32;
+template <bool NT, bool UA> struct StF32<1, NT, UA> {
     static PF_DEV void run(float* p, const float* v) { if (NT) __builtin_nontemporal_store(v[0], p); else *p = v[0]; }
 };
-template <bool NT> struct StF32<2, NT> {
+template <bool NT, bool UA> struct StF32<2, NT, UA> {
     static PF_DEV void run(float* p, const float* v) {
         f32x2 r = {v[0], v[1]};
-        if (NT) __builtin_nontemporal_store(r, (f32x2*)p); else *(f32x2*)p = r;
+        typedef typename VT<UA>::f2 V; if (NT) __builtin_nontemporal_store(r, (V*)p); else *(V*)p = r;
     }
 };
-template <bool NT> struct StF32<4, NT> {
+template <bool NT, bool UA> struct StF32<4, NT, UA> {
     static PF_DEV void run(float* p, const float* v) {
         f32x4 r = {v[0], v[1], v[2], v[3]};
-        if (NT) __builtin_nontemporal_store(r, (f32x4*)p); else *(f32x4*)p = r;
+        typedef typename VT<UA>::f4 V; if (NT) __builtin_nontemporal_store(r, (V*)p); else *(V*)p = r;
     }
 };
-template <bool NT> struct StF32<8, NT> {
-    static PF_DEV void run(float* p, const float* v) { StF32<4, NT>::run(p, v); StF32<4, NT>::run(p + 4, v + 4); }
+template <bool NT, bool UA> struct StF32<8, NT, UA> {
+    static PF_DEV void run(float* p, const float* v) { StF32<4, NT, UA>::run(p, v); StF32<4, NT, UA>::run(p + 4, v + 4); }
 };
-template <int N, bool NT> PF_DEV void pf_st(u16* p, const float* v) { StBf16<N, NT>::run(p, v); }
-template <int N, bool NT> PF_DEV void pf_st(float* p, const float* v) { StF32<N, NT>::run(p, v); }
+template <int N, bool NT, bool UA = false> PF_DEV void pf_st(u16* p, const float* v) { StBf16<N, NT, UA>::run(p, v); }
+template <int N, bool NT, bool UA = false> PF_DEV void pf_st(float* p, const float* v) { StF32<N, NT, UA>::run(p, v); }
 PF_DEV void pf_st1(u16* p, float v) { *p = pf_f2bf(v); }
 PF_DEV void pf_st1(float* p, float v) { *p = v; }
 
