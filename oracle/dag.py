@@ -26,6 +26,10 @@ keepdim=0):
   transpose            swaps the last two dims
   rot_pairs            out[2i] = -x[2i+1], out[2i+1] = x[2i] on the last dim
   const                a scalar (rank 0)
+  roll                 out[..., i, ...] = x[..., (i - shift) mod S, ...] along dim (torch.roll / np.roll);
+                       the paper's Case 1 reads a roll by 3 followed by a prefix slice as
+                       input index (S + i - shift) mod S
+  slice                x[..., start:stop, ...] along dim
 """
 import math
 import re
@@ -189,6 +193,23 @@ def run(graph, inputs, dtype=np.float64, observer=None):
                 if a[0].ndim < 2:
                     raise ValueError("transpose needs rank >= 2")
                 v = np.ascontiguousarray(np.swapaxes(a[0], -1, -2))
+            elif op == "roll":
+                x = a[0]
+                d = int(n.attrs["dim"])
+                if not -x.ndim <= d < x.ndim:
+                    raise ValueError("roll dim out of range")
+                v = np.roll(x, int(n.attrs["shift"]), axis=d)
+            elif op == "slice":
+                x = a[0]
+                d = int(n.attrs["dim"])
+                if not -x.ndim <= d < x.ndim:
+                    raise ValueError("slice dim out of range")
+                lo, hi = int(n.attrs["start"]), int(n.attrs["stop"])
+                if not 0 <= lo < hi <= x.shape[d]:
+                    raise ValueError("slice bounds")
+                idx = [slice(None)] * x.ndim
+                idx[d] = slice(lo, hi)
+                v = np.ascontiguousarray(x[tuple(idx)])
             elif op == "rot_pairs":
                 x = a[0]
                 if x.ndim < 1 or x.shape[-1] % 2:

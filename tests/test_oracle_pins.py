@@ -355,3 +355,51 @@ def test_f32_mode_is_the_same_definition_in_single_precision():
     y32 = dag.run(w.text, w.inputs, dtype=np.float32)[0]
     assert y32.dtype == np.float32
     np.testing.assert_allclose(y32, y64, rtol=1e-5, atol=1e-5)
+
+
+# ------------------------------------------------------------- roll and slice
+def _view_graph(shape, steps):
+    g = Builder()
+    t = g.input("f32", shape)
+    for op, attrs in steps:
+        t = g.op(op, [t], "f32", **attrs)
+    g.output(t)
+    return g.text()
+
+
+def test_roll_then_prefix_slice_is_the_index_formula_of_case_1():
+    # out[i, j, :] = x[(S + i - shift) mod S, (S + j - shift) mod S, :] for i, j < SC
+    S, SC, C, shift = 7, 5, 3, 3
+    x = f32(np.arange(S * S * C).reshape(S, S, C))
+    text = _view_graph((S, S, C), [("roll", dict(shift=shift, dim=0)), ("roll", dict(shift=shift, dim=1)),
+                                   ("slice", dict(dim=0, start=0, stop=SC)), ("slice", dict(dim=1, start=0, stop=SC))])
+    y = run1(text, [x])
+    assert y.shape == (SC, SC, C)
+    for i, j in itertools.product(range(SC), range(SC)):
+        np.testing.assert_array_equal(y[i, j], x[(S + i - shift) % S, (S + j - shift) % S])
+
+
+def test_roll_identities_and_slice_offsets():
+    x = f32(np.arange(24).reshape(2, 3, 4))
+    np.testing.assert_array_equal(run1(_view_graph((2, 3, 4), [("roll", dict(shift=0, dim=1))]), [x]), x)
+    np.testing.assert_array_equal(run1(_view_graph((2, 3, 4), [("roll", dict(shift=3, dim=1))]), [x]), x)
+    np.testing.assert_array_equal(run1(_view_graph((2, 3, 4), [("roll", dict(shift=1, dim=2)), ("roll", dict(shift=-1, dim=2))]), [x]), x)
+    y = run1(_view_graph((2, 3, 4), [("roll", dict(shift=1, dim=-1))]), [x])
+    assert y[0, 0].tolist() == [3, 0, 1, 2]                      # elements move towards higher indices
+    z = run1(_view_graph((2, 3, 4), [("slice", dict(dim=2, start=1, stop=3)), ("slice", dict(dim=1, start=2, stop=3))]), [x])
+    assert z.shape == (2, 1, 2) and z[1, 0].tolist() == [21, 22]
+    # a roll after a slice wraps inside the cut, not inside the source
+    w = run1(_view_graph((2, 3, 4), [("slice", dict(dim=2, start=0, stop=3)), ("roll", dict(shift=1, dim=2))]), [x])
+    assert w[0, 0].tolist() == [2, 0, 1]
+
+
+def test_case_1_subgraph_outputs_sum_and_layernorm():
+    w = configs.roll_slice_add_layernorm(S=9, SC=6, C=8, dtype="f32")
+    add, ln = dag.run(w.text, w.inputs)
+    x, r = w.inputs[0].astype(np.float64), w.inputs[1].astype(np.float64)
+    want = r + np.roll(x, (3, 3), axis=(0, 1))[:6, :6]
+    np.testing.assert_array_equal(add, want)
+    v = want.var(axis=-1)
+    g, b = w.inputs[2].astype(np.float64), w.inputs[3].astype(np.float64)
+    np.testing.assert_allclose(((ln - b) / g).var(axis=-1), v / (v + 1e-5), rtol=1e-10)
+    assert np.abs(((ln - b) / g).mean(axis=-1)).max() < 1e-12

@@ -143,3 +143,35 @@ def cfg4_rmsnorm_rope(batch=4, positions=2048, heads=32, dim=128, seed=3):
     return Workload("cfg4_rmsnorm_rope_bf16_%dx%dx%dx%d" % shape, g.text(), ins,
                     ["bf16", "bf16", "f32", "f32"], [shape, (dim,), (positions, 1, dim), (positions, 1, dim)],
                     ["bf16"], [shape], meta={"eps": 1e-6, "base": 10000.0}).finish()
+
+
+def roll_slice_add_layernorm(S=133, SC=128, C=96, shift=3, dtype="bf16", seed=5):
+    """The paper's Case 1 subgraph: x [S,S,C] rolled by `shift` along dims 0 and 1, cut to
+    [SC,SC,C], added to a residual, LayerNorm over C (eps 1e-5); both the sum and the
+    normalised tensor are outputs.  Routes in the paper: (133,128,96), (70,64,192), (35,32,384)."""
+    g = Builder()
+    x = g.input(dtype, (S, S, C))
+    r = g.input(dtype, (SC, SC, C))
+    gamma = g.input(dtype, (C,))
+    beta = g.input(dtype, (C,))
+    t = g.op("roll", [x], dtype, shift=shift, dim=0)
+    t = g.op("roll", [t], dtype, shift=shift, dim=1)
+    t = g.op("slice", [t], dtype, dim=0, start=0, stop=SC)
+    t = g.op("slice", [t], dtype, dim=1, start=0, stop=SC)
+    h = g.op("add", [r, t], dtype)
+    mu = g.op("mean", [h], dtype)
+    d = g.op("sub", [h, mu], dtype)
+    v = g.op("mean", [g.op("mul", [d, d], dtype)], dtype)
+    inv = g.op("rsqrt", [g.op("add", [v, g.const(1e-5, "f32")], dtype)], dtype)
+    y = g.op("add", [g.op("mul", [g.op("mul", [d, inv], dtype), gamma], dtype), beta], dtype)
+    g.output(h)
+    g.output(y)
+    ins = [_tensor(seed, 0, (S, S, C), dtype), _tensor(seed, 1, (SC, SC, C), dtype),
+           _tensor(seed, 2, (C,), dtype, 1.0, 0.1), _tensor(seed, 3, (C,), dtype, 0.0, 0.1)]
+    w = Workload("roll_slice_add_layernorm_%s_S%d_SC%d_C%d" % (dtype, S, SC, C), g.text(), ins,
+                 [dtype] * 4, [(S, S, C), (SC, SC, C), (C,), (C,)], [dtype, dtype], [(SC, SC, C), (SC, SC, C)],
+                 meta={"eps": 1e-5, "shift": shift}).finish()
+    # the rolled-and-cut window touches SC*SC of the S*S rows of x: bytes that must move
+    isz = ITEMSIZE[dtype]
+    w.algorithmic_bytes = isz * (SC * SC * C * 4 + 2 * C)
+    return w
