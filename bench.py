@@ -230,6 +230,8 @@ def per_config_table(torch, pf, configs, Runner, alloc_outputs, stream, w3, fuse
     table["cfg4_rmsnorm_rope"] = entry(configs.cfg4_rmsnorm_rope(), 5)          # 5 x 136 MB > 512 MB between reuses
     table["cfg2_masked_softmax"] = entry(configs.cfg2_masked_softmax(), 16)     # 16 x 34 MB
     table["cfg1_add_layernorm"] = entry(configs.cfg1_add_layernorm(), 4)        # launch-bound either way
+    # the paper's Case 1 at its D96 route (roll + slice + add + LayerNorm, two outputs, bf16)
+    table["case1_roll_slice_add_layernorm_D96"] = entry(configs.roll_slice_add_layernorm(), 40)
     return table
 
 

@@ -66,6 +66,10 @@ typedef enum {
     PF_OP_VAR,       /* mean((x-mean)^2) * n/(n-correction); attr correction=0   */
     PF_OP_TRANSPOSE, /* swaps the last two dims                                  */
     PF_OP_ROT_PAIRS, /* out[2i] = -x[2i+1], out[2i+1] = x[2i] on the last dim    */
+    PF_OP_ROLL,      /* attrs shift=<int>, dim=<int>: out[i] = x[(i - shift) mod S] along dim
+                        (the roll of the paper's Case 1); folded into the loads of its consumer */
+    PF_OP_SLICE,     /* attrs dim=<int>, start=<int>, stop=<int>: x[start:stop] along dim;
+                        folded into the loads of its consumer                     */
     PF_OP_COUNT_
 } pf_op;
 

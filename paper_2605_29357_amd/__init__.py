@@ -17,7 +17,7 @@ F32, BF16, F64 = 0, 1, 2
 DTYPES = {"f32": F32, "bf16": BF16, "f64": F64}
 DTYPE_NAMES = {v: k for k, v in DTYPES.items()}
 OPS = ["input", "const", "add", "sub", "mul", "div", "exp", "tanh", "sigmoid", "gelu", "rsqrt",
-       "sum", "max", "mean", "var", "transpose", "rot_pairs"]
+       "sum", "max", "mean", "var", "transpose", "rot_pairs", "roll", "slice"]
 TEMPLATES = ["ew_flat", "row_resident", "tile", "row_loop"]
 
 

@@ -29,6 +29,7 @@ struct Emit {
     std::string s;                       // source being built
     std::map<int, int> operand_of;       // node -> operand index (plain reads)
     std::map<int, int> toperand_of;      // node -> operand index (transposed reads)
+    std::map<int, int> voperand_of;      // roll / slice node -> operand index (reads through its index map)
     std::set<int> members;
     std::map<int, int> kind;             // member/operand node -> 2 full, 1 row-uniform
     bool precise = false;
@@ -65,7 +66,7 @@ struct Emit {
         if (n.op == PF_OP_CONST) return lit(n.value);
         (void)consumer;
         if (in_kernel(p)) return kind.at(p) == 2 ? strf("v%d[%s]", p, slot(j).c_str()) : strf("s%d[u]", p);
-        int oi = operand_of.at(p);
+        int oi = is_view(n.op) ? voperand_of.at(p) : operand_of.at(p);
         const bool h = hoisted.count(oi) != 0;
         if (operand_kind(oi) == 2) return h ? strf("x%d[%s]", oi, j.c_str()) : strf("x%d[%s]", oi, slot(j).c_str());
         return h ? strf("x%d[0]", oi) : strf("x%d[u]", oi);
@@ -86,12 +87,13 @@ struct Emit {
     int node_kind(int id) const {
         const Node& n = g.nodes[id];
         if (is_reduction(n.op)) return 1;
+        if (is_view(n.op)) return 2;
         if (grp.tmpl != PF_T_ROW_RESIDENT && grp.tmpl != PF_T_ROW_LOOP) return 2;
         if (grp.cols == 1) return 2;
         // row-uniform iff every operand is
         for (int p : n.in) {
             if (g.nodes[p].op == PF_OP_CONST) continue;
-            int k = in_kernel(p) ? kind.at(p) : operand_kind(operand_of.at(p));
+            int k = in_kernel(p) ? kind.at(p) : operand_kind(is_view(g.nodes[p].op) ? voperand_of.at(p) : operand_of.at(p));
             if (k == 2) return 2;
         }
         return 1;
@@ -118,9 +120,9 @@ struct Emit {
         };
         const std::string loops = strf("    _Pragma(\"unroll\") for (int u = 0; u < %d; ++u) _Pragma(\"unroll\") for (int j = 0; j < %d; %s)", RU,
                                        N, n.op == PF_OP_ROT_PAIRS ? "j += 2" : "++j");
-        if (n.op == PF_OP_TRANSPOSE) {
-            // value arrives through the transposed operand
-            int oi = toperand_of.at(n.in[0]);
+        if (n.op == PF_OP_TRANSPOSE || is_view(n.op)) {
+            // value arrives through the transposed / index-mapped operand
+            int oi = is_view(n.op) ? voperand_of.at(id) : toperand_of.at(n.in[0]);
             line(strf("    float v%d[%d];", id, RU * N));
             line(loops + strf(" v%d[%s] = x%d[%s];", id, slot("j").c_str(), oi, slot("j").c_str()));
             return;
@@ -216,7 +218,7 @@ struct Emit {
         if (RU > 1)
             for (size_t oi = 0; oi < grp.operands.size(); ++oi) {
                 const Operand& o = grp.operands[oi];
-                const bool inner_const = nlead == 0 || o.stride[nlead - 1] == 0;
+                const bool inner_const = nlead == 0 || (o.stride[nlead - 1] == 0 && !o.mapped(nlead - 1));
                 if (lead_zero(o, nlead) || (inner_const && inner % RU == 0)) hoisted.insert((int)oi);
             }
 
@@ -247,7 +249,7 @@ struct Emit {
             std::string base;
             if (lead_zero(o, nlead)) base = strf("(%s)0", idx_t());
             else if (lead_mergeable(o, nlead)) base = strf("row[u] * %lld", (long long)o.stride[nlead - 1]);
-            else base = lead_offset(o, "row0") + strf(" + (%s)u * %lld", idx_t(), (long long)o.stride[nlead - 1]);
+            else base = lead_offset_row_u(o, nlead);
             if (operand_kind((int)oi) == 1) {
                 line(strf("    float x%zu[%d];", oi, reps));
                 line(strf("    _Pragma(\"unroll\") for (int u = 0; u < %d; ++u) x%zu[u] = pf_ld1(p%zu + %s);", reps, oi, oi, base.c_str()));
@@ -257,7 +259,10 @@ struct Emit {
             line(strf("    float x%zu[%d];", oi, reps * N));
             line(strf("    _Pragma(\"unroll\") for (int u = 0; u < %d; ++u) _Pragma(\"unroll\") for (int k = 0; k < K; ++k) {", reps));
             line(strf("        const %s c0 = (%s)(k * T + lane) * VEC;", idx_t(), idx_t()));
-            if (ragged) {
+            if (last_mapped(o)) {     // rolled / sliced along the row: gather element by element
+                line(strf("        _Pragma(\"unroll\") for (int j = 0; j < VEC; ++j) x%zu[u * N + k * VEC + j] = (c0 + j < C) ? pf_ld1(p%zu + %s + %s * %lld) : 0.0f;",
+                          oi, oi, base.c_str(), mapexpr(o, rd - 1, "(c0 + j)").c_str(), (long long)o.stride[rd - 1]));
+            } else if (ragged) {
                 line(strf("        if (c0 + VEC <= C) pf_ld<VEC, %s, true>(p%zu + %s + c0, &x%zu[u * N + k * VEC]);", nt ? "true" : "false", oi,
                           base.c_str(), oi));
                 line(strf("        else { _Pragma(\"unroll\") for (int j = 0; j < VEC; ++j) x%zu[u * N + k * VEC + j] = (c0 + j < C) ? pf_ld1(p%zu + %s + c0 + j) : 0.0f; }",
@@ -458,7 +463,11 @@ struct Emit {
                 std::string base = lead_zero(o, nlead) ? strf("(%s)0", idx_t())
                                    : lead_mergeable(o, nlead) ? strf("row[0] * %lld", (long long)o.stride[nlead - 1])
                                                               : lead_offset(o, "row[0]");
-                if (ragged) {
+                if (last_mapped(o)) {
+                    line(strf("        float x%zu[VEC];", oi));
+                    line(strf("        _Pragma(\"unroll\") for (int j = 0; j < VEC; ++j) x%zu[j] = (c0 + j < C) ? pf_ld1(p%zu + %s + %s * %lld) : 0.0f;", oi,
+                              oi, base.c_str(), mapexpr(o, rd - 1, "(c0 + j)").c_str(), (long long)o.stride[rd - 1]));
+                } else if (ragged) {
                     line(strf("        float x%zu[VEC];", oi));
                     line(strf("        if (c0 + VEC <= C) pf_ld<VEC, false, true>(p%zu + %s + c0, x%zu);", oi, base.c_str(), oi));
                     line(strf("        else { _Pragma(\"unroll\") for (int j = 0; j < VEC; ++j) x%zu[j] = (c0 + j < C) ? pf_ld1(p%zu + %s + c0 + j) : 0.0f; }",
@@ -580,7 +589,11 @@ struct Emit {
             if (!straddle) {
                 std::string base = lead_offset(o, "row");
                 if (operand_kind((int)oi) == 1) line(strf("    const float x%zu[1] = {pf_ld1(p%zu + %s)};", oi, oi, base.c_str()));
-                else {
+                else if (last_mapped(o)) {
+                    line(strf("    float x%zu[VEC];", oi));
+                    line(strf("    _Pragma(\"unroll\") for (int j = 0; j < VEC; ++j) x%zu[j] = pf_ld1(p%zu + %s + %s * %lld);", oi, oi, base.c_str(),
+                              mapexpr(o, rd - 1, "(col0 + j)").c_str(), (long long)o.stride[rd - 1]));
+                } else {
                     line(strf("    float x%zu[VEC];", oi));
                     line(strf("    pf_ld<VEC, %s>(p%zu + %s + col0, x%zu);", nt ? "true" : "false", oi, base.c_str(), oi));
                 }
@@ -694,18 +707,20 @@ struct Emit {
             }
             std::string base = lead_offset_n(o, rd - 2);
             const int64_t sr = o.stride[rd - 2], sc = o.stride[rd - 1];
-            const bool vec_ok = sc == 1 && (C % 4 == 0) && (sr % 4 == 0) && lead_strides_multiple_of(o, 4, rd - 2);
+            const bool vec_ok = sc == 1 && (C % 4 == 0) && (sr % 4 == 0) && lead_strides_multiple_of(o, 4, rd - 2) && !o.mapped(rd - 1) &&
+                                o.const_offset % 4 == 0;
             line("    _Pragma(\"unroll\") for (int i = 0; i < 4; ++i) {");
             line(strf("        const %s rr = r0 + ty + 16 * i, cc = c0 + tx * 4;", idx_t()));
             line(strf("        const %s rc = rr < R ? rr : R - 1;", idx_t()));
             if (vec_ok) {
-                line(strf("        if (cc < C) pf_ld<4, false>(p%zu + %s + rc * %lld + cc, &x%zu[i * 4]);", oi, base.c_str(), (long long)sr, oi));
+                line(strf("        if (cc < C) pf_ld<4, false>(p%zu + %s + %s * %lld + cc, &x%zu[i * 4]);", oi, base.c_str(),
+                          mapexpr(o, rd - 2, "rc").c_str(), (long long)sr, oi));
                 line(strf("        else { _Pragma(\"unroll\") for (int j = 0; j < 4; ++j) x%zu[i * 4 + j] = 0.0f; }", oi));
             } else {
                 line("        _Pragma(\"unroll\") for (int j = 0; j < 4; ++j) {");
                 line(strf("            const %s cj = cc + j < C ? cc + j : C - 1;", idx_t()));
-                line(strf("            x%zu[i * 4 + j] = pf_ld1(p%zu + %s + rc * %lld + cj * %lld);", oi, oi, base.c_str(), (long long)sr,
-                          (long long)sc));
+                line(strf("            x%zu[i * 4 + j] = pf_ld1(p%zu + %s + %s * %lld + %s * %lld);", oi, oi, base.c_str(),
+                          mapexpr(o, rd - 2, "rc").c_str(), (long long)sr, mapexpr(o, rd - 1, "cj").c_str(), (long long)sc));
                 line("        }");
             }
             line("    }");
@@ -731,7 +746,7 @@ struct Emit {
 
     // ---------------------------------------------------------------- addressing
     bool is_contiguous_full(const Operand& o) const {
-        if (o.transposed) return false;
+        if (o.transposed || any_mapped(o, rd)) return false;
         int64_t st = 1;
         for (int k = rd - 1; k >= 0; --k) {
             if (grp.domain[k] != 1 && o.stride[k] != st) return false;
@@ -747,8 +762,25 @@ struct Emit {
     bool need_decomp = false;
     int decomp_dims = 0;
 
+    // index of dim k as the source tensor sees it: roll / slice steps applied to the consumer's index
+    std::string mapexpr(const Operand& o, int k, const std::string& idx) const {
+        std::string e = idx;
+        for (auto& st : o.steps[k]) {
+            if (st.mod) e = strf("((%s + %lld) %% %lld)", e.c_str(), (long long)st.add, (long long)st.mod);
+            else e = strf("(%s + %lld)", e.c_str(), (long long)st.add);
+        }
+        return e;
+    }
+    bool any_mapped(const Operand& o, int nlead) const {
+        for (int k = 0; k < nlead; ++k)
+            if (o.mapped(k)) return true;
+        return false;
+    }
+    bool last_mapped(const Operand& o) const { return rd > 0 && o.mapped(rd - 1); }
+
     // can the leading offset be written as row * stride? (strides nest like the domain)
     bool lead_mergeable(const Operand& o, int nlead) const {
+        if (any_mapped(o, nlead)) return false;
         for (int k = 0; k + 1 < nlead; ++k)
             if (o.stride[k] != o.stride[k + 1] * grp.domain[k + 1]) return false;
         return true;
@@ -788,9 +820,20 @@ struct Emit {
         for (int k = 0; k < nlead; ++k) {
             if (!o.stride[k]) continue;
             if (!e.empty()) e += " + ";
-            e += strf("i%d * %lld", k, (long long)o.stride[k]);
+            e += strf("%s * %lld", mapexpr(o, k, strf("i%d", k)).c_str(), (long long)o.stride[k]);
         }
         return "(" + e + ")";
+    }
+    // row template: offset of row u of the team's row group (outer indices shared, inner index + u)
+    std::string lead_offset_row_u(const Operand& o, int nlead) const {
+        std::string e;
+        for (int k = 0; k < nlead; ++k) {
+            if (!o.stride[k]) continue;
+            if (!e.empty()) e += " + ";
+            const std::string idx = k == nlead - 1 ? strf("(i%d + (%s)u)", k, idx_t()) : strf("i%d", k);
+            e += strf("%s * %lld", mapexpr(o, k, idx).c_str(), (long long)o.stride[k]);
+        }
+        return e.empty() ? strf("(%s)0", idx_t()) : "(" + e + ")";
     }
     std::string row_var = "row";
     std::string lead_offset(const Operand& o, const std::string& rv) {
@@ -800,15 +843,16 @@ struct Emit {
     // offset of one element from (row, col) without pre-computed indices (gather path)
     std::string element_offset(const Operand& o, const std::string& rv, const std::string& cv) const {
         const int nlead = rd > 0 ? rd - 1 : 0;
-        std::string e = strf("%s * %lld", cv.c_str(), rd > 0 ? (long long)o.stride[rd - 1] : 0LL);
+        std::string e = strf("%s * %lld", rd > 0 ? mapexpr(o, rd - 1, cv).c_str() : cv.c_str(), rd > 0 ? (long long)o.stride[rd - 1] : 0LL);
         if (lead_zero(o, nlead)) return e;
         if (lead_mergeable(o, nlead)) return e + strf(" + %s * %lld", rv.c_str(), (long long)o.stride[nlead - 1]);
         // decompose inline
         std::string cur = rv;
         for (int k = nlead - 1; k >= 0; --k) {
-            if (k == 0) e += strf(" + (%s) * %lld", cur.c_str(), (long long)o.stride[0]);
+            if (k == 0) e += strf(" + %s * %lld", mapexpr(o, 0, "(" + cur + ")").c_str(), (long long)o.stride[0]);
             else {
-                e += strf(" + ((%s) %% %lld) * %lld", cur.c_str(), (long long)grp.domain[k], (long long)o.stride[k]);
+                e += strf(" + %s * %lld", mapexpr(o, k, strf("((%s) %% %lld)", cur.c_str(), (long long)grp.domain[k])).c_str(),
+                          (long long)o.stride[k]);
                 cur = strf("((%s) / %lld)", cur.c_str(), (long long)grp.domain[k]);
             }
         }
@@ -836,6 +880,8 @@ struct Emit {
     }
     void signature() {
         line(strf("extern \"C\" __global__ void __launch_bounds__(%d) %s(%s) {", grp.block, grp.kernel_name.c_str(), param_list().c_str()));
+        for (size_t oi = 0; oi < grp.operands.size(); ++oi)     // source dims a sliced window pins to one index
+            if (grp.operands[oi].const_offset) line(strf("    p%zu += %lld;", oi, (long long)grp.operands[oi].const_offset));
     }
 
     void recompute_kinds() {
@@ -847,7 +893,8 @@ struct Emit {
         rd = (int)grp.domain.size();
         for (int id : grp.nodes) members.insert(id);
         for (size_t oi = 0; oi < grp.operands.size(); ++oi) {
-            if (grp.operands[oi].via_transpose) toperand_of[grp.operands[oi].node] = (int)oi;
+            if (grp.operands[oi].view >= 0) voperand_of[grp.operands[oi].view] = (int)oi;
+            else if (grp.operands[oi].via_transpose) toperand_of[grp.operands[oi].node] = (int)oi;
             else operand_of[grp.operands[oi].node] = (int)oi;
         }
         // a transpose that moves no data is planned as a plain operand

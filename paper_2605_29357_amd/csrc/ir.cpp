@@ -37,7 +37,7 @@ std::string strf(const char* fmt, ...) {
 
 static const char* kOpNames[PF_OP_COUNT_] = {
     "input", "const", "add", "sub", "mul", "div", "exp", "tanh", "sigmoid", "gelu",
-    "rsqrt", "sum", "max", "mean", "var", "transpose", "rot_pairs"};
+    "rsqrt", "sum", "max", "mean", "var", "transpose", "rot_pairs", "roll", "slice"};
 
 const char* op_name(pf_op op) { return (op >= 0 && op < PF_OP_COUNT_) ? kOpNames[op] : "?"; }
 
@@ -91,6 +91,13 @@ int graph_add_input(pf_graph& g, pf_dtype dt, const Shape& shape) {
     return (int)g.nodes.size() - 1;
 }
 
+static long long parse_ll_attr(const std::string& k, const std::string& v) {
+    char* end = nullptr;
+    long long x = strtoll(v.c_str(), &end, 10);
+    if (end == v.c_str() || *end) fail(PF_E_COMPILE, "attribute %s needs an integer, got '%s'", k.c_str(), v.c_str());
+    return x;
+}
+
 static int parse_int_attr(const std::string& k, const std::string& v) {
     char* end = nullptr;
     long x = strtol(v.c_str(), &end, 10);
@@ -111,7 +118,7 @@ int graph_add_node(pf_graph& g, pf_op op, const std::vector<int>& in,
     n.in = in;
     const size_t want = op == PF_OP_CONST ? 0 : is_binary(op) ? 2 : 1;
     if (in.size() != want) fail(PF_E_COMPILE, "%%%d: %s takes %zu operand(s), got %zu", id, op_name(op), want, in.size());
-    bool have_value = false;
+    bool have_value = false, have_dim = false, have_shift = false, have_start = false, have_stop = false;
     for (auto& kv : attrs) {
         const std::string &k = kv.first, &v = kv.second;
         if (k == "value" && op == PF_OP_CONST) {
@@ -124,6 +131,18 @@ int graph_add_node(pf_graph& g, pf_op op, const std::vector<int>& in,
             if (n.keepdim != 0 && n.keepdim != 1) fail(PF_E_COMPILE, "%%%d: keepdim must be 0 or 1", id);
         } else if (k == "correction" && op == PF_OP_VAR) {
             n.correction = parse_int_attr(k, v);
+        } else if (k == "dim" && is_view(op)) {
+            n.dim = parse_int_attr(k, v);
+            have_dim = true;
+        } else if (k == "shift" && op == PF_OP_ROLL) {
+            n.shift = parse_ll_attr(k, v);
+            have_shift = true;
+        } else if (k == "start" && op == PF_OP_SLICE) {
+            n.start = parse_ll_attr(k, v);
+            have_start = true;
+        } else if (k == "stop" && op == PF_OP_SLICE) {
+            n.stop = parse_ll_attr(k, v);
+            have_stop = true;
         } else if (k == "approx" && op == PF_OP_GELU) {
             if (v == "tanh") n.gelu_erf = 0;
             else if (v == "erf") n.gelu_erf = 1;
@@ -150,6 +169,22 @@ int graph_add_node(pf_graph& g, pf_op op, const std::vector<int>& in,
         if (s.size() < 2) fail(PF_E_COMPILE, "%%%d: transpose needs rank >= 2", id);
         n.shape = s;
         std::swap(n.shape[s.size() - 1], n.shape[s.size() - 2]);
+    } else if (is_view(op)) {
+        const Shape& s = g.nodes[in[0]].shape;
+        const int r = (int)s.size();
+        if (!have_dim) fail(PF_E_COMPILE, "%%%d: %s needs dim=", id, op_name(op));
+        if (n.dim < -r || n.dim >= r) fail(PF_E_COMPILE, "%%%d: dim %d out of range for rank %d", id, n.dim, r);
+        if (n.dim < 0) n.dim += r;
+        n.shape = s;
+        if (op == PF_OP_ROLL) {
+            if (!have_shift) fail(PF_E_COMPILE, "%%%d: roll needs shift=", id);
+        } else {
+            if (!have_start || !have_stop) fail(PF_E_COMPILE, "%%%d: slice needs start= and stop=", id);
+            if (n.start < 0 || n.start >= n.stop || n.stop > s[n.dim])
+                fail(PF_E_COMPILE, "%%%d: slice [%lld:%lld] out of bounds for a dim of %lld", id, (long long)n.start, (long long)n.stop,
+                     (long long)s[n.dim]);
+            n.shape[n.dim] = n.stop - n.start;
+        }
     } else if (op == PF_OP_ROT_PAIRS) {
         const Shape& s = g.nodes[in[0]].shape;
         if (s.empty() || (s.back() & 1)) fail(PF_E_COMPILE, "%%%d: rot_pairs needs an even last dim", id);
@@ -309,6 +344,8 @@ std::string graph_print(const pf_graph& g) {
         else if (n.op == PF_OP_GELU) out += strf(" {approx=%s}", n.gelu_erf ? "erf" : "tanh");
         else if (n.op == PF_OP_VAR) out += strf(" {correction=%d, keepdim=%d}", n.correction, n.keepdim);
         else if (is_reduction(n.op)) out += strf(" {keepdim=%d}", n.keepdim);
+        else if (n.op == PF_OP_ROLL) out += strf(" {shift=%lld, dim=%d}", (long long)n.shift, n.dim);
+        else if (n.op == PF_OP_SLICE) out += strf(" {dim=%d, start=%lld, stop=%lld}", n.dim, (long long)n.start, (long long)n.stop);
         out += strf(" : %s\n", dtype_name(n.dtype));
     }
     for (int o : g.outputs) out += strf("out %%%d\n", o);

@@ -34,6 +34,7 @@ bool op_from_name(const std::string& name, pf_op* op);
 bool is_reduction(pf_op op);
 bool is_unary(pf_op op);
 bool is_binary(pf_op op);
+inline bool is_view(pf_op op) { return op == PF_OP_ROLL || op == PF_OP_SLICE; }
 
 // A node of the computational graph (Def. 3.1): operator type, operands,
 // inferred output shape, and the dtype it has when stored.
@@ -47,6 +48,9 @@ struct Node {
     int keepdim = 1;      // reductions
     int correction = 0;   // var
     int gelu_erf = 0;     // gelu: 0 tanh form, 1 erf form
+    int dim = 0;          // roll, slice: normalised to [0, rank)
+    int64_t shift = 0;    // roll
+    int64_t start = 0, stop = 0;   // slice
     bool is_output = false;
 };
 
@@ -71,6 +75,13 @@ Shape broadcast_shapes(const Shape& a, const Shape& b);
 
 // ---- plan.cpp ----
 
+// One step of an index remapping along one dim, applied to the consumer's index:
+// slice: idx + add; roll: (idx + add) mod size (add = size - shift mod size).
+struct ViewStep {
+    int64_t add = 0;
+    int64_t mod = 0;   // 0: no wrap
+};
+
 // How a kernel reads one external tensor inside its iteration domain.
 struct Operand {
     int node = -1;            // producing node (graph input or earlier group's member)
@@ -80,6 +91,12 @@ struct Operand {
     int64_t stride[PF_MAX_RANK] = {0, 0, 0, 0};
     bool transposed = false;  // read through a swap of the last two dims (data really moves)
     bool via_transpose = false;  // requested by a transpose node (even when it moves no data)
+    // read through a chain of roll / slice nodes ending in node `view` (-1: read directly):
+    // per domain dim the steps that turn the consumer's index into the source index
+    int view = -1;
+    std::vector<ViewStep> steps[PF_MAX_RANK];
+    int64_t const_offset = 0;    // contribution of source dims the domain does not iterate over
+    bool mapped(int k) const { return !steps[k].empty(); }
     // where the bytes live
     int graph_input = -1;     // index into d_inputs, or
     int64_t ws_offset = -1;   // byte offset into the workspace, or

@@ -59,6 +59,12 @@ struct Builder {
 
     bool grouped(int n) const { return group_of[n] >= 0; }
 
+    // the tensor a chain of roll / slice nodes finally reads
+    int root_of(int id) const {
+        while (is_view(g.nodes[id].op)) id = g.nodes[id].in[0];
+        return id;
+    }
+
     // kind of node n if it were a member of a group with domain d: 2 full, 1 row-uniform, 0 neither
     int kind_in(const Node& n, const Shape& d) const {
         Shape c = canon(n.shape);
@@ -81,6 +87,13 @@ struct Builder {
         if (grp.nodes.size() >= 60) return false;
         for (int p : n.in)
             if (group_of[p] == gi && !usable_in_kernel(p)) return false;
+        if (is_view(n.op)) {
+            // read through index arithmetic from the chain's root, which must already be in memory
+            if (group_of[root_of(id)] == gi) return false;
+            return kind_in(n, grp.domain) == 2;
+        }
+        for (int p : n.in)                                    // a view operand is read from its root
+            if (is_view(g.nodes[p].op) && group_of[p] != gi && group_of[root_of(p)] == gi) return false;
         if (n.op == PF_OP_TRANSPOSE) {
             if (group_of[n.in[0]] == gi) return false;          // operand must already be in memory
             if (grp.tmpl != PF_T_EW_FLAT && grp.tmpl != PF_T_TILE) return false;
@@ -131,7 +144,11 @@ struct Builder {
                 continue;
             }
             int cand = -1;
-            for (int p : n.in) cand = std::max(cand, group_of[p]);
+            for (int p : n.in) {
+                cand = std::max(cand, group_of[p]);
+                if (is_view(g.nodes[p].op)) cand = std::max(cand, group_of[root_of(p)]);
+            }
+            if (is_view(n.op)) cand = std::max(cand, group_of[root_of((int)i)]);
             int last = (int)groups.size() - 1;
             if (cand >= 0 && can_join((int)i, cand)) join((int)i, cand);
             else if (last > cand && last >= 0 && can_join((int)i, last)) join((int)i, last);
@@ -237,13 +254,77 @@ void make_plan(const pf_graph& g, const pf_options& opt, Plan& plan) {
             }
             grp.operands.push_back(o);
         };
+        // a tensor read through a chain of roll / slice nodes ending in node v
+        auto add_view_operand = [&](int v) {
+            for (auto& o : grp.operands)
+                if (o.view == v) return;
+            const int root = b.root_of(v);
+            Operand o;
+            o.node = root;
+            o.view = v;
+            o.shape = g.nodes[v].shape;              // the window that is read
+            if (input_slot[root] >= 0) {
+                o.graph_input = input_slot[root];
+                o.dtype = g.nodes[root].dtype;
+            } else if (ws_off[root] >= 0) {
+                o.ws_offset = ws_off[root];
+                o.dtype = mem_dtype[root];
+            } else if (output_slot[root] >= 0) {
+                o.graph_output = output_slot[root];
+                o.dtype = g.nodes[root].dtype;
+            } else {
+                fail(PF_E_COMPILE, "internal: node %%%d read through a view before it is materialised", root);
+            }
+            const Shape& rs = g.nodes[root].shape;
+            const Shape& vs = g.nodes[v].shape;
+            const int r = (int)rs.size();
+            // steps per source dim, in the order they apply to the consumer's index (v back to the root)
+            std::vector<std::vector<ViewStep>> steps(r);
+            for (int cur = v; is_view(g.nodes[cur].op); cur = g.nodes[cur].in[0]) {
+                const Node& vn = g.nodes[cur];
+                ViewStep st;
+                if (vn.op == PF_OP_SLICE) {
+                    st.add = vn.start;
+                } else {
+                    const int64_t size = g.nodes[vn.in[0]].shape[vn.dim];
+                    int64_t sh = vn.shift % size;
+                    if (sh < 0) sh += size;
+                    st.add = (size - sh) % size;
+                    st.mod = size;
+                }
+                if (st.add || st.mod) steps[vn.dim].push_back(st);
+            }
+            int64_t stride = 1;
+            for (int d = r - 1; d >= 0; --d) {
+                const int k = rd - (r - d);           // domain dim this source dim lines up with
+                const bool iterated = k >= 0 && vs[d] != 1;
+                if (iterated) {
+                    if (vs[d] != bg.domain[k]) fail(PF_E_COMPILE, "internal: view operand %%%d does not fit the domain", v);
+                    o.stride[k] = stride;
+                    o.steps[k] = steps[d];
+                } else {
+                    if (vs[d] != 1) fail(PF_E_COMPILE, "internal: view operand %%%d rank exceeds domain", v);
+                    int64_t idx = 0;                  // the window has one element here: a constant source index
+                    for (auto& st : steps[d]) idx = st.mod ? (idx + st.add) % st.mod : idx + st.add;
+                    o.const_offset += idx * stride;
+                }
+                stride *= rs[d];
+            }
+            grp.operands.push_back(o);
+        };
         for (int id : bg.nodes) {
             const Node& n = g.nodes[id];
+            if (is_view(n.op)) {
+                add_view_operand(id);
+                continue;
+            }
             for (int p : n.in) {
                 if (g.nodes[p].op == PF_OP_CONST) continue;
                 bool inside = b.group_of[p] == (int)gi && b.usable_in_kernel(p);
                 if (n.op == PF_OP_TRANSPOSE) add_operand(p, true);
-                else if (!inside) add_operand(p, false);
+                else if (inside) continue;
+                else if (is_view(g.nodes[p].op)) add_view_operand(p);
+                else add_operand(p, false);
             }
         }
 
@@ -251,8 +332,19 @@ void make_plan(const pf_graph& g, const pf_options& opt, Plan& plan) {
         for (int id : bg.nodes) {
             const Node& n = g.nodes[id];
             bool outside_use = false;
-            for (int c : b.consumers[id])
-                if (b.group_of[c] != (int)gi || !b.usable_in_kernel(id) || g.nodes[c].op == PF_OP_TRANSPOSE) outside_use = true;
+            for (int c : b.consumers[id]) {
+                const pf_op cop = g.nodes[c].op;
+                if (is_view(n.op)) {
+                    // readers of a view go to its root, except a transpose, which needs the window in memory
+                    if (cop == PF_OP_TRANSPOSE) outside_use = true;
+                    continue;
+                }
+                if (b.group_of[c] != (int)gi || !b.usable_in_kernel(id) || cop == PF_OP_TRANSPOSE || is_view(cop)) outside_use = true;
+            }
+            // anything downstream of a view chain rooted here reads this node from memory
+            if (!is_view(n.op))
+                for (size_t q = 0; q < g.nodes.size() && !outside_use; ++q)
+                    if (is_view(g.nodes[q].op) && b.root_of((int)q) == id) outside_use = true;
             if (!n.is_output && !outside_use) continue;
             const bool row_scalar = is_reduction(n.op) || (b.kind_in(n, bg.domain) == 1);
             if (n.is_output) {

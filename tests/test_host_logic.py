@@ -177,3 +177,26 @@ def test_keepdim0_reduction_is_read_back_from_memory_by_its_consumers():
     g.output(y)
     e = pf.Exec(g.text())
     assert e.info()["n_kernels"] == 2
+
+
+def test_roll_and_slice_fold_into_the_consumer():
+    w = configs.roll_slice_add_layernorm()
+    e = pf.Exec(w.text)
+    assert e.info()["n_kernels"] == 1 and e.group_info(0)["template"] == "row_resident"
+    assert "% 133" in e.source(0)                                # the roll became index arithmetic
+    g = pf.Graph(w.text)
+    assert pf.Graph(g.text()).text() == g.text()
+    assert g.node_info(7)["shape"] == (128, 128, 96)
+
+
+@pytest.mark.parametrize("text,frag", [
+    ("in %0 : f32[4,6]\n%1 = slice(%0) {dim=1, start=2, stop=7} : f32\nout %1\n", "out of bounds"),
+    ("in %0 : f32[4,6]\n%1 = slice(%0) {dim=1, start=3, stop=3} : f32\nout %1\n", "out of bounds"),
+    ("in %0 : f32[4,6]\n%1 = roll(%0) {shift=1, dim=2} : f32\nout %1\n", "out of range"),
+    ("in %0 : f32[4,6]\n%1 = roll(%0) {dim=1} : f32\nout %1\n", "shift"),
+    ("in %0 : f32[4,6]\n%1 = slice(%0) {start=0, stop=2} : f32\nout %1\n", "dim"),
+])
+def test_ill_formed_views_are_compile_errors(text, frag):
+    with pytest.raises(pf.PfError) as e:
+        pf.Exec(text)
+    assert e.value.status == pf.PF_E_COMPILE and frag in str(e.value)
