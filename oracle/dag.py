@@ -19,7 +19,10 @@ keepdim=0):
   rsqrt                1 / sqrt(x)
   gelu approx=tanh     0.5 x (1 + tanh(sqrt(2/pi) (x + 0.044715 x^3)))
        approx=erf      0.5 x (1 + erf(x / sqrt 2))
-  sum max mean         over the last dim; max propagates NaN
+  maximum minimum      element-wise, NaN-propagating (torch.maximum; clamp(x, min=c) = maximum(x, c))
+  sum max mean         over the last dim (dim=-1, default) or the one before it (dim=-2, the
+                       sequence dim of the paper's Case 2: masked mean pooling sums over s in
+                       out[b,d] = sum_s h[b,s,d] m[b,s,d] / max(sum_s m[b,s,d], 1e-9)); max propagates NaN
   var                  mean((x - mean x)^2) * n / (n - correction); the
                        LayerNorm of the paper's Case 1 divides by n
                        (correction 0) and adds eps inside the square root
@@ -108,11 +111,6 @@ def _erf(x):
     return np.vectorize(math.erf, otypes=[x.dtype])(x)
 
 
-def _reduce_max(x):
-    # np.max already propagates NaN
-    return np.max(x, axis=-1, keepdims=True)
-
-
 def run(graph, inputs, dtype=np.float64, observer=None):
     """Evaluate the DAG node by node.
 
@@ -156,6 +154,10 @@ def run(graph, inputs, dtype=np.float64, observer=None):
                 v = a[0] * a[1]
             elif op == "div":
                 v = a[0] / a[1]
+            elif op == "maximum":
+                v = np.maximum(a[0], a[1])
+            elif op == "minimum":
+                v = np.minimum(a[0], a[1])
             elif op == "exp":
                 v = np.exp(a[0])
             elif op == "tanh":
@@ -173,22 +175,23 @@ def run(graph, inputs, dtype=np.float64, observer=None):
                     v = ft(0.5) * x * (ft(1.0) + _erf(x / ft(math.sqrt(2.0))))
             elif op in ("sum", "max", "mean", "var"):
                 x = a[0]
-                if x.ndim < 1:
-                    raise ValueError("reduction of a scalar")
+                ax = int(n.attrs.get("dim", -1))
+                if ax not in (-1, -2) or x.ndim < -ax:
+                    raise ValueError("reduction dim must be -1 or -2 and exist")
                 if op == "sum":
-                    v = np.sum(x, axis=-1, keepdims=True)
+                    v = np.sum(x, axis=ax, keepdims=True)
                 elif op == "max":
-                    v = _reduce_max(x)
+                    v = np.max(x, axis=ax, keepdims=True)            # np.max propagates NaN
                 elif op == "mean":
-                    v = np.sum(x, axis=-1, keepdims=True) / ft(x.shape[-1])
+                    v = np.sum(x, axis=ax, keepdims=True) / ft(x.shape[ax])
                 else:
-                    cnt = x.shape[-1]
-                    mu = np.sum(x, axis=-1, keepdims=True) / ft(cnt)
+                    cnt = x.shape[ax]
+                    mu = np.sum(x, axis=ax, keepdims=True) / ft(cnt)
                     d = x - mu
                     corr = int(n.attrs.get("correction", 0))
-                    v = np.sum(d * d, axis=-1, keepdims=True) / ft(cnt - corr)
+                    v = np.sum(d * d, axis=ax, keepdims=True) / ft(cnt - corr)
                 if int(n.attrs.get("keepdim", 1)) == 0:
-                    v = v[..., 0]
+                    v = np.squeeze(v, axis=ax)
             elif op == "transpose":
                 if a[0].ndim < 2:
                     raise ValueError("transpose needs rank >= 2")

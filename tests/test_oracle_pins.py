@@ -403,3 +403,50 @@ def test_case_1_subgraph_outputs_sum_and_layernorm():
     g, b = w.inputs[2].astype(np.float64), w.inputs[3].astype(np.float64)
     np.testing.assert_allclose(((ln - b) / g).var(axis=-1), v / (v + 1e-5), rtol=1e-10)
     assert np.abs(((ln - b) / g).mean(axis=-1)).max() < 1e-12
+
+
+# ------------------------------------------------ reductions over the second-to-last dim
+def test_column_reductions_match_numpy_and_closed_forms():
+    x = f32(np.random.default_rng(5).normal(size=(3, 6, 5)))
+    xd = x.astype(np.float64)
+    g = Builder()
+    i = g.input("f32", x.shape)
+    g.output(g.op("sum", [i], "f32", dim=-2, keepdim=0))
+    g.output(g.op("mean", [i], "f32", dim=-2))
+    g.output(g.op("max", [i], "f32", dim=-2, keepdim=0))
+    g.output(g.op("var", [i], "f32", dim=-2, keepdim=0))
+    s, m, mx, v = dag.run(g.text(), [x])
+    assert s.shape == (3, 5) and m.shape == (3, 1, 5)
+    np.testing.assert_allclose(s, xd.sum(axis=1), rtol=1e-14)
+    np.testing.assert_allclose(m[:, 0], xd.mean(axis=1), rtol=1e-14, atol=1e-16)
+    np.testing.assert_array_equal(mx, xd.max(axis=1))
+    np.testing.assert_allclose(v, xd.var(axis=1), rtol=1e-13)
+    ones = np.ones((2, 7, 4), np.float32)
+    g = Builder()
+    i = g.input("f32", ones.shape)
+    g.output(g.op("sum", [i], "f32", dim=-2, keepdim=0))
+    np.testing.assert_array_equal(dag.run(g.text(), [ones])[0], 7.0)      # counts the 7, not the 4
+
+
+def test_maximum_minimum_and_nan():
+    g = Builder()
+    a = g.input("f32", (4,))
+    c = g.const(1e-9, "f32")
+    g.output(g.op("maximum", [a, c], "f32"))
+    g.output(g.op("minimum", [a, c], "f32"))
+    hi, lo = dag.run(g.text(), [f32([0.0, 2.0, -1.0, np.nan])])
+    assert hi[:3].tolist() == [1e-9, 2.0, 1e-9] and np.isnan(hi[3])
+    assert lo[:3].tolist() == [0.0, 1e-9, -1.0] and np.isnan(lo[3])
+
+
+def test_masked_mean_pooling_is_the_mean_over_unmasked_tokens():
+    w = configs.masked_mean_pooling(B=4, S=9, D=6)
+    out = dag.run(w.text, w.inputs)[0]
+    h = dag.upconvert(w.inputs[1], "bf16")
+    assert out.shape == (4, 6)
+    for b, n in enumerate(w.meta["lens"]):
+        if n == 0:
+            np.testing.assert_array_equal(out[b], 0.0)           # 0 / max(0, 1e-9)
+        else:
+            np.testing.assert_allclose(out[b], h[b, :n].mean(axis=0), rtol=1e-14, atol=1e-16)
+    assert w.meta["lens"][0] == 0 and max(w.meta["lens"]) > 1

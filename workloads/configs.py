@@ -175,3 +175,23 @@ def roll_slice_add_layernorm(S=133, SC=128, C=96, shift=3, dtype="bf16", seed=5)
     isz = ITEMSIZE[dtype]
     w.algorithmic_bytes = isz * (SC * SC * C * 4 + 2 * C)
     return w
+
+
+def masked_mean_pooling(B=32, S=512, D=1024, seed=6):
+    """The paper's Case 2 subgraph: out[b,d] = sum_s h[b,s,d] m[b,s,d] / max(sum_s m[b,s,d], 1e-9),
+    hidden states bf16, mask fp32 (0/1 per token, expanded over d), output fp32 [B,D]."""
+    g = Builder()
+    m = g.input("f32", (B, S, D))
+    h = g.input("bf16", (B, S, D))
+    num = g.op("sum", [g.op("mul", [h, m], "f32")], "f32", dim=-2, keepdim=0)
+    den = g.op("sum", [m], "f32", dim=-2, keepdim=0)
+    out = g.op("div", [num, g.op("maximum", [den, g.const(1e-9, "f32")], "f32")], "f32")
+    g.output(out)
+    # token lengths vary per sequence; one sequence is fully masked (denominator clamps)
+    lens = [0] + [1 + rng.randint(seed, 99, b, 0, S) for b in range(1, B)]
+    mask = np.zeros((B, S, D), np.float32)
+    for b, n in enumerate(lens):
+        mask[b, :n, :] = 1.0
+    ins = [mask, _tensor(seed, 1, (B, S, D), "bf16")]
+    return Workload("masked_mean_pooling_B%d_S%d_D%d" % (B, S, D), g.text(), ins, ["f32", "bf16"], [(B, S, D)] * 2,
+                    ["f32"], [(B, D)], meta={"lens": lens}).finish()
