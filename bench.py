@@ -232,6 +232,7 @@ def per_config_table(torch, pf, configs, Runner, alloc_outputs, stream, w3, fuse
     table["cfg1_add_layernorm"] = entry(configs.cfg1_add_layernorm(), 4)        # launch-bound either way
     # the paper's Case 1 at its D96 route (roll + slice + add + LayerNorm, two outputs, bf16)
     table["case1_roll_slice_add_layernorm_D96"] = entry(configs.roll_slice_add_layernorm(), 40)
+    table["case2_masked_mean_pooling"] = entry(configs.masked_mean_pooling(), 6)   # 6 x 101 MB
     return table
 
 

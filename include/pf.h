@@ -62,7 +62,8 @@ typedef enum {
     PF_OP_SIGMOID,   /* 1 / (1 + exp(-x))                                        */
     PF_OP_GELU,      /* attr approx=tanh (default) | erf                         */
     PF_OP_RSQRT,     /* 1 / sqrt(x)                                              */
-    PF_OP_SUM, PF_OP_MAX, PF_OP_MEAN,   /* attr keepdim=1|0; max propagates NaN  */
+    PF_OP_SUM, PF_OP_MAX, PF_OP_MEAN,   /* attrs keepdim=1|0, dim=-1|-2 (which dim is reduced;
+                                           -2 is the sequence dim of the paper's Case 2); max propagates NaN */
     PF_OP_VAR,       /* mean((x-mean)^2) * n/(n-correction); attr correction=0   */
     PF_OP_TRANSPOSE, /* swaps the last two dims                                  */
     PF_OP_ROT_PAIRS, /* out[2i] = -x[2i+1], out[2i+1] = x[2i] on the last dim    */
@@ -70,6 +71,7 @@ typedef enum {
                         (the roll of the paper's Case 1); folded into the loads of its consumer */
     PF_OP_SLICE,     /* attrs dim=<int>, start=<int>, stop=<int>: x[start:stop] along dim;
                         folded into the loads of its consumer                     */
+    PF_OP_MAXIMUM, PF_OP_MINIMUM,   /* element-wise, NaN-propagating; clamp(x, min=c) = maximum(x, c) */
     PF_OP_COUNT_
 } pf_op;
 
@@ -130,7 +132,8 @@ typedef struct {
     int tune_row_lanes;    /* row templates: lanes per row (power of two)                         */
     int tune_row_unroll;   /* row templates: rows in flight per team of lanes                     */
     int tune_flat_unroll;  /* ew_flat: 16-byte vectors per lane                                   */
-    int reserved[3];       /* must be zero */
+    int tune_col_block;    /* col_reduce: lanes per workgroup (power of two, 64..1024)             */
+    int reserved[2];       /* must be zero */
 } pf_options;
 
 void pf_options_default(pf_options* h_opt);
@@ -140,7 +143,7 @@ void pf_options_default(pf_options* h_opt);
 pf_status pf_compile(const pf_graph* g, const pf_options* h_opt, pf_exec** e);
 void      pf_exec_destroy(pf_exec* e);
 
-typedef enum { PF_T_EW_FLAT = 0, PF_T_ROW_RESIDENT = 1, PF_T_TILE = 2, PF_T_ROW_LOOP = 3 } pf_template;
+typedef enum { PF_T_EW_FLAT = 0, PF_T_ROW_RESIDENT = 1, PF_T_TILE = 2, PF_T_ROW_LOOP = 3, PF_T_COL_REDUCE = 4 } pf_template;
 
 typedef struct {
     int      n_kernels;          /* number of kernel launches per pf_execute              */

@@ -17,8 +17,8 @@ F32, BF16, F64 = 0, 1, 2
 DTYPES = {"f32": F32, "bf16": BF16, "f64": F64}
 DTYPE_NAMES = {v: k for k, v in DTYPES.items()}
 OPS = ["input", "const", "add", "sub", "mul", "div", "exp", "tanh", "sigmoid", "gelu", "rsqrt",
-       "sum", "max", "mean", "var", "transpose", "rot_pairs", "roll", "slice"]
-TEMPLATES = ["ew_flat", "row_resident", "tile", "row_loop"]
+       "sum", "max", "mean", "var", "transpose", "rot_pairs", "roll", "slice", "maximum", "minimum"]
+TEMPLATES = ["ew_flat", "row_resident", "tile", "row_loop", "col_reduce"]
 
 
 class PfError(RuntimeError):
@@ -33,7 +33,8 @@ class _Attr(C.Structure):
 
 class _Options(C.Structure):
     _fields_ = [("fuse", C.c_int), ("intermediates_f32", C.c_int), ("tune_row_lanes", C.c_int),
-                ("tune_row_unroll", C.c_int), ("tune_flat_unroll", C.c_int), ("reserved", C.c_int * 3)]
+                ("tune_row_unroll", C.c_int), ("tune_flat_unroll", C.c_int), ("tune_col_block", C.c_int),
+                ("reserved", C.c_int * 2)]
 
 
 class _NodeInfo(C.Structure):

@@ -11,6 +11,9 @@
 //                 kernel makes three passes over the row instead)
 //   TILE          groups that read a tensor through a swap of its last two
 //                 dims; 64x64 tiles staged through LDS
+//   COL_REDUCE    reductions over the second-to-last dim (pooling over the
+//                 sequence dim, the paper's Case 2) with an elementwise
+//                 prologue and an epilogue on the reduced shape
 #include <cmath>
 #include <cstring>
 #include <set>
@@ -30,6 +33,8 @@ struct Emit {
     std::map<int, int> operand_of;       // node -> operand index (plain reads)
     std::map<int, int> toperand_of;      // node -> operand index (transposed reads)
     std::map<int, int> voperand_of;      // roll / slice node -> operand index (reads through its index map)
+    std::map<int, int> coperand_of;      // node -> operand index (reads of a column reduction's epilogue)
+    std::map<int, int> plan_kind;        // member node -> kind the planner gave it (3: column-uniform)
     std::set<int> members;
     std::map<int, int> kind;             // member/operand node -> 2 full, 1 row-uniform
     bool precise = false;
@@ -51,7 +56,10 @@ struct Emit {
     bool in_kernel(int p) const {
         if (!members.count(p)) return false;
         const Node& n = g.nodes[p];
-        return !(is_reduction(n.op) && !n.keepdim);
+        return !(is_reduction(n.op) && !n.keepdim && n.red_dim == -1);
+    }
+    bool epilogue_node(int id) const {
+        return grp.tmpl == PF_T_COL_REDUCE && plan_kind.at(id) == 3 && !is_reduction(g.nodes[id].op);
     }
 
     // Register layout of a value inside a lane: RU rows ("u") times NN slots ("j").
@@ -64,9 +72,8 @@ struct Emit {
     std::string ref(int consumer, int p, const std::string& j) const {
         const Node& n = g.nodes[p];
         if (n.op == PF_OP_CONST) return lit(n.value);
-        (void)consumer;
         if (in_kernel(p)) return kind.at(p) == 2 ? strf("v%d[%s]", p, slot(j).c_str()) : strf("s%d[u]", p);
-        int oi = is_view(n.op) ? voperand_of.at(p) : operand_of.at(p);
+        int oi = is_view(n.op) ? voperand_of.at(p) : epilogue_node(consumer) ? coperand_of.at(p) : operand_of.at(p);
         const bool h = hoisted.count(oi) != 0;
         if (operand_kind(oi) == 2) return h ? strf("x%d[%s]", oi, j.c_str()) : strf("x%d[%s]", oi, slot(j).c_str());
         return h ? strf("x%d[0]", oi) : strf("x%d[u]", oi);
@@ -75,6 +82,7 @@ struct Emit {
     // 2: varies along the last dim (array per lane); 1: uniform along it (scalar per row)
     int operand_kind(int oi) const {
         const Operand& o = grp.operands[oi];
+        if (o.coluni) return 1;               // one value per epilogue lane
         if (grp.tmpl == PF_T_TILE) return 2;
         if (grp.tmpl == PF_T_EW_FLAT && straddle) return 2;
         if (rd == 0) return 1;
@@ -88,6 +96,7 @@ struct Emit {
         const Node& n = g.nodes[id];
         if (is_reduction(n.op)) return 1;
         if (is_view(n.op)) return 2;
+        if (grp.tmpl == PF_T_COL_REDUCE) return plan_kind.at(id) == 3 ? 1 : 2;
         if (grp.tmpl != PF_T_ROW_RESIDENT && grp.tmpl != PF_T_ROW_LOOP) return 2;
         if (grp.cols == 1) return 2;
         // row-uniform iff every operand is
@@ -115,6 +124,8 @@ struct Emit {
                 case PF_OP_SIGMOID: return "pf_sigmoid(" + a(0) + ")";
                 case PF_OP_GELU: return std::string(n.gelu_erf ? "pf_gelu_erf(" : "pf_gelu_tanh(") + a(0) + ")";
                 case PF_OP_RSQRT: return "pf_rsqrt(" + a(0) + ")";
+                case PF_OP_MAXIMUM: return "pf_max_nan(" + a(0) + ", " + a(1) + ")";
+                case PF_OP_MINIMUM: return "pf_min_nan(" + a(0) + ", " + a(1) + ")";
                 default: fail(PF_E_COMPILE, "internal: %s is not elementwise", op_name(n.op));
             }
         };
@@ -540,6 +551,259 @@ struct Emit {
         line("}");
     }
 
+    // ================================================================ COL_REDUCE
+    // Domain [lead..., S, DD]; reductions run over S.  A workgroup of TX x TY
+    // lanes owns one leading index and W = TX*VEC adjacent columns: lane (tx, ty)
+    // walks rows ty, ty+TY, ... with 16-byte loads along DD (U rows in flight),
+    // applies the prologue and accumulates VEC columns in registers.  Partial
+    // sums meet by wave shuffles across ty, then in LDS across waves; lane c < W
+    // finishes column c: it evaluates the epilogue once and stores one element.
+    // A variance takes a second walk over the rows (mean first).
+    void gen_col() {
+        if (rd < 2) fail(PF_E_COMPILE, "internal: column reduction of rank < 2");
+        const int64_t S = grp.domain[rd - 2], DD = grp.domain[rd - 1];
+        int64_t L = 1;
+        for (int k = 0; k < rd - 2; ++k) L *= grp.domain[k];
+        const int nlead = rd - 2;
+        int min_item = 4, n_vec_ops = 0;
+        for (auto& o : grp.operands)
+            if (!o.coluni && o.stride[rd - 1] != 0) {
+                min_item = std::min(min_item, itemsize(o.dtype));
+                ++n_vec_ops;
+            }
+        for (auto& st : grp.stores)
+            if (!st.col_uniform) min_item = std::min(min_item, itemsize(st.dtype));
+        int vec = 16 / min_item;
+        while (vec > 1 && vec > DD) vec >>= 1;
+        const bool ragged = DD % vec != 0;
+        const int64_t vcols = (DD + vec - 1) / vec;
+        int TX = 1;
+        while (TX < 16 && TX < vcols) TX <<= 1;
+        if (opt.tune_row_lanes > 0) {
+            TX = opt.tune_row_lanes;
+            if (TX & (TX - 1) || TX > 64) fail(PF_E_INVALID, "tune_row_lanes must be a power of two <= 64 for column reductions");
+        }
+        const int64_t CT = (vcols + TX - 1) / TX;
+        const int64_t blocks = L * CT;
+        // lanes along S: enough workgroups x lanes to fill the chip, never more than rows
+        int TY = 1024 / TX;
+        while (TY > 1 && (TY / 2) * TX >= 64 && (TY > S || blocks * TX * TY > (int64_t)512 * 1024)) TY >>= 1;
+        if (opt.tune_col_block > 0) {
+            if (opt.tune_col_block & (opt.tune_col_block - 1) || opt.tune_col_block > 1024 || opt.tune_col_block < 64 || opt.tune_col_block < TX)
+                fail(PF_E_INVALID, "tune_col_block must be a power of two in [64, 1024], at least the lanes per row");
+            TY = opt.tune_col_block / TX;
+        }
+        auto lds_bytes = [&](int ty) { return (int64_t)n_red_slots() * ((int64_t)(TX * ty / 64) + 1) * TX * vec * (precise ? 8 : 4); };
+        while (TY > 1 && (TY / 2) * TX >= 64 && lds_bytes(TY) > 60 * 1024) TY >>= 1;
+        if (lds_bytes(TY) > 64 * 1024) fail(PF_E_COMPILE, "column reduction group needs %lld bytes of LDS", (long long)lds_bytes(TY));
+        const int block = TX * TY;
+        // rows in flight per lane; at least four trips of the row loop measured best (B=32, S=512, D=1024:
+        // 18.0 us with U = 2 against 18.9 us with U = 4 at 16 x 64 lanes)
+        int U = 4;
+        while (U > 1 && ((int64_t)U * TY * 4 > S || U * vec * std::max(n_vec_ops, 1) > 64)) U >>= 1;
+        if (opt.tune_row_unroll > 0) U = opt.tune_row_unroll;
+        RU = U;
+        NN = vec;
+        const int W = TX * vec, NW = block / 64;
+        grp.block = block;
+        grp.grid = blocks;
+        grp.lanes_per_row = TX;
+        grp.vec = vec;
+        grp.chunks_per_lane = U;
+        const char* acc = precise ? "double" : "float";
+
+        // reduction slots in LDS (a variance takes two: sum, then squared deviations)
+        std::map<int, int> slot_of;
+        int n_red = 0;
+        bool any_var = false;
+        for (int id : grp.nodes)
+            if (is_reduction(g.nodes[id].op)) {
+                slot_of[id] = n_red;
+                n_red += g.nodes[id].op == PF_OP_VAR ? 2 : 1;
+                any_var |= g.nodes[id].op == PF_OP_VAR;
+            }
+        // operands that do not change along S are loaded once
+        hoisted.clear();
+        for (size_t oi = 0; oi < grp.operands.size(); ++oi)
+            if (!grp.operands[oi].coluni && grp.operands[oi].stride[rd - 2] == 0) hoisted.insert((int)oi);
+
+        signature();
+        line(strf("    constexpr int TX = %d, TY = %d, VEC = %d, U = %d, W = %d, NW = %d, BLOCK = %d;", TX, TY, vec, U, W, NW, block));
+        line(strf("    constexpr %s S = %lld, DD = %lld, CT = %lld;", idx_t(), (long long)S, (long long)DD, (long long)CT));
+        line(strf("    __shared__ %s part[%d][NW][W];", acc, n_red));
+        line(strf("    __shared__ %s tot[%d][W];", acc, n_red));
+        line("    const int tx = threadIdx.x % TX, ty = threadIdx.x / TX, wave = threadIdx.x >> 6;");
+        line(strf("    const %s ct = blockIdx.x %% CT, lead = blockIdx.x / CT;", idx_t()));
+        line(strf("    const %s d0 = ct * W + (%s)tx * VEC;", idx_t(), idx_t()));
+        // lanes whose columns lie outside still take part in shuffles and barriers; they read column block 0
+        line(strf("    const bool col_ok = d0 < DD;"));
+        line(strf("    const %s dc = col_ok ? d0 : 0;", idx_t()));
+        emit_lead_decomposition("lead", nlead);
+        auto load_vec = [&](size_t oi, const std::string& off, const std::string& dst, const char* ind) {
+            const Operand& o = grp.operands[oi];
+            const bool nt = numel(o.shape) * itemsize(o.dtype) >= (int64_t(1) << 22);
+            if (ragged) {
+                line(strf("%sif (dc + VEC <= DD) pf_ld<VEC, %s, true>(p%zu + %s + dc, %s);", ind, nt ? "true" : "false", oi, off.c_str(), dst.c_str()));
+                line(strf("%selse { _Pragma(\"unroll\") for (int j = 0; j < VEC; ++j) (%s)[j] = pf_ld1(p%zu + %s + (dc + j < DD ? dc + j : DD - 1)); }", ind,
+                          dst.c_str(), oi, off.c_str()));
+            } else {
+                line(strf("%spf_ld<VEC, %s>(p%zu + %s + dc, %s);", ind, nt ? "true" : "false", oi, off.c_str(), dst.c_str()));
+            }
+        };
+        for (size_t oi = 0; oi < grp.operands.size(); ++oi) {
+            if (!hoisted.count((int)oi)) continue;
+            const Operand& o = grp.operands[oi];
+            std::string base = lead_offset_n(o, nlead);
+            if (o.stride[rd - 1] == 0) line(strf("    float x%zu[1]; x%zu[0] = pf_ld1(p%zu + %s);", oi, oi, oi, base.c_str()));
+            else {
+                line(strf("    float x%zu[VEC];", oi));
+                load_vec(oi, base, strf("x%zu", oi), "    ");
+            }
+        }
+        for (int pass = 0; pass < (any_var ? 2 : 1); ++pass) {
+            // accumulators of this pass
+            for (int id : grp.nodes) {
+                const Node& n = g.nodes[id];
+                if (!is_reduction(n.op)) continue;
+                if (pass == 0) {
+                    if (n.op == PF_OP_MAX) line(strf("    float a%d[VEC]; _Pragma(\"unroll\") for (int j = 0; j < VEC; ++j) a%d[j] = -__builtin_inff();", id, id));
+                    else line(strf("    %s a%d[VEC]; _Pragma(\"unroll\") for (int j = 0; j < VEC; ++j) a%d[j] = 0;", acc, id, id));
+                } else if (n.op == PF_OP_VAR) {
+                    line(strf("    %s mu%d[VEC], q%d[VEC];", acc, id, id));
+                    line(strf("    _Pragma(\"unroll\") for (int j = 0; j < VEC; ++j) { mu%d[j] = tot[%d][tx * VEC + j] / (%s)%lld; q%d[j] = 0; }", id,
+                              slot_of.at(id), acc, (long long)S, id));
+                }
+            }
+            line(strf("    for (%s sb = ty; sb < S; sb += (%s)TY * U) {   // pass %d", idx_t(), idx_t(), pass));
+            line(strf("        %s row[U]; bool row_ok[U];", idx_t()));
+            line(strf("        _Pragma(\"unroll\") for (int u = 0; u < U; ++u) { const %s t = sb + (%s)u * TY; row_ok[u] = t < S; row[u] = row_ok[u] ? t : S - 1; }",
+                      idx_t(), idx_t()));
+            for (size_t oi = 0; oi < grp.operands.size(); ++oi) {
+                const Operand& o = grp.operands[oi];
+                if (o.coluni || hoisted.count((int)oi)) continue;
+                std::string base = lead_offset_n(o, nlead);
+                if (o.stride[rd - 1] == 0) {
+                    line(strf("        float x%zu[U];", oi));
+                    line(strf("        _Pragma(\"unroll\") for (int u = 0; u < U; ++u) x%zu[u] = pf_ld1(p%zu + %s + row[u] * %lld);", oi, oi, base.c_str(),
+                              (long long)o.stride[rd - 2]));
+                } else {
+                    line(strf("        float x%zu[U * VEC];", oi));
+                    line("        _Pragma(\"unroll\") for (int u = 0; u < U; ++u) {");
+                    load_vec(oi, strf("%s + row[u] * %lld", base.c_str(), (long long)o.stride[rd - 2]), strf("&x%zu[u * VEC]", oi), "            ");
+                    line("        }");
+                }
+            }
+            for (int id : grp.nodes) {
+                const Node& n = g.nodes[id];
+                if (is_reduction(n.op)) {
+                    const std::string xj = ref(id, n.in[0], "j");
+                    const std::string open = "        _Pragma(\"unroll\") for (int u = 0; u < U; ++u) if (row_ok[u]) _Pragma(\"unroll\") for (int j = 0; j < VEC; ++j)";
+                    if (pass == 0) {
+                        if (n.op == PF_OP_MAX) line(open + strf(" a%d[j] = pf_max_nan(a%d[j], %s);", id, id, xj.c_str()));
+                        else line(open + strf(" a%d[j] += (%s)(%s);", id, acc, xj.c_str()));
+                    } else if (n.op == PF_OP_VAR) {
+                        line(open + strf(" { const %s d = (%s)(%s) - mu%d[j]; q%d[j] += d * d; }", acc, acc, xj.c_str(), id, id));
+                    }
+                    continue;
+                }
+                if (plan_kind.at(id) == 2) emit_elementwise(id, vec);
+            }
+            if (pass == 0) {
+                int sp = 0;
+                for (auto& st : grp.stores) {
+                    const int cnt = 1 + (int)st.also_outputs.size();
+                    if (!st.col_uniform)
+                        for (int c = 0; c < cnt; ++c) {
+                            const bool nt = numel(st.shape) * itemsize(st.dtype) >= (int64_t(1) << 22);
+                            line("        _Pragma(\"unroll\") for (int u = 0; u < U; ++u) if (row_ok[u] && col_ok) {");
+                            line(strf("            const %s o = (lead * S + row[u]) * DD + d0;", idx_t()));
+                            if (ragged) {
+                                line(strf("            if (d0 + VEC <= DD) pf_st<VEC, %s, true>(q%d + o, &v%d[u * VEC]);", nt ? "true" : "false", sp + c, st.node));
+                                line(strf("            else { _Pragma(\"unroll\") for (int j = 0; j < VEC; ++j) if (d0 + j < DD) pf_st1(q%d + o + j, v%d[u * VEC + j]); }",
+                                          sp + c, st.node));
+                            } else {
+                                line(strf("            pf_st<VEC, %s>(q%d + o, &v%d[u * VEC]);", nt ? "true" : "false", sp + c, st.node));
+                            }
+                            line("        }");
+                        }
+                    sp += cnt;
+                }
+            }
+            line("    }");
+            // combine: across ty inside a wave by shuffles, across waves in LDS
+            for (int id : grp.nodes) {
+                const Node& n = g.nodes[id];
+                if (!is_reduction(n.op)) continue;
+                if (pass == 1 && n.op != PF_OP_VAR) continue;
+                const int sl = slot_of.at(id) + pass;
+                const std::string a = strf(pass == 0 ? "a%d" : "q%d", id);
+                const bool mx = n.op == PF_OP_MAX;
+                line("    _Pragma(\"unroll\") for (int j = 0; j < VEC; ++j) {");
+                line(strf("        %s t = %s[j];", mx ? "float" : acc, a.c_str()));
+                if (TX < 64) {
+                    if (mx) line("        _Pragma(\"unroll\") for (int m = TX; m < 64; m <<= 1) t = pf_max_nan(t, __shfl_xor(t, m, 64));");
+                    else line("        _Pragma(\"unroll\") for (int m = TX; m < 64; m <<= 1) t += __shfl_xor(t, m, 64);");
+                }
+                line(strf("        if ((threadIdx.x & 63) < TX) part[%d][wave][tx * VEC + j] = t;", sl));
+                line("    }");
+            }
+            line("    __syncthreads();");
+            line("    for (int c = threadIdx.x; c < W; c += BLOCK) {");
+            for (int id : grp.nodes) {
+                const Node& n = g.nodes[id];
+                if (!is_reduction(n.op)) continue;
+                if (pass == 1 && n.op != PF_OP_VAR) continue;
+                const int sl = slot_of.at(id) + pass;
+                // with TX == 64 a wave holds one ty; otherwise 64 / TX of them, already combined
+                if (n.op == PF_OP_MAX) {
+                    line(strf("        { float t = (float)part[%d][0][c]; for (int w = 1; w < NW; ++w) t = pf_max_nan(t, (float)part[%d][w][c]); tot[%d][c] = t; }",
+                              sl, sl, sl));
+                } else {
+                    line(strf("        { %s t = part[%d][0][c]; for (int w = 1; w < NW; ++w) t += part[%d][w][c]; tot[%d][c] = t; }", acc, sl, sl, sl));
+                }
+            }
+            line("    }");
+            line("    __syncthreads();");
+        }
+        // epilogue: lane c finishes column c of this workgroup's W columns
+        RU = 1;
+        line("    for (int c = threadIdx.x; c < W; c += BLOCK) {");
+        line(strf("        const %s col = ct * W + c;", idx_t()));
+        line("        if (col >= DD) continue;");
+        line("        constexpr int u = 0; (void)u;");
+        for (int id : grp.nodes) {
+            const Node& n = g.nodes[id];
+            if (!is_reduction(n.op)) continue;
+            const int sl = slot_of.at(id);
+            if (n.op == PF_OP_SUM || n.op == PF_OP_MAX) line(strf("        float s%d[1]; s%d[0] = (float)tot[%d][c];", id, id, sl));
+            else if (n.op == PF_OP_MEAN) line(strf("        float s%d[1]; s%d[0] = (float)(tot[%d][c] / (%s)%lld);", id, id, sl, acc, (long long)S));
+            else line(strf("        float s%d[1]; s%d[0] = (float)(tot[%d][c] / (%s)%lld);", id, id, sl + 1, acc, (long long)(S - n.correction)));
+        }
+        for (size_t oi = 0; oi < grp.operands.size(); ++oi) {
+            const Operand& o = grp.operands[oi];
+            if (!o.coluni) continue;
+            line(strf("        float x%zu[1]; x%zu[0] = pf_ld1(p%zu + %s + col * %lld);", oi, oi, oi, lead_offset_n(o, nlead).c_str(),
+                      (long long)o.stride[rd - 1]));
+        }
+        for (int id : grp.nodes)
+            if (epilogue_node(id)) emit_elementwise(id, 1);
+        int sp = 0;
+        for (auto& st : grp.stores) {
+            const int cnt = 1 + (int)st.also_outputs.size();
+            if (st.col_uniform)
+                for (int c = 0; c < cnt; ++c) line(strf("        pf_st1(q%d + lead * DD + col, s%d[0]);", sp + c, st.node));
+            sp += cnt;
+        }
+        line("    }");
+        line("}");
+    }
+
+    int n_red_slots() const {
+        int n = 0;
+        for (int id : grp.nodes)
+            if (is_reduction(g.nodes[id].op)) n += g.nodes[id].op == PF_OP_VAR ? 2 : 1;
+        return n;
+    }
     int operand_kind_pre(const Operand& o) const { return rd > 0 && (o.stride[rd - 1] != 0 || grp.cols == 1) ? 2 : 1; }
 
     // ================================================================ EW_FLAT
@@ -892,8 +1156,10 @@ struct Emit {
     void run(int index) {
         rd = (int)grp.domain.size();
         for (int id : grp.nodes) members.insert(id);
+        for (size_t m = 0; m < grp.nodes.size(); ++m) plan_kind[grp.nodes[m]] = m < grp.node_kind.size() ? grp.node_kind[m] : 2;
         for (size_t oi = 0; oi < grp.operands.size(); ++oi) {
-            if (grp.operands[oi].view >= 0) voperand_of[grp.operands[oi].view] = (int)oi;
+            if (grp.operands[oi].coluni) coperand_of[grp.operands[oi].node] = (int)oi;
+            else if (grp.operands[oi].view >= 0) voperand_of[grp.operands[oi].view] = (int)oi;
             else if (grp.operands[oi].via_transpose) toperand_of[grp.operands[oi].node] = (int)oi;
             else operand_of[grp.operands[oi].node] = (int)oi;
         }
@@ -925,9 +1191,10 @@ struct Emit {
             case PF_T_EW_FLAT: gen_flat(); break;
             case PF_T_ROW_RESIDENT: gen_row(); break;
             case PF_T_TILE: gen_tile(); break;
+            case PF_T_COL_REDUCE: gen_col(); break;
             default: fail(PF_E_COMPILE, "template not implemented");
         }
-        std::string nm = grp.tmpl == PF_T_EW_FLAT ? "pf_ew" : grp.tmpl == PF_T_ROW_RESIDENT ? "pf_row" : grp.tmpl == PF_T_TILE ? "pf_tile" : "pf_loop";
+        std::string nm = grp.tmpl == PF_T_EW_FLAT ? "pf_ew" : grp.tmpl == PF_T_ROW_RESIDENT ? "pf_row" : grp.tmpl == PF_T_TILE ? "pf_tile" : grp.tmpl == PF_T_COL_REDUCE ? "pf_col" : "pf_loop";
         int shown = 0;
         for (int id : grp.nodes) {
             if (shown == 8) { nm += "_etc"; break; }

@@ -166,6 +166,11 @@ PF_DEV float pf_max_nan(float a, float b) {       // max that propagates NaN
     return (a != a) ? a : ((b != b) ? b : m);
 }
 
+PF_DEV float pf_min_nan(float a, float b) {       // min that propagates NaN
+    float m = fminf(a, b);
+    return (a != a) ? a : ((b != b) ? b : m);
+}
+
 // ---- reductions across the T lanes that share a row ----
 // T <= 64: the lanes are consecutive lanes of one wave.  T > 64: whole waves;
 // wave results meet in LDS (one slot set per call site, so one barrier each).

@@ -37,7 +37,7 @@ std::string strf(const char* fmt, ...) {
 
 static const char* kOpNames[PF_OP_COUNT_] = {
     "input", "const", "add", "sub", "mul", "div", "exp", "tanh", "sigmoid", "gelu",
-    "rsqrt", "sum", "max", "mean", "var", "transpose", "rot_pairs", "roll", "slice"};
+    "rsqrt", "sum", "max", "mean", "var", "transpose", "rot_pairs", "roll", "slice", "maximum", "minimum"};
 
 const char* op_name(pf_op op) { return (op >= 0 && op < PF_OP_COUNT_) ? kOpNames[op] : "?"; }
 
@@ -57,7 +57,9 @@ bool is_unary(pf_op op) {
     return op == PF_OP_EXP || op == PF_OP_TANH || op == PF_OP_SIGMOID || op == PF_OP_GELU || op == PF_OP_RSQRT ||
            op == PF_OP_ROT_PAIRS;
 }
-bool is_binary(pf_op op) { return op == PF_OP_ADD || op == PF_OP_SUB || op == PF_OP_MUL || op == PF_OP_DIV; }
+bool is_binary(pf_op op) {
+    return op == PF_OP_ADD || op == PF_OP_SUB || op == PF_OP_MUL || op == PF_OP_DIV || op == PF_OP_MAXIMUM || op == PF_OP_MINIMUM;
+}
 
 Shape broadcast_shapes(const Shape& a, const Shape& b) {
     size_t r = a.size() > b.size() ? a.size() : b.size();
@@ -131,6 +133,9 @@ int graph_add_node(pf_graph& g, pf_op op, const std::vector<int>& in,
             if (n.keepdim != 0 && n.keepdim != 1) fail(PF_E_COMPILE, "%%%d: keepdim must be 0 or 1", id);
         } else if (k == "correction" && op == PF_OP_VAR) {
             n.correction = parse_int_attr(k, v);
+        } else if (k == "dim" && is_reduction(op)) {
+            n.red_dim = parse_int_attr(k, v);
+            if (n.red_dim != -1 && n.red_dim != -2) fail(PF_E_COMPILE, "%%%d: reductions take dim=-1 or dim=-2", id);
         } else if (k == "dim" && is_view(op)) {
             n.dim = parse_int_attr(k, v);
             have_dim = true;
@@ -159,11 +164,13 @@ int graph_add_node(pf_graph& g, pf_op op, const std::vector<int>& in,
     } else if (is_reduction(op)) {
         const Shape& s = g.nodes[in[0]].shape;
         if (s.empty()) fail(PF_E_COMPILE, "%%%d: cannot reduce a scalar", id);
-        if (op == PF_OP_VAR && s.back() - n.correction <= 0)
-            fail(PF_E_COMPILE, "%%%d: var over %lld elements with correction %d", id, (long long)s.back(), n.correction);
+        if ((int)s.size() < -n.red_dim) fail(PF_E_COMPILE, "%%%d: dim %d needs rank >= %d", id, n.red_dim, -n.red_dim);
+        const size_t ax = s.size() + n.red_dim;
+        if (op == PF_OP_VAR && s[ax] - n.correction <= 0)
+            fail(PF_E_COMPILE, "%%%d: var over %lld elements with correction %d", id, (long long)s[ax], n.correction);
         n.shape = s;
-        if (n.keepdim) n.shape.back() = 1;
-        else n.shape.pop_back();
+        if (n.keepdim) n.shape[ax] = 1;
+        else n.shape.erase(n.shape.begin() + ax);
     } else if (op == PF_OP_TRANSPOSE) {
         const Shape& s = g.nodes[in[0]].shape;
         if (s.size() < 2) fail(PF_E_COMPILE, "%%%d: transpose needs rank >= 2", id);
@@ -342,8 +349,8 @@ std::string graph_print(const pf_graph& g) {
         out += ")";
         if (n.op == PF_OP_CONST) out += strf(" {value=%.17g}", n.value);
         else if (n.op == PF_OP_GELU) out += strf(" {approx=%s}", n.gelu_erf ? "erf" : "tanh");
-        else if (n.op == PF_OP_VAR) out += strf(" {correction=%d, keepdim=%d}", n.correction, n.keepdim);
-        else if (is_reduction(n.op)) out += strf(" {keepdim=%d}", n.keepdim);
+        else if (n.op == PF_OP_VAR) out += strf(" {correction=%d, keepdim=%d, dim=%d}", n.correction, n.keepdim, n.red_dim);
+        else if (is_reduction(n.op)) out += strf(" {keepdim=%d, dim=%d}", n.keepdim, n.red_dim);
         else if (n.op == PF_OP_ROLL) out += strf(" {shift=%lld, dim=%d}", (long long)n.shift, n.dim);
         else if (n.op == PF_OP_SLICE) out += strf(" {dim=%d, start=%lld, stop=%lld}", n.dim, (long long)n.start, (long long)n.stop);
         out += strf(" : %s\n", dtype_name(n.dtype));

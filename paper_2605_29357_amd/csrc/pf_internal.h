@@ -49,6 +49,7 @@ struct Node {
     int correction = 0;   // var
     int gelu_erf = 0;     // gelu: 0 tanh form, 1 erf form
     int dim = 0;          // roll, slice: normalised to [0, rank)
+    int red_dim = -1;     // reductions: -1 (last dim) or -2 (the dim before it)
     int64_t shift = 0;    // roll
     int64_t start = 0, stop = 0;   // slice
     bool is_output = false;
@@ -91,6 +92,7 @@ struct Operand {
     int64_t stride[PF_MAX_RANK] = {0, 0, 0, 0};
     bool transposed = false;  // read through a swap of the last two dims (data really moves)
     bool via_transpose = false;  // requested by a transpose node (even when it moves no data)
+    bool coluni = false;         // read by the epilogue of a column reduction (stride 0 along dim -2)
     // read through a chain of roll / slice nodes ending in node `view` (-1: read directly):
     // per domain dim the steps that turn the consumer's index into the source index
     int view = -1;
@@ -108,6 +110,7 @@ struct Store {
     pf_dtype dtype = PF_F32;
     Shape shape;
     bool row_scalar = false;   // one value per row of the domain
+    bool col_uniform = false;  // one value per (leading index, column): result of a reduction over dim -2
     int graph_output = -1;     // index into d_outputs, or
     int64_t ws_offset = -1;    // byte offset into the workspace
     std::vector<int> also_outputs;  // further graph-output slots receiving the same values
@@ -116,6 +119,7 @@ struct Store {
 struct Group {
     pf_template tmpl = PF_T_EW_FLAT;
     std::vector<int> nodes;        // members in topological order (const nodes folded in)
+    std::vector<int> node_kind;    // per member: 2 full, 1 row-uniform, 3 column-uniform
     Shape domain;                  // iteration domain, rank-aligned full shape
     int64_t rows = 1, cols = 1;    // product of leading dims, last dim
     std::vector<Operand> operands; // external reads

@@ -9,7 +9,10 @@
 //   - reductions over the last dim of a full value (their result is
 //     row-uniform and may be consumed inside the same kernel),
 //   - transposes of tensors that already sit in memory (read through a swap of
-//     the last two dims; the group then iterates in tiles).
+//     the last two dims; the group then iterates in tiles),
+//   - reductions over the second-to-last dim of a full value (the pooling over
+//     the sequence dim of the paper's Case 2) followed by an epilogue of
+//     elementwise nodes on the reduced ("column-uniform") shape.
 // Boundaries fall where the domain changes (a transpose of a value computed in
 // the same kernel, a broadcast that grows the shape) and where a reduction
 // would have to join a tiled group.  Groups are numbered in execution order;
@@ -37,6 +40,15 @@ Shape row_scalar_of(const Shape& d) {
     return canon(r);
 }
 
+// like canon, but keeps the two innermost dims: the domain of a reduction over dim -2
+Shape canon_min2(const Shape& s) {
+    size_t i = 0;
+    while (i + 2 < s.size() && s[i] == 1) ++i;
+    return Shape(s.begin() + i, s.end());
+}
+
+bool is_col_reduction(const Node& n) { return is_reduction(n.op) && n.red_dim == -2; }
+
 struct Builder {
     const pf_graph& g;
     const pf_options& opt;
@@ -46,12 +58,17 @@ struct Builder {
         pf_template tmpl;
         Shape domain;
         std::vector<int> nodes;
+        std::vector<int> kinds;                 // per member: 2 full, 1 row-uniform, 3 column-uniform
         bool has_rowuni = false;
+        bool has_view = false;                  // a member is, or reads through, a roll / slice
+        Shape epilogue;                         // COL_REDUCE: canonical shape of the column-uniform members
     };
+    std::vector<int> kind_of;                   // per node, kind inside its group
     std::vector<G> groups;
 
     Builder(const pf_graph& gr, const pf_options& o) : g(gr), opt(o) {
         group_of.assign(g.nodes.size(), -1);
+        kind_of.assign(g.nodes.size(), 0);
         consumers.resize(g.nodes.size());
         for (size_t i = 0; i < g.nodes.size(); ++i)
             for (int p : g.nodes[i].in) consumers[p].push_back((int)i);
@@ -76,9 +93,18 @@ struct Builder {
     // May a member of the group be read in-kernel by a consumer?  A reduction
     // with keepdim=0 has a shape that aligns differently under broadcasting,
     // so its consumers always read it back from memory.
+    // A reduction over dim -2 is only ever consumed in its kernel by nodes of its
+    // own reduced shape, for which alignment is not an issue.
     bool usable_in_kernel(int p) const {
         const Node& n = g.nodes[p];
-        return !(is_reduction(n.op) && !n.keepdim);
+        return !(is_reduction(n.op) && !n.keepdim && n.red_dim == -1);
+    }
+
+    bool reads_view(const Node& n) const {
+        if (is_view(n.op)) return true;
+        for (int p : n.in)
+            if (is_view(g.nodes[p].op)) return true;
+        return false;
     }
 
     bool can_join(int id, int gi) const {
@@ -87,6 +113,26 @@ struct Builder {
         if (grp.nodes.size() >= 60) return false;
         for (int p : n.in)
             if (group_of[p] == gi && !usable_in_kernel(p)) return false;
+        if (is_col_reduction(n)) {
+            // joins a flat elementwise prologue, or further reductions of the same domain
+            if (grp.tmpl != PF_T_EW_FLAT && grp.tmpl != PF_T_COL_REDUCE) return false;
+            if (grp.has_view || grp.has_rowuni || grp.domain.size() < 2) return false;
+            const int x = n.in[0];
+            if (group_of[x] == gi && kind_of[x] != 2) return false;
+            return canon(g.nodes[x].shape) == grp.domain;
+        }
+        if (grp.tmpl == PF_T_COL_REDUCE) {
+            if (reads_view(n) || n.op == PF_OP_TRANSPOSE || is_reduction(n.op) || n.op == PF_OP_ROT_PAIRS) return false;
+            bool on_reduced = false;
+            for (int p : n.in)
+                if (group_of[p] == gi && kind_of[p] == 3) on_reduced = true;
+            if (!on_reduced) return canon(n.shape) == grp.domain;      // prologue
+            // epilogue: everything it reads inside the kernel has the reduced shape, and so has the node
+            if (canon(n.shape) != grp.epilogue) return false;
+            for (int p : n.in)
+                if (group_of[p] == gi && (kind_of[p] != 3 || canon(g.nodes[p].shape) != grp.epilogue)) return false;
+            return true;
+        }
         if (is_view(n.op)) {
             // read through index arithmetic from the chain's root, which must already be in memory
             if (group_of[root_of(id)] == gi) return false;
@@ -120,16 +166,33 @@ struct Builder {
         G& grp = groups[gi];
         grp.nodes.push_back(id);
         group_of[id] = gi;
-        if (n.op == PF_OP_TRANSPOSE) grp.tmpl = PF_T_TILE;
-        if (is_reduction(n.op)) grp.tmpl = PF_T_ROW_RESIDENT;
-        if (kind_in(n, grp.domain) == 1 || is_reduction(n.op)) grp.has_rowuni = true;
+        int k = 2;
+        if (is_col_reduction(n)) {
+            if (grp.tmpl != PF_T_COL_REDUCE) grp.epilogue = canon(n.shape);
+            grp.tmpl = PF_T_COL_REDUCE;
+            k = 3;
+        } else if (grp.tmpl == PF_T_COL_REDUCE) {
+            for (int p : n.in)
+                if (group_of[p] == gi && kind_of[p] == 3) k = 3;
+        } else {
+            if (n.op == PF_OP_TRANSPOSE) grp.tmpl = PF_T_TILE;
+            if (is_reduction(n.op)) grp.tmpl = PF_T_ROW_RESIDENT;
+            if (kind_in(n, grp.domain) == 1 || is_reduction(n.op)) {
+                grp.has_rowuni = true;
+                k = 1;
+            }
+            if (reads_view(n)) grp.has_view = true;
+        }
+        kind_of[id] = k;
+        grp.kinds.push_back(k);
     }
 
     void seed(int id) {
         const Node& n = g.nodes[id];
         G grp;
         grp.tmpl = PF_T_EW_FLAT;
-        if (is_reduction(n.op)) grp.domain = canon(g.nodes[n.in[0]].shape);
+        if (is_col_reduction(n)) grp.domain = canon_min2(g.nodes[n.in[0]].shape);
+        else if (is_reduction(n.op)) grp.domain = canon(g.nodes[n.in[0]].shape);
         else grp.domain = canon(n.shape);
         groups.push_back(grp);
         join(id, (int)groups.size() - 1);
@@ -191,6 +254,7 @@ void make_plan(const pf_graph& g, const pf_options& opt, Plan& plan) {
         Group grp;
         grp.tmpl = bg.tmpl;
         grp.nodes = bg.nodes;
+        grp.node_kind = bg.kinds;
         grp.domain = bg.domain;
         grp.cols = bg.domain.empty() ? 1 : bg.domain.back();
         grp.rows = 1;
@@ -198,11 +262,23 @@ void make_plan(const pf_graph& g, const pf_options& opt, Plan& plan) {
         const int rd = (int)bg.domain.size();
 
         // external reads
-        auto add_operand = [&](int p, bool transposed) {
+        // Column-uniform members line up with the domain minus its dim -2; an operand
+        // of theirs gets stride 0 there.  `epi_keep`: they carry that dim with size 1.
+        const bool is_col = bg.tmpl == PF_T_COL_REDUCE;
+        Shape dom_keep = bg.domain, dom_drop = bg.domain;
+        bool epi_keep = true;
+        if (is_col) {
+            dom_keep[rd - 2] = 1;
+            dom_drop.erase(dom_drop.begin() + (rd - 2));
+            epi_keep = bg.epilogue == canon(dom_keep);
+            if (!epi_keep && bg.epilogue != canon(dom_drop)) fail(PF_E_COMPILE, "internal: epilogue shape of a column reduction");
+        }
+        auto add_operand = [&](int p, bool transposed, bool coluni = false) {
             for (auto& o : grp.operands)
-                if (o.node == p && o.via_transpose == transposed) return;
+                if (o.node == p && o.via_transpose == transposed && o.coluni == coluni) return;
             Operand o;
             o.node = p;
+            o.coluni = coluni;
             o.transposed = transposed;
             o.via_transpose = transposed;
             o.shape = g.nodes[p].shape;
@@ -243,11 +319,27 @@ void make_plan(const pf_graph& g, const pf_options& opt, Plan& plan) {
                     return;
                 }
             }
+            if (coluni && !epi_keep) {
+                // right-align against the domain without dim -2, then skip over that dim
+                const int re = rd - 1;
+                if ((int)s.size() > re) fail(PF_E_COMPILE, "internal: operand %%%d rank exceeds the reduced domain", p);
+                int64_t st = 1;
+                for (int j = (int)s.size() - 1; j >= 0; --j) {
+                    const int ke = re - ((int)s.size() - j);
+                    if (s[j] != 1 && s[j] != dom_drop[ke])
+                        fail(PF_E_COMPILE, "internal: operand %%%d does not broadcast into the reduced domain", p);
+                    o.stride[ke < rd - 2 ? ke : rd - 1] = s[j] == 1 ? 0 : st;
+                    st *= s[j];
+                }
+                grp.operands.push_back(o);
+                return;
+            }
+            const Shape& dom = coluni ? dom_keep : bg.domain;
             if ((int)s.size() > rd) fail(PF_E_COMPILE, "internal: operand %%%d rank exceeds domain", p);
             int64_t st = 1;
             for (int j = (int)s.size() - 1; j >= 0; --j) {
                 int k = rd - ((int)s.size() - j);
-                if (s[j] != 1 && s[j] != bg.domain[k])
+                if (s[j] != 1 && s[j] != dom[k])
                     fail(PF_E_COMPILE, "internal: operand %%%d does not broadcast into the domain", p);
                 o.stride[k] = s[j] == 1 ? 0 : st;
                 st *= s[j];
@@ -312,24 +404,27 @@ void make_plan(const pf_graph& g, const pf_options& opt, Plan& plan) {
             }
             grp.operands.push_back(o);
         };
-        for (int id : bg.nodes) {
+        for (size_t m = 0; m < bg.nodes.size(); ++m) {
+            const int id = bg.nodes[m];
             const Node& n = g.nodes[id];
             if (is_view(n.op)) {
                 add_view_operand(id);
                 continue;
             }
+            const bool epilogue_node = is_col && bg.kinds[m] == 3 && !is_reduction(n.op);
             for (int p : n.in) {
                 if (g.nodes[p].op == PF_OP_CONST) continue;
                 bool inside = b.group_of[p] == (int)gi && b.usable_in_kernel(p);
                 if (n.op == PF_OP_TRANSPOSE) add_operand(p, true);
                 else if (inside) continue;
                 else if (is_view(g.nodes[p].op)) add_view_operand(p);
-                else add_operand(p, false);
+                else add_operand(p, false, epilogue_node);
             }
         }
 
         // writes: members that are graph outputs or read by another kernel
-        for (int id : bg.nodes) {
+        for (size_t m = 0; m < bg.nodes.size(); ++m) {
+            const int id = bg.nodes[m];
             const Node& n = g.nodes[id];
             bool outside_use = false;
             for (int c : b.consumers[id]) {
@@ -346,13 +441,15 @@ void make_plan(const pf_graph& g, const pf_options& opt, Plan& plan) {
                 for (size_t q = 0; q < g.nodes.size() && !outside_use; ++q)
                     if (is_view(g.nodes[q].op) && b.root_of((int)q) == id) outside_use = true;
             if (!n.is_output && !outside_use) continue;
-            const bool row_scalar = is_reduction(n.op) || (b.kind_in(n, bg.domain) == 1);
+            const bool col_uniform = is_col && bg.kinds[m] == 3;
+            const bool row_scalar = !is_col && (is_reduction(n.op) || (b.kind_in(n, bg.domain) == 1));
             if (n.is_output) {
                 Store s;
                 s.node = id;
                 s.dtype = n.dtype;
                 s.shape = n.shape;
                 s.row_scalar = row_scalar;
+                s.col_uniform = col_uniform;
                 s.graph_output = output_slot[id];
                 for (size_t k = 0; k < g.outputs.size(); ++k)
                     if (g.outputs[k] == id && (int)k != output_slot[id]) s.also_outputs.push_back((int)k);
@@ -368,6 +465,7 @@ void make_plan(const pf_graph& g, const pf_options& opt, Plan& plan) {
                 s.dtype = opt.intermediates_f32 ? PF_F32 : n.dtype;
                 s.shape = n.shape;
                 s.row_scalar = row_scalar;
+                s.col_uniform = col_uniform;
                 s.ws_offset = (int64_t)ws;
                 ws_off[id] = (int64_t)ws;
                 mem_dtype[id] = s.dtype;

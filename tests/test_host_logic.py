@@ -33,7 +33,8 @@ def test_struct_layouts_match_the_header():
 
 def test_text_round_trip_and_shape_inference_agree_with_the_oracle_reader():
     for w in [configs.cfg1_add_layernorm(rows=4, cols=8), configs.cfg2_masked_softmax(heads=2, seq=8),
-              configs.cfg3_bias_gelu_gate(rows=4, cols=8), configs.cfg4_rmsnorm_rope(1, 4, 2, 8)] + \
+              configs.cfg3_bias_gelu_gate(rows=4, cols=8), configs.cfg4_rmsnorm_rope(1, 4, 2, 8),
+              configs.roll_slice_add_layernorm(S=9, SC=6, C=8), configs.masked_mean_pooling(B=2, S=5, D=8)] + \
              [dags.cfg5(k, max_rows=4) for k in range(0, 256, 17)]:
         g = pf.Graph(w.text)
         t1 = g.text()
@@ -80,6 +81,10 @@ def test_node_by_node_construction_equals_parsing():
     ("in %0 : f32[4]\n%1 = const() : f32\n", "value"),
     ("in %0 : f32[4]\n%1 = exp(%0) : f32\n", "no outputs"),
     ("in %0 : f32[4]\nout %0\n", "graph input"),
+    ("in %0 : f32[4,6]\n%1 = sum(%0) {dim=-3} : f32\nout %1\n", "dim=-1 or dim=-2"),
+    ("in %0 : f32[6]\n%1 = sum(%0) {dim=-2} : f32\nout %1\n", "rank"),
+    ("in %0 : f32[1,6]\n%1 = var(%0) {dim=-2, correction=1} : f32\nout %1\n", "correction"),
+    ("in %0 : f32[4]\n%1 = maximum(%0) : f32\nout %1\n", "takes 2"),
 ])
 def test_ill_formed_graphs_are_compile_errors(text, frag):
     with pytest.raises(pf.PfError) as e:
@@ -200,3 +205,29 @@ def test_ill_formed_views_are_compile_errors(text, frag):
     with pytest.raises(pf.PfError) as e:
         pf.Exec(text)
     assert e.value.status == pf.PF_E_COMPILE and frag in str(e.value)
+
+
+def test_case_2_pooling_over_the_sequence_dim_is_one_column_reduction_kernel():
+    w = configs.masked_mean_pooling(B=4, S=64, D=256)
+    e = pf.Exec(w.text)
+    assert e.info()["n_kernels"] == 1 and e.info()["workspace_bytes"] == 0
+    assert e.info()["planned_bytes"] == w.algorithmic_bytes
+    gi = e.group_info(0)
+    assert gi["template"] == "col_reduce" and len(gi["nodes"]) == 5
+    src = e.source(0)
+    assert "S = 64" in src and "DD = 256" in src and "pf_max_nan" in src and "double a" in src    # fp32 output: fp64 accumulators
+    assert pf.Exec(w.text, fuse=False).info()["n_kernels"] == 5
+    g = pf.Graph(w.text)
+    assert "dim=-2" in g.text() and g.node_info(3)["shape"] == (4, 256)
+    # a full-shape consumer of the reduced value cannot stay in the kernel
+    b = Builder()
+    x = b.input("f32", (8, 16))
+    m = b.op("mean", [x], "f32", dim=-2, keepdim=1)
+    b.output(b.op("sub", [x, m], "f32"))
+    assert [gi["template"] for gi in pf.Exec(b.text()).groups()] == ["col_reduce", "ew_flat"]
+    # reductions over different dims of the same tensor do not share a kernel
+    b = Builder()
+    x = b.input("f32", (8, 16))
+    b.output(b.op("sum", [x], "f32", dim=-2))
+    b.output(b.op("sum", [x], "f32"))
+    assert sorted(gi["template"] for gi in pf.Exec(b.text()).groups()) == ["col_reduce", "row_resident"]
