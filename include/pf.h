@@ -131,7 +131,7 @@ typedef struct {
     /* tiling overrides for experiments; 0 = let the planner choose from the shape */
     int tune_row_lanes;    /* row templates: lanes per row (power of two)                         */
     int tune_row_unroll;   /* row templates: rows in flight per team of lanes                     */
-    int tune_flat_unroll;  /* ew_flat: 16-byte vectors per lane                                   */
+    int tune_flat_unroll;  /* ew_flat: 16-byte vectors per lane; tile: consecutive tiles per XCD  */
     int tune_col_block;    /* col_reduce: lanes per workgroup (power of two, 64..1024)             */
     int reserved[2];       /* must be zero */
 } pf_options;

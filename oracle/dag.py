@@ -98,12 +98,20 @@ def parse(text):
 
 
 def upconvert(arr, dtype, to=np.float64):
-    """Exact widening of stored bits ('f32' float32 array, 'bf16' uint16 bits)."""
+    """Exact widening of stored bits ('f32' float32 array; 'bf16' and 'f16' uint16 bits)."""
     if dtype == "f32":
         return np.asarray(arr, dtype=np.float32).astype(to)
     if dtype == "bf16":
         u = np.asarray(arr, dtype=np.uint16).astype(np.uint32) << np.uint32(16)
         return u.view(np.float32).astype(to)
+    if dtype == "f16":
+        # IEEE binary16: sign, 5 exponent bits (bias 15), 10 fraction bits
+        u = np.asarray(arr, dtype=np.uint16).astype(np.int64)
+        ex, frac = (u >> 10) & 31, u & 1023
+        mag = np.where(ex == 0, np.ldexp(frac.astype(np.float64), -24),                     # zero and subnormals
+                       np.ldexp((1024 + frac).astype(np.float64), (ex - 25).astype(np.int32)))
+        mag = np.where(ex == 31, np.where(frac == 0, np.inf, np.nan), mag)
+        return np.where((u >> 15) == 1, -mag, mag).astype(to)
     raise ValueError(dtype)
 
 

@@ -21,7 +21,7 @@ from .dag import upconvert
 
 
 def score_pair(cand, cand_dtype, ref, ref_dtype, rtol, atol, equal_nan=False):
-    """cand/ref: stored arrays ('f32' float32, 'bf16' uint16 bits, 'f64' float64)."""
+    """cand/ref: stored arrays ('f32' float32, 'bf16' / 'f16' uint16 bits, 'f64' float64)."""
     a = _widen(cand, cand_dtype).ravel()
     b = _widen(ref, ref_dtype).ravel()
     if a.size != b.size:

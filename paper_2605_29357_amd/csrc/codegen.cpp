@@ -920,7 +920,16 @@ struct Emit {
         for (int k = 0; k < rd - 2; ++k) L *= grp.domain[k];
         const int64_t tr = (R + 63) / 64, tc = (C + 63) / 64;
         grp.block = 256;
-        grp.grid = L * tr * tc;
+        // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Runs of G consecutive
+        // tiles go to the same XCD, so tiles that share cache lines (rows whose length is no multiple
+        // of a line) meet in one L2 instead of being fetched and written back twice, while the XCDs
+        // still work on neighbouring regions (one long run per XCD put them a power-of-two stride
+        // apart on square shapes and cost 15%).
+        const int64_t tiles = L * tr * tc;
+        const int G = opt.tune_flat_unroll > 0 ? opt.tune_flat_unroll : 16;   // 8...32 measured within 4% of each other
+        const bool xcd_remap = tiles >= 64 && G > 1;
+        const int64_t rounds = (tiles + 8 * G - 1) / (8 * G);
+        grp.grid = xcd_remap ? rounds * 8 * G : tiles;
         grp.vec = 4;
         grp.chunks_per_lane = 4;
         grp.lanes_per_row = 0;
@@ -933,7 +942,13 @@ struct Emit {
         line(strf("    constexpr %s C = %lld, R = %lld, TR = %lld, TC = %lld;", idx_t(), (long long)C, (long long)R, (long long)tr,
                   (long long)tc));
         line(strf("    __shared__ float tile[%d][64][65];", std::max(n_t, 1)));
-        line(strf("    const %s b = blockIdx.x;", idx_t()));
+        if (xcd_remap) {
+            line(strf("    const %s slot = blockIdx.x / 8;", idx_t()));
+            line(strf("    const %s b = ((slot / %d) * 8 + blockIdx.x %% 8) * %d + slot %% %d;", idx_t(), G, G, G));
+            line(strf("    if (b >= %lld) return;", (long long)tiles));
+        } else {
+            line(strf("    const %s b = blockIdx.x;", idx_t()));
+        }
         line(strf("    const %s tcol = b %% TC, trow = (b / TC) %% TR, lead = b / (TC * TR);", idx_t()));
         line(strf("    const %s r0 = trow * 64, c0 = tcol * 64;", idx_t()));
         line("    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;");
@@ -951,7 +966,9 @@ struct Emit {
             if (vec_ok) {
                 line(strf("        if (cc < C && rr < R) pf_ld<4, false>(p%zu + %s + cc * R + rr, t4);", oi, base.c_str()));
             } else {
-                line(strf("        if (cc < C) { _Pragma(\"unroll\") for (int j = 0; j < 4; ++j) if (rr + j < R) t4[j] = pf_ld1(p%zu + %s + cc * R + rr + j); }",
+                // rows of a length that is no multiple of four: full vectors at element alignment, scalars at the row end
+                line(strf("        if (cc < C && rr + 4 <= R) pf_ld<4, false, true>(p%zu + %s + cc * R + rr, t4);", oi, base.c_str()));
+                line(strf("        else if (cc < C) { _Pragma(\"unroll\") for (int j = 0; j < 4; ++j) if (rr + j < R) t4[j] = pf_ld1(p%zu + %s + cc * R + rr + j); }",
                           oi, base.c_str()));
             }
             line(strf("        _Pragma(\"unroll\") for (int j = 0; j < 4; ++j) tile[%d][ty + 16 * i][tx * 4 + j] = t4[j];", ti));
@@ -981,6 +998,10 @@ struct Emit {
                           mapexpr(o, rd - 2, "rc").c_str(), (long long)sr, oi));
                 line(strf("        else { _Pragma(\"unroll\") for (int j = 0; j < 4; ++j) x%zu[i * 4 + j] = 0.0f; }", oi));
             } else {
+                const bool ua_ok = sc == 1 && !o.mapped(rd - 1);     // contiguous along the row, merely not 16-byte aligned
+                if (ua_ok)
+                    line(strf("        if (cc + 4 <= C) pf_ld<4, false, true>(p%zu + %s + %s * %lld + cc, &x%zu[i * 4]); else", oi, base.c_str(),
+                              mapexpr(o, rd - 2, "rc").c_str(), (long long)sr, oi));
                 line("        _Pragma(\"unroll\") for (int j = 0; j < 4; ++j) {");
                 line(strf("            const %s cj = cc + j < C ? cc + j : C - 1;", idx_t()));
                 line(strf("            x%zu[i * 4 + j] = pf_ld1(p%zu + %s + %s * %lld + %s * %lld);", oi, oi, base.c_str(),
@@ -999,9 +1020,11 @@ struct Emit {
                 line(strf("        const %s rr = r0 + ty + 16 * i, cc = c0 + tx * 4;", idx_t()));
                 line(strf("        const %s o = (lead * R + rr) * C + cc;", idx_t()));
                 if (st_vec) line(strf("        if (rr < R && cc < C) pf_st<4, false>(q%d + o, &v%d[i * 4]);", sp, st.node));
-                else
-                    line(strf("        if (rr < R) { _Pragma(\"unroll\") for (int j = 0; j < 4; ++j) if (cc + j < C) pf_st1(q%d + o + j, v%d[i * 4 + j]); }",
+                else {
+                    line(strf("        if (rr < R && cc + 4 <= C) pf_st<4, false, true>(q%d + o, &v%d[i * 4]);", sp, st.node));
+                    line(strf("        else if (rr < R) { _Pragma(\"unroll\") for (int j = 0; j < 4; ++j) if (cc + j < C) pf_st1(q%d + o + j, v%d[i * 4 + j]); }",
                               sp, st.node));
+                }
                 line("    }");
             }
         }

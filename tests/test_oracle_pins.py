@@ -11,7 +11,7 @@ import numpy as np
 import pytest
 
 from oracle import dag
-from workloads import configs
+from workloads import configs, rng
 from workloads.irtext import Builder
 
 
@@ -450,3 +450,58 @@ def test_masked_mean_pooling_is_the_mean_over_unmasked_tokens():
         else:
             np.testing.assert_allclose(out[b], h[b, :n].mean(axis=0), rtol=1e-14, atol=1e-16)
     assert w.meta["lens"][0] == 0 and max(w.meta["lens"]) > 1
+
+
+# ---- IEEE binary16 storage (fp16 task instances) ----
+
+def test_fp16_widening_matches_hand_decoded_patterns_and_every_pattern_of_the_library_type():
+    u = np.array([0x3C00, 0x3C01, 0x7BFF, 0x0001, 0x03FF, 0x0400, 0xC000, 0x7C00, 0xFC00, 0x8000, 0x3555], np.uint16)
+    got = dag.upconvert(u, "f16")
+    want = [1.0, 1.0 + 2.0 ** -10, 65504.0, 2.0 ** -24, 1023 * 2.0 ** -24, 2.0 ** -14, -2.0, np.inf, -np.inf, -0.0,
+            (1024 + 0x155) * 2.0 ** -12]
+    np.testing.assert_array_equal(got, want)
+    assert np.signbit(got[9]) and np.isnan(dag.upconvert(np.array([0x7E00, 0xFFFF], np.uint16), "f16")).all()
+    every = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    lib = every.view(np.float16).astype(np.float64)            # NumPy's own binary16 decoder
+    mine = dag.upconvert(every, "f16")
+    np.testing.assert_array_equal(np.isnan(mine), np.isnan(lib))
+    ok = ~np.isnan(lib)
+    np.testing.assert_array_equal(mine[ok], lib[ok])
+    np.testing.assert_array_equal(np.signbit(mine[ok]), np.signbit(lib[ok]))
+
+
+def test_fp16_storage_rounding_is_round_to_nearest_even_in_one_step():
+    r = rng.round_to_f16_bits
+    x = np.array([1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11, 1.0 + 2.0 ** -11 + 2.0 ** -40, 65519.999, 65520.0, 1e6, -1e6,
+                  2.0 ** -25, 2.0 ** -25 * (1 + 2.0 ** -30), 3 * 2.0 ** -25, 2.0 ** -14 - 2.0 ** -25, -0.0, 0.0, np.inf, -np.inf])
+    want = [0x3C00, 0x3C02, 0x3C01, 0x7BFF, 0x7C00, 0x7C00, 0xFC00,
+            0x0000, 0x0001, 0x0002, 0x0400, 0x8000, 0x0000, 0x7C00, 0xFC00]
+    assert r(x).tolist() == want                                # ties to even, overflow to inf, gradual underflow
+    assert r(np.array([np.nan]))[0] & 0x7C00 == 0x7C00 and r(np.array([np.nan]))[0] & 0x03FF != 0
+    # every finite binary16 value survives a round trip
+    every = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    vals = dag.upconvert(every, "f16")
+    fin = np.isfinite(vals)
+    np.testing.assert_array_equal(r(vals[fin]), every[fin])
+    # a double-rounding trap: 1 + 2^-11 + 2^-30 must round up although fp32 would first drop the 2^-30
+    assert r(np.array([1.0 + 2.0 ** -11 + 2.0 ** -30]))[0] == 0x3C01
+    # agreement with the library's conversion on a few thousand doubles across the range, and monotonicity
+    z = rng.normal(11, 0, 4096) * np.exp(rng.normal(11, 1, 4096) * 4.0)
+    with np.errstate(over="ignore"):
+        np.testing.assert_array_equal(r(z), z.astype(np.float16).view(np.uint16))
+    zs = np.sort(np.abs(z))
+    zs = zs[zs < 65000.0]
+    assert np.all(np.diff(dag.upconvert(r(zs), "f16")) >= 0)
+
+
+def test_fp16_graphs_are_evaluated_on_the_widened_bits():
+    w = configs.cfg3_bias_gelu_gate(rows=3, cols=8, dtype="f16")
+    a, bias, b = [dag.upconvert(t, "f16") for t in w.inputs]
+    u = a + bias
+    want = 0.5 * u * (1 + np.tanh(np.sqrt(2 / np.pi) * (u + 0.044715 * u ** 3))) * b
+    np.testing.assert_allclose(dag.run(w.text, w.inputs)[0], want, rtol=1e-14, atol=1e-300)
+    m = configs.causal_mask_bits(4, "f16")
+    assert np.isneginf(dag.upconvert(m, "f16")[0, 1]) and dag.upconvert(m, "f16")[1, 1] == 0.0
+    s = dag.run(configs.cfg2_masked_softmax(heads=1, seq=4, dtype="f16").text, configs.cfg2_masked_softmax(heads=1, seq=4, dtype="f16").inputs)[0]
+    np.testing.assert_allclose(s.sum(axis=-1), 1.0, rtol=1e-14)
+    assert s[0, 0, 0] == 1.0 and s[0, 0, 1] == 0.0

@@ -87,3 +87,20 @@ def test_signed_zeros_compare_equal_but_differ_in_bits():
 def test_empty_pair():
     r = score_pair(f32([]), "f32", f32([]), "f32", 0, 0)
     assert r["n"] == 0 and r["allclose"] == 1 and r["max_abs"] == 0 and r["bit_identical"] == 1
+
+
+def test_fp16_pairs_are_scored_on_the_widened_values():
+    # 0x4000 = 2.0, 0x4001 = 2 + 2^-9, 0x3C00 = 1.0, 0x7C00 = inf, 0x7E00 = NaN
+    cand = np.array([0x3C00, 0x4001, 0x3C00, 0x7C00, 0x7E00, 0x0001], np.uint16)
+    ref = np.array([0x3C00, 0x4000, 0xBC00, 0x7C00, 0x3C00, 0x0000], np.uint16)
+    r = score_pair(cand, "f16", ref, "f16", rtol=1e-3, atol=1e-5)
+    assert r["n"] == 6 and r["nan_cand"] == 1 and r["nan_ref"] == 0 and r["inf_cand"] == 1 and r["inf_ref"] == 1
+    assert r["max_abs"] == 2.0                      # 1 vs -1; the NaN element is left out of the maxima
+    assert r["max_rel"] == np.inf                   # 2^-24 against a zero reference
+    # violations: 2+2^-9 vs 2 (0.00195 > 1e-5 + 2e-3? no: allowed 0.00201) passes; 1 vs -1 fails; NaN fails;
+    # 2^-24 vs 0 passes on atol; equal infinities pass
+    assert r["n_viol"] == 2 and r["allclose"] == 0 and r["bit_identical"] == 0
+    same = score_pair(ref, "f16", ref, "f16", rtol=0.0, atol=0.0)
+    assert same["allclose"] == 1 and same["bit_identical"] == 1 and same["max_abs"] == 0.0
+    mixed = score_pair(np.array([0x4001], np.uint16), "f16", np.array([2.0], np.float32), "f32", rtol=0.0, atol=2.0 ** -9)
+    assert mixed["max_abs"] == 2.0 ** -9 and mixed["allclose"] == 1

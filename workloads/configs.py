@@ -12,10 +12,10 @@ import numpy as np
 from . import rng
 from .irtext import Builder
 
-ITEMSIZE = {"f32": 4, "bf16": 2}
+ITEMSIZE = {"f32": 4, "bf16": 2, "f16": 2}
 # comparison tolerances against the fp64 oracle, by dtype of the graph output
-RTOL = {"f32": 1e-5, "bf16": 2e-2}
-ATOL = {"f32": 1e-5, "bf16": 1e-5}
+RTOL = {"f32": 1e-5, "bf16": 2e-2, "f16": 1e-3}
+ATOL = {"f32": 1e-5, "bf16": 1e-5, "f16": 1e-5}
 
 
 @dataclass
@@ -70,43 +70,43 @@ def cfg1_add_layernorm(rows=64, cols=768, seed=0, use_var_op=False):
                     ["f32"], [(rows, cols)], meta={"eps": 1e-5}).finish()
 
 
-def causal_mask_bits(n):
-    """Additive causal mask [n, n] in bf16 bits: 0 on and below the diagonal, -inf above."""
+def causal_mask_bits(n, dtype="bf16"):
+    """Additive causal mask [n, n] as 16-bit patterns: 0 on and below the diagonal, -inf above."""
     m = np.zeros((n, n), dtype=np.uint16)
-    m[np.triu_indices(n, k=1)] = np.uint16(0xFF80)
+    m[np.triu_indices(n, k=1)] = np.uint16({"bf16": 0xFF80, "f16": 0xFC00}[dtype])
     return m
 
 
-def cfg2_masked_softmax(heads=32, seq=512, seed=1):
-    """Scaled, causally masked softmax over the last dim, bf16; scale = 1/sqrt(64)."""
+def cfg2_masked_softmax(heads=32, seq=512, seed=1, dtype="bf16"):
+    """Scaled, causally masked softmax over the last dim, bf16 (or fp16); scale = 1/sqrt(64)."""
     g = Builder()
-    z = g.input("bf16", (heads, seq, seq))
-    m = g.input("bf16", (seq, seq))
-    s = g.const(0.125, "bf16")
-    t = g.op("add", [g.op("mul", [z, s], "bf16"), m], "bf16")
-    mx = g.op("max", [t], "bf16")
-    e = g.op("exp", [g.op("sub", [t, mx], "bf16")], "bf16")
-    y = g.op("div", [e, g.op("sum", [e], "bf16")], "bf16")
+    z = g.input(dtype, (heads, seq, seq))
+    m = g.input(dtype, (seq, seq))
+    s = g.const(0.125, dtype)
+    t = g.op("add", [g.op("mul", [z, s], dtype), m], dtype)
+    mx = g.op("max", [t], dtype)
+    e = g.op("exp", [g.op("sub", [t, mx], dtype)], dtype)
+    y = g.op("div", [e, g.op("sum", [e], dtype)], dtype)
     g.output(y)
-    ins = [_tensor(seed, 0, (heads, seq, seq), "bf16", 0.0, 2.0), causal_mask_bits(seq)]
-    return Workload("cfg2_masked_softmax_bf16_%dx%dx%d" % (heads, seq, seq), g.text(), ins,
-                    ["bf16", "bf16"], [(heads, seq, seq), (seq, seq)],
-                    ["bf16"], [(heads, seq, seq)], meta={"scale": 0.125}).finish()
+    ins = [_tensor(seed, 0, (heads, seq, seq), dtype, 0.0, 2.0), causal_mask_bits(seq, dtype)]
+    return Workload("cfg2_masked_softmax_%s_%dx%dx%d" % (dtype, heads, seq, seq), g.text(), ins,
+                    [dtype, dtype], [(heads, seq, seq), (seq, seq)],
+                    [dtype], [(heads, seq, seq)], meta={"scale": 0.125}).finish()
 
 
-def cfg3_bias_gelu_gate(rows=8192, cols=11008, seed=2):
-    """out = gelu_tanh(a + bias) * b, bf16, bias broadcast over rows."""
+def cfg3_bias_gelu_gate(rows=8192, cols=11008, seed=2, dtype="bf16"):
+    """out = gelu_tanh(a + bias) * b, bf16 (or fp16), bias broadcast over rows."""
     g = Builder()
-    a = g.input("bf16", (rows, cols))
-    bias = g.input("bf16", (cols,))
-    b = g.input("bf16", (rows, cols))
-    y = g.op("mul", [g.op("gelu", [g.op("add", [a, bias], "bf16")], "bf16", approx="tanh"), b], "bf16")
+    a = g.input(dtype, (rows, cols))
+    bias = g.input(dtype, (cols,))
+    b = g.input(dtype, (rows, cols))
+    y = g.op("mul", [g.op("gelu", [g.op("add", [a, bias], dtype)], dtype, approx="tanh"), b], dtype)
     g.output(y)
-    ins = [_tensor(seed, 0, (rows, cols), "bf16"), _tensor(seed, 1, (cols,), "bf16", 0.0, 0.02),
-           _tensor(seed, 2, (rows, cols), "bf16")]
-    return Workload("cfg3_bias_gelu_gate_bf16_%dx%d" % (rows, cols), g.text(), ins,
-                    ["bf16"] * 3, [(rows, cols), (cols,), (rows, cols)],
-                    ["bf16"], [(rows, cols)]).finish()
+    ins = [_tensor(seed, 0, (rows, cols), dtype), _tensor(seed, 1, (cols,), dtype, 0.0, 0.02),
+           _tensor(seed, 2, (rows, cols), dtype)]
+    return Workload("cfg3_bias_gelu_gate_%s_%dx%d" % (dtype, rows, cols), g.text(), ins,
+                    [dtype] * 3, [(rows, cols), (cols,), (rows, cols)],
+                    [dtype], [(rows, cols)]).finish()
 
 
 def rotary_tables(positions, dim, base=10000.0):
@@ -123,26 +123,26 @@ def rotary_tables(positions, dim, base=10000.0):
     return cos.astype(np.float32), sin.astype(np.float32)
 
 
-def cfg4_rmsnorm_rope(batch=4, positions=2048, heads=32, dim=128, seed=3):
-    """Weighted RMSNorm over the last dim (eps = 1e-6) then rotary embedding, bf16."""
+def cfg4_rmsnorm_rope(batch=4, positions=2048, heads=32, dim=128, seed=3, dtype="bf16"):
+    """Weighted RMSNorm over the last dim (eps = 1e-6) then rotary embedding, bf16 (or fp16)."""
     g = Builder()
     shape = (batch, positions, heads, dim)
-    x = g.input("bf16", shape)
-    w = g.input("bf16", (dim,))
+    x = g.input(dtype, shape)
+    w = g.input(dtype, (dim,))
     cos = g.input("f32", (positions, 1, dim))
     sin = g.input("f32", (positions, 1, dim))
-    ms = g.op("mean", [g.op("mul", [x, x], "bf16")], "bf16")
+    ms = g.op("mean", [g.op("mul", [x, x], dtype)], dtype)
     eps = g.const(1e-6, "f32")
-    inv = g.op("rsqrt", [g.op("add", [ms, eps], "bf16")], "bf16")
-    n = g.op("mul", [g.op("mul", [x, inv], "bf16"), w], "bf16")
-    y = g.op("add", [g.op("mul", [n, cos], "bf16"),
-                     g.op("mul", [g.op("rot_pairs", [n], "bf16"), sin], "bf16")], "bf16")
+    inv = g.op("rsqrt", [g.op("add", [ms, eps], dtype)], dtype)
+    n = g.op("mul", [g.op("mul", [x, inv], dtype), w], dtype)
+    y = g.op("add", [g.op("mul", [n, cos], dtype),
+                     g.op("mul", [g.op("rot_pairs", [n], dtype), sin], dtype)], dtype)
     g.output(y)
     c, s = rotary_tables(positions, dim)
-    ins = [_tensor(seed, 0, shape, "bf16"), _tensor(seed, 1, (dim,), "bf16", 1.0, 0.1), c, s]
-    return Workload("cfg4_rmsnorm_rope_bf16_%dx%dx%dx%d" % shape, g.text(), ins,
-                    ["bf16", "bf16", "f32", "f32"], [shape, (dim,), (positions, 1, dim), (positions, 1, dim)],
-                    ["bf16"], [shape], meta={"eps": 1e-6, "base": 10000.0}).finish()
+    ins = [_tensor(seed, 0, shape, dtype), _tensor(seed, 1, (dim,), dtype, 1.0, 0.1), c, s]
+    return Workload("cfg4_rmsnorm_rope_%s_%dx%dx%dx%d" % ((dtype,) + shape), g.text(), ins,
+                    [dtype, dtype, "f32", "f32"], [shape, (dim,), (positions, 1, dim), (positions, 1, dim)],
+                    [dtype], [shape], meta={"eps": 1e-6, "base": 10000.0}).finish()
 
 
 def roll_slice_add_layernorm(S=133, SC=128, C=96, shift=3, dtype="bf16", seed=5):
@@ -177,12 +177,12 @@ def roll_slice_add_layernorm(S=133, SC=128, C=96, shift=3, dtype="bf16", seed=5)
     return w
 
 
-def masked_mean_pooling(B=32, S=512, D=1024, seed=6):
+def masked_mean_pooling(B=32, S=512, D=1024, seed=6, dtype="bf16"):
     """The paper's Case 2 subgraph: out[b,d] = sum_s h[b,s,d] m[b,s,d] / max(sum_s m[b,s,d], 1e-9),
     hidden states bf16, mask fp32 (0/1 per token, expanded over d), output fp32 [B,D]."""
     g = Builder()
     m = g.input("f32", (B, S, D))
-    h = g.input("bf16", (B, S, D))
+    h = g.input(dtype, (B, S, D))
     num = g.op("sum", [g.op("mul", [h, m], "f32")], "f32", dim=-2, keepdim=0)
     den = g.op("sum", [m], "f32", dim=-2, keepdim=0)
     out = g.op("div", [num, g.op("maximum", [den, g.const(1e-9, "f32")], "f32")], "f32")
@@ -192,6 +192,6 @@ def masked_mean_pooling(B=32, S=512, D=1024, seed=6):
     mask = np.zeros((B, S, D), np.float32)
     for b, n in enumerate(lens):
         mask[b, :n, :] = 1.0
-    ins = [mask, _tensor(seed, 1, (B, S, D), "bf16")]
-    return Workload("masked_mean_pooling_B%d_S%d_D%d" % (B, S, D), g.text(), ins, ["f32", "bf16"], [(B, S, D)] * 2,
+    ins = [mask, _tensor(seed, 1, (B, S, D), dtype)]
+    return Workload("masked_mean_pooling_%s_B%d_S%d_D%d" % (dtype, B, S, D), g.text(), ins, ["f32", dtype], [(B, S, D)] * 2,
                     ["f32"], [(B, D)], meta={"lens": lens}).finish()

@@ -59,7 +59,8 @@ def randint(seed, tensor, index, lo, hi):
 
 # ---- storage dtypes -------------------------------------------------------
 # fp32 tensors are numpy float32 arrays; bf16 tensors are numpy uint16 arrays
-# holding the upper 16 bits of the fp32 pattern.
+# holding the upper 16 bits of the fp32 pattern; fp16 tensors are numpy uint16
+# arrays holding IEEE binary16 patterns.
 
 def round_to_f32(x64):
     return x64.astype(np.float32)
@@ -73,6 +74,25 @@ def round_to_bf16_bits(x64):
     r = ((u + np.uint32(0x7FFF) + lsb) >> np.uint32(16)).astype(np.uint16)
     r[nan] = np.uint16(0x7FC0)
     return r
+
+
+def round_to_f16_bits(x64):
+    """fp64 -> IEEE binary16 in one round-to-nearest-even step; uint16 bits.
+
+    binary16: 1 sign, 5 exponent (bias 15), 10 fraction bits; normal range 2^-14 ... 65504,
+    subnormals are multiples of 2^-24; anything that rounds to 2^16 or more becomes infinity.
+    """
+    x = np.asarray(x64, dtype=np.float64)
+    a = np.abs(x)
+    with np.errstate(all="ignore"):
+        _, k = np.frexp(a)                                   # a = f * 2^k, f in [0.5, 1)
+        e = np.maximum(k.astype(np.int64) - 1, -14)          # subnormals share the exponent of 2^-14
+        q = np.rint(np.ldexp(a, (10 - e).astype(np.int32)))  # significand in units of 2^(e-10); rint rounds half to even
+        bits = (e + 14) * 1024 + q                           # the hidden bit of q supplies the +1 of the exponent field
+    bits = np.where(np.isfinite(a), np.minimum(bits, 0x7C00), 0x7C00)      # overflow and infinity
+    bits = np.where(a == 0, 0, bits)
+    bits = np.where(np.isnan(x), 0x7E00, bits).astype(np.uint16)
+    return (bits | (np.signbit(x).astype(np.uint16) << np.uint16(15))).astype(np.uint16)
 
 
 def normal_stored(seed, tensor, n, dtype, mean=0.0, std=1.0, chunk=1 << 18):
@@ -101,9 +121,11 @@ def _normal_range(seed, tensor, start, count, mean, std):
 
 
 def store(x64, dtype):
-    """Round an fp64 array once to the named storage dtype ('f32' | 'bf16')."""
+    """Round an fp64 array once to the named storage dtype ('f32' | 'bf16' | 'f16')."""
     if dtype == "f32":
         return round_to_f32(x64)
     if dtype == "bf16":
         return round_to_bf16_bits(x64)
+    if dtype == "f16":
+        return round_to_f16_bits(x64)
     raise ValueError(dtype)
