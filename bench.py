@@ -43,6 +43,10 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the per-config table")
     ap.add_argument("--sets", type=int, default=2, help="distinct buffer sets rotated through (cold cache)")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the main line: the ten-shape task instances, shape-aware tiling against a static one")
+    ap.add_argument("--cfg5", action="store_true",
+                    help="instead of the main line: fused against op-by-op time of each of the 256 random DAGs")
     return ap.parse_args()
 
 
@@ -66,6 +70,12 @@ def main():
     assert torch.cuda.is_available(), "no GPU"
     pf.lib()
     stream = torch.cuda.current_stream()
+    if args.sweep:
+        print(json.dumps({"sweep": sweep_table(torch, pf, Runner, alloc_outputs, stream)}))
+        return
+    if args.cfg5:
+        print(json.dumps({"cfg5": cfg5_table(torch, pf, Runner, alloc_outputs, stream)}))
+        return
 
     # ---------------------------------------------------------------- workload
     w = configs.cfg3_bias_gelu_gate()
@@ -234,6 +244,95 @@ def per_config_table(torch, pf, configs, Runner, alloc_outputs, stream, w3, fuse
     table["case1_roll_slice_add_layernorm_D96"] = entry(configs.roll_slice_add_layernorm(), 40)
     table["case2_masked_mean_pooling"] = entry(configs.masked_mean_pooling(), 6)   # 6 x 101 MB
     return table
+
+
+def _rotating(torch, r, w, alloc_outputs, min_bytes=600e6, max_sets=48):
+    """Enough copies of a workload's buffers that more than the Infinity Cache is touched between reuses."""
+    n = int(max(2, min(max_sets, min_bytes // max(w.algorithmic_bytes, 1) + 1)))
+    ins = [r.d_in] + [[t.clone() for t in r.d_in] for _ in range(n - 1)]
+    outs = [alloc_outputs(w, poison=False) for _ in range(n)]
+    return ins, outs
+
+
+def sweep_table(torch, pf, Runner, alloc_outputs, stream):
+    """Task instances (one operator sequence at ten shapes): per member the fused kernel with the tiling the
+    planner derives from the shape, the same kernel with the tiling of member 0 forced onto every member (a
+    static tiling), and the op-by-op run.  A static tiling the template cannot realise is a compile failure."""
+    from workloads import sweeps
+    table = {}
+    for fam in sweeps.FAMILIES:
+        rows, static = [], None
+        for k in range(10):
+            w = sweeps.member(fam, k)
+            f = Runner(w)
+            gi = f.exe.group_info(0)
+            if static is None and gi["template"] in ("row_resident", "col_reduce"):
+                static = {"tune_row_lanes": gi["lanes_per_row"]}
+                if gi["template"] == "col_reduce":
+                    static["tune_col_block"] = gi["block_threads"]
+            ins, outs = _rotating(torch, f, w, alloc_outputs)
+            fm, _ = time_runner(torch, f, stream, ins, outs, warmup=10, trials=50, max_rounds=2)
+            u = Runner(w, fuse=False, intermediates_f32=False, upload=False)
+            um, _ = time_runner(torch, u, stream, ins, outs, warmup=5, trials=30, max_rounds=1)
+            row = {"member": w.name, "bytes": w.algorithmic_bytes, "template": gi["template"], "lanes_per_row": gi["lanes_per_row"],
+                   "block": gi["block_threads"], "fused_us": fm, "GBps": w.algorithmic_bytes / fm / 1e3, "unfused_us": um,
+                   "unfused_kernels": u.info["n_kernels"]}
+            if static:
+                try:
+                    s = Runner(w, upload=False, **static)
+                    sm, _ = time_runner(torch, s, stream, ins, outs, warmup=10, trials=50, max_rounds=2)
+                    row["static_us"] = sm
+                except pf.PfError as e:
+                    row["static_us"] = None                          # the paper's error class 2
+                    row["static_error"] = str(e)[:120]
+            rows.append(row)
+            del f, u, ins, outs
+        ok = [r for r in rows if r.get("static_us")]
+        summary = {"geomean_speedup_vs_unfused": float(np.exp(np.mean([np.log(r["unfused_us"] / r["fused_us"]) for r in rows]))),
+                   "static_tiling": static}
+        if static:
+            summary["static_compile_failures"] = len(rows) - len(ok)
+            summary["geomean_static_over_shape_aware"] = float(np.exp(np.mean([np.log(r["static_us"] / r["fused_us"]) for r in ok])))
+            summary["worst_static_over_shape_aware"] = float(max(r["static_us"] / r["fused_us"] for r in ok))
+        table[fam] = {"members": rows, "summary": summary}
+    return table
+
+
+def cfg5_table(torch, pf, Runner, alloc_outputs, stream):
+    """The 256 random fusible DAGs: fused and op-by-op device time each (median of 12 runs after 3 warm-ups; inputs
+    are resident, one buffer set), kernel counts, algorithmic and planned bytes."""
+    from paper_2605_29357_amd.torch_util import TORCH_DT, HipEvent
+    from workloads import dags
+
+    def med_time(r, outs, n=12):
+        for _ in range(3):
+            r.run(outs, stream)
+        evs = [(HipEvent(), HipEvent()) for _ in range(n)]
+        for e in evs:
+            r.run(outs, stream, events=e)
+        torch.cuda.synchronize()
+        return float(np.median([a.elapsed_us(b) for a, b in evs]))
+
+    rows = []
+    for k in range(dags.N_DAGS):
+        w = dags.cfg5(k, with_inputs=False)
+        f = Runner(w, fuse=True, upload=False)
+        u = Runner(w, fuse=False, intermediates_f32=False, upload=False)
+        f.d_in = u.d_in = [(torch.rand(tuple(s), device="cuda") + 0.5).to(TORCH_DT[dt]) for dt, s in zip(w.input_dtypes, w.input_shapes)]
+        outs = alloc_outputs(w, poison=False)
+        rows.append({"dag": w.name, "bytes": w.algorithmic_bytes, "planned_bytes": f.info["planned_bytes"],
+                     "fused_us": med_time(f, outs), "unfused_us": med_time(u, outs), "fused_kernels": f.info["n_kernels"],
+                     "unfused_kernels": u.info["n_kernels"], "templates": [g["template"] for g in f.exe.groups()]})
+        del f, u, outs
+    tf, tu = sum(r["fused_us"] for r in rows), sum(r["unfused_us"] for r in rows)
+    big = [r for r in rows if r["bytes"] >= 16e6 and r["fused_kernels"] == 1]
+    return {"dags": rows,
+            "summary": {"fused_us_total": tf, "unfused_us_total": tu, "speedup_total": tu / tf,
+                        "geomean_speedup": float(np.exp(np.mean([np.log(r["unfused_us"] / r["fused_us"]) for r in rows]))),
+                        "fused_kernels": sum(r["fused_kernels"] for r in rows), "unfused_kernels": sum(r["unfused_kernels"] for r in rows),
+                        "algorithmic_GBps_total": sum(r["bytes"] for r in rows) / tf / 1e3,
+                        "single_kernel_dags_over_16MB": len(big),
+                        "their_median_pct_of_peak": float(np.median([100 * r["bytes"] / r["fused_us"] / 1e3 / HBM_PEAK_GBS for r in big])) if big else None}}
 
 
 def cpu_baseline(w, to_host_bits, ref, cand, dt, configs):

@@ -44,8 +44,10 @@ typedef enum {
     PF_E_NOMEM = -4
 } pf_status;
 
-/* Storage dtypes.  PF_F64 is accepted only as the reference side of pf_score. */
-typedef enum { PF_F32 = 0, PF_BF16 = 1, PF_F64 = 2 } pf_dtype;
+/* Storage dtypes.  PF_F16 is IEEE binary16.  PF_F64 is accepted only as the reference side of
+ * pf_score / pf_score_ladder.  Scored pairs: a candidate of f32, bf16 or f16 against a reference
+ * of the same dtype, f32 or f64; an f32 candidate also against a bf16 or f16 reference. */
+typedef enum { PF_F32 = 0, PF_BF16 = 1, PF_F64 = 2, PF_F16 = 3 } pf_dtype;
 
 /*
  * Operator types (the set tau ranges over).  Binary operators broadcast
@@ -108,6 +110,15 @@ pf_status pf_graph_output(pf_graph* g, int node);
  * graph.  print: buf may be NULL / cap 0 to query *needed (bytes incl. NUL). */
 pf_status pf_graph_parse(const char* h_text, size_t len, pf_graph** g);
 pf_status pf_graph_print(const pf_graph* g, char* h_buf, size_t cap, size_t* needed);
+
+/* A member G_i of a task instance (Sec. 3.1: subgraphs sharing the operator-type sequence but
+ * varying in shape and dtype): a new graph with the operators of g, input k given shape
+ * h_shapes[k*PF_MAX_RANK .. +h_ranks[k]) (host arrays, one entry per graph input in order), and every
+ * tensor of dtype from_dtype re-typed to to_dtype (both -1: dtypes unchanged).  All shapes are
+ * inferred again; attributes that do not fit the new shapes (slice bounds, variance sizes) and
+ * operands that no longer broadcast are PF_E_COMPILE.  The caller owns *out. */
+pf_status pf_graph_variant(const pf_graph* g, const int* h_ranks, const int64_t* h_shapes, int from_dtype, int to_dtype,
+                           pf_graph** out);
 
 typedef struct {
     pf_op    op;
@@ -226,7 +237,7 @@ pf_status pf_score(const pf_pair* h_pairs, int n_pairs, pf_score_result* d_resul
 #define PF_LADDER_LEVELS 11   /* tolerance indices t = -10 .. 0 */
 #define PF_ES_LEVELS 15       /* t = -10 .. 4 (|E| = 3 error categories, t up to |E|+1) */
 
-/* rtol(t), atol(t) = 10^(k t) with the per-dtype slopes of Appendix F (bf16, f32, f64);
+/* rtol(t), atol(t) = 10^(k t) with the per-dtype slopes of Appendix F (bf16, f16, f32, f64);
  * t > 0 gives the values of t = 0. */
 pf_status pf_tolerance(pf_dtype dtype, int t, double* h_rtol, double* h_atol);
 

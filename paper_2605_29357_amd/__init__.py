@@ -13,8 +13,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpf.so")
 
 PF_OK, PF_E_INVALID, PF_E_COMPILE, PF_E_RUNTIME, PF_E_NOMEM = 0, -1, -2, -3, -4
-F32, BF16, F64 = 0, 1, 2
-DTYPES = {"f32": F32, "bf16": BF16, "f64": F64}
+F32, BF16, F64, F16 = 0, 1, 2, 3
+DTYPES = {"f32": F32, "bf16": BF16, "f64": F64, "f16": F16}
 DTYPE_NAMES = {v: k for k, v in DTYPES.items()}
 OPS = ["input", "const", "add", "sub", "mul", "div", "exp", "tanh", "sigmoid", "gelu", "rsqrt",
        "sum", "max", "mean", "var", "transpose", "rot_pairs", "roll", "slice", "maximum", "minimum"]
@@ -109,6 +109,7 @@ def lib():
         "pf_graph_output": [vp, C.c_int],
         "pf_graph_parse": [C.c_char_p, sz, C.POINTER(vp)],
         "pf_graph_print": [vp, C.c_char_p, sz, C.POINTER(sz)],
+        "pf_graph_variant": [vp, ip, C.POINTER(C.c_int64), C.c_int, C.c_int, C.POINTER(vp)],
         "pf_graph_size": [vp, ip, ip, ip],
         "pf_graph_node_info": [vp, C.c_int, C.POINTER(_NodeInfo)],
         "pf_compile": [vp, C.POINTER(_Options), C.POINTER(vp)],
@@ -194,6 +195,22 @@ class Graph:
         buf = C.create_string_buffer(need.value)
         _check(lib().pf_graph_print(self._h, buf, need.value, C.byref(need)))
         return buf.value.decode()
+
+    def variant(self, shapes, from_dtype=None, to_dtype=None):
+        """The same operators at other input shapes (one per graph input) and, optionally, another dtype."""
+        n = len(shapes)
+        ranks = (C.c_int * max(n, 1))(*[len(s) for s in shapes])
+        flat = (C.c_int64 * (max(n, 1) * 4))()
+        for k, s in enumerate(shapes):
+            for d, v in enumerate(s):
+                flat[k * 4 + d] = int(v)
+        if self.size()[1] != n:
+            raise PfError(PF_E_INVALID, "graph has %d inputs, %d shapes given" % (self.size()[1], n))
+        g = Graph.__new__(Graph)
+        g._h = C.c_void_p()
+        _check(lib().pf_graph_variant(self._h, ranks, flat, DTYPES[from_dtype] if from_dtype else -1,
+                                      DTYPES[to_dtype] if to_dtype else -1, C.byref(g._h)))
+        return g
 
     def size(self):
         a, b, c = C.c_int(), C.c_int(), C.c_int()

@@ -119,6 +119,30 @@ pf_status pf_graph_parse(const char* h_text, size_t len, pf_graph** g) {
     });
 }
 
+pf_status pf_graph_variant(const pf_graph* g, const int* h_ranks, const int64_t* h_shapes, int from_dtype, int to_dtype,
+                           pf_graph** out) {
+    return guarded([&] {
+        need(g, "g");
+        need(out, "out");
+        *out = nullptr;
+        if (!g->inputs.empty()) {
+            need(h_ranks, "h_ranks");
+            need(h_shapes, "h_shapes");
+        }
+        if ((from_dtype < 0) != (to_dtype < 0)) pf::fail(PF_E_INVALID, "from_dtype and to_dtype must both be given or both be -1");
+        for (int d : {from_dtype, to_dtype})
+            if (d >= 0 && d != PF_F32 && d != PF_BF16 && d != PF_F16) pf::fail(PF_E_INVALID, "dtype %d is not a tensor dtype", d);
+        pf_graph* ng = new pf_graph();
+        try {
+            pf::graph_variant(*g, h_ranks, h_shapes, from_dtype, to_dtype, *ng);
+        } catch (...) {
+            delete ng;
+            throw;
+        }
+        *out = ng;
+    });
+}
+
 pf_status pf_graph_print(const pf_graph* g, char* h_buf, size_t cap, size_t* needed) {
     pf_status st = PF_OK;
     pf_status outer = guarded([&] {
@@ -304,15 +328,17 @@ StagedPairs stage_pairs(const pf_pair* h_pairs, int n_pairs, void* d_workspace, 
     const unsigned long long chunk = pf::score_chunk_elems();
     for (int i = 0; i < n_pairs; ++i) {
         const pf_pair& p = h_pairs[i];
-        if (p.cand_dtype != PF_F32 && p.cand_dtype != PF_BF16) pf::fail(PF_E_INVALID, "pair %d: candidate dtype must be f32 or bf16", i);
-        if (p.ref_dtype != PF_F32 && p.ref_dtype != PF_BF16 && p.ref_dtype != PF_F64) pf::fail(PF_E_INVALID, "pair %d: bad reference dtype", i);
+        if (p.cand_dtype != PF_F32 && p.cand_dtype != PF_BF16 && p.cand_dtype != PF_F16)
+            pf::fail(PF_E_INVALID, "pair %d: candidate dtype must be f32, bf16 or f16", i);
+        if (!pf::score_combo_supported(p.cand_dtype, p.ref_dtype))
+            pf::fail(PF_E_INVALID, "pair %d: unsupported dtype combination (candidate %d, reference %d)", i, p.cand_dtype, p.ref_dtype);
         if (p.n && (!p.d_cand || !p.d_ref)) pf::fail(PF_E_INVALID, "pair %d: NULL buffer", i);
         if (((uintptr_t)p.d_cand | (uintptr_t)p.d_ref) & 15) pf::fail(PF_E_INVALID, "pair %d: buffers must be 16-byte aligned", i);
         if (!(p.rtol >= 0.0) || !(p.atol >= 0.0)) pf::fail(PF_E_INVALID, "pair %d: tolerances must be >= 0", i);
     }
     std::vector<int> order(n_pairs);
     for (int i = 0; i < n_pairs; ++i) order[i] = i;
-    auto combo = [&](int i) { return h_pairs[i].cand_dtype * 3 + h_pairs[i].ref_dtype; };
+    auto combo = [&](int i) { return h_pairs[i].cand_dtype * 4 + h_pairs[i].ref_dtype; };
     std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return combo(a) < combo(b); });
     memset(&sp.ranges, 0, sizeof sp.ranges);
     unsigned long long total = 0;
@@ -389,7 +415,8 @@ pf_status pf_score_ladder(const pf_pair* h_pairs, int n_pairs, pf_ladder_result*
         check_score_args(h_pairs, n_pairs, d_results, d_workspace, workspace_bytes, pf_score_ladder_workspace_bytes(n_pairs));
         StagedPairs sp = stage_pairs(h_pairs, n_pairs, d_workspace, stream);
         pf::LadderTable table;
-        for (int dt = 0; dt < 2; ++dt)
+        memset(&table, 0, sizeof table);
+        for (int dt : {(int)PF_F32, (int)PF_BF16, (int)PF_F16})
             for (int k = 0; k < PF_LADDER_LEVELS; ++k) pf::tolerance_at((pf_dtype)dt, k - (PF_LADDER_LEVELS - 1), &table.rtol[dt][k], &table.atol[dt][k]);
         hipError_t err = pf::launch_ladder(sp.d_pairs, sp.d_start, n_pairs, sp.ranges, table, d_results, (pf_ladder_result*)sp.d_rest,
                                            (hipStream_t)stream);

@@ -50,7 +50,7 @@ struct Emit {
         if (std::isinf(v)) return v > 0 ? "__builtin_inff()" : "(-__builtin_inff())";
         return strf("((float)%a)", v);
     }
-    const char* ctype(pf_dtype d) const { return d == PF_BF16 ? "u16" : "float"; }
+    const char* ctype(pf_dtype d) const { return d == PF_BF16 ? "u16" : d == PF_F16 ? "f16" : "float"; }
     const char* idx_t() const { return wide ? "long long" : "unsigned"; }
 
     bool in_kernel(int p) const {
@@ -175,19 +175,23 @@ struct Emit {
         const bool ragged = C % vec != 0;
         const int64_t chunks = (C + vec - 1) / vec;
         const int per_lane_max = 32 / vec > 0 ? 32 / vec : 1;      // keep <= 32 floats per value per lane
+        // Lanes per row.  Every lane of a team pays the cross-lane reductions (log2 T shuffle steps per
+        // reduction, doubled for fp64 accumulators), so the smallest team that still issues whole cache
+        // lines per load is the cheapest: about 16 elements per lane and value (measured over rows of
+        // 24 ... 11008 elements, fp32 and bf16: 16-element lanes are up to 2x faster than 8-element
+        // ones on fp32 LayerNorm rows of 96 ... 768 and never more than 10% slower).
+        const int k_target = std::max(1, 16 / vec);
         int T = 1;
-        while (T < 16 && T < chunks) T <<= 1;       // a team's load should cover whole cache lines
-        // two 16-byte chunks per lane and row leave room for several rows in flight (measured best
-        // on 512-element bf16 rows: 32 lanes x 2 chunks x 2 rows)
-        while (T < 1024 && (chunks + T - 1) / T > std::min<int64_t>(per_lane_max, 2)) T <<= 1;
+        while (T < 8 && T < chunks) T <<= 1;        // a team's load covers at least one 128-byte line
+        while (T < 1024 && (chunks + T - 1) / T > std::min(per_lane_max, k_target)) T <<= 1;
         while ((chunks + T - 1) / T > per_lane_max && T < 1024) T <<= 1;
         int64_t K = (chunks + T - 1) / T;
         if (K * vec > 64) {          // the row does not fit in the registers of 1024 lanes: stream it
             gen_loop(vec, ragged);
             return;
         }
-        // few rows: spread each row over more lanes to cut latency
-        while (K > 1 && T < 1024 && R * T < 256 * 256) {
+        // few rows: spread each row over more lanes until about six waves per CU exist
+        while (K > 1 && T < 1024 && R * T < 256 * 64 * 6) {
             T <<= 1;
             K = (chunks + T - 1) / T;
         }
@@ -202,9 +206,14 @@ struct Emit {
         // independent loads per lane are what keeps HBM busy
         const int nlead = rd > 0 ? rd - 1 : 0;
         scan_decomp(nlead);
+        // Rows in flight per team.  More independent loads per lane help only while enough waves remain
+        // to fill the chip twice over: one extra row per 262144 lanes (4096 waves), at most four, and
+        // at most 32 elements per lane and value.  (Measured: 2 rows on 16384 x 512 bf16 rows and 4 on
+        // 262144 x 128 are 8% and 3% faster than one; on 2M-element problems any more than one row is
+        // 10 ... 100% slower.)
         int ru = 1;
-        if (T <= 64 && R * T >= 256 * 256 * 4) {
-            ru = 8;
+        if (T <= 64) {
+            while (ru < 4 && R * T >= (int64_t)262144 * ru * 2) ru <<= 1;
             while (ru > 1 && ru * N > 32) ru >>= 1;
         }
         if (opt.tune_row_unroll > 0) ru = T <= 64 ? opt.tune_row_unroll : 1;

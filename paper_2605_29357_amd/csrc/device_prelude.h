@@ -10,6 +10,7 @@ namespace pf {
 static const char* kDevicePrelude = R"PF(
 typedef unsigned short u16;
 typedef unsigned int u32;
+typedef _Float16 f16;                      // IEEE binary16 tensors (bf16 tensors are addressed as u16)
 typedef u32 u32x2 __attribute__((ext_vector_type(2)));
 typedef u32 u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
@@ -83,6 +84,33 @@ template <bool NT, bool UA> struct LdF32<8, NT, UA> {
         LdF32<4, NT, UA>::run(p, o); LdF32<4, NT, UA>::run(p + 4, o + 4);
     }
 };
+// fp16: the same accesses as bf16, then an exact hardware widening of each half
+PF_DEV float pf_h2f(u32 bits) { return (float)__builtin_bit_cast(f16, (u16)bits); }
+template <int N, bool NT, bool UA> struct LdF16;
+template <bool NT, bool UA> struct LdF16<1, NT, UA> {
+    static PF_DEV void run(const f16* p, float* o) { o[0] = (float)(NT ? __builtin_nontemporal_load(p) : *p); }
+};
+template <bool NT, bool UA> struct LdF16<2, NT, UA> {
+    static PF_DEV void run(const f16* p, float* o) {
+        typedef typename VT<UA>::b1 V; u32 r = NT ? __builtin_nontemporal_load((const V*)p) : *(const V*)p;
+        o[0] = pf_h2f(r & 0xffffu); o[1] = pf_h2f(r >> 16);
+    }
+};
+template <bool NT, bool UA> struct LdF16<4, NT, UA> {
+    static PF_DEV void run(const f16* p, float* o) {
+        typedef typename VT<UA>::b2 V; u32x2 r = NT ? __builtin_nontemporal_load((const V*)p) : *(const V*)p;
+        o[0] = pf_h2f(r.x & 0xffffu); o[1] = pf_h2f(r.x >> 16); o[2] = pf_h2f(r.y & 0xffffu); o[3] = pf_h2f(r.y >> 16);
+    }
+};
+template <bool NT, bool UA> struct LdF16<8, NT, UA> {
+    static PF_DEV void run(const f16* p, float* o) {
+        typedef typename VT<UA>::b4 V; u32x4 r = NT ? __builtin_nontemporal_load((const V*)p) : *(const V*)p;
+        o[0] = pf_h2f(r.x & 0xffffu); o[1] = pf_h2f(r.x >> 16); o[2] = pf_h2f(r.y & 0xffffu); o[3] = pf_h2f(r.y >> 16);
+        o[4] = pf_h2f(r.z & 0xffffu); o[5] = pf_h2f(r.z >> 16); o[6] = pf_h2f(r.w & 0xffffu); o[7] = pf_h2f(r.w >> 16);
+    }
+};
+template <int N, bool NT, bool UA = false> PF_DEV void pf_ld(const f16* p, float* o) { LdF16<N, NT, UA>::run(p, o); }
+PF_DEV float pf_ld1(const f16* p) { return (float)*p; }
 template <int N, bool NT, bool UA = false> PF_DEV void pf_ld(const u16* p, float* o) { LdBf16<N, NT, UA>::run(p, o); }
 template <int N, bool NT, bool UA = false> PF_DEV void pf_ld(const float* p, float* o) { LdF32<N, NT, UA>::run(p, o); }
 PF_DEV float pf_ld1(const u16* p) { return pf_bits2f((u32)*p << 16); }
@@ -130,6 +158,32 @@ template <bool NT, bool UA> struct StF32<4, NT, UA> {
 template <bool NT, bool UA> struct StF32<8, NT, UA> {
     static PF_DEV void run(float* p, const float* v) { StF32<4, NT, UA>::run(p, v); StF32<4, NT, UA>::run(p + 4, v + 4); }
 };
+// fp16 stores: one round-to-nearest-even conversion per element (the default rounding mode), packed in pairs
+PF_DEV u32 pf_pack_f16(float lo, float hi) { return (u32)__builtin_bit_cast(u16, (f16)lo) | ((u32)__builtin_bit_cast(u16, (f16)hi) << 16); }
+template <int N, bool NT, bool UA> struct StF16;
+template <bool NT, bool UA> struct StF16<1, NT, UA> {
+    static PF_DEV void run(f16* p, const float* v) { f16 r = (f16)v[0]; if (NT) __builtin_nontemporal_store(r, p); else *p = r; }
+};
+template <bool NT, bool UA> struct StF16<2, NT, UA> {
+    static PF_DEV void run(f16* p, const float* v) {
+        u32 r = pf_pack_f16(v[0], v[1]);
+        typedef typename VT<UA>::b1 V; if (NT) __builtin_nontemporal_store(r, (V*)p); else *(V*)p = r;
+    }
+};
+template <bool NT, bool UA> struct StF16<4, NT, UA> {
+    static PF_DEV void run(f16* p, const float* v) {
+        u32x2 r = {pf_pack_f16(v[0], v[1]), pf_pack_f16(v[2], v[3])};
+        typedef typename VT<UA>::b2 V; if (NT) __builtin_nontemporal_store(r, (V*)p); else *(V*)p = r;
+    }
+};
+template <bool NT, bool UA> struct StF16<8, NT, UA> {
+    static PF_DEV void run(f16* p, const float* v) {
+        u32x4 r = {pf_pack_f16(v[0], v[1]), pf_pack_f16(v[2], v[3]), pf_pack_f16(v[4], v[5]), pf_pack_f16(v[6], v[7])};
+        typedef typename VT<UA>::b4 V; if (NT) __builtin_nontemporal_store(r, (V*)p); else *(V*)p = r;
+    }
+};
+template <int N, bool NT, bool UA = false> PF_DEV void pf_st(f16* p, const float* v) { StF16<N, NT, UA>::run(p, v); }
+PF_DEV void pf_st1(f16* p, float v) { *p = (f16)v; }
 template <int N, bool NT, bool UA = false> PF_DEV void pf_st(u16* p, const float* v) { StBf16<N, NT, UA>::run(p, v); }
 template <int N, bool NT, bool UA = false> PF_DEV void pf_st(float* p, const float* v) { StF32<N, NT, UA>::run(p, v); }
 PF_DEV void pf_st1(u16* p, float v) { *p = pf_f2bf(v); }

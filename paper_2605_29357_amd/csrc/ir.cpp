@@ -50,7 +50,7 @@ bool op_from_name(const std::string& name, pf_op* op) {
     return false;
 }
 
-const char* dtype_name(pf_dtype d) { return d == PF_F32 ? "f32" : d == PF_BF16 ? "bf16" : "f64"; }
+const char* dtype_name(pf_dtype d) { return d == PF_F32 ? "f32" : d == PF_BF16 ? "bf16" : d == PF_F16 ? "f16" : "f64"; }
 
 bool is_reduction(pf_op op) { return op == PF_OP_SUM || op == PF_OP_MAX || op == PF_OP_MEAN || op == PF_OP_VAR; }
 bool is_unary(pf_op op) {
@@ -75,7 +75,7 @@ Shape broadcast_shapes(const Shape& a, const Shape& b) {
 }
 
 static void check_dtype(pf_dtype dt) {
-    if (dt != PF_F32 && dt != PF_BF16) fail(PF_E_COMPILE, "unsupported tensor dtype %d (f32 and bf16 only)", (int)dt);
+    if (dt != PF_F32 && dt != PF_BF16 && dt != PF_F16) fail(PF_E_COMPILE, "unsupported tensor dtype %d (f32, bf16 and f16 only)", (int)dt);
 }
 
 int graph_add_input(pf_graph& g, pf_dtype dt, const Shape& shape) {
@@ -258,6 +258,7 @@ struct Cursor {
 pf_dtype parse_dtype(const std::string& w, int line_no) {
     if (w == "f32") return PF_F32;
     if (w == "bf16") return PF_BF16;
+    if (w == "f16") return PF_F16;
     fail(PF_E_COMPILE, "line %d: unknown dtype '%s'", line_no, w.c_str());
 }
 
@@ -332,6 +333,41 @@ void graph_parse(const std::string& text, pf_graph& g) {
             graph_add_node(g, op, in, attrs, dt);
         }
     }
+}
+
+// The same operator sequence at other input shapes / another dtype (the members G_i of a task
+// instance, paper Sec. 3.1): the graph is printed, its input lines are rewritten, tensors of dtype
+// `from` become `to`, and the text is parsed again, which re-infers every shape and re-validates
+// the attributes (slice bounds, reduction sizes) against the new shapes.
+void graph_variant(const pf_graph& g, const int* ranks, const int64_t* shapes, int from, int to, pf_graph& out) {
+    const std::string text = graph_print(g);
+    const std::string f = from >= 0 ? dtype_name((pf_dtype)from) : "", t = to >= 0 ? dtype_name((pf_dtype)to) : "";
+    std::string res;
+    size_t pos = 0, k = 0;
+    while (pos < text.size()) {
+        size_t nl = text.find('\n', pos);
+        if (nl == std::string::npos) nl = text.size();
+        std::string line = text.substr(pos, nl - pos);
+        pos = nl + 1;
+        if (line.compare(0, 3, "in ") == 0) {
+            const size_t colon = line.find(':'), br = line.find('[');
+            std::string dt = line.substr(colon + 2, br - colon - 2);
+            if (from >= 0 && dt == f) dt = t;
+            if (k >= g.inputs.size()) fail(PF_E_INVALID, "internal: input count");
+            const int r = ranks[k];
+            if (r < 0 || r > PF_MAX_RANK) fail(PF_E_INVALID, "input %zu: rank %d out of range", k, r);
+            line = line.substr(0, colon + 2) + dt + "[";
+            for (int d = 0; d < r; ++d) line += strf(d ? ",%lld" : "%lld", (long long)shapes[k * PF_MAX_RANK + d]);
+            line += "]";
+            ++k;
+        } else if (line.compare(0, 1, "%") == 0 && from >= 0) {
+            const size_t colon = line.rfind(": ");
+            if (colon != std::string::npos && line.substr(colon + 2) == f) line = line.substr(0, colon + 2) + t;
+        }
+        res += line;
+        res += '\n';
+    }
+    graph_parse(res, out);
 }
 
 std::string graph_print(const pf_graph& g) {

@@ -20,6 +20,7 @@ void tolerance_at(pf_dtype dtype, int t, double* rtol, double* atol) {
     double kr, ka;
     switch (dtype) {
         case PF_BF16: kr = 1.796 / 5.0; ka = 1.0; break;
+        case PF_F16: kr = 3.0 / 5.0; ka = 1.0; break;
         case PF_F32: kr = 5.886 / 5.0; ka = 1.0; break;
         case PF_F64: kr = 7.0 / 5.0; ka = 7.0 / 5.0; break;
         default: fail(PF_E_INVALID, "no tolerance table for dtype %d", (int)dtype);

@@ -27,7 +27,7 @@ inline int64_t numel(const Shape& s) {
     for (int64_t d : s) n *= d;
     return n;
 }
-inline int itemsize(pf_dtype d) { return d == PF_BF16 ? 2 : d == PF_F32 ? 4 : 8; }
+inline int itemsize(pf_dtype d) { return (d == PF_BF16 || d == PF_F16) ? 2 : d == PF_F32 ? 4 : 8; }
 const char* dtype_name(pf_dtype d);
 const char* op_name(pf_op op);
 bool op_from_name(const std::string& name, pf_op* op);
@@ -72,6 +72,7 @@ int graph_add_node(pf_graph& g, pf_op op, const std::vector<int>& in,
 void graph_add_output(pf_graph& g, int node);
 void graph_parse(const std::string& text, pf_graph& g);
 std::string graph_print(const pf_graph& g);
+void graph_variant(const pf_graph& g, const int* ranks, const int64_t* shapes, int from, int to, pf_graph& out);
 Shape broadcast_shapes(const Shape& a, const Shape& b);
 
 // ---- plan.cpp ----

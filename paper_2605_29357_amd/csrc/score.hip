@@ -45,6 +45,13 @@ template <> struct Elem<PF_BF16> {
     }
     static __device__ __forceinline__ raw load1(const void* base, unsigned long long i) { return ((const unsigned short*)base)[i]; }
 };
+template <> struct Elem<PF_F16> {
+    using raw = unsigned int;                         // IEEE binary16 bits in the low half
+    static __device__ __forceinline__ float widen32(raw r) { return (float)__builtin_bit_cast(_Float16, (unsigned short)r); }
+    static __device__ __forceinline__ double widen(raw r) { return (double)widen32(r); }
+    static __device__ __forceinline__ void load8(const void* base, unsigned long long i, raw* out) { Elem<PF_BF16>::load8(base, i, out); }
+    static __device__ __forceinline__ raw load1(const void* base, unsigned long long i) { return ((const unsigned short*)base)[i]; }
+};
 template <> struct Elem<PF_F64> {
     using raw = unsigned long long;
     static __device__ __forceinline__ double widen(raw r) { return __longlong_as_double((long long)r); }
@@ -163,7 +170,7 @@ __device__ __forceinline__ void score_chunk(const pf::PairDev& pr, unsigned long
 
 __device__ __forceinline__ double wave_max(double v);
 
-// ---- fp32 screening path (both sides f32 or bf16) --------------------------
+// ---- fp32 screening path (both sides f32, bf16 or fp16) ---------------------
 // Almost every element can be classified without fp64: with a, b widened to
 // fp32, d32 = |a - b| carries a relative error of 2^-24 (and is exact when it
 // is subnormal), so comparing it against thresholds that are pulled 2e-6 to
@@ -190,12 +197,13 @@ __device__ __forceinline__ Screen make_screen(const pf::PairDev& pr) {
     return sc;
 }
 
-// Eight consecutive elements as loaded: packed 32-bit words (4 for bf16, 8 for f32).
+// Eight consecutive elements as loaded: packed 32-bit words (4 for bf16 / fp16, 8 for f32).
 template <int DT> struct Vec8 {
-    static constexpr int NW = DT == PF_BF16 ? 4 : 8;
+    static constexpr bool HALF = DT == PF_BF16 || DT == PF_F16;
+    static constexpr int NW = HALF ? 4 : 8;
     unsigned int w[NW];
     __device__ __forceinline__ void load(const void* base, unsigned long long i) {
-        const u32x4* p = (const u32x4*)((const char*)base + i * (DT == PF_BF16 ? 2 : 4));
+        const u32x4* p = (const u32x4*)((const char*)base + i * (HALF ? 2 : 4));
 #pragma unroll
         for (int k = 0; k < NW / 4; ++k) {
             const u32x4 r = __builtin_nontemporal_load(p + k);
@@ -205,11 +213,12 @@ template <int DT> struct Vec8 {
     // element j widened to fp32 (exact)
     __device__ __forceinline__ float f32(int j) const {
         if (DT == PF_BF16) return __uint_as_float((j & 1) ? (w[j >> 1] & 0xffff0000u) : (w[j >> 1] << 16));
+        if (DT == PF_F16) return Elem<PF_F16>::widen32((j & 1) ? (w[j >> 1] >> 16) : (w[j >> 1] & 0xffffu));
         return __uint_as_float(w[j]);
     }
     // element j as Elem<DT>::raw
     __device__ __forceinline__ unsigned int raw(int j) const {
-        if (DT == PF_BF16) return (j & 1) ? (w[j >> 1] >> 16) : (w[j >> 1] & 0xffffu);
+        if (HALF) return (j & 1) ? (w[j >> 1] >> 16) : (w[j >> 1] & 0xffffu);
         return w[j];
     }
 };
@@ -546,6 +555,10 @@ hipError_t launch_score(const PairDev* d_pairs, const unsigned long long* d_bloc
     PF_LAUNCH(PF_BF16, PF_F32)
     PF_LAUNCH(PF_BF16, PF_BF16)
     PF_LAUNCH(PF_BF16, PF_F64)
+    PF_LAUNCH(PF_F32, PF_F16)
+    PF_LAUNCH(PF_F16, PF_F32)
+    PF_LAUNCH(PF_F16, PF_F16)
+    PF_LAUNCH(PF_F16, PF_F64)
 #undef PF_LAUNCH
     hipLaunchKernelGGL(score_final_kernel, dim3(n_pairs), dim3(64), 0, stream, d_pairs, n_pairs, d_results, d_slots);
     return hipGetLastError();
@@ -565,6 +578,10 @@ hipError_t launch_ladder(const PairDev* d_pairs, const unsigned long long* d_blo
     PF_LAUNCH(PF_BF16, PF_F32)
     PF_LAUNCH(PF_BF16, PF_BF16)
     PF_LAUNCH(PF_BF16, PF_F64)
+    PF_LAUNCH(PF_F32, PF_F16)
+    PF_LAUNCH(PF_F16, PF_F32)
+    PF_LAUNCH(PF_F16, PF_F16)
+    PF_LAUNCH(PF_F16, PF_F64)
 #undef PF_LAUNCH
     hipLaunchKernelGGL(ladder_final_kernel, dim3(n_pairs), dim3(64), 0, stream, d_pairs, n_pairs, d_results, d_slots);
     return hipGetLastError();

@@ -17,11 +17,19 @@ struct PairDev {
     int orig;               // index of this pair in the caller's array
 };
 
-// blocks of each (candidate dtype, reference dtype) combination: a contiguous range
+// blocks of each (candidate dtype, reference dtype) combination, indexed by pf_dtype: a contiguous range
 struct ScoreRanges {
-    unsigned long long first[2][3];
-    unsigned long long count[2][3];
+    unsigned long long first[4][4];
+    unsigned long long count[4][4];
 };
+// combinations with a kernel instantiation: candidate f32 / bf16 / f16 against a reference of the
+// same dtype, f32 or f64; an f32 candidate also against a bf16 or f16 reference
+inline bool score_combo_supported(int cd, int rd) {
+    if (cd == PF_F64 || cd < 0 || cd > PF_F16 || rd < 0 || rd > PF_F16) return false;
+    if (cd == PF_BF16 && rd == PF_F16) return false;
+    if (cd == PF_F16 && rd == PF_BF16) return false;
+    return true;
+}
 
 constexpr int kScoreSlots = 64;   // partial result slots per pair
 
@@ -33,10 +41,10 @@ struct PairBatch {
     int first, count, last, pad_;
 };
 
-// tolerances of every ladder level, per candidate dtype (f32, bf16)
+// tolerances of every ladder level, per candidate dtype (indexed by pf_dtype; the f64 row is unused)
 struct LadderTable {
-    double rtol[2][PF_LADDER_LEVELS];
-    double atol[2][PF_LADDER_LEVELS];
+    double rtol[4][PF_LADDER_LEVELS];
+    double atol[4][PF_LADDER_LEVELS];
 };
 
 unsigned long long score_chunk_elems();

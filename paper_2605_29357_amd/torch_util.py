@@ -10,19 +10,19 @@ import torch
 
 import paper_2605_29357_amd as pf
 
-TORCH_DT = {"f32": torch.float32, "bf16": torch.bfloat16, "f64": torch.float64}
+TORCH_DT = {"f32": torch.float32, "bf16": torch.bfloat16, "f64": torch.float64, "f16": torch.float16}
 
 
 def to_device(arr, dtype):
     """Stored numpy bits -> device tensor of the matching torch dtype."""
-    if dtype == "bf16":
-        return torch.from_numpy(np.ascontiguousarray(arr).view(np.int16)).cuda().view(torch.bfloat16)
+    if dtype in ("bf16", "f16"):
+        return torch.from_numpy(np.ascontiguousarray(arr).view(np.int16)).cuda().view(TORCH_DT[dtype])
     return torch.from_numpy(np.ascontiguousarray(arr)).cuda()
 
 
 def to_host_bits(t, dtype):
-    """Device tensor -> stored numpy bits (uint16 for bf16, float32/float64 otherwise)."""
-    if dtype == "bf16":
+    """Device tensor -> stored numpy bits (uint16 for bf16 / fp16, float32/float64 otherwise)."""
+    if dtype in ("bf16", "f16"):
         return t.view(torch.int16).cpu().numpy().view(np.uint16)
     return t.cpu().numpy()
 

@@ -1,0 +1,183 @@
+"""GPU parity for IEEE binary16 (fp16) tensors: loads widen exactly, stores round once to
+nearest-even, the named subgraphs and a set of random DAGs re-typed to fp16 match the fp64
+oracle at rtol 1e-3 / atol 1e-5 (the paper's fp16 tolerance at t = -5), and the scorer
+handles fp16 pairs bit-for-bit like the oracle scorer.
+"""
+import re
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2605_29357_amd as pf
+from oracle import metric
+from oracle.score import score_pair
+from paper_2605_29357_amd.torch_util import ladder_on_gpu
+from tests.harness import (Runner, check_against_oracle, oracle_outputs, oracle_score_dict, score_on_gpu, to_device,
+                           to_host_bits)
+from workloads import configs, dags, rng
+from workloads.irtext import Builder
+
+pytestmark = pytest.mark.gpu
+
+
+def _both(w, kernels=1):
+    refs = oracle_outputs(w)
+    r = Runner(w)
+    if kernels is not None:
+        assert r.info["n_kernels"] == kernels
+    outs = r.run()
+    torch.cuda.synchronize()
+    check_against_oracle(w, outs, refs=refs, what=w.name)
+    u = Runner(w, fuse=False, intermediates_f32=True)
+    uo = u.run()
+    torch.cuda.synchronize()
+    check_against_oracle(w, uo, refs=refs, what=w.name + " unfused")
+    return outs, uo
+
+
+@pytest.mark.parametrize("make", [
+    lambda: configs.cfg2_masked_softmax(heads=2, seq=512, dtype="f16"),
+    lambda: configs.cfg2_masked_softmax(heads=3, seq=133, dtype="f16"),
+    lambda: configs.cfg3_bias_gelu_gate(rows=64, cols=11008, dtype="f16"),
+    lambda: configs.cfg3_bias_gelu_gate(rows=7, cols=133, dtype="f16"),
+    lambda: configs.cfg4_rmsnorm_rope(1, 64, 4, 128, dtype="f16"),
+    lambda: configs.roll_slice_add_layernorm(S=35, SC=32, C=384, dtype="f16"),
+    lambda: configs.roll_slice_add_layernorm(S=11, SC=7, C=10, dtype="f16"),
+    lambda: configs.masked_mean_pooling(B=4, S=100, D=264, dtype="f16"),
+])
+def test_named_subgraphs_in_fp16(make):
+    w = make()
+    assert "f16" in w.text
+    _both(w, kernels=1)
+
+
+def test_fp16_store_rounds_to_nearest_even_bit_exactly_and_loads_widen_exactly():
+    # x + 0 with fp32 input and fp16 output is a pure rounding step
+    vals = np.array([1.0, 1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11, 65504.0, 65519.0, 65520.0, 1e6, -1e6, 2.0 ** -24, 2.0 ** -25,
+                     3 * 2.0 ** -25, 1e-10, 6.1e-5, 0.0, -0.0, np.inf, -np.inf], dtype=np.float32)
+    g = np.random.default_rng(0)
+    vals = np.concatenate([vals, g.normal(size=4079).astype(np.float32), (g.normal(size=2048) * 1e-5).astype(np.float32),
+                           g.integers(0, 2 ** 32, size=4096, dtype=np.uint64).astype(np.uint32).view(np.float32)])
+    vals = vals[~np.isnan(vals)]
+    b = Builder()
+    i = b.input("f32", (vals.size,))
+    b.output(b.op("add", [i, b.const(0.0, "f32")], "f16"))
+    w = configs.Workload("round16", b.text(), [vals], ["f32"], [(vals.size,)], ["f16"], [(vals.size,)]).finish()
+    out = Runner(w).run()[0]
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(to_host_bits(out, "f16"), rng.round_to_f16_bits(vals.astype(np.float64) + 0.0))
+    # every one of the 65536 patterns widens to the value the oracle decodes (fp16 in, fp32 out); NaNs stay NaN
+    every = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    b = Builder()
+    i = b.input("f16", (65536,))
+    b.output(b.op("mul", [i, b.const(1.0, "f32")], "f32"))
+    w = configs.Workload("widen16", b.text(), [every], ["f16"], [(65536,)], ["f32"], [(65536,)]).finish()
+    out = Runner(w).run()[0].cpu().numpy().astype(np.float64)
+    want = oracle_outputs(w)[0]
+    np.testing.assert_array_equal(np.isnan(out), np.isnan(want))
+    np.testing.assert_array_equal(out[~np.isnan(want)], want[~np.isnan(want)])
+
+
+def _retype(w32):
+    """An fp32 random DAG with every tensor re-typed to fp16 and its inputs re-rounded."""
+    text = re.sub(r"\bf32\b", "f16", w32.text)
+    ins = [rng.store(np.asarray(a, np.float64), "f16") for a in w32.inputs]
+    return configs.Workload(w32.name.replace("f32", "f16"), text, ins, ["f16"] * len(ins), w32.input_shapes,
+                            ["f16"] * len(w32.output_dtypes), w32.output_shapes, meta=dict(w32.meta)).finish()
+
+
+def test_random_dags_retyped_to_fp16():
+    done = 0
+    for k in range(dags.N_DAGS):
+        if "_f32_" not in dags.cfg5(k, with_inputs=False).name:
+            continue
+        w = _retype(dags.cfg5(k, max_rows=96))
+        refs = oracle_outputs(w)
+        # fp16 holds magnitudes up to 65504 and the tolerance is 100 times looser than the one the DAG was
+        # drawn for; keep the DAGs whose outputs stay in range
+        if any((~np.isfinite(r)).any() or np.abs(r).max() > 3e4 for r in refs):
+            continue
+        print("dag", k, w.name, flush=True)
+        fused = Runner(w)
+        outs = fused.run()
+        torch.cuda.synchronize()
+        check_against_oracle(w, outs, refs=refs, what=w.name)
+        unfused = Runner(w, fuse=False, intermediates_f32=True)
+        uo = unfused.run()
+        torch.cuda.synchronize()
+        check_against_oracle(w, uo, refs=refs, what=w.name + " unfused")
+        specs = [(o, "f16", u, "f16", configs.RTOL["f16"], configs.ATOL["f16"], False) for o, u in zip(outs, uo)]
+        for o, u, got in zip(outs, uo, score_on_gpu(specs)):
+            assert got == oracle_score_dict(to_host_bits(o, "f16"), "f16", to_host_bits(u, "f16"), "f16", configs.RTOL["f16"],
+                                            configs.ATOL["f16"])
+        done += 1
+        if done == 24:
+            break
+    assert done == 24
+
+
+def _pair(n, cd, rd, seed, rtol, atol):
+    base = rng.normal(seed, 0, n)
+    noise = rng.normal(seed, 1, n)
+    ref64 = base.copy()
+    cand64 = base * (1 + noise * rtol) + noise * atol * 0.5
+    if n >= 64:
+        idx = np.random.default_rng(seed).choice(n, size=40, replace=False)
+        cand64[idx[0:5]] = np.nan
+        ref64[idx[3:9]] = np.nan
+        cand64[idx[9:12]] = np.inf
+        ref64[idx[11:14]] = np.inf
+        ref64[idx[14]] = -np.inf
+        cand64[idx[14]] = np.inf
+        ref64[idx[15:20]] = 0.0
+        cand64[idx[20:23]] = 0.0
+        ref64[idx[20:23]] = 0.0
+        cand64[idx[23]] = 7e4                      # overflows fp16 to +inf, stays finite in fp32 / fp64
+        cand64[idx[24:30]] *= 1e-6                 # fp16 subnormals
+        ref64[idx[24:30]] *= 1e-6
+    store = {"f32": lambda x: x.astype(np.float32), "f16": rng.round_to_f16_bits, "f64": lambda x: x.astype(np.float64)}
+    return store[cd](cand64), store[rd](ref64)
+
+
+def test_fp16_pairs_are_scored_bit_for_bit_like_the_oracle():
+    cases = [(1, "f16", "f16"), (7, "f16", "f32"), (63, "f16", "f64"), (1000, "f32", "f16"), (8192, "f16", "f16"),
+             (8193, "f16", "f32"), (100003, "f16", "f64"), (3000017, "f16", "f16"), (1234567, "f32", "f16")]
+    specs, wants = [], []
+    for k, (n, cd, rd) in enumerate(cases):
+        for rtol, atol, en in [(1e-3, 1e-5, False), (0.0, 0.0, True), (1e-6, 1e-9, False)]:
+            c, r = _pair(n, cd, rd, 300 + k, max(rtol, 1e-4), max(atol, 1e-6))
+            specs.append((to_device(c, cd), cd, to_device(r, rd), rd, rtol, atol, en))
+            wants.append(oracle_score_dict(c, cd, r, rd, rtol, atol, en))
+    with np.errstate(all="ignore"):
+        got = score_on_gpu(specs)
+    for i, (g, w) in enumerate(zip(got, wants)):
+        assert g == w, (cases[i // 3], g, w)
+    # identical buffers
+    c, _ = _pair(50000, "f16", "f16", 9, 1e-3, 1e-5)
+    g = score_on_gpu([(to_device(c, "f16"), "f16", to_device(c.copy(), "f16"), "f16", 0.0, 0.0, True)])[0]
+    assert g["bit_identical"] == 1 and g["allclose"] == 1 and g["max_abs"] == 0.0
+    # bf16 against fp16 has no kernel: refused, not mis-scored
+    with pytest.raises(pf.PfError) as e:
+        score_on_gpu([(to_device(c, "f16"), "bf16", to_device(c, "f16"), "f16", 0.0, 0.0, False)])
+    assert e.value.status == pf.PF_E_INVALID
+
+
+def test_fp16_ladder_and_tolerance_table():
+    for t in range(-10, 5):
+        assert pf.tolerance("f16", t) == metric.tolerance("f16", t)
+    assert pf.tolerance("f16", -5) == (1e-3, 1e-5)
+    cases = [(5, "f16", "f16"), (16385, "f16", "f32"), (300007, "f16", "f16"), (77777, "f16", "f64")]
+    specs, wants = [], []
+    for k, (n, cd, rd) in enumerate(cases):
+        g = np.random.default_rng(60 + k)
+        base = rng.normal(60 + k, 0, n)
+        cand = base * (1 + 10.0 ** g.uniform(-8, 0.5, n) * g.choice([-1, 1], n)) + 10.0 ** g.uniform(-12, -2, n)
+        store = {"f32": lambda x: x.astype(np.float32), "f16": rng.round_to_f16_bits, "f64": lambda x: x.astype(np.float64)}
+        c, r = store[cd](cand), store[rd](base)
+        specs.append((to_device(c, cd), cd, to_device(r, rd), rd, False))
+        wants.append((n, [score_pair(c, cd, r, rd, *metric.tolerance(cd, t), False)["n_viol"] for t in metric.LADDER]))
+    got = ladder_on_gpu(specs)
+    for g, w in zip(got, wants):
+        assert g[0] == w[0] and g[1] == w[1], (g, w)
+    assert len(set(wants[2][1])) > 4

@@ -1,0 +1,54 @@
+"""GPU parity over task instances: one operator sequence at ten shapes (and three dtypes).
+
+The planner's grouping is the rewrite; it has to hold for every member of the instance (the
+paper's multi-graph requirement, Sec. 3.1), while the tiling is chosen per member.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2605_29357_amd as pf
+from tests.harness import Runner, check_against_oracle
+from workloads import sweeps
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("family", sweeps.FAMILIES)
+def test_every_member_of_the_instance_is_one_kernel_and_matches_the_oracle(family):
+    base = pf.Graph(sweeps.member(family, 0).text)
+    partitions, tilings = set(), set()
+    for k in range(10):
+        w = sweeps.member(family, k)
+        print(family, k, w.name, flush=True)
+        # the member is the base graph at other shapes: the library re-infers every shape itself
+        assert base.variant(w.input_shapes).text() == pf.Graph(w.text).text()
+        r = Runner(w)
+        assert r.info["n_kernels"] == 1 and r.info["workspace_bytes"] == 0
+        gi = r.exe.group_info(0)
+        partitions.add(tuple(gi["nodes"]))
+        tilings.add((gi["template"], gi["lanes_per_row"], gi["block_threads"], r.exe.source(0).count("pf_ld<")))
+        outs = r.run()
+        torch.cuda.synchronize()
+        check_against_oracle(w, outs, what=w.name)
+        del r, outs
+    assert len(partitions) == 1                     # the same rewrite for every member
+    if family != "bias_gelu_gate":
+        assert len(tilings) >= 3, tilings           # but not the same tiling
+    last = {sweeps.bucket(s[-1]) for s in sweeps.SHAPES[family]}
+    assert {1, 2} <= last
+
+
+@pytest.mark.parametrize("family,dtypes", [("bias_gelu_gate", ["bf16", "f16", "f32"]), ("masked_softmax", ["bf16", "f16", "f32"]),
+                                           ("rmsnorm_rope", ["bf16", "f16"])])
+def test_dtype_variants_of_an_instance(family, dtypes):
+    base = pf.Graph(sweeps.member(family, 3, dtypes[0]).text)
+    for dt in dtypes[1:]:
+        for k in (1, 3, 6):
+            w = sweeps.member(family, k, dt)
+            assert base.variant(w.input_shapes, dtypes[0], dt).text() == pf.Graph(w.text).text()
+            r = Runner(w)
+            assert r.info["n_kernels"] == 1
+            outs = r.run()
+            torch.cuda.synchronize()
+            check_against_oracle(w, outs, what=w.name)

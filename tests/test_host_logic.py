@@ -70,7 +70,7 @@ def test_node_by_node_construction_equals_parsing():
     ("in %0 : f32[4]\n%1 = add(%0) : f32\nout %1\n", "takes 2"),
     ("in %0 : f32[4]\nin %1 : f32[5]\n%2 = add(%0, %1) : f32\nout %2\n", "broadcast"),
     ("in %0 : f32[4]\n%1 = frob(%0) : f32\nout %1\n", "unknown operator"),
-    ("in %0 : f16[4]\n%1 = exp(%0) : f32\nout %1\n", "dtype"),
+    ("in %0 : f64[4]\n%1 = exp(%0) : f32\nout %1\n", "dtype"),
     ("in %0 : f32[4]\n%2 = exp(%0) : f32\nout %2\n", "consecutive"),
     ("in %0 : f32[4]\n%1 = exp(%1) : f32\nout %1\n", "earlier"),
     ("in %0 : f32[4]\n%1 = transpose(%0) : f32\nout %1\n", "rank"),
@@ -231,3 +231,13 @@ def test_case_2_pooling_over_the_sequence_dim_is_one_column_reduction_kernel():
     b.output(b.op("sum", [x], "f32", dim=-2))
     b.output(b.op("sum", [x], "f32"))
     assert sorted(gi["template"] for gi in pf.Exec(b.text()).groups()) == ["col_reduce", "row_resident"]
+
+
+def test_fp16_tensors_parse_print_and_compile():
+    w = configs.cfg3_bias_gelu_gate(rows=4, cols=8, dtype="f16")
+    g = pf.Graph(w.text)
+    assert g.text().count("f16") == 6 and pf.Graph(g.text()).text() == g.text()
+    e = pf.Exec(w.text)
+    assert e.info()["n_kernels"] == 1 and e.info()["algorithmic_bytes"] == w.algorithmic_bytes == 2 * (4 * 8 * 3 + 8)
+    assert "const f16* __restrict__" in e.source(0)
+    assert pf.tolerance("f16", -5) == (1e-3, 1e-5) and pf.tolerance("f16", 0) == (1.0, 1.0)

@@ -71,7 +71,11 @@ def cfg1_add_layernorm(rows=64, cols=768, seed=0, use_var_op=False):
 
 
 def causal_mask_bits(n, dtype="bf16"):
-    """Additive causal mask [n, n] as 16-bit patterns: 0 on and below the diagonal, -inf above."""
+    """Additive causal mask [n, n] in the stored form of `dtype`: 0 on and below the diagonal, -inf above."""
+    if dtype == "f32":
+        m = np.zeros((n, n), dtype=np.float32)
+        m[np.triu_indices(n, k=1)] = -np.inf
+        return m
     m = np.zeros((n, n), dtype=np.uint16)
     m[np.triu_indices(n, k=1)] = np.uint16({"bf16": 0xFF80, "f16": 0xFC00}[dtype])
     return m
