@@ -44,7 +44,8 @@ class _NodeInfo(C.Structure):
 
 class _PlanInfo(C.Structure):
     _fields_ = [("n_kernels", C.c_int), ("n_inputs", C.c_int), ("n_outputs", C.c_int),
-                ("algorithmic_bytes", C.c_uint64), ("workspace_bytes", C.c_uint64), ("planned_bytes", C.c_uint64)]
+                ("algorithmic_bytes", C.c_uint64), ("workspace_bytes", C.c_uint64), ("planned_bytes", C.c_uint64),
+                ("n_groups", C.c_int), ("reserved_", C.c_int)]
 
 
 class _GroupInfo(C.Structure):
@@ -260,7 +261,7 @@ class Exec:
         return d
 
     def groups(self):
-        return [self.group_info(i) for i in range(self.info()["n_kernels"])]
+        return [self.group_info(i) for i in range(self.info()["n_groups"])]
 
     def source(self, i):
         need = C.c_size_t()

@@ -201,6 +201,13 @@ pf_status pf_compile(const pf_graph* g, const pf_options* h_opt, pf_exec** e) {
         int idx = 0;
         for (auto& grp : ex->plan.groups) {
             pf::generate_source(*g, opt, grp, idx++);
+            if (grp.scratch_bytes) {     // partial results of a split reduction live at the end of the workspace
+                const uint64_t at = (ex->plan.workspace_bytes + 255) / 256 * 256;
+                grp.scratch_offset = (int64_t)at;
+                ex->plan.workspace_bytes = at + grp.scratch_bytes;
+                grp.bytes_written += grp.scratch_bytes;
+                grp.bytes_read += grp.scratch_bytes;
+            }
             pf::jit_compile(grp);
         }
         ex->n_inputs = (int)g->inputs.size();
@@ -222,7 +229,10 @@ pf_status pf_exec_info(const pf_exec* e, pf_plan_info* h_info) {
         need(e, "e");
         need(h_info, "h_info");
         memset(h_info, 0, sizeof *h_info);
-        h_info->n_kernels = (int)e->plan.groups.size();
+        h_info->n_groups = (int)e->plan.groups.size();
+        h_info->reserved_ = 0;
+        h_info->n_kernels = 0;
+        for (auto& grp : e->plan.groups) h_info->n_kernels += grp.kernel2_name.empty() ? 1 : 2;
         h_info->n_inputs = e->n_inputs;
         h_info->n_outputs = e->n_outputs;
         h_info->algorithmic_bytes = e->plan.algorithmic_bytes;

@@ -16,6 +16,7 @@
 //                 prologue and an epilogue on the reduced shape
 #include <cmath>
 #include <cstring>
+#include <functional>
 #include <set>
 
 #include "device_prelude.h"
@@ -593,10 +594,21 @@ struct Emit {
             if (TX & (TX - 1) || TX > 64) fail(PF_E_INVALID, "tune_row_lanes must be a power of two <= 64 for column reductions");
         }
         const int64_t CT = (vcols + TX - 1) / TX;
-        const int64_t blocks = L * CT;
+        const int64_t tiles = L * CT;
+        bool any_var = false;
+        for (int id : grp.nodes) any_var |= g.nodes[id].op == PF_OP_VAR;
+        // Few (leading index, column tile) pairs and many rows: split the rows over SP workgroups per
+        // tile.  Each writes its partial results to scratch memory; a second, small kernel combines
+        // them and runs the epilogue.  (No waiting between workgroups anywhere.)
+        int SP = 1;
+        // (worth a second launch once an unsplit workgroup of 1024 lanes would walk eight or more rows per lane)
+        if (tiles < 128 && S >= 8 * (1024 / TX) && !any_var)
+            while (tiles * SP < 512 && S / (SP * 2) >= 32 && SP < 256) SP <<= 1;
+        const int64_t SB = (S + SP - 1) / SP;          // rows per workgroup
+        const int64_t blocks = tiles * SP;
         // lanes along S: enough workgroups x lanes to fill the chip, never more than rows
         int TY = 1024 / TX;
-        while (TY > 1 && (TY / 2) * TX >= 64 && (TY > S || blocks * TX * TY > (int64_t)512 * 1024)) TY >>= 1;
+        while (TY > 1 && (TY / 2) * TX >= 64 && (TY > SB || blocks * TX * TY > (int64_t)512 * 1024)) TY >>= 1;
         if (opt.tune_col_block > 0) {
             if (opt.tune_col_block & (opt.tune_col_block - 1) || opt.tune_col_block > 1024 || opt.tune_col_block < 64 || opt.tune_col_block < TX)
                 fail(PF_E_INVALID, "tune_col_block must be a power of two in [64, 1024], at least the lanes per row");
@@ -609,7 +621,7 @@ struct Emit {
         // rows in flight per lane; at least four trips of the row loop measured best (B=32, S=512, D=1024:
         // 18.0 us with U = 2 against 18.9 us with U = 4 at 16 x 64 lanes)
         int U = 4;
-        while (U > 1 && ((int64_t)U * TY * 4 > S || U * vec * std::max(n_vec_ops, 1) > 64)) U >>= 1;
+        while (U > 1 && ((int64_t)U * TY * 4 > SB || U * vec * std::max(n_vec_ops, 1) > 64)) U >>= 1;
         if (opt.tune_row_unroll > 0) U = opt.tune_row_unroll;
         RU = U;
         NN = vec;
@@ -624,25 +636,39 @@ struct Emit {
         // reduction slots in LDS (a variance takes two: sum, then squared deviations)
         std::map<int, int> slot_of;
         int n_red = 0;
-        bool any_var = false;
         for (int id : grp.nodes)
             if (is_reduction(g.nodes[id].op)) {
                 slot_of[id] = n_red;
                 n_red += g.nodes[id].op == PF_OP_VAR ? 2 : 1;
-                any_var |= g.nodes[id].op == PF_OP_VAR;
             }
+        const bool split = SP > 1;
+        if (split) {
+            grp.scratch_bytes = (uint64_t)blocks * n_red * W * (precise ? 8 : 4);
+            grp.kernel2_name = grp.kernel_name + "_fin";
+            grp.grid2 = tiles;
+            grp.block2 = W < 64 ? 64 : W;
+        }
         // operands that do not change along S are loaded once
         hoisted.clear();
         for (size_t oi = 0; oi < grp.operands.size(); ++oi)
             if (!grp.operands[oi].coluni && grp.operands[oi].stride[rd - 2] == 0) hoisted.insert((int)oi);
 
-        signature();
-        line(strf("    constexpr int TX = %d, TY = %d, VEC = %d, U = %d, W = %d, NW = %d, BLOCK = %d;", TX, TY, vec, U, W, NW, block));
-        line(strf("    constexpr %s S = %lld, DD = %lld, CT = %lld;", idx_t(), (long long)S, (long long)DD, (long long)CT));
+        const std::string extra = split ? strf("%s* __restrict__ scratch", acc) : "";
+        signature(extra);
+        line(strf("    constexpr int TX = %d, TY = %d, VEC = %d, U = %d, W = %d, NW = %d, BLOCK = %d, SP = %d, NRED = %d;", TX, TY, vec, U, W, NW, block,
+                  SP, n_red));
+        line(strf("    constexpr %s S = %lld, DD = %lld, CT = %lld, SB = %lld;", idx_t(), (long long)S, (long long)DD, (long long)CT, (long long)SB));
         line(strf("    __shared__ %s part[%d][NW][W];", acc, n_red));
         line(strf("    __shared__ %s tot[%d][W];", acc, n_red));
         line("    const int tx = threadIdx.x % TX, ty = threadIdx.x / TX, wave = threadIdx.x >> 6;");
-        line(strf("    const %s ct = blockIdx.x %% CT, lead = blockIdx.x / CT;", idx_t()));
+        if (split) {
+            line(strf("    const %s seg = blockIdx.x %% SP, tile = blockIdx.x / SP;", idx_t()));
+            line(strf("    const %s ct = tile %% CT, lead = tile / CT;", idx_t()));
+            line(strf("    const %s s_begin = seg * SB, s_end = s_begin + SB < S ? s_begin + SB : S;   // may be empty for the last segments", idx_t()));
+        } else {
+            line(strf("    const %s ct = blockIdx.x %% CT, lead = blockIdx.x / CT;", idx_t()));
+            line(strf("    constexpr %s s_begin = 0, s_end = S;", idx_t()));
+        }
         line(strf("    const %s d0 = ct * W + (%s)tx * VEC;", idx_t(), idx_t()));
         // lanes whose columns lie outside still take part in shuffles and barriers; they read column block 0
         line(strf("    const bool col_ok = d0 < DD;"));
@@ -683,9 +709,9 @@ struct Emit {
                               slot_of.at(id), acc, (long long)S, id));
                 }
             }
-            line(strf("    for (%s sb = ty; sb < S; sb += (%s)TY * U) {   // pass %d", idx_t(), idx_t(), pass));
+            line(strf("    for (%s sb = s_begin + ty; sb < s_end; sb += (%s)TY * U) {   // pass %d", idx_t(), idx_t(), pass));
             line(strf("        %s row[U]; bool row_ok[U];", idx_t()));
-            line(strf("        _Pragma(\"unroll\") for (int u = 0; u < U; ++u) { const %s t = sb + (%s)u * TY; row_ok[u] = t < S; row[u] = row_ok[u] ? t : S - 1; }",
+            line(strf("        _Pragma(\"unroll\") for (int u = 0; u < U; ++u) { const %s t = sb + (%s)u * TY; row_ok[u] = t < s_end; row[u] = row_ok[u] ? t : s_end - 1; }",
                       idx_t(), idx_t()));
             for (size_t oi = 0; oi < grp.operands.size(); ++oi) {
                 const Operand& o = grp.operands[oi];
@@ -776,33 +802,70 @@ struct Emit {
         }
         // epilogue: lane c finishes column c of this workgroup's W columns
         RU = 1;
+        auto emit_epilogue = [&](const std::function<std::string(int)>& total) {
+            line(strf("        const %s col = ct * W + c;", idx_t()));
+            line("        if (col >= DD) continue;");
+            line("        constexpr int u = 0; (void)u;");
+            for (int id : grp.nodes) {
+                const Node& n = g.nodes[id];
+                if (!is_reduction(n.op)) continue;
+                const int sl = slot_of.at(id);
+                if (n.op == PF_OP_SUM || n.op == PF_OP_MAX) line(strf("        float s%d[1]; s%d[0] = (float)%s;", id, id, total(sl).c_str()));
+                else if (n.op == PF_OP_MEAN) line(strf("        float s%d[1]; s%d[0] = (float)(%s / (%s)%lld);", id, id, total(sl).c_str(), acc, (long long)S));
+                else line(strf("        float s%d[1]; s%d[0] = (float)(%s / (%s)%lld);", id, id, total(sl + 1).c_str(), acc, (long long)(S - n.correction)));
+            }
+            for (size_t oi = 0; oi < grp.operands.size(); ++oi) {
+                const Operand& o = grp.operands[oi];
+                if (!o.coluni) continue;
+                line(strf("        float x%zu[1]; x%zu[0] = pf_ld1(p%zu + %s + col * %lld);", oi, oi, oi, lead_offset_n(o, nlead).c_str(),
+                          (long long)o.stride[rd - 1]));
+            }
+            for (int id : grp.nodes)
+                if (epilogue_node(id)) emit_elementwise(id, 1);
+            int sp = 0;
+            for (auto& st : grp.stores) {
+                const int cnt = 1 + (int)st.also_outputs.size();
+                if (st.col_uniform)
+                    for (int c = 0; c < cnt; ++c) line(strf("        pf_st1(q%d + lead * DD + col, s%d[0]);", sp + c, st.node));
+                sp += cnt;
+            }
+        };
+        if (!split) {
+            line("    for (int c = threadIdx.x; c < W; c += BLOCK) {");
+            emit_epilogue([](int sl) { return strf("tot[%d][c]", sl); });
+            line("    }");
+            line("}");
+            return;
+        }
+        // split rows: publish this workgroup's partial results ...
+        line("    for (int c = threadIdx.x; c < W; c += BLOCK)");
+        line(strf("        _Pragma(\"unroll\") for (int r = 0; r < NRED; ++r) scratch[(((%s)tile * SP + seg) * NRED + r) * W + c] = tot[r][c];", idx_t()));
+        line("}");
+        // ... and combine them, one workgroup per (leading index, column tile), one lane per column
+        const std::string name1 = grp.kernel_name;
+        grp.kernel_name = grp.kernel2_name;
+        const int block1 = grp.block;
+        grp.block = grp.block2;
+        signature(strf("const %s* __restrict__ scratch", acc));
+        grp.kernel_name = name1;
+        grp.block = block1;
+        line(strf("    constexpr int W = %d, SP = %d, NRED = %d, BLOCK = %d;", W, SP, n_red, grp.block2));
+        line(strf("    constexpr %s DD = %lld, CT = %lld;", idx_t(), (long long)DD, (long long)CT));
+        line(strf("    const %s tile = blockIdx.x, ct = tile %% CT, lead = tile / CT;", idx_t()));
+        emit_lead_decomposition("lead", nlead);
         line("    for (int c = threadIdx.x; c < W; c += BLOCK) {");
-        line(strf("        const %s col = ct * W + c;", idx_t()));
-        line("        if (col >= DD) continue;");
-        line("        constexpr int u = 0; (void)u;");
+        line(strf("        %s fin[NRED];", acc));
         for (int id : grp.nodes) {
             const Node& n = g.nodes[id];
             if (!is_reduction(n.op)) continue;
             const int sl = slot_of.at(id);
-            if (n.op == PF_OP_SUM || n.op == PF_OP_MAX) line(strf("        float s%d[1]; s%d[0] = (float)tot[%d][c];", id, id, sl));
-            else if (n.op == PF_OP_MEAN) line(strf("        float s%d[1]; s%d[0] = (float)(tot[%d][c] / (%s)%lld);", id, id, sl, acc, (long long)S));
-            else line(strf("        float s%d[1]; s%d[0] = (float)(tot[%d][c] / (%s)%lld);", id, id, sl + 1, acc, (long long)(S - n.correction)));
+            const std::string at = strf("scratch[(((%s)tile * SP + k) * NRED + %d) * W + c]", idx_t(), sl);
+            if (n.op == PF_OP_MAX)
+                line(strf("        { float t = -__builtin_inff(); for (int k = 0; k < SP; ++k) t = pf_max_nan(t, (float)%s); fin[%d] = t; }", at.c_str(), sl));
+            else
+                line(strf("        { %s t = 0; for (int k = 0; k < SP; ++k) t += %s; fin[%d] = t; }", acc, at.c_str(), sl));
         }
-        for (size_t oi = 0; oi < grp.operands.size(); ++oi) {
-            const Operand& o = grp.operands[oi];
-            if (!o.coluni) continue;
-            line(strf("        float x%zu[1]; x%zu[0] = pf_ld1(p%zu + %s + col * %lld);", oi, oi, oi, lead_offset_n(o, nlead).c_str(),
-                      (long long)o.stride[rd - 1]));
-        }
-        for (int id : grp.nodes)
-            if (epilogue_node(id)) emit_elementwise(id, 1);
-        int sp = 0;
-        for (auto& st : grp.stores) {
-            const int cnt = 1 + (int)st.also_outputs.size();
-            if (st.col_uniform)
-                for (int c = 0; c < cnt; ++c) line(strf("        pf_st1(q%d + lead * DD + col, s%d[0]);", sp + c, st.node));
-            sp += cnt;
-        }
+        emit_epilogue([](int sl) { return strf("fin[%d]", sl); });
         line("    }");
         line("}");
     }
@@ -1174,8 +1237,10 @@ struct Emit {
             for (size_t c = 0; c < 1 + st.also_outputs.size(); ++c, ++sp) p += strf("%sq%d", p.empty() ? "" : ", ", sp);
         return p;
     }
-    void signature() {
-        line(strf("extern \"C\" __global__ void __launch_bounds__(%d) %s(%s) {", grp.block, grp.kernel_name.c_str(), param_list().c_str()));
+    void signature(const std::string& extra = "") {
+        std::string params = param_list();
+        if (!extra.empty()) params += (params.empty() ? "" : ", ") + extra;
+        line(strf("extern \"C\" __global__ void __launch_bounds__(%d) %s(%s) {", grp.block, grp.kernel_name.c_str(), params.c_str()));
         for (size_t oi = 0; oi < grp.operands.size(); ++oi)     // source dims a sliced window pins to one index
             if (grp.operands[oi].const_offset) line(strf("    p%zu += %lld;", oi, (long long)grp.operands[oi].const_offset));
     }
@@ -1240,6 +1305,7 @@ struct Emit {
         size_t pos;
         while ((pos = s.find("PFKNAME")) != std::string::npos) s.replace(pos, 7, nm);
         grp.kernel_name = nm;
+        if (!grp.kernel2_name.empty()) grp.kernel2_name = nm + "_fin";
         grp.source = s;
     }
 };

@@ -11,6 +11,7 @@ struct pf_exec {
     bool loaded = false;
     std::vector<void*> modules;     // hipModule_t
     std::vector<void*> functions;   // hipFunction_t
+    std::vector<void*> functions2;  // hipFunction_t of a group's second kernel, or null
 };
 
 namespace pf {

@@ -124,6 +124,14 @@ struct Group {
     Shape domain;                  // iteration domain, rank-aligned full shape
     int64_t rows = 1, cols = 1;    // product of leading dims, last dim
     std::vector<Operand> operands; // external reads
+    // a column reduction whose rows are split over several workgroups: partial results go to scratch
+    // memory (a slice of the workspace, passed as the last kernel argument) and a second kernel of
+    // the same module combines them
+    uint64_t scratch_bytes = 0;
+    int64_t scratch_offset = -1;
+    std::string kernel2_name;
+    int64_t grid2 = 0;
+    int block2 = 0;
     std::vector<Store> stores;     // writes
     // launch configuration (filled by codegen)
     int block = 256;

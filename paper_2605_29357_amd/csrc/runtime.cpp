@@ -110,6 +110,7 @@ void exec_load(pf_exec& e) {
     if (e.loaded) return;
     e.modules.assign(e.plan.groups.size(), nullptr);
     e.functions.assign(e.plan.groups.size(), nullptr);
+    e.functions2.assign(e.plan.groups.size(), nullptr);
     for (size_t i = 0; i < e.plan.groups.size(); ++i) {
         Group& grp = e.plan.groups[i];
         hipModule_t mod = nullptr;
@@ -120,6 +121,11 @@ void exec_load(pf_exec& e) {
         err = hipModuleGetFunction(&fn, mod, grp.kernel_name.c_str());
         if (err != hipSuccess) fail(PF_E_RUNTIME, "hipModuleGetFunction(%s): %s", grp.kernel_name.c_str(), hipGetErrorString(err));
         e.functions[i] = fn;
+        if (!grp.kernel2_name.empty()) {
+            err = hipModuleGetFunction(&fn, mod, grp.kernel2_name.c_str());
+            if (err != hipSuccess) fail(PF_E_RUNTIME, "hipModuleGetFunction(%s): %s", grp.kernel2_name.c_str(), hipGetErrorString(err));
+            e.functions2[i] = fn;
+        }
     }
     e.loaded = true;
 }
@@ -129,6 +135,7 @@ void exec_unload(pf_exec& e) {
         if (m) (void)hipModuleUnload((hipModule_t)m);
     e.modules.clear();
     e.functions.clear();
+    e.functions2.clear();
     e.loaded = false;
 }
 
@@ -150,21 +157,24 @@ void exec_run(pf_exec& e, const void* const* d_inputs, void* const* d_outputs, v
             ptrs[n++] = s.graph_output >= 0 ? d_outputs[s.graph_output] : (void*)((char*)d_ws + s.ws_offset);
             for (int k : s.also_outputs) ptrs[n++] = d_outputs[k];
         }
+        if (grp.scratch_bytes) ptrs[n++] = (char*)d_ws + grp.scratch_offset;
         for (int k = 0; k < n; ++k) args[k] = &ptrs[k];
         // events, when given, bracket the kernels themselves (dispatch timestamps), not the
         // launch calls: the first kernel carries the start event, the last one the stop event
+        const bool two = e.functions2[i] != nullptr;
         hipEvent_t ev0 = i == 0 ? (hipEvent_t)start_event : nullptr;
         hipEvent_t ev1 = i + 1 == e.plan.groups.size() ? (hipEvent_t)stop_event : nullptr;
-        hipError_t err;
-        if ((ev0 || ev1) && (uint64_t)grp.grid * (uint64_t)grp.block < (1ull << 32))
-            err = hipExtModuleLaunchKernel((hipFunction_t)e.functions[i], (uint32_t)(grp.grid * grp.block), 1, 1, (uint32_t)grp.block, 1, 1,
-                                           0, (hipStream_t)stream, args, nullptr, ev0, ev1, 0);
-        else {
-            if (ev0) (void)hipEventRecord(ev0, (hipStream_t)stream);
-            err = hipModuleLaunchKernel((hipFunction_t)e.functions[i], (unsigned)grp.grid, 1, 1, (unsigned)grp.block, 1, 1, 0,
-                                        (hipStream_t)stream, args, nullptr);
-            if (ev1 && err == hipSuccess) (void)hipEventRecord(ev1, (hipStream_t)stream);
-        }
+        auto launch = [&](void* fn, int64_t grid, int block, hipEvent_t a, hipEvent_t b) -> hipError_t {
+            if ((a || b) && (uint64_t)grid * (uint64_t)block < (1ull << 32))
+                return hipExtModuleLaunchKernel((hipFunction_t)fn, (uint32_t)(grid * block), 1, 1, (uint32_t)block, 1, 1, 0, (hipStream_t)stream,
+                                                args, nullptr, a, b, 0);
+            if (a) (void)hipEventRecord(a, (hipStream_t)stream);
+            hipError_t r = hipModuleLaunchKernel((hipFunction_t)fn, (unsigned)grid, 1, 1, (unsigned)block, 1, 1, 0, (hipStream_t)stream, args, nullptr);
+            if (b && r == hipSuccess) (void)hipEventRecord(b, (hipStream_t)stream);
+            return r;
+        };
+        hipError_t err = launch(e.functions[i], grp.grid, grp.block, ev0, two ? nullptr : ev1);
+        if (err == hipSuccess && two) err = launch(e.functions2[i], grp.grid2, grp.block2, nullptr, ev1);
         if (err != hipSuccess) fail(PF_E_RUNTIME, "launch of %s failed: %s", grp.kernel_name.c_str(), hipGetErrorString(err));
     }
 }

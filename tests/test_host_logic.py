@@ -219,6 +219,13 @@ def test_case_2_pooling_over_the_sequence_dim_is_one_column_reduction_kernel():
     assert pf.Exec(w.text, fuse=False).info()["n_kernels"] == 5
     g = pf.Graph(w.text)
     assert "dim=-2" in g.text() and g.node_info(3)["shape"] == (4, 256)
+    # few column tiles and many rows: rows split over workgroups, partial sums combined by a second kernel
+    sp = pf.Exec(configs.masked_mean_pooling(B=1, S=2048, D=512).text)
+    assert sp.info()["n_kernels"] == 2 and len(sp.groups()) == 1 and sp.info()["workspace_bytes"] > 0
+    assert "_fin(" in sp.source(0) and "scratch" in sp.source(0)
+    with pytest.raises(pf.PfError) as err:
+        sp.execute([256, 512], [1024], 0, 0)                         # the partial sums need the workspace
+    assert err.value.status == pf.PF_E_RUNTIME
     # a full-shape consumer of the reduced value cannot stay in the kernel
     b = Builder()
     x = b.input("f32", (8, 16))
