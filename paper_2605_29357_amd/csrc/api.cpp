@@ -335,7 +335,6 @@ StagedPairs stage_pairs(const pf_pair* h_pairs, int n_pairs, void* d_workspace, 
     sp.d_pairs = (pf::PairDev*)d_workspace;
     sp.d_start = (unsigned long long*)((char*)d_workspace + pairs_bytes);
     sp.d_rest = (char*)d_workspace + staged_head_bytes(n_pairs);
-    const unsigned long long chunk = pf::score_chunk_elems();
     for (int i = 0; i < n_pairs; ++i) {
         const pf_pair& p = h_pairs[i];
         if (p.cand_dtype != PF_F32 && p.cand_dtype != PF_BF16 && p.cand_dtype != PF_F16)
@@ -370,6 +369,8 @@ StagedPairs stage_pairs(const pf_pair* h_pairs, int n_pairs, void* d_workspace, 
             b.pairs[k].equal_nan = p.equal_nan;
             b.pairs[k].orig = order[first + k];
             b.start[k] = total;
+            const unsigned long long chunk = pf::score_chunk_elems(p.n);
+            b.pairs[k].chunk = chunk;
             const unsigned long long nb = (p.n + chunk - 1) / chunk;
             if (sp.ranges.count[p.cand_dtype][p.ref_dtype] == 0) sp.ranges.first[p.cand_dtype][p.ref_dtype] = total;
             sp.ranges.count[p.cand_dtype][p.ref_dtype] += nb;

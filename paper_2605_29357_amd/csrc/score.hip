@@ -19,7 +19,7 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kBlock = 256;
-constexpr int kPerThread = 64;                       // elements per thread per block-chunk
+constexpr int kPerThread = 64;                       // elements per thread per block-chunk (small pairs)
 constexpr int kSlots = pf::kScoreSlots;              // partial results per pair (spreads the atomics)
 constexpr unsigned long long kChunk = (unsigned long long)kBlock * kPerThread;
 
@@ -169,6 +169,11 @@ __device__ __forceinline__ void score_chunk(const pf::PairDev& pr, unsigned long
 }
 
 __device__ __forceinline__ double wave_max(double v);
+__device__ __forceinline__ float wave_max32(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
 
 // ---- fp32 screening path (both sides f32, bf16 or fp16) ---------------------
 // Almost every element can be classified without fp64: with a, b widened to
@@ -203,7 +208,9 @@ template <int DT> struct Vec8 {
     static constexpr int NW = HALF ? 4 : 8;
     unsigned int w[NW];
     __device__ __forceinline__ void load(const void* base, unsigned long long i) {
-        const u32x4* p = (const u32x4*)((const char*)base + i * (HALF ? 2 : 4));
+        // the buffers are device memory: say so, or the accesses are compiled as generic (flat) ones
+        typedef const __attribute__((address_space(1))) u32x4* gptr;
+        const gptr p = (gptr)((const char*)base + i * (HALF ? 2 : 4));
 #pragma unroll
         for (int k = 0; k < NW / 4; ++k) {
             const u32x4 r = __builtin_nontemporal_load(p + k);
@@ -215,6 +222,12 @@ template <int DT> struct Vec8 {
         if (DT == PF_BF16) return __uint_as_float((j & 1) ? (w[j >> 1] & 0xffff0000u) : (w[j >> 1] << 16));
         if (DT == PF_F16) return Elem<PF_F16>::widen32((j & 1) ? (w[j >> 1] >> 16) : (w[j >> 1] & 0xffffu));
         return __uint_as_float(w[j]);
+    }
+    // a raw element widened to fp32 (exact)
+    static __device__ __forceinline__ float widen32(unsigned int r) {
+        if (DT == PF_BF16) return __uint_as_float(r << 16);
+        if (DT == PF_F16) return Elem<PF_F16>::widen32(r);
+        return __uint_as_float(r);
     }
     // element j as Elem<DT>::raw
     __device__ __forceinline__ unsigned int raw(int j) const {
@@ -229,14 +242,18 @@ __device__ __forceinline__ void score_chunk_fast(const pf::PairDev& pr, unsigned
     const Screen sc = make_screen(pr);
     const int zero_tol = (pr.rtol == 0.0) & (pr.atol == 0.0);
     const int force_exact = !sc.viol_decidable;
+    // the lean screen needs an absolute tolerance fp32 can represent comfortably (then every allowed
+    // error bound is >= 1e-30 and needs no guard of its own)
+    const bool lean = !force_exact && sc.atol_lo >= 1e-30f;
     // wave-shared lower bounds of the exact maxima (rounded to fp32 and pulled down)
-    double wave_abs = seed_abs, wave_rel = seed_rel;
-    float thr_abs = wave_abs >= 1e-30 ? (float)wave_abs * 0.999998f : 0.0f;
-    float thr_rel = wave_rel >= 1e-30 ? (float)wave_rel * 0.999998f : 0.0f;
+    float wave_abs = (float)seed_abs, wave_rel = (float)seed_rel;
+    float thr_abs = wave_abs >= 1e-30f ? wave_abs * 0.999998f : 0.0f;
+    float thr_rel = wave_rel >= 1e-30f ? wave_rel * 0.999998f : 0.0f;
     unsigned int xor_acc = 0;
     const unsigned long long nvec = (end - begin) / 8;
     const unsigned long long iters = (nvec + kBlock - 1) / kBlock;
-    // the next vector is already on its way while the current one is screened
+    // the next vector is already on its way while the current one is screened (two vectors ahead
+    // cost registers, hence resident waves, and measured 7% slower)
     Vec8<CD> na;
     Vec8<RD> nb;
     if (threadIdx.x < nvec) {
@@ -254,47 +271,78 @@ __device__ __forceinline__ void score_chunk_fast(const pf::PairDev& pr, unsigned
         }
         unsigned int fmask = 0;          // bit j: element j needs the exact path
         unsigned int nv = 0;
+        // full classification of element j: certainly inside the tolerance, certainly outside (counted
+        // here), or flagged for the exact path (undecided, NaN/Inf, possible new maximum).  Branch-free on
+        // purpose (bitwise | and &): short-circuit forms turn into exec-mask juggling.
+        auto classify = [&](int j) {
+            const float a = va.f32(j), b = vb.f32(j);
+            const float d = fabsf(a - b), ab = fabsf(b);
+            const float lo = __builtin_fmaf(sc.rtol_lo, ab, sc.atol_lo);
+            const float hi = __builtin_fmaf(sc.rtol_hi, ab, sc.atol_hi);
+            // thresholds below 1e-30 are too close to the fp32 subnormal range to be trusted
+            const int ok = (d == 0.0f) | ((d <= lo) & (lo >= 1e-30f));
+            const int out = (d > hi) & ((hi >= 1e-30f) | zero_tol);
+            const float pr_rel = thr_rel * ab;
+            const int f = (!(ok | out)) | (!(d < __builtin_inff())) | (d > thr_abs) | (d > pr_rel) | ((pr_rel < 1e-30f) & (d != 0.0f)) |
+                          force_exact;
+            nv += out & !f;
+            fmask |= (unsigned)f << j;
+        };
         if (live) {
             if (CD == RD) {
 #pragma unroll
                 for (int k = 0; k < Vec8<CD>::NW; ++k) xor_acc |= va.w[k] ^ vb.w[k];
             }
-            // branch-free on purpose (bitwise | and &): short-circuit forms turn into
-            // exec-mask juggling that costs more than the arithmetic
+            if (lean) {
+                // One bound per element, one comparison: an element passes when |a-b| <= m with
+                //   m = clamp(thr_rel |b| - 1e-30, 0, min(rtol_lo |b| + atol_lo, thr_abs)),
+                // i.e. inside the tolerance, not a new maximum of either error, and (the lower clamp)
+                // never a non-zero error against a reference too small for fp32 to judge.  NaN and
+                // infinities fail the comparison.
+                const float ta = fminf(thr_abs, 3.0e38f), tr = fminf(thr_rel, 3.0e38f);
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const float a = va.f32(j), b = vb.f32(j);
-                const float d = fabsf(a - b), ab = fabsf(b);
-                const float lo = __builtin_fmaf(sc.rtol_lo, ab, sc.atol_lo);
-                const float hi = __builtin_fmaf(sc.rtol_hi, ab, sc.atol_hi);
-                // thresholds below 1e-30 are too close to the fp32 subnormal range to be trusted
-                const int ok = (d == 0.0f) | ((d <= lo) & (lo >= 1e-30f));
-                const int out = (d > hi) & ((hi >= 1e-30f) | zero_tol);
-                const float pr_rel = thr_rel * ab;
-                // undecided tolerance test, NaN/Inf (d is then NaN or inf), or a possible new maximum
-                const int f = (!(ok | out)) | (!(d < __builtin_inff())) | (d > thr_abs) | (d > pr_rel) | ((pr_rel < 1e-30f) & (d != 0.0f)) |
-                              force_exact;
-                nv += out & !f;
-                fmask |= (unsigned)f << j;
+                for (int j = 0; j < 8; ++j) {
+                    const float a = va.f32(j), b = vb.f32(j);
+                    const float d = fabsf(a - b), ab = fabsf(b);
+                    const float lo = __builtin_fmaf(sc.rtol_lo, ab, sc.atol_lo);
+                    const float m = __builtin_amdgcn_fmed3f(__builtin_fmaf(tr, ab, -1e-30f), 0.0f, fminf(lo, ta));
+                    fmask |= (d <= m) ? 0u : (1u << j);
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) classify(j);
             }
         }
-        acc.n_viol += nv;
+        acc.n_viol += nv;                // violations the full classification decided on its own
         if (__any(fmask != 0)) {
-            // exact fp64 evaluation of the flagged elements only; the trip count is the
-            // largest number of flagged elements in any lane of the wave
+            // the flagged elements only; the trip count is the largest number of flagged elements in
+            // any lane of the wave
             while (fmask) {
                 const int j = __builtin_ctz(fmask);
                 fmask &= fmask - 1;
                 unsigned int ea = va.raw(0), eb = vb.raw(0);
 #pragma unroll
                 for (int t = 1; t < 8; ++t) { ea = j == t ? va.raw(t) : ea; eb = j == t ? vb.raw(t) : eb; }
+                if (lean) {
+                    // certainly outside the tolerance and certainly no new maximum: counted without fp64
+                    const float a = Vec8<CD>::widen32(ea), b = Vec8<RD>::widen32(eb);
+                    const float d = fabsf(a - b), ab = fabsf(b);
+                    const float hi = __builtin_fmaf(sc.rtol_hi, ab, sc.atol_hi), pr_rel = thr_rel * ab;
+                    if ((d > hi) & (d < __builtin_inff()) & (d <= thr_abs) & (d <= pr_rel) & (pr_rel >= 1e-30f)) {
+                        acc.n_viol += 1;
+                        continue;
+                    }
+                }
                 score_exact<CD, RD>(ea, eb, pr, acc);
             }
-            if (__any((acc.max_abs > wave_abs) | (acc.max_rel > wave_rel))) {
-                wave_abs = fmax(wave_abs, wave_max(acc.max_abs));
-                wave_rel = fmax(wave_rel, wave_max(acc.max_rel));
-                thr_abs = wave_abs >= 1e-30 ? (float)wave_abs * 0.999998f : 0.0f;
-                thr_rel = wave_rel >= 1e-30 ? (float)wave_rel * 0.999998f : 0.0f;
+            // the thresholds are fp32 lower bounds, so the wave-wide maxima are taken in fp32 (the rounding
+            // of the conversion is far inside the 2e-6 by which the thresholds are pulled down)
+            const float la = (float)acc.max_abs, lr = (float)acc.max_rel;
+            if (__any((la > wave_abs) | (lr > wave_rel))) {
+                wave_abs = fmaxf(wave_abs, wave_max32(la));
+                wave_rel = fmaxf(wave_rel, wave_max32(lr));
+                thr_abs = wave_abs >= 1e-30f ? wave_abs * 0.999998f : 0.0f;
+                thr_rel = wave_rel >= 1e-30f ? wave_rel * 0.999998f : 0.0f;
             }
         }
     }
@@ -330,14 +378,55 @@ __global__ void __launch_bounds__(64) score_upload_kernel(pf::PairBatch batch, p
     if (i == 0 && batch.last) block_start[batch.first + batch.count] = batch.start[batch.count];
 }
 
-__global__ void __launch_bounds__(kBlock) score_init_kernel(int n_pairs, pf_score_result* slots) {
-    const int p = blockIdx.x * blockDim.x + threadIdx.x;
-    if (p < n_pairs * kSlots) {
+__device__ __forceinline__ void raise_max(double* slot, double v);
+
+// Clears the partial-result slots of a pair and seeds its maxima.  The cheap screen of the main
+// kernel passes an element only when it cannot raise a running maximum, so a wave that starts from
+// zero sends its first elements through the exact path one record at a time.  Here 32 workgroups
+// per pair evaluate one element per lane exactly (8192 evenly spread elements per pair) and raise
+// the pair's seed: the seeds are errors of real elements (a maximum may count an element twice),
+// and a sample of that size leaves about one element in 8192 above them.
+constexpr int kSeedBlocks = 32;
+template <int CD, int RD>
+__device__ __forceinline__ void seed_sample(const pf::PairDev& pr, unsigned long long k, Acc& acc) {
+    const unsigned long long want = (unsigned long long)kSeedBlocks * kBlock;
+    const unsigned long long stride = pr.n > want ? pr.n / want : 1;
+    const unsigned long long i = k * stride;
+    if (i < pr.n) score_exact<CD, RD>(Elem<CD>::load1(pr.cand, i), Elem<RD>::load1(pr.ref, i), pr, acc);
+}
+
+__global__ void __launch_bounds__(kBlock) score_init_kernel(pf::PairDev* pairs, int n_pairs, pf_score_result* slots) {
+    const int p = blockIdx.x / kSeedBlocks, part = blockIdx.x % kSeedBlocks;
+    if (p >= n_pairs) return;
+    if (threadIdx.x < kSlots / kSeedBlocks) {
         pf_score_result z;
         z.max_abs = 0.0; z.max_rel = 0.0; z.n = 0; z.n_viol = 0;
         z.nan_cand = z.nan_ref = z.inf_cand = z.inf_ref = 0;
         z.allclose = 0; z.bit_identical = 0; z.reserved_ = 0;
-        slots[p] = z;
+        slots[(size_t)p * kSlots + part * (kSlots / kSeedBlocks) + threadIdx.x] = z;
+    }
+    const pf::PairDev pr = pairs[p];
+    Acc acc;
+    const unsigned long long k = (unsigned long long)part * kBlock + threadIdx.x;
+    switch (pr.cand_dtype * 4 + pr.ref_dtype) {
+        case PF_F32 * 4 + PF_F32: seed_sample<PF_F32, PF_F32>(pr, k, acc); break;
+        case PF_F32 * 4 + PF_BF16: seed_sample<PF_F32, PF_BF16>(pr, k, acc); break;
+        case PF_F32 * 4 + PF_F16: seed_sample<PF_F32, PF_F16>(pr, k, acc); break;
+        case PF_BF16 * 4 + PF_F32: seed_sample<PF_BF16, PF_F32>(pr, k, acc); break;
+        case PF_BF16 * 4 + PF_BF16: seed_sample<PF_BF16, PF_BF16>(pr, k, acc); break;
+        case PF_F16 * 4 + PF_F32: seed_sample<PF_F16, PF_F32>(pr, k, acc); break;
+        case PF_F16 * 4 + PF_F16: seed_sample<PF_F16, PF_F16>(pr, k, acc); break;
+        default: break;          // fp64 references are not screened: no seed needed
+    }
+    __shared__ double s_abs[kBlock / 64], s_rel[kBlock / 64];
+    const double wa = wave_max(acc.max_abs), wr = wave_max(acc.max_rel);
+    if ((threadIdx.x & 63) == 0) { s_abs[threadIdx.x >> 6] = wa; s_rel[threadIdx.x >> 6] = wr; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double ma = s_abs[0], mr = s_rel[0];
+        for (int w = 1; w < kBlock / 64; ++w) { ma = fmax(ma, s_abs[w]); mr = fmax(mr, s_rel[w]); }
+        if (ma > 0.0) raise_max(&pairs[p].seed_abs, ma);
+        if (mr > 0.0) raise_max(&pairs[p].seed_rel, mr);
     }
 }
 
@@ -361,27 +450,31 @@ __global__ void __launch_bounds__(kBlock) score_kernel(const pf::PairDev* pairs,
         if (block_start[mid] <= bid) lo = mid; else hi = mid;
     }
     const pf::PairDev pr = pairs[lo];
-    const unsigned long long begin = (bid - block_start[lo]) * kChunk;
-    const unsigned long long end = begin + kChunk < pr.n ? begin + kChunk : pr.n;
+    const unsigned long long begin = (bid - block_start[lo]) * pr.chunk;
+    const unsigned long long end = begin + pr.chunk < pr.n ? begin + pr.chunk : pr.n;
     Acc acc;
     // maxima other blocks of this pair have already published: a head start for the screening thresholds
     pf_score_result* my_slot = slots + (size_t)lo * kSlots + (bid - block_start[lo]) % kSlots;
     if (RD == PF_F64) {
         score_chunk<CD, RD>(pr, begin, end, acc);
     } else {
-        const double seed_abs = __longlong_as_double((long long)__atomic_load_n((unsigned long long*)&my_slot->max_abs, __ATOMIC_RELAXED));
-        const double seed_rel = __longlong_as_double((long long)__atomic_load_n((unsigned long long*)&my_slot->max_rel, __ATOMIC_RELAXED));
+        const double seed_abs = fmax(pr.seed_abs, __longlong_as_double((long long)__atomic_load_n((unsigned long long*)&my_slot->max_abs, __ATOMIC_RELAXED)));
+        const double seed_rel = fmax(pr.seed_rel, __longlong_as_double((long long)__atomic_load_n((unsigned long long*)&my_slot->max_rel, __ATOMIC_RELAXED)));
         score_chunk_fast<CD, RD>(pr, begin, end, acc, seed_abs, seed_rel);
     }
-    acc.max_rel = fmax(acc.max_rel, __ddiv_rn(acc.keep_d, acc.keep_b));
-    // block reduction: waves by shuffle, then LDS
+    if (RD == PF_F64) acc.max_rel = fmax(acc.max_rel, __ddiv_rn(acc.keep_d, acc.keep_b));   // only score_one defers a division
+    // block reduction: waves by shuffle, then LDS.  On the screened path a lane has anything to report
+    // only if it went through the exact path, so most waves find all-zero inputs and skip the shuffles.
     __shared__ double s_abs[kBlock / 64], s_rel[kBlock / 64];
     __shared__ unsigned long long s_cnt[kBlock / 64][6];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const double wa = wave_max(acc.max_abs), wr = wave_max(acc.max_rel);
+    double wa = 0.0, wr = 0.0;
+    if (__any((acc.max_abs > 0.0) | (acc.max_rel > 0.0))) { wa = wave_max(acc.max_abs); wr = wave_max(acc.max_rel); }
     unsigned long long c[6] = {acc.n_viol, acc.bitdiff, acc.nan_c, acc.nan_r, acc.inf_c, acc.inf_r};
+    if (__any((c[0] | c[1] | c[2] | c[3] | c[4] | c[5]) != 0)) {
 #pragma unroll
-    for (int k = 0; k < 6; ++k) c[k] = wave_sum(c[k]);
+        for (int k = 0; k < 6; ++k) c[k] = wave_sum(c[k]);
+    }
     if (lane == 0) {
         s_abs[wave] = wa; s_rel[wave] = wr;
 #pragma unroll
@@ -477,8 +570,8 @@ __global__ void __launch_bounds__(kBlock) ladder_kernel(const pf::PairDev* pairs
         if (block_start[mid] <= bid) lo = mid; else hi = mid;
     }
     const pf::PairDev pr = pairs[lo];
-    const unsigned long long begin = (bid - block_start[lo]) * kChunk;
-    const unsigned long long end = begin + kChunk < pr.n ? begin + kChunk : pr.n;
+    const unsigned long long begin = (bid - block_start[lo]) * pr.chunk;
+    const unsigned long long end = begin + pr.chunk < pr.n ? begin + pr.chunk : pr.n;
     const double* rt = table.rtol[CD];
     const double* at = table.atol[CD];
     unsigned int cnt[PF_LADDER_LEVELS];
@@ -534,7 +627,8 @@ __global__ void __launch_bounds__(256) copy_kernel(u32x4* __restrict__ dst, cons
 
 namespace pf {
 
-unsigned long long score_chunk_elems() { return kChunk; }
+// Elements per workgroup (four times longer chunks for large pairs measured 4-6% slower).
+unsigned long long score_chunk_elems(unsigned long long n) { (void)n; return kChunk; }
 
 hipError_t launch_score_upload(const PairBatch& batch, PairDev* d_pairs, unsigned long long* d_block_start, hipStream_t stream) {
     hipLaunchKernelGGL(score_upload_kernel, dim3(1), dim3(64), 0, stream, batch, d_pairs, d_block_start);
@@ -543,8 +637,7 @@ hipError_t launch_score_upload(const PairBatch& batch, PairDev* d_pairs, unsigne
 
 hipError_t launch_score(const PairDev* d_pairs, const unsigned long long* d_block_start, int n_pairs, const ScoreRanges& ranges,
                         pf_score_result* d_results, pf_score_result* d_slots, hipStream_t stream) {
-    const int nbs = (n_pairs * kSlots + kBlock - 1) / kBlock;
-    hipLaunchKernelGGL(score_init_kernel, dim3(nbs), dim3(kBlock), 0, stream, n_pairs, d_slots);
+    hipLaunchKernelGGL(score_init_kernel, dim3(n_pairs * kSeedBlocks), dim3(kBlock), 0, stream, const_cast<PairDev*>(d_pairs), n_pairs, d_slots);
 #define PF_LAUNCH(CD, RD)                                                                                                  \
     if (ranges.count[CD][RD])                                                                                              \
         hipLaunchKernelGGL((score_kernel<CD, RD>), dim3((unsigned)ranges.count[CD][RD]), dim3(kBlock), 0, stream, d_pairs,   \

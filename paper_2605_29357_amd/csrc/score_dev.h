@@ -15,6 +15,8 @@ struct PairDev {
     double rtol, atol;
     int equal_nan;
     int orig;               // index of this pair in the caller's array
+    unsigned long long chunk;   // elements per workgroup
+    double seed_abs, seed_rel;  // device side only: largest errors of a sample, raised by the seeding kernel
 };
 
 // blocks of each (candidate dtype, reference dtype) combination, indexed by pf_dtype: a contiguous range
@@ -47,7 +49,7 @@ struct LadderTable {
     double atol[4][PF_LADDER_LEVELS];
 };
 
-unsigned long long score_chunk_elems();
+unsigned long long score_chunk_elems(unsigned long long n);
 hipError_t launch_ladder(const PairDev* d_pairs, const unsigned long long* d_block_start, int n_pairs, const ScoreRanges& ranges,
                          const LadderTable& table, pf_ladder_result* d_results, pf_ladder_result* d_slots, hipStream_t stream);
 hipError_t launch_score_upload(const PairBatch& batch, PairDev* d_pairs, unsigned long long* d_block_start, hipStream_t stream);
