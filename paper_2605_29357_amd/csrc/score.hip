@@ -236,6 +236,8 @@ template <int DT> struct Vec8 {
     }
 };
 
+__device__ __forceinline__ void raise_max(double* slot, double v);
+
 template <int CD, int RD>
 __device__ __forceinline__ void score_chunk_fast(const pf::PairDev& pr, unsigned long long begin, unsigned long long end, Acc& acc,
                                                  double seed_abs, double seed_rel) {
@@ -245,10 +247,19 @@ __device__ __forceinline__ void score_chunk_fast(const pf::PairDev& pr, unsigned
     // the lean screen needs an absolute tolerance fp32 can represent comfortably (then every allowed
     // error bound is >= 1e-30 and needs no guard of its own)
     const bool lean = !force_exact && sc.atol_lo >= 1e-30f;
-    // wave-shared lower bounds of the exact maxima (rounded to fp32 and pulled down)
-    float wave_abs = (float)seed_abs, wave_rel = (float)seed_rel;
-    float thr_abs = wave_abs >= 1e-30f ? wave_abs * 0.999998f : 0.0f;
-    float thr_rel = wave_rel >= 1e-30f ? wave_rel * 0.999998f : 0.0f;
+    // Errors of real elements this lane knows of (the pair's sampled seed and its own maximum): the
+    // screening thresholds are their fp32 lower bounds, per lane.  Nothing is exchanged while the
+    // kernel runs; every scheme tried cost more than it saved in a kernel of short-lived waves:
+    // cross-lane shuffles ~1400 cycles of latency per exchange, a read-before-atomic on global
+    // memory ~3000, and atomics of many waves on one address serialise (up to a 4x slower kernel).
+    double known_abs = seed_abs, known_rel = seed_rel;
+    float thr_abs, thr_rel;
+    auto refresh = [&]() {
+        const float ka = (float)known_abs, kr = (float)known_rel;     // the rounding is far inside the 2e-6 pulled off below
+        thr_abs = ka >= 1e-30f ? ka * 0.999998f : 0.0f;
+        thr_rel = kr >= 1e-30f ? kr * 0.999998f : 0.0f;
+    };
+    refresh();
     unsigned int xor_acc = 0;
     const unsigned long long nvec = (end - begin) / 8;
     const unsigned long long iters = (nvec + kBlock - 1) / kBlock;
@@ -332,17 +343,20 @@ __device__ __forceinline__ void score_chunk_fast(const pf::PairDev& pr, unsigned
                         acc.n_viol += 1;
                         continue;
                     }
+                    // certainly inside the tolerance: exactly no new maximum either?  (fp64, no division; the
+                    // many elements of quantised data that tie a known maximum end here)
+                    if ((d <= __builtin_fmaf(sc.rtol_lo, ab, sc.atol_lo)) & (d < __builtin_inff()) & (ab < __builtin_inff())) {
+                        const double d64 = fabs(__dsub_rn((double)a, (double)b)), ab64 = fabs((double)b);
+                        if ((d64 <= known_abs) & (d64 <= known_rel * ab64 * 0.999999999999999)) continue;
+                    }
                 }
                 score_exact<CD, RD>(ea, eb, pr, acc);
             }
-            // the thresholds are fp32 lower bounds, so the wave-wide maxima are taken in fp32 (the rounding
-            // of the conversion is far inside the 2e-6 by which the thresholds are pulled down)
-            const float la = (float)acc.max_abs, lr = (float)acc.max_rel;
-            if (__any((la > wave_abs) | (lr > wave_rel))) {
-                wave_abs = fmaxf(wave_abs, wave_max32(la));
-                wave_rel = fmaxf(wave_rel, wave_max32(lr));
-                thr_abs = wave_abs >= 1e-30f ? wave_abs * 0.999998f : 0.0f;
-                thr_rel = wave_rel >= 1e-30f ? wave_rel * 0.999998f : 0.0f;
+            // a lane's own maximum raises its thresholds at once
+            if ((acc.max_abs > known_abs) | (acc.max_rel > known_rel)) {
+                known_abs = fmax(known_abs, acc.max_abs);
+                known_rel = fmax(known_rel, acc.max_rel);
+                refresh();
             }
         }
     }
@@ -382,28 +396,29 @@ __device__ __forceinline__ void raise_max(double* slot, double v);
 
 // Clears the partial-result slots of a pair and seeds its maxima.  The cheap screen of the main
 // kernel passes an element only when it cannot raise a running maximum, so a wave that starts from
-// zero sends its first elements through the exact path one record at a time.  Here 32 workgroups
-// per pair evaluate one element per lane exactly (8192 evenly spread elements per pair) and raise
+// zero sends its first elements through the exact path one record at a time.  Here 256 workgroups
+// per pair evaluate one element per lane exactly (65536 evenly spread elements per pair) and raise
 // the pair's seed: the seeds are errors of real elements (a maximum may count an element twice),
-// and a sample of that size leaves about one element in 8192 above them.
-constexpr int kSeedBlocks = 32;
+// and a sample of that size leaves about one element in 65536 above them.
+constexpr int kSeedBlocks = 256;
 template <int CD, int RD>
 __device__ __forceinline__ void seed_sample(const pf::PairDev& pr, unsigned long long k, Acc& acc) {
-    const unsigned long long want = (unsigned long long)kSeedBlocks * kBlock;
-    const unsigned long long stride = pr.n > want ? pr.n / want : 1;
-    const unsigned long long i = k * stride;
+    // one sample per 64 elements, at most 65536 per pair: small pairs are not worth more
+    const unsigned long long want = pr.n / 64 < (unsigned long long)kSeedBlocks * kBlock ? pr.n / 64 : (unsigned long long)kSeedBlocks * kBlock;
+    if (k >= want) return;
+    const unsigned long long i = k * (pr.n / want);
     if (i < pr.n) score_exact<CD, RD>(Elem<CD>::load1(pr.cand, i), Elem<RD>::load1(pr.ref, i), pr, acc);
 }
 
 __global__ void __launch_bounds__(kBlock) score_init_kernel(pf::PairDev* pairs, int n_pairs, pf_score_result* slots) {
     const int p = blockIdx.x / kSeedBlocks, part = blockIdx.x % kSeedBlocks;
     if (p >= n_pairs) return;
-    if (threadIdx.x < kSlots / kSeedBlocks) {
+    if (part < kSlots && threadIdx.x == 0) {
         pf_score_result z;
         z.max_abs = 0.0; z.max_rel = 0.0; z.n = 0; z.n_viol = 0;
         z.nan_cand = z.nan_ref = z.inf_cand = z.inf_ref = 0;
         z.allclose = 0; z.bit_identical = 0; z.reserved_ = 0;
-        slots[(size_t)p * kSlots + part * (kSlots / kSeedBlocks) + threadIdx.x] = z;
+        slots[(size_t)p * kSlots + part] = z;
     }
     const pf::PairDev pr = pairs[p];
     Acc acc;
@@ -440,7 +455,7 @@ __device__ __forceinline__ void raise_max(double* slot, double v) {
 // pairs by dtype combination, so each instantiation owns a contiguous range of
 // blocks and is register-allocated for its own path only.
 template <int CD, int RD>
-__global__ void __launch_bounds__(kBlock) score_kernel(const pf::PairDev* pairs, const unsigned long long* block_start,
+__global__ void __launch_bounds__(kBlock) score_kernel(pf::PairDev* pairs, const unsigned long long* block_start,
                                                        int n_pairs, pf_score_result* slots, unsigned long long block_offset) {
     // which pair does this block belong to: largest p with block_start[p] <= bid
     int lo = 0, hi = n_pairs;
@@ -458,46 +473,45 @@ __global__ void __launch_bounds__(kBlock) score_kernel(const pf::PairDev* pairs,
     if (RD == PF_F64) {
         score_chunk<CD, RD>(pr, begin, end, acc);
     } else {
-        const double seed_abs = fmax(pr.seed_abs, __longlong_as_double((long long)__atomic_load_n((unsigned long long*)&my_slot->max_abs, __ATOMIC_RELAXED)));
-        const double seed_rel = fmax(pr.seed_rel, __longlong_as_double((long long)__atomic_load_n((unsigned long long*)&my_slot->max_rel, __ATOMIC_RELAXED)));
-        score_chunk_fast<CD, RD>(pr, begin, end, acc, seed_abs, seed_rel);
+        score_chunk_fast<CD, RD>(pr, begin, end, acc, pr.seed_abs, pr.seed_rel);
     }
     if (RD == PF_F64) acc.max_rel = fmax(acc.max_rel, __ddiv_rn(acc.keep_d, acc.keep_b));   // only score_one defers a division
-    // block reduction: waves by shuffle, then LDS.  On the screened path a lane has anything to report
-    // only if it went through the exact path, so most waves find all-zero inputs and skip the shuffles.
-    __shared__ double s_abs[kBlock / 64], s_rel[kBlock / 64];
-    __shared__ unsigned long long s_cnt[kBlock / 64][6];
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    double wa = 0.0, wr = 0.0;
-    if (__any((acc.max_abs > 0.0) | (acc.max_rel > 0.0))) { wa = wave_max(acc.max_abs); wr = wave_max(acc.max_rel); }
+    // Block reduction.  On the screened path a lane has something to report only if it went through
+    // the exact path, so few lanes do: they fold their values into LDS with atomics (one round trip)
+    // instead of every wave walking a chain of ~100 dependent cross-lane shuffles, which used to make
+    // up a third of a wave's lifetime.  Waves in which many lanes report reduce by shuffles first.
+    __shared__ unsigned long long s_red[8];      // max_abs bits, max_rel bits, six counts
+    const int lane = threadIdx.x & 63;
+    if (threadIdx.x < 8) s_red[threadIdx.x] = 0;
+    __syncthreads();
+    double wa = acc.max_abs, wr = acc.max_rel;
     unsigned long long c[6] = {acc.n_viol, acc.bitdiff, acc.nan_c, acc.nan_r, acc.inf_c, acc.inf_r};
-    if (__any((c[0] | c[1] | c[2] | c[3] | c[4] | c[5]) != 0)) {
+    if (CD == RD) c[1] = (__any(acc.bitdiff != 0) && lane == 0) ? 1u : 0u;      // only "any difference" matters
+    const bool mine = (wa > 0.0) | (wr > 0.0) | ((c[0] | c[2] | c[3] | c[4] | c[5]) != 0);
+    if (__popcll(__ballot(mine)) > 16) {
+        wa = wave_max(wa); wr = wave_max(wr);
 #pragma unroll
-        for (int k = 0; k < 6; ++k) c[k] = wave_sum(c[k]);
+        for (int k = 0; k < 6; ++k) if (k != 1) c[k] = wave_sum(c[k]);
+        if (lane != 0) { wa = 0.0; wr = 0.0; c[0] = c[2] = c[3] = c[4] = c[5] = 0; }
     }
-    if (lane == 0) {
-        s_abs[wave] = wa; s_rel[wave] = wr;
+    // errors are >= 0 and never NaN, so their bit patterns order like the values
+    if (wa > 0.0) atomicMax(&s_red[0], (unsigned long long)__double_as_longlong(wa));
+    if (wr > 0.0) atomicMax(&s_red[1], (unsigned long long)__double_as_longlong(wr));
 #pragma unroll
-        for (int k = 0; k < 6; ++k) s_cnt[wave][k] = c[k];
-    }
+    for (int k = 0; k < 6; ++k) if (c[k]) atomicAdd(&s_red[2 + k], c[k]);
     __syncthreads();
     if (threadIdx.x == 0) {
-        double ma = s_abs[0], mr = s_rel[0];
+        const double ma = __longlong_as_double((long long)s_red[0]), mr = __longlong_as_double((long long)s_red[1]);
         unsigned long long t[6];
 #pragma unroll
-        for (int k = 0; k < 6; ++k) t[k] = s_cnt[0][k];
-        for (int w = 1; w < kBlock / 64; ++w) {
-            ma = fmax(ma, s_abs[w]); mr = fmax(mr, s_rel[w]);
-#pragma unroll
-            for (int k = 0; k < 6; ++k) t[k] += s_cnt[w][k];
-        }
+        for (int k = 0; k < 6; ++k) t[k] = s_red[2 + k];
         // one of kSlots partial results of this pair; the final kernel folds them
         pf_score_result* r = my_slot;
-        // errors are >= 0 and never NaN, so their bit patterns order like the values
-        if (ma > 0.0) raise_max(&r->max_abs, ma);
-        if (mr > 0.0) raise_max(&r->max_rel, mr);
+        // nothing at the end of a workgroup waits for memory: no value is read back
+        if (ma > 0.0) atomicMax((unsigned long long*)&r->max_abs, (unsigned long long)__double_as_longlong(ma));
+        if (mr > 0.0) atomicMax((unsigned long long*)&r->max_rel, (unsigned long long)__double_as_longlong(mr));
         if (t[0]) atomicAdd((unsigned long long*)&r->n_viol, t[0]);
-        if (t[1]) atomicAdd((unsigned long long*)&r->reserved_, t[1]);
+        if (t[1]) __atomic_store_n((unsigned long long*)&r->reserved_, 1ull, __ATOMIC_RELAXED);   // a flag: any non-zero value will do
         if (t[2]) atomicAdd((unsigned long long*)&r->nan_cand, t[2]);
         if (t[3]) atomicAdd((unsigned long long*)&r->nan_ref, t[3]);
         if (t[4]) atomicAdd((unsigned long long*)&r->inf_cand, t[4]);
@@ -511,7 +525,8 @@ __global__ void __launch_bounds__(64) score_final_kernel(const pf::PairDev* pair
     const int p = blockIdx.x;
     if (p >= n_pairs) return;
     const pf_score_result s = slots[(size_t)p * kSlots + threadIdx.x];
-    const double ma = wave_max(s.max_abs), mr = wave_max(s.max_rel);
+    // screened pairs publish their maxima in the pair record, fp64-reference pairs in the slots
+    const double ma = fmax(wave_max(s.max_abs), pairs[p].seed_abs), mr = fmax(wave_max(s.max_rel), pairs[p].seed_rel);
     const unsigned long long nv = wave_sum(s.n_viol), bd = wave_sum(s.reserved_);
     const unsigned long long nc = wave_sum(s.nan_cand), nr = wave_sum(s.nan_ref);
     const unsigned long long ic = wave_sum(s.inf_cand), ir = wave_sum(s.inf_ref);
@@ -640,7 +655,8 @@ hipError_t launch_score(const PairDev* d_pairs, const unsigned long long* d_bloc
     hipLaunchKernelGGL(score_init_kernel, dim3(n_pairs * kSeedBlocks), dim3(kBlock), 0, stream, const_cast<PairDev*>(d_pairs), n_pairs, d_slots);
 #define PF_LAUNCH(CD, RD)                                                                                                  \
     if (ranges.count[CD][RD])                                                                                              \
-        hipLaunchKernelGGL((score_kernel<CD, RD>), dim3((unsigned)ranges.count[CD][RD]), dim3(kBlock), 0, stream, d_pairs,   \
+        hipLaunchKernelGGL((score_kernel<CD, RD>), dim3((unsigned)ranges.count[CD][RD]), dim3(kBlock), 0, stream,            \
+                           const_cast<PairDev*>(d_pairs),                                                                  \
                            d_block_start, n_pairs, d_slots, ranges.first[CD][RD]);
     PF_LAUNCH(PF_F32, PF_F32)
     PF_LAUNCH(PF_F32, PF_BF16)
