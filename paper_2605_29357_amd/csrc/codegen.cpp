@@ -191,11 +191,30 @@ struct Emit {
             gen_loop(vec, ragged);
             return;
         }
+        // Padding: K * T chunk slots for `chunks` chunks.  When more than a tenth of the slots is empty,
+        // half or twice the lanes may fit better (17 chunks: 8 x 3 instead of 16 x 2; 1376 chunks:
+        // 512 x 3 instead of 1024 x 2, measured 15% faster).
+        auto slots = [&](int t) { return ((chunks + t - 1) / t) * t; };
+        if (slots(T) * 10 > chunks * 11) {
+            int best = T;
+            if (T >= 16 && (chunks + T / 2 - 1) / (T / 2) <= per_lane_max && slots(T / 2) < slots(best)) best = T / 2;
+            if (T < 1024 && slots(T * 2) < slots(best)) best = T * 2;
+            T = best;
+            K = (chunks + T - 1) / T;
+        }
         // few rows: spread each row over more lanes until about six waves per CU exist
         while (K > 1 && T < 1024 && R * T < 256 * 64 * 6) {
             T <<= 1;
             K = (chunks + T - 1) / T;
         }
+        // Bandwidth regime (24 MB or more cross the kernel; smaller problems are latency-bound and lose 5-15%): with few long rows, more and lighter lanes keep
+        // more loads in flight; spread until the chip is filled twice, as long as no padding is added
+        // (556 x 4096 fp32 rows: 1024 lanes x 4 elements are 20% faster than 256 x 16).
+        if ((int64_t)(grp.bytes_read + grp.bytes_written) >= (int64_t(24) << 20))
+            while (K > 1 && T < 1024 && R * T < 256 * 64 * 32 && slots(T * 2) <= slots(T)) {
+                T <<= 1;
+                K = (chunks + T - 1) / T;
+            }
         if (opt.tune_row_lanes > 0) {
             T = opt.tune_row_lanes;
             if (T & (T - 1) || T > 1024) fail(PF_E_INVALID, "tune_row_lanes must be a power of two <= 1024");
@@ -213,7 +232,7 @@ struct Emit {
         // 262144 x 128 are 8% and 3% faster than one; on 2M-element problems any more than one row is
         // 10 ... 100% slower.)
         int ru = 1;
-        if (T <= 64) {
+        if (T <= 64 && !ragged) {      // ragged rows measured 15% slower with a second row in flight
             while (ru < 4 && R * T >= (int64_t)262144 * ru * 2) ru <<= 1;
             while (ru > 1 && ru * N > 32) ru >>= 1;
         }
