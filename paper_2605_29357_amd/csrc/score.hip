@@ -396,14 +396,14 @@ __device__ __forceinline__ void raise_max(double* slot, double v);
 
 // Clears the partial-result slots of a pair and seeds its maxima.  The cheap screen of the main
 // kernel passes an element only when it cannot raise a running maximum, so a wave that starts from
-// zero sends its first elements through the exact path one record at a time.  Here 256 workgroups
-// per pair evaluate one element per lane exactly (65536 evenly spread elements per pair) and raise
+// zero sends its first elements through the exact path one record at a time.  Here 64 workgroups
+// per pair evaluate one element per lane exactly (16384 evenly spread elements per pair) and raise
 // the pair's seed: the seeds are errors of real elements (a maximum may count an element twice),
-// and a sample of that size leaves about one element in 65536 above them.
-constexpr int kSeedBlocks = 256;
+// and a sample of that size leaves about one element in 16384 above them.
+constexpr int kSeedBlocks = 64;
 template <int CD, int RD>
 __device__ __forceinline__ void seed_sample(const pf::PairDev& pr, unsigned long long k, Acc& acc) {
-    // one sample per 64 elements, at most 65536 per pair: small pairs are not worth more
+    // one sample per 64 elements, at most 16384 per pair: small pairs are not worth more
     const unsigned long long want = pr.n / 64 < (unsigned long long)kSeedBlocks * kBlock ? pr.n / 64 : (unsigned long long)kSeedBlocks * kBlock;
     if (k >= want) return;
     const unsigned long long i = k * (pr.n / want);
@@ -413,12 +413,12 @@ __device__ __forceinline__ void seed_sample(const pf::PairDev& pr, unsigned long
 __global__ void __launch_bounds__(kBlock) score_init_kernel(pf::PairDev* pairs, int n_pairs, pf_score_result* slots) {
     const int p = blockIdx.x / kSeedBlocks, part = blockIdx.x % kSeedBlocks;
     if (p >= n_pairs) return;
-    if (part < kSlots && threadIdx.x == 0) {
+    for (int k = part * kBlock + threadIdx.x; k < kSlots; k += kSeedBlocks * kBlock) {     // every slot, whatever the two constants
         pf_score_result z;
         z.max_abs = 0.0; z.max_rel = 0.0; z.n = 0; z.n_viol = 0;
         z.nan_cand = z.nan_ref = z.inf_cand = z.inf_ref = 0;
         z.allclose = 0; z.bit_identical = 0; z.reserved_ = 0;
-        slots[(size_t)p * kSlots + part] = z;
+        slots[(size_t)p * kSlots + k] = z;
     }
     const pf::PairDev pr = pairs[p];
     Acc acc;

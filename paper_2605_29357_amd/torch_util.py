@@ -47,7 +47,8 @@ class Runner:
         self.exe = pf.Exec(w.text, fuse=fuse, intermediates_f32=intermediates_f32, **tune)
         self.info = self.exe.info()
         ws = self.info["workspace_bytes"]
-        self.ws = torch.empty(max(ws, 256), dtype=torch.uint8, device="cuda") if ws else None
+        # scratch for values that cross kernels; poisoned (NaN bit patterns) so that nothing can rely on its content
+        self.ws = torch.full((max(ws, 256),), 255, dtype=torch.uint8, device="cuda") if ws else None
         self.d_in = [to_device(a, dt) for a, dt in zip(w.inputs, w.input_dtypes)] if upload else None
 
     def run(self, outs=None, stream=None, events=None):
@@ -114,7 +115,7 @@ def score_on_gpu(pairs_spec, stream=None):
         pairs.append(p)
     res = torch.zeros(max(n, 1) * ctypes.sizeof(pf.ScoreResult), dtype=torch.uint8, device="cuda")
     wsb = pf.score_workspace_bytes(n)
-    ws = torch.empty(max(wsb, 256), dtype=torch.uint8, device="cuda")
+    ws = torch.full((max(wsb, 256),), 255, dtype=torch.uint8, device="cuda")   # a caller's workspace holds anything: poison it
     s = stream if stream is not None else torch.cuda.current_stream()
     pf.score(pairs, res.data_ptr(), ws.data_ptr(), ws.numel(), s.cuda_stream)
     s.synchronize()
@@ -133,7 +134,7 @@ def ladder_on_gpu(pairs_spec, stream=None):
         p.cand_dtype, p.ref_dtype, p.equal_nan = pf.DTYPES[cd], pf.DTYPES[rd], int(en)
         pairs.append(p)
     res = torch.zeros(max(n, 1) * ctypes.sizeof(pf.LadderResult), dtype=torch.uint8, device="cuda")
-    ws = torch.empty(max(pf.score_ladder_workspace_bytes(n), 256), dtype=torch.uint8, device="cuda")
+    ws = torch.full((max(pf.score_ladder_workspace_bytes(n), 256),), 255, dtype=torch.uint8, device="cuda")   # poisoned, as above
     s = stream if stream is not None else torch.cuda.current_stream()
     pf.score_ladder(pairs, res.data_ptr(), ws.data_ptr(), ws.numel(), s.cuda_stream)
     s.synchronize()
