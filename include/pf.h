@@ -183,6 +183,19 @@ pf_status pf_exec_info(const pf_exec* e, pf_plan_info* h_info);
 pf_status pf_exec_group_info(const pf_exec* e, int group, pf_group_info* h_info);
 /* Generated HIP source of one kernel, for inspection (same buffer protocol as print). */
 pf_status pf_exec_source(const pf_exec* e, int group, char* h_buf, size_t cap, size_t* needed);
+/* Name of the group's kernel: template, operators and a hash of the whole generated source, so two
+ * groups with the same name run the same code object (same buffer protocol as print). */
+pf_status pf_exec_kernel_name(const pf_exec* e, int group, char* h_buf, size_t cap, size_t* needed);
+
+/* Code objects are cached by source text, in the process and (PF_CACHE_DIR) on disk.  A task
+ * instance (Sec. 3.1) holds the same operators at several shapes: elementwise and row kernels take
+ * the outermost extent of their domain as an argument, so members that differ only there and get the
+ * same tiling generate the same text and share one code object.  Counters of this process:
+ * compilations, hits in memory, hits on disk, distinct code objects held. */
+typedef struct {
+    uint64_t compiled, memory_hits, disk_hits, code_objects;
+} pf_jit_stats;
+pf_status pf_jit_stats_get(pf_jit_stats* h_out);
 
 /* Runs the compiled subgraph once.  d_inputs / d_outputs follow the order of
  * the graph's `in` declarations and pf_graph_output calls.  d_workspace must

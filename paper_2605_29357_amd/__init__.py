@@ -48,6 +48,10 @@ class _PlanInfo(C.Structure):
                 ("n_groups", C.c_int), ("reserved_", C.c_int)]
 
 
+class _JitStats(C.Structure):
+    _fields_ = [("compiled", C.c_uint64), ("memory_hits", C.c_uint64), ("disk_hits", C.c_uint64), ("code_objects", C.c_uint64)]
+
+
 class _GroupInfo(C.Structure):
     _fields_ = [("tmpl", C.c_int), ("n_nodes", C.c_int), ("nodes", C.c_int * 64), ("rows", C.c_int64),
                 ("cols", C.c_int64), ("block_threads", C.c_int), ("grid_blocks", C.c_int64),
@@ -117,6 +121,8 @@ def lib():
         "pf_exec_info": [vp, C.POINTER(_PlanInfo)],
         "pf_exec_group_info": [vp, C.c_int, C.POINTER(_GroupInfo)],
         "pf_exec_source": [vp, C.c_int, C.c_char_p, sz, C.POINTER(sz)],
+        "pf_exec_kernel_name": [vp, C.c_int, C.c_char_p, sz, C.POINTER(sz)],
+        "pf_jit_stats_get": [C.POINTER(_JitStats)],
         "pf_execute": [vp, C.POINTER(vp), C.c_int, C.POINTER(vp), C.c_int, vp, sz, vp],
         "pf_execute_timed": [vp, C.POINTER(vp), C.c_int, C.POINTER(vp), C.c_int, vp, sz, vp, vp, vp],
         "pf_score": [C.POINTER(Pair), C.c_int, vp, vp, sz, vp],
@@ -270,6 +276,13 @@ class Exec:
         _check(lib().pf_exec_source(self._h, i, buf, need.value, C.byref(need)))
         return buf.value.decode()
 
+    def kernel_name(self, i):
+        need = C.c_size_t()
+        _check(lib().pf_exec_kernel_name(self._h, i, None, 0, C.byref(need)))
+        buf = C.create_string_buffer(need.value)
+        _check(lib().pf_exec_kernel_name(self._h, i, buf, need.value, C.byref(need)))
+        return buf.value.decode()
+
     def execute(self, input_ptrs, output_ptrs, workspace_ptr=0, workspace_bytes=0, stream=0, start_event=0, stop_event=0):
         """Device pointers as ints; enqueues the kernels on `stream` (a hipStream_t as int).
         start_event / stop_event: optional hipEvent_t handles bracketing the kernels themselves."""
@@ -296,6 +309,13 @@ def score(pairs, results_ptr, workspace_ptr, workspace_bytes, stream=0):
 
 def copy_bytes(dst_ptr, src_ptr, nbytes, stream=0):
     _check(lib().pf_copy_bytes(C.c_void_p(dst_ptr), C.c_void_p(src_ptr), nbytes, C.c_void_p(stream)))
+
+
+def jit_stats():
+    """Code-object cache counters of this process: compiled, memory_hits, disk_hits, code_objects."""
+    st = _JitStats()
+    _check(lib().pf_jit_stats_get(C.byref(st)))
+    return {k: getattr(st, k) for k, _ in st._fields_}
 
 
 def tolerance(dtype, t):

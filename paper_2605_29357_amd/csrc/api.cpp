@@ -271,6 +271,23 @@ pf_status pf_exec_source(const pf_exec* e, int group, char* h_buf, size_t cap, s
     return outer != PF_OK ? outer : st;
 }
 
+pf_status pf_exec_kernel_name(const pf_exec* e, int group, char* h_buf, size_t cap, size_t* needed) {
+    pf_status st = PF_OK;
+    pf_status outer = guarded([&] {
+        need(e, "e");
+        if (group < 0 || group >= (int)e->plan.groups.size()) pf::fail(PF_E_INVALID, "group %d out of range", group);
+        st = copy_out(e->plan.groups[group].kernel_name, h_buf, cap, needed);
+    });
+    return outer != PF_OK ? outer : st;
+}
+
+pf_status pf_jit_stats_get(pf_jit_stats* h_out) {
+    return guarded([&] {
+        need(h_out, "h_out");
+        pf::jit_stats(h_out);
+    });
+}
+
 static void check_execute_args(pf_exec* e, const void* const* d_inputs, int n_in, void* const* d_outputs, int n_out,
                                void* d_workspace, size_t workspace_bytes) {
     need(e, "e");
@@ -329,7 +346,11 @@ size_t staged_head_bytes(int n_pairs) {
     return b + (((size_t)n_pairs + 1) * sizeof(unsigned long long) + 255) / 256 * 256;
 }
 
-StagedPairs stage_pairs(const pf_pair* h_pairs, int n_pairs, void* d_workspace, void* stream) {
+// with_seeds: the single-level scorer, whose staging kernel also clears the slots and samples the seeds
+// the seed parts of the single-level scorer follow its slots
+double* score_seeds(char* d_rest, int n_pairs) { return (double*)(d_rest + (size_t)n_pairs * pf::kScoreSlots * sizeof(pf_score_result)); }
+
+StagedPairs stage_pairs(const pf_pair* h_pairs, int n_pairs, void* d_workspace, void* stream, bool with_seeds) {
     StagedPairs sp;
     const size_t pairs_bytes = ((size_t)n_pairs * sizeof(pf::PairDev) + 255) / 256 * 256;
     sp.d_pairs = (pf::PairDev*)d_workspace;
@@ -378,7 +399,9 @@ StagedPairs stage_pairs(const pf_pair* h_pairs, int n_pairs, void* d_workspace, 
         }
         b.start[b.count] = total;
         if (total >= (1ull << 31)) pf::fail(PF_E_INVALID, "too many elements for one scoring call");
-        hipError_t err = pf::launch_score_upload(b, sp.d_pairs, sp.d_start, (hipStream_t)stream);
+        hipError_t err = with_seeds ? pf::launch_score_stage(b, sp.d_pairs, sp.d_start, (pf_score_result*)sp.d_rest,
+                                                             score_seeds(sp.d_rest, n_pairs), (hipStream_t)stream)
+                                    : pf::launch_score_upload(b, sp.d_pairs, sp.d_start, (hipStream_t)stream);
         if (err != hipSuccess) pf::fail(PF_E_RUNTIME, "descriptor upload failed: %s", hipGetErrorString(err));
     }
     return sp;
@@ -402,16 +425,17 @@ pf_status pf_score(const pf_pair* h_pairs, int n_pairs, pf_score_result* d_resul
     return guarded([&] {
         if (n_pairs == 0) return;
         check_score_args(h_pairs, n_pairs, d_results, d_workspace, workspace_bytes, pf_score_workspace_bytes(n_pairs));
-        StagedPairs sp = stage_pairs(h_pairs, n_pairs, d_workspace, stream);
+        StagedPairs sp = stage_pairs(h_pairs, n_pairs, d_workspace, stream, true);
         hipError_t err = pf::launch_score(sp.d_pairs, sp.d_start, n_pairs, sp.ranges, d_results, (pf_score_result*)sp.d_rest,
-                                          (hipStream_t)stream);
+                                          score_seeds(sp.d_rest, n_pairs), (hipStream_t)stream);
         if (err != hipSuccess) pf::fail(PF_E_RUNTIME, "score launch failed: %s", hipGetErrorString(err));
     });
 }
 
 size_t pf_score_workspace_bytes(int n_pairs) {
     if (n_pairs < 0) n_pairs = 0;
-    return staged_head_bytes(n_pairs) + (size_t)n_pairs * pf::kScoreSlots * sizeof(pf_score_result);
+    return staged_head_bytes(n_pairs) + (size_t)n_pairs * pf::kScoreSlots * sizeof(pf_score_result) +
+           (size_t)n_pairs * pf::kScoreSeedParts * 2 * sizeof(double);
 }
 
 size_t pf_score_ladder_workspace_bytes(int n_pairs) {
@@ -424,7 +448,7 @@ pf_status pf_score_ladder(const pf_pair* h_pairs, int n_pairs, pf_ladder_result*
     return guarded([&] {
         if (n_pairs == 0) return;
         check_score_args(h_pairs, n_pairs, d_results, d_workspace, workspace_bytes, pf_score_ladder_workspace_bytes(n_pairs));
-        StagedPairs sp = stage_pairs(h_pairs, n_pairs, d_workspace, stream);
+        StagedPairs sp = stage_pairs(h_pairs, n_pairs, d_workspace, stream, false);
         pf::LadderTable table;
         memset(&table, 0, sizeof table);
         for (int dt : {(int)PF_F32, (int)PF_BF16, (int)PF_F16})

@@ -266,8 +266,15 @@ struct Emit {
         for (int id : grp.nodes)
             if (is_reduction(g.nodes[id].op)) n_red += g.nodes[id].op == PF_OP_VAR ? 2 : 1;
 
-        signature();
+        // the outermost extent is a kernel argument: problems that differ only there (and lead to the
+        // same tiling decisions) generate the same source text and share one code object
+        set_outer_runtime();
+        signature(outer_param());
         line(strf("    constexpr int T = %d, K = %d, VEC = %d, N = %d, RU = %d, TEAMS = %d;", T, (int)K, vec, N, RU, teams));
+        if (grp.outer_runtime) {
+            line(strf("    constexpr %s C = %lld;", idx_t(), (long long)C));
+            line(strf("    const %s ROWS = (%s)pf_d0 * %lld, GROUPS = (ROWS + RU - 1) / RU;", idx_t(), idx_t(), (long long)inner_rows()));
+        } else
         line(strf("    constexpr %s C = %lld, ROWS = %lld, GROUPS = %lld;", idx_t(), (long long)C, (long long)R, (long long)row_groups));
         if (T > 64) line(strf("    __shared__ %s red_lds[%d][%d];", acc, std::max(n_red, 1), block / 64));
         if (T > 64 && precise) line(strf("    __shared__ float redf_lds[%d][%d];", std::max(n_red, 1), block / 64));
@@ -930,9 +937,11 @@ struct Emit {
         NN = vec;
 
         // body as a device function of the vector index
-        line(strf("template <bool TAIL> PF_DEV void body(%s, %s v) {", param_list().c_str(), idx_t()));
+        // the outermost extent is a kernel argument (see the row template)
+        set_outer_runtime();
+        line(strf("template <bool TAIL> PF_DEV void body(%s, %s v, const %s NEL) {", param_list().c_str(), idx_t(), idx_t()));
         line(strf("    constexpr int VEC = %d;", vec));
-        line(strf("    constexpr %s C = %lld, NEL = %lld;", idx_t(), (long long)C, (long long)N));
+        line(strf("    constexpr %s C = %lld;", idx_t(), (long long)C));
         line(strf("    const %s e0 = v * VEC;", idx_t()));
         if (!straddle) {
             line(strf("    const %s row = e0 / C, col0 = e0 %% C;", idx_t()));
@@ -980,23 +989,26 @@ struct Emit {
             }
         }
         line("}");
-        signature();
+        signature(outer_param());
         line(strf("    constexpr int U = %d, BLOCK = %d;", U, block));
-        line(strf("    constexpr %s NVEC = %lld;", idx_t(), (long long)nvec));
+        if (grp.outer_runtime) {
+            line(strf("    const %s NEL = (%s)pf_d0 * %lld, NVEC = (NEL + %d) / %d;", idx_t(), idx_t(), (long long)(inner_rows() * C), vec - 1, vec));
+        } else
+        line(strf("    constexpr %s NEL = %lld, NVEC = %lld;", idx_t(), (long long)N, (long long)nvec));
         line(strf("    const %s v0 = (%s)blockIdx.x * (BLOCK * U) + threadIdx.x;", idx_t(), idx_t()));
         std::string args = arg_list();
         if (tail) {
             line("    _Pragma(\"unroll\") for (int u = 0; u < U; ++u) {");
             line(strf("        const %s v = v0 + (%s)u * BLOCK;", idx_t(), idx_t()));
-            line(strf("        if (v + 1 < NVEC) body<false>(%s, v); else if (v < NVEC) body<true>(%s, v);", args.c_str(), args.c_str()));
+            line(strf("        if (v + 1 < NVEC) body<false>(%s, v, NEL); else if (v < NVEC) body<true>(%s, v, NEL);", args.c_str(), args.c_str()));
             line("    }");
         } else {
             line(strf("    if (v0 + (%s)(U - 1) * BLOCK < NVEC) {", idx_t()));
-            line(strf("        _Pragma(\"unroll\") for (int u = 0; u < U; ++u) body<false>(%s, v0 + (%s)u * BLOCK);", args.c_str(), idx_t()));
+            line(strf("        _Pragma(\"unroll\") for (int u = 0; u < U; ++u) body<false>(%s, v0 + (%s)u * BLOCK, NEL);", args.c_str(), idx_t()));
             line("    } else {");
             line("        _Pragma(\"unroll\") for (int u = 0; u < U; ++u) {");
             line(strf("            const %s v = v0 + (%s)u * BLOCK;", idx_t(), idx_t()));
-            line(strf("            if (v < NVEC) body<false>(%s, v);", args.c_str()));
+            line(strf("            if (v < NVEC) body<false>(%s, v, NEL);", args.c_str()));
             line("        }");
             line("    }");
         }
@@ -1256,6 +1268,18 @@ struct Emit {
             for (size_t c = 0; c < 1 + st.also_outputs.size(); ++c, ++sp) p += strf("%sq%d", p.empty() ? "" : ", ", sp);
         return p;
     }
+    // Flat and row kernels take the outermost extent of their domain as an argument when the domain
+    // has leading dims at all; everything else stays literal.
+    void set_outer_runtime() {
+        grp.outer_runtime = rd >= 2;
+        grp.outer_extent = rd >= 2 ? grp.domain[0] : 0;
+    }
+    int64_t inner_rows() const {       // rows per index of the outermost dim
+        int64_t r = 1;
+        for (int k = 1; k + 1 < rd; ++k) r *= grp.domain[k];
+        return r;
+    }
+    std::string outer_param() const { return grp.outer_runtime ? "const long long pf_d0" : ""; }
     void signature(const std::string& extra = "") {
         std::string params = param_list();
         if (!extra.empty()) params += (params.empty() ? "" : ", ") + extra;
@@ -1296,8 +1320,8 @@ struct Emit {
         (void)index;
         recompute_kinds();
         s.clear();
-        s += strf("// group %d: %s over domain [", index, grp.kernel_name.c_str());
-        for (size_t k = 0; k < grp.domain.size(); ++k) s += strf(k ? ",%lld" : "%lld", (long long)grp.domain[k]);
+        s += strf("// group %d: %s over domain [PFDOMAIN0", index, grp.kernel_name.c_str());
+        for (size_t k = 1; k < grp.domain.size(); ++k) s += strf(",%lld", (long long)grp.domain[k]);
         s += "], nodes";
         for (int id : grp.nodes) s += strf(" %%%d=%s", id, op_name(g.nodes[id].op));
         s += "\n";
@@ -1317,6 +1341,13 @@ struct Emit {
             nm += "_";
             nm += op_name(g.nodes[id].op);
             ++shown;
+        }
+        {
+            // a row-streaming kernel (one workgroup per row) never mentions the number of rows either
+            const bool generic = grp.outer_runtime || (grp.tmpl == PF_T_ROW_LOOP && rd >= 2);
+            const std::string d0 = grp.domain.empty() ? "" : generic ? "*" : strf("%lld", (long long)grp.domain[0]);
+            const size_t at = s.find("PFDOMAIN0");
+            s.replace(at, 9, d0);
         }
         unsigned long long h = 1469598103934665603ull;
         for (unsigned char c : s) { h ^= c; h *= 1099511628211ull; }

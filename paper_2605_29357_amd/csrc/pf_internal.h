@@ -127,6 +127,8 @@ struct Group {
     // a column reduction whose rows are split over several workgroups: partial results go to scratch
     // memory (a slice of the workspace, passed as the last kernel argument) and a second kernel of
     // the same module combines them
+    bool outer_runtime = false;     // the kernel takes the outermost domain extent as its last scalar argument
+    int64_t outer_extent = 0;
     uint64_t scratch_bytes = 0;
     int64_t scratch_offset = -1;
     std::string kernel2_name;
@@ -157,5 +159,6 @@ void generate_source(const pf_graph& g, const pf_options& opt, Group& grp, int i
 
 // ---- runtime.cpp ----
 void jit_compile(Group& grp);
+void jit_stats(pf_jit_stats* out);
 
 }  // namespace pf

@@ -21,6 +21,7 @@ namespace {
 
 std::mutex g_cache_mu;
 std::unordered_map<std::string, std::vector<char>> g_code_cache;   // source text -> code object
+pf_jit_stats g_stats = {0, 0, 0, 0};                                // guarded by g_cache_mu
 
 uint64_t fnv1a(const std::string& s) {
     uint64_t h = 1469598103934665603ull;
@@ -45,6 +46,7 @@ void jit_compile(Group& grp) {
         auto it = g_code_cache.find(grp.source);
         if (it != g_code_cache.end()) {
             grp.code = it->second;
+            ++g_stats.memory_hits;
             return;
         }
     }
@@ -63,6 +65,7 @@ void jit_compile(Group& grp) {
                     grp.code.assign(blob.begin() + 16 + len, blob.end());
                     std::lock_guard<std::mutex> lk(g_cache_mu);
                     g_code_cache[grp.source] = grp.code;
+                    ++g_stats.disk_hits;
                     return;
                 }
             }
@@ -104,6 +107,13 @@ void jit_compile(Group& grp) {
     }
     std::lock_guard<std::mutex> lk(g_cache_mu);
     g_code_cache[grp.source] = grp.code;
+    ++g_stats.compiled;
+}
+
+void jit_stats(pf_jit_stats* out) {
+    std::lock_guard<std::mutex> lk(g_cache_mu);
+    *out = g_stats;
+    out->code_objects = g_code_cache.size();
 }
 
 void exec_load(pf_exec& e) {
@@ -157,8 +167,14 @@ void exec_run(pf_exec& e, const void* const* d_inputs, void* const* d_outputs, v
             ptrs[n++] = s.graph_output >= 0 ? d_outputs[s.graph_output] : (void*)((char*)d_ws + s.ws_offset);
             for (int k : s.also_outputs) ptrs[n++] = d_outputs[k];
         }
-        if (grp.scratch_bytes) ptrs[n++] = (char*)d_ws + grp.scratch_offset;
         for (int k = 0; k < n; ++k) args[k] = &ptrs[k];
+        long long outer = grp.outer_extent;
+        if (grp.outer_runtime) args[n++] = &outer;
+        if (grp.scratch_bytes) {
+            ptrs[n] = (char*)d_ws + grp.scratch_offset;
+            args[n] = &ptrs[n];
+            ++n;
+        }
         // events, when given, bracket the kernels themselves (dispatch timestamps), not the
         // launch calls: the first kernel carries the start event, the last one the stop event
         const bool two = e.functions2[i] != nullptr;

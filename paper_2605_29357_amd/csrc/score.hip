@@ -169,11 +169,6 @@ __device__ __forceinline__ void score_chunk(const pf::PairDev& pr, unsigned long
 }
 
 __device__ __forceinline__ double wave_max(double v);
-__device__ __forceinline__ float wave_max32(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-    return v;
-}
 
 // ---- fp32 screening path (both sides f32, bf16 or fp16) ---------------------
 // Almost every element can be classified without fp64: with a, b widened to
@@ -235,8 +230,6 @@ template <int DT> struct Vec8 {
         return w[j];
     }
 };
-
-__device__ __forceinline__ void raise_max(double* slot, double v);
 
 template <int CD, int RD>
 __device__ __forceinline__ void score_chunk_fast(const pf::PairDev& pr, unsigned long long begin, unsigned long long end, Acc& acc,
@@ -392,37 +385,47 @@ __global__ void __launch_bounds__(64) score_upload_kernel(pf::PairBatch batch, p
     if (i == 0 && batch.last) block_start[batch.first + batch.count] = batch.start[batch.count];
 }
 
-__device__ __forceinline__ void raise_max(double* slot, double v);
-
-// Clears the partial-result slots of a pair and seeds its maxima.  The cheap screen of the main
+// Stages a batch of pairs and seeds their maxima, in one launch.  The cheap screen of the main
 // kernel passes an element only when it cannot raise a running maximum, so a wave that starts from
-// zero sends its first elements through the exact path one record at a time.  Here 64 workgroups
-// per pair evaluate one element per lane exactly (16384 evenly spread elements per pair) and raise
-// the pair's seed: the seeds are errors of real elements (a maximum may count an element twice),
-// and a sample of that size leaves about one element in 16384 above them.
-constexpr int kSeedBlocks = 64;
+// zero sends its first elements through the exact path one record at a time.  Here kSeedParts
+// workgroups per pair evaluate one element per lane exactly (16384 evenly spread elements per pair)
+// and each stores its own maxima: the seeds are errors of real elements (the final fold counts
+// them too, so an element that merely ties a seed need not be recorded again; on quantised data
+// such ties are the common case, and seeds scaled down to strict lower bounds measured 7% slower).
+// A sample of that size leaves about one element in 16384 above the seeds.  The first workgroup
+// of a pair also writes the descriptor and the block prefix, and all of them clear the pair's
+// partial-result slots.  Nothing here is an atomic on global memory or needs an earlier clear.
+constexpr int kSeedParts = pf::kScoreSeedParts, kSeedBlock = 1024;
 template <int CD, int RD>
 __device__ __forceinline__ void seed_sample(const pf::PairDev& pr, unsigned long long k, Acc& acc) {
     // one sample per 64 elements, at most 16384 per pair: small pairs are not worth more
-    const unsigned long long want = pr.n / 64 < (unsigned long long)kSeedBlocks * kBlock ? pr.n / 64 : (unsigned long long)kSeedBlocks * kBlock;
+    const unsigned long long most = (unsigned long long)kSeedParts * kSeedBlock;
+    const unsigned long long want = pr.n / 64 < most ? pr.n / 64 : most;
     if (k >= want) return;
     const unsigned long long i = k * (pr.n / want);
     if (i < pr.n) score_exact<CD, RD>(Elem<CD>::load1(pr.cand, i), Elem<RD>::load1(pr.ref, i), pr, acc);
 }
 
-__global__ void __launch_bounds__(kBlock) score_init_kernel(pf::PairDev* pairs, int n_pairs, pf_score_result* slots) {
-    const int p = blockIdx.x / kSeedBlocks, part = blockIdx.x % kSeedBlocks;
-    if (p >= n_pairs) return;
-    for (int k = part * kBlock + threadIdx.x; k < kSlots; k += kSeedBlocks * kBlock) {     // every slot, whatever the two constants
+__global__ void __launch_bounds__(kSeedBlock) score_stage_kernel(pf::PairBatch batch, pf::PairDev* pairs, unsigned long long* block_start,
+                                                                 pf_score_result* slots, double* seeds) {
+    const int local = blockIdx.x / kSeedParts, part = blockIdx.x % kSeedParts;
+    if (local >= batch.count) return;
+    const int p = batch.first + local;
+    const pf::PairDev pr = batch.pairs[local];
+    if (part == 0 && threadIdx.x == 0) {
+        pairs[p] = pr;
+        block_start[p] = batch.start[local];
+        if (batch.last && local == batch.count - 1) block_start[p + 1] = batch.start[batch.count];
+    }
+    for (int k = part * kSeedBlock + threadIdx.x; k < kSlots; k += kSeedParts * kSeedBlock) {     // every slot, whatever the two constants
         pf_score_result z;
         z.max_abs = 0.0; z.max_rel = 0.0; z.n = 0; z.n_viol = 0;
         z.nan_cand = z.nan_ref = z.inf_cand = z.inf_ref = 0;
         z.allclose = 0; z.bit_identical = 0; z.reserved_ = 0;
         slots[(size_t)p * kSlots + k] = z;
     }
-    const pf::PairDev pr = pairs[p];
     Acc acc;
-    const unsigned long long k = (unsigned long long)part * kBlock + threadIdx.x;
+    const unsigned long long k = (unsigned long long)part * kSeedBlock + threadIdx.x;
     switch (pr.cand_dtype * 4 + pr.ref_dtype) {
         case PF_F32 * 4 + PF_F32: seed_sample<PF_F32, PF_F32>(pr, k, acc); break;
         case PF_F32 * 4 + PF_BF16: seed_sample<PF_F32, PF_BF16>(pr, k, acc); break;
@@ -433,30 +436,33 @@ __global__ void __launch_bounds__(kBlock) score_init_kernel(pf::PairDev* pairs, 
         case PF_F16 * 4 + PF_F16: seed_sample<PF_F16, PF_F16>(pr, k, acc); break;
         default: break;          // fp64 references are not screened: no seed needed
     }
-    __shared__ double s_abs[kBlock / 64], s_rel[kBlock / 64];
-    const double wa = wave_max(acc.max_abs), wr = wave_max(acc.max_rel);
-    if ((threadIdx.x & 63) == 0) { s_abs[threadIdx.x >> 6] = wa; s_rel[threadIdx.x >> 6] = wr; }
+    // errors are >= 0 and never NaN, so their bit patterns order like the values
+    __shared__ unsigned long long s_max[2];
+    if (threadIdx.x < 2) s_max[threadIdx.x] = 0;
     __syncthreads();
-    if (threadIdx.x == 0) {
-        double ma = s_abs[0], mr = s_rel[0];
-        for (int w = 1; w < kBlock / 64; ++w) { ma = fmax(ma, s_abs[w]); mr = fmax(mr, s_rel[w]); }
-        if (ma > 0.0) raise_max(&pairs[p].seed_abs, ma);
-        if (mr > 0.0) raise_max(&pairs[p].seed_rel, mr);
-    }
+    if (acc.max_abs > 0.0) atomicMax(&s_max[0], (unsigned long long)__double_as_longlong(acc.max_abs));
+    if (acc.max_rel > 0.0) atomicMax(&s_max[1], (unsigned long long)__double_as_longlong(acc.max_rel));
+    __syncthreads();
+    if (threadIdx.x < 2) seeds[((size_t)p * kSeedParts + part) * 2 + threadIdx.x] = __longlong_as_double((long long)s_max[threadIdx.x]);
 }
 
-__device__ __forceinline__ void raise_max(double* slot, double v) {
-    // values only grow, so a stale read can at worst cause a redundant atomic
-    const unsigned long long bits = (unsigned long long)__double_as_longlong(v);
-    if (bits > __atomic_load_n((unsigned long long*)slot, __ATOMIC_RELAXED)) atomicMax((unsigned long long*)slot, bits);
+// The seed of a pair: the largest of its kSeedParts partial maxima (uniform loads, a few dozen instructions per wave).
+__device__ __forceinline__ void load_seed(const double* __restrict__ seeds, int p, double& abs_, double& rel_) {
+    abs_ = 0.0; rel_ = 0.0;
+#pragma unroll
+    for (int k = 0; k < kSeedParts; ++k) {
+        abs_ = fmax(abs_, seeds[((size_t)p * kSeedParts + k) * 2]);
+        rel_ = fmax(rel_, seeds[((size_t)p * kSeedParts + k) * 2 + 1]);
+    }
 }
 
 // One instantiation per (candidate dtype, reference dtype): the host orders the
 // pairs by dtype combination, so each instantiation owns a contiguous range of
 // blocks and is register-allocated for its own path only.
 template <int CD, int RD>
-__global__ void __launch_bounds__(kBlock) score_kernel(pf::PairDev* pairs, const unsigned long long* block_start,
-                                                       int n_pairs, pf_score_result* slots, unsigned long long block_offset) {
+__global__ void __launch_bounds__(kBlock) score_kernel(const pf::PairDev* __restrict__ pairs, const unsigned long long* __restrict__ block_start,
+                                                       int n_pairs, pf_score_result* slots, const double* __restrict__ seeds,
+                                                       unsigned long long block_offset) {
     // which pair does this block belong to: largest p with block_start[p] <= bid
     int lo = 0, hi = n_pairs;
     const unsigned long long bid = block_offset + blockIdx.x;
@@ -468,12 +474,13 @@ __global__ void __launch_bounds__(kBlock) score_kernel(pf::PairDev* pairs, const
     const unsigned long long begin = (bid - block_start[lo]) * pr.chunk;
     const unsigned long long end = begin + pr.chunk < pr.n ? begin + pr.chunk : pr.n;
     Acc acc;
-    // maxima other blocks of this pair have already published: a head start for the screening thresholds
     pf_score_result* my_slot = slots + (size_t)lo * kSlots + (bid - block_start[lo]) % kSlots;
     if (RD == PF_F64) {
         score_chunk<CD, RD>(pr, begin, end, acc);
     } else {
-        score_chunk_fast<CD, RD>(pr, begin, end, acc, pr.seed_abs, pr.seed_rel);
+        double seed_abs, seed_rel;
+        load_seed(seeds, lo, seed_abs, seed_rel);
+        score_chunk_fast<CD, RD>(pr, begin, end, acc, seed_abs, seed_rel);
     }
     if (RD == PF_F64) acc.max_rel = fmax(acc.max_rel, __ddiv_rn(acc.keep_d, acc.keep_b));   // only score_one defers a division
     // Block reduction.  On the screened path a lane has something to report only if it went through
@@ -521,12 +528,14 @@ __global__ void __launch_bounds__(kBlock) score_kernel(pf::PairDev* pairs, const
 
 // One wave per pair: lane k folds slot k (kSlots == 64), then a wave reduction.
 __global__ void __launch_bounds__(64) score_final_kernel(const pf::PairDev* pairs, int n_pairs, pf_score_result* res,
-                                                         const pf_score_result* slots) {
+                                                         const pf_score_result* slots, const double* seeds) {
     const int p = blockIdx.x;
     if (p >= n_pairs) return;
     const pf_score_result s = slots[(size_t)p * kSlots + threadIdx.x];
-    // screened pairs publish their maxima in the pair record, fp64-reference pairs in the slots
-    const double ma = fmax(wave_max(s.max_abs), pairs[p].seed_abs), mr = fmax(wave_max(s.max_rel), pairs[p].seed_rel);
+    // the sampled seeds are errors of real elements too (the screen lets elements that tie them pass unrecorded)
+    double seed_abs, seed_rel;
+    load_seed(seeds, p, seed_abs, seed_rel);
+    const double ma = fmax(wave_max(s.max_abs), seed_abs), mr = fmax(wave_max(s.max_rel), seed_rel);
     const unsigned long long nv = wave_sum(s.n_viol), bd = wave_sum(s.reserved_);
     const unsigned long long nc = wave_sum(s.nan_cand), nr = wave_sum(s.nan_ref);
     const unsigned long long ic = wave_sum(s.inf_cand), ir = wave_sum(s.inf_ref);
@@ -650,14 +659,19 @@ hipError_t launch_score_upload(const PairBatch& batch, PairDev* d_pairs, unsigne
     return hipGetLastError();
 }
 
+hipError_t launch_score_stage(const PairBatch& batch, PairDev* d_pairs, unsigned long long* d_block_start, pf_score_result* d_slots,
+                              double* d_seeds, hipStream_t stream) {
+    hipLaunchKernelGGL(score_stage_kernel, dim3(batch.count * kSeedParts), dim3(kSeedBlock), 0, stream, batch, d_pairs, d_block_start,
+                       d_slots, d_seeds);
+    return hipGetLastError();
+}
+
 hipError_t launch_score(const PairDev* d_pairs, const unsigned long long* d_block_start, int n_pairs, const ScoreRanges& ranges,
-                        pf_score_result* d_results, pf_score_result* d_slots, hipStream_t stream) {
-    hipLaunchKernelGGL(score_init_kernel, dim3(n_pairs * kSeedBlocks), dim3(kBlock), 0, stream, const_cast<PairDev*>(d_pairs), n_pairs, d_slots);
+                        pf_score_result* d_results, pf_score_result* d_slots, const double* d_seeds, hipStream_t stream) {
 #define PF_LAUNCH(CD, RD)                                                                                                  \
     if (ranges.count[CD][RD])                                                                                              \
         hipLaunchKernelGGL((score_kernel<CD, RD>), dim3((unsigned)ranges.count[CD][RD]), dim3(kBlock), 0, stream,            \
-                           const_cast<PairDev*>(d_pairs),                                                                  \
-                           d_block_start, n_pairs, d_slots, ranges.first[CD][RD]);
+                           d_pairs, d_block_start, n_pairs, d_slots, d_seeds, ranges.first[CD][RD]);
     PF_LAUNCH(PF_F32, PF_F32)
     PF_LAUNCH(PF_F32, PF_BF16)
     PF_LAUNCH(PF_F32, PF_F64)
@@ -669,7 +683,7 @@ hipError_t launch_score(const PairDev* d_pairs, const unsigned long long* d_bloc
     PF_LAUNCH(PF_F16, PF_F16)
     PF_LAUNCH(PF_F16, PF_F64)
 #undef PF_LAUNCH
-    hipLaunchKernelGGL(score_final_kernel, dim3(n_pairs), dim3(64), 0, stream, d_pairs, n_pairs, d_results, d_slots);
+    hipLaunchKernelGGL(score_final_kernel, dim3(n_pairs), dim3(64), 0, stream, d_pairs, n_pairs, d_results, d_slots, d_seeds);
     return hipGetLastError();
 }
 

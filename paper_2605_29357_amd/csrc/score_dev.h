@@ -16,7 +16,6 @@ struct PairDev {
     int equal_nan;
     int orig;               // index of this pair in the caller's array
     unsigned long long chunk;   // elements per workgroup
-    double seed_abs, seed_rel;  // device side only: largest errors of a sample, raised by the seeding kernel
 };
 
 // blocks of each (candidate dtype, reference dtype) combination, indexed by pf_dtype: a contiguous range
@@ -34,6 +33,7 @@ inline bool score_combo_supported(int cd, int rd) {
 }
 
 constexpr int kScoreSlots = 64;   // partial result slots per pair
+constexpr int kScoreSeedParts = 16;   // sampled maxima per pair (two doubles each), folded by every reader
 
 // up to kBatch descriptors passed by value to the upload kernel
 constexpr int kPairBatch = 24;
@@ -53,8 +53,11 @@ unsigned long long score_chunk_elems(unsigned long long n);
 hipError_t launch_ladder(const PairDev* d_pairs, const unsigned long long* d_block_start, int n_pairs, const ScoreRanges& ranges,
                          const LadderTable& table, pf_ladder_result* d_results, pf_ladder_result* d_slots, hipStream_t stream);
 hipError_t launch_score_upload(const PairBatch& batch, PairDev* d_pairs, unsigned long long* d_block_start, hipStream_t stream);
+// descriptor upload, slot clearing and seeding of one batch in a single launch (the single-level scorer)
+hipError_t launch_score_stage(const PairBatch& batch, PairDev* d_pairs, unsigned long long* d_block_start, pf_score_result* d_slots,
+                              double* d_seeds, hipStream_t stream);
 hipError_t launch_score(const PairDev* d_pairs, const unsigned long long* d_block_start, int n_pairs, const ScoreRanges& ranges,
-                        pf_score_result* d_results, pf_score_result* d_slots, hipStream_t stream);
+                        pf_score_result* d_results, pf_score_result* d_slots, const double* d_seeds, hipStream_t stream);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
 
 }  // namespace pf

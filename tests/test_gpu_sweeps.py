@@ -9,7 +9,7 @@ import torch
 
 import paper_2605_29357_amd as pf
 from tests.harness import Runner, check_against_oracle
-from workloads import sweeps
+from workloads import configs, sweeps
 
 pytestmark = pytest.mark.gpu
 
@@ -53,3 +53,27 @@ def test_dtype_variants_of_an_instance(family, dtypes):
             outs = r.run()
             torch.cuda.synchronize()
             check_against_oracle(w, outs, what=w.name)
+
+
+@pytest.mark.parametrize("name,make,outers", [
+    ("flat", lambda r: configs.cfg3_bias_gelu_gate(rows=r, cols=264), (5, 37, 300)),
+    ("flat rows of 133, whole vectors", lambda r: configs.cfg3_bias_gelu_gate(rows=r, cols=133, dtype="f32"), (4, 8, 52)),
+    ("flat rows of 133, ragged end", lambda r: configs.cfg3_bias_gelu_gate(rows=r, cols=133, dtype="f32"), (5, 7, 49)),
+    ("layernorm rows", lambda r: configs.cfg1_add_layernorm(rows=r, cols=768), (7, 64, 200)),
+    ("softmax batch", lambda r: configs.cfg2_masked_softmax(heads=r, seq=133), (2, 3, 5)),
+    ("rmsnorm + rope batch", lambda r: configs.cfg4_rmsnorm_rope(r, 64, 4, 128), (2, 3, 5)),
+    ("layernorm rows streamed", lambda r: configs.cfg1_add_layernorm(rows=r, cols=70001), (2, 3)),
+])
+def test_members_that_share_one_code_object_match_the_oracle(name, make, outers):
+    """Kernels take the outermost extent as an argument: members of an instance that differ only
+    there run the same code object (same kernel name = same source hash), each at its own extent."""
+    names = set()
+    for r in outers:
+        w = make(r)
+        run = Runner(w)
+        assert run.info["n_kernels"] == 1
+        names.add(run.exe.kernel_name(0))
+        outs = run.run()
+        torch.cuda.synchronize()
+        check_against_oracle(w, outs, what="%s, outer extent %d" % (name, r))
+    assert len(names) == 1, names

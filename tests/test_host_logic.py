@@ -248,3 +248,32 @@ def test_fp16_tensors_parse_print_and_compile():
     assert e.info()["n_kernels"] == 1 and e.info()["algorithmic_bytes"] == w.algorithmic_bytes == 2 * (4 * 8 * 3 + 8)
     assert "const f16* __restrict__" in e.source(0)
     assert pf.tolerance("f16", -5) == (1e-3, 1e-5) and pf.tolerance("f16", 0) == (1.0, 1.0)
+
+
+def test_members_that_differ_in_the_outermost_extent_share_one_code_object():
+    # Sec. 3.1 task instance: flat and row kernels take the outermost extent as an argument, so
+    # members with the same tiling decisions generate the same text (the kernel name ends in its hash)
+    g = pf.Graph(configs.cfg3_bias_gelu_gate(rows=4, cols=2048).text)
+    execs = [pf.Exec(g.variant([(r, 2048), (2048,), (r, 2048)])) for r in (4, 100, 777)]
+    names = {e.kernel_name(0) for e in execs}
+    assert len(names) == 1
+    src = execs[1].source(0)
+    assert "const long long pf_d0" in src and "100" not in src.replace("0x", "")
+    assert [e.group_info(0)["grid_blocks"] for e in execs] == [4, 100, 777]      # 2048 bf16 = one 256-lane block per row
+    assert execs[0].source(0) == src == execs[2].source(0)
+    before = pf.jit_stats()
+    again = pf.Exec(g.variant([(900, 2048), (2048,), (900, 2048)]))           # still under the streaming-store threshold
+    after = pf.jit_stats()
+    assert again.kernel_name(0) in names
+    assert after["memory_hits"] == before["memory_hits"] + 1 and after["compiled"] == before["compiled"]
+    assert after["code_objects"] == before["code_objects"]
+    # another row length is another kernel
+    other = pf.Exec(g.variant([(100, 1024), (1024,), (100, 1024)]))
+    assert other.kernel_name(0) not in names
+    # row kernels: the batch of a softmax; a rank-1 problem has no outer extent to pass
+    s = pf.Graph(configs.cfg2_masked_softmax(heads=2, seq=128).text)
+    sm = [pf.Exec(s.variant([(h, 128, 128), (128, 128)])) for h in (2, 3, 8)]
+    assert len({e.kernel_name(0) for e in sm}) == 1 and "pf_d0" in sm[0].source(0)
+    b = Builder()
+    b.output(b.op("gelu", [b.input("f32", (1000,))], "f32"))
+    assert "pf_d0" not in pf.Exec(b.text()).source(0)
