@@ -32,7 +32,7 @@ HBM_PEAK_GBS = 8000.0
 # same counter reads for a 256 MiB plain copy; figures in profiles/bench_cfg3_hbm_traffic_pmc.md).
 # Keyed by kernel name, which ends in a hash of the specialised source: a changed kernel has a
 # new name and reports traffic = null until the counters are taken again.
-MEASURED_TRAFFIC_BYTES = {"pf_ew_add_gelu_mul_7c8cf422": 541152579}
+MEASURED_TRAFFIC_BYTES = {"pf_ew_add_gelu_mul_99c1c841": 541149795}
 
 
 def parse():
@@ -71,7 +71,8 @@ def main():
     pf.lib()
     stream = torch.cuda.current_stream()
     if args.sweep:
-        print(json.dumps({"sweep": sweep_table(torch, pf, Runner, alloc_outputs, stream)}))
+        print(json.dumps({"sweep": sweep_table(torch, pf, Runner, alloc_outputs, stream),
+                          "outer_extent_reuse": reuse_table(torch, pf, Runner, alloc_outputs, stream)}))
         return
     if args.cfg5:
         print(json.dumps({"cfg5": cfg5_table(torch, pf, Runner, alloc_outputs, stream)}))
@@ -295,6 +296,48 @@ def sweep_table(torch, pf, Runner, alloc_outputs, stream):
             summary["geomean_static_over_shape_aware"] = float(np.exp(np.mean([np.log(r["static_us"] / r["fused_us"]) for r in ok])))
             summary["worst_static_over_shape_aware"] = float(max(r["static_us"] / r["fused_us"] for r in ok))
         table[fam] = {"members": rows, "summary": summary}
+    return table
+
+
+def reuse_table(torch, pf, Runner, alloc_outputs, stream):
+    """One operator sequence at several outermost extents (batch, rows): flat and row kernels take that extent as
+    an argument, so members with the same tiling run one code object.  Per member: kernel name, wall time of
+    pf_compile (a JIT compilation or a cache hit) and the fused kernel's device time."""
+    import time
+    import types
+    from paper_2605_29357_amd.torch_util import TORCH_DT
+    from workloads import configs
+    fams = {
+        "bias_gelu_gate": (configs.cfg3_bias_gelu_gate(rows=8, cols=11008), lambda r: [(r, 11008), (11008,), (r, 11008)], (1024, 2048, 4096, 8192)),
+        "masked_softmax": (configs.cfg2_masked_softmax(heads=2, seq=512), lambda h: [(h, 512, 512), (512, 512)], (8, 16, 32, 64)),
+        "rmsnorm_rope": (configs.cfg4_rmsnorm_rope(2, 2048, 32, 128), lambda b: [(b, 2048, 32, 128), (128,), (2048, 1, 128), (2048, 1, 128)], (2, 4, 8)),
+        "add_layernorm": (configs.cfg1_add_layernorm(rows=8, cols=768), lambda r: [(r, 768), (r, 768), (768,), (768,)], (16384, 32768, 65536, 131072)),
+    }
+    table = {}
+    for fam, (base, shapes_of, extents) in fams.items():
+        g0 = pf.Graph(base.text)
+        rows = []
+        for x in extents:
+            shapes = shapes_of(x)
+            before = pf.jit_stats()
+            t0 = time.perf_counter()
+            g = g0.variant(shapes)
+            w = types.SimpleNamespace(text=g.text(), inputs=None, input_dtypes=base.input_dtypes, input_shapes=shapes,
+                                      output_dtypes=base.output_dtypes, output_shapes=[shapes[0]] * len(base.output_dtypes), name=fam)
+            f = Runner(w, upload=False)
+            compile_ms = (time.perf_counter() - t0) * 1e3
+            after = pf.jit_stats()
+            w.algorithmic_bytes = f.info["algorithmic_bytes"]
+            f.d_in = [(torch.rand(tuple(sh), device="cuda") + 0.5).to(TORCH_DT[dt]) for dt, sh in zip(w.input_dtypes, shapes)]
+            ins, outs = _rotating(torch, f, w, alloc_outputs)
+            fm, _ = time_runner(torch, f, stream, ins, outs, warmup=10, trials=50, max_rounds=2)
+            rows.append({"outer_extent": x, "kernel": f.exe.kernel_name(0), "pf_compile_ms": compile_ms,
+                         "jit_compiled": after["compiled"] - before["compiled"],
+                         "cache_hits": after["memory_hits"] + after["disk_hits"] - before["memory_hits"] - before["disk_hits"],
+                         "grid": f.exe.group_info(0)["grid_blocks"], "bytes": w.algorithmic_bytes, "fused_us": fm,
+                         "GBps": w.algorithmic_bytes / fm / 1e3})
+            del f, ins, outs
+        table[fam] = {"members": rows, "code_objects": len({r["kernel"] for r in rows})}
     return table
 
 
