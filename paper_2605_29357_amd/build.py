@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpf.so")
-SOURCES = ["api.cpp", "ir.cpp", "plan.cpp", "codegen.cpp", "runtime.cpp", "metric.cpp", "score.hip"]
+SOURCES = ["api.cpp", "ir.cpp", "rewrite.cpp", "plan.cpp", "codegen.cpp", "runtime.cpp", "metric.cpp", "score.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 

@@ -197,10 +197,18 @@ pf_status pf_compile(const pf_graph* g, const pf_options* h_opt, pf_exec** e) {
             if (r) pf::fail(PF_E_INVALID, "pf_options.reserved must be zero");
         std::unique_ptr<pf_exec> ex(new pf_exec());
         ex->opt = opt;
-        pf::make_plan(*g, opt, ex->plan);
+        // fused plans work on a rewritten copy (transposes of computed values pushed down to the operands)
+        pf_graph work;
+        if (opt.fuse) pf::sink_transposes(*g, opt, work);
+        else work = *g;
+        pf::make_plan(work, opt, ex->plan);
         int idx = 0;
         for (auto& grp : ex->plan.groups) {
-            pf::generate_source(*g, opt, grp, idx++);
+            for (int id : grp.nodes) {
+                const int user = opt.fuse ? work.nodes[id].orig : id;
+                if (user >= 0) grp.user_nodes.push_back(user);
+            }
+            pf::generate_source(work, opt, grp, idx++);
             if (grp.scratch_bytes) {     // partial results of a split reduction live at the end of the workspace
                 const uint64_t at = (ex->plan.workspace_bytes + 255) / 256 * 256;
                 grp.scratch_offset = (int64_t)at;
@@ -249,8 +257,8 @@ pf_status pf_exec_group_info(const pf_exec* e, int group, pf_group_info* h_info)
         const pf::Group& grp = e->plan.groups[group];
         memset(h_info, 0, sizeof *h_info);
         h_info->tmpl = grp.tmpl;
-        h_info->n_nodes = (int)grp.nodes.size();
-        for (size_t i = 0; i < grp.nodes.size() && i < 64; ++i) h_info->nodes[i] = grp.nodes[i];
+        h_info->n_nodes = (int)std::min<size_t>(grp.user_nodes.size(), 64);
+        for (size_t i = 0; i < grp.user_nodes.size() && i < 64; ++i) h_info->nodes[i] = grp.user_nodes[i];
         h_info->rows = grp.rows;
         h_info->cols = grp.cols;
         h_info->block_threads = grp.block;

@@ -73,11 +73,19 @@ struct Emit {
     std::string ref(int consumer, int p, const std::string& j) const {
         const Node& n = g.nodes[p];
         if (n.op == PF_OP_CONST) return lit(n.value);
-        if (in_kernel(p)) return kind.at(p) == 2 ? strf("v%d[%s]", p, slot(j).c_str()) : strf("s%d[u]", p);
-        int oi = is_view(n.op) ? voperand_of.at(p) : epilogue_node(consumer) ? coperand_of.at(p) : operand_of.at(p);
+        if (in_kernel(p) && !reads_alias(consumer, p)) return kind.at(p) == 2 ? strf("v%d[%s]", p, slot(j).c_str()) : strf("s%d[u]", p);
+        int oi = is_view(n.op) ? voperand_of.at(p) : epilogue_node(consumer) ? coperand_of.at(p) : reads_alias(consumer, p) ? toperand_of.at(p) : operand_of.at(p);
         const bool h = hoisted.count(oi) != 0;
         if (operand_kind(oi) == 2) return h ? strf("x%d[%s]", oi, j.c_str()) : strf("x%d[%s]", oi, slot(j).c_str());
         return h ? strf("x%d[0]", oi) : strf("x%d[u]", oi);
+    }
+
+    // does the consumer read p through an orientation change that moves no data?
+    bool reads_alias(int consumer, int p) const {
+        const Node& c = g.nodes[consumer];
+        for (size_t k = 0; k < c.in.size(); ++k)
+            if (c.in[k] == p && c.reads_alias(k)) return true;
+        return false;
     }
 
     // 2: varies along the last dim (array per lane); 1: uniform along it (scalar per row)
@@ -103,7 +111,8 @@ struct Emit {
         // row-uniform iff every operand is
         for (int p : n.in) {
             if (g.nodes[p].op == PF_OP_CONST) continue;
-            int k = in_kernel(p) ? kind.at(p) : operand_kind(is_view(g.nodes[p].op) ? voperand_of.at(p) : operand_of.at(p));
+            int k = in_kernel(p) && !reads_alias(id, p) ? kind.at(p)
+                    : operand_kind(is_view(g.nodes[p].op) ? voperand_of.at(p) : reads_alias(id, p) ? toperand_of.at(p) : operand_of.at(p));
             if (k == 2) return 2;
         }
         return 1;

@@ -53,6 +53,10 @@ struct Node {
     int64_t shift = 0;    // roll
     int64_t start = 0, stop = 0;   // slice
     bool is_output = false;
+    // set by the rewrite that runs ahead of planning (never by the parser):
+    int orig = -1;                 // the user's node this one computes (a value recomputed in the other orientation keeps it)
+    std::vector<char> alias_t;     // per operand: read through a swap of its last two dims that moves no data
+    bool reads_alias(size_t k) const { return k < alias_t.size() && alias_t[k]; }
 };
 
 }  // namespace pf
@@ -120,6 +124,7 @@ struct Store {
 struct Group {
     pf_template tmpl = PF_T_EW_FLAT;
     std::vector<int> nodes;        // members in topological order (const nodes folded in)
+    std::vector<int> user_nodes;   // the caller's node ids the members compute (what reports show)
     std::vector<int> node_kind;    // per member: 2 full, 1 row-uniform, 3 column-uniform
     Shape domain;                  // iteration domain, rank-aligned full shape
     int64_t rows = 1, cols = 1;    // product of leading dims, last dim
@@ -153,6 +158,9 @@ struct Plan {
 };
 
 void make_plan(const pf_graph& g, const pf_options& opt, Plan& plan);
+
+// ---- rewrite.cpp ----
+void sink_transposes(const pf_graph& g, const pf_options& opt, pf_graph& out);
 
 // ---- codegen.cpp ----
 void generate_source(const pf_graph& g, const pf_options& opt, Group& grp, int index);

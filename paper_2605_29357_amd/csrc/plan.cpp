@@ -113,6 +113,8 @@ struct Builder {
         if (grp.nodes.size() >= 60) return false;
         for (int p : n.in)
             if (group_of[p] == gi && !usable_in_kernel(p)) return false;
+        for (size_t k = 0; k < n.in.size(); ++k)               // read in the other orientation: from memory only
+            if (n.reads_alias(k) && group_of[n.in[k]] == gi) return false;
         if (is_col_reduction(n)) {
             // joins a flat elementwise prologue, or further reductions of the same domain
             if (grp.tmpl != PF_T_EW_FLAT && grp.tmpl != PF_T_COL_REDUCE) return false;
@@ -297,8 +299,8 @@ void make_plan(const pf_graph& g, const pf_options& opt, Plan& plan) {
             Shape s = canon(o.shape);
             if (transposed) {
                 // the operand as seen after swapping its last two dims
-                const Shape& full = g.nodes[p].shape;
-                Shape t = full;
+                Shape t = g.nodes[p].shape;
+                if (t.size() < 2) t.insert(t.begin(), 2 - t.size(), 1);
                 std::swap(t[t.size() - 1], t[t.size() - 2]);
                 Shape tc = canon(t);
                 const int64_t r_o = t[t.size() - 2], c_o = t[t.size() - 1];
@@ -412,10 +414,11 @@ void make_plan(const pf_graph& g, const pf_options& opt, Plan& plan) {
                 continue;
             }
             const bool epilogue_node = is_col && bg.kinds[m] == 3 && !is_reduction(n.op);
-            for (int p : n.in) {
+            for (size_t k = 0; k < n.in.size(); ++k) {
+                const int p = n.in[k];
                 if (g.nodes[p].op == PF_OP_CONST) continue;
                 bool inside = b.group_of[p] == (int)gi && b.usable_in_kernel(p);
-                if (n.op == PF_OP_TRANSPOSE) add_operand(p, true);
+                if (n.op == PF_OP_TRANSPOSE || n.reads_alias(k)) add_operand(p, true);
                 else if (inside) continue;
                 else if (is_view(g.nodes[p].op)) add_view_operand(p);
                 else add_operand(p, false, epilogue_node);
@@ -435,6 +438,8 @@ void make_plan(const pf_graph& g, const pf_options& opt, Plan& plan) {
                     continue;
                 }
                 if (b.group_of[c] != (int)gi || !b.usable_in_kernel(id) || cop == PF_OP_TRANSPOSE || is_view(cop)) outside_use = true;
+                for (size_t k = 0; k < g.nodes[c].in.size(); ++k)
+                    if (g.nodes[c].in[k] == id && g.nodes[c].reads_alias(k)) outside_use = true;
             }
             // anything downstream of a view chain rooted here reads this node from memory
             if (!is_view(n.op))
