@@ -163,6 +163,17 @@ struct Builder {
         return false;
     }
 
+    // does a member of group gi read, from memory, a tensor that node id reads too?
+    bool shares_operand(int id, int gi) const {
+        for (int p : g.nodes[id].in) {
+            if (g.nodes[p].op == PF_OP_CONST || group_of[p] == gi) continue;
+            for (int m : groups[gi].nodes)
+                for (int q : g.nodes[m].in)
+                    if (q == p) return true;
+        }
+        return false;
+    }
+
     void join(int id, int gi) {
         const Node& n = g.nodes[id];
         G& grp = groups[gi];
@@ -215,8 +226,14 @@ struct Builder {
             }
             if (is_view(n.op)) cand = std::max(cand, group_of[root_of((int)i)]);
             int last = (int)groups.size() - 1;
-            if (cand >= 0 && can_join((int)i, cand)) join((int)i, cand);
-            else if (last > cand && last >= 0 && can_join((int)i, last)) join((int)i, last);
+            int pick = -1;
+            if (cand >= 0 && can_join((int)i, cand)) pick = cand;
+            // otherwise any later group will do; one that already reads an operand of this node saves its bytes
+            // (not for a transpose: it is pure data movement and belongs with its readers, which come next)
+            for (int gi = last; gi > cand && pick < 0 && n.op != PF_OP_TRANSPOSE; --gi)
+                if (shares_operand((int)i, gi) && can_join((int)i, gi)) pick = gi;
+            if (pick < 0 && last > cand && can_join((int)i, last)) pick = last;
+            if (pick >= 0) join((int)i, pick);
             else seed((int)i);
         }
     }

@@ -132,6 +132,13 @@ struct Sinker {
             if (n.op == PF_OP_TRANSPOSE && n.shape.size() >= 2) {
                 const int v = n.in[0];
                 const Node& x = src.nodes[v];
+                if (x.op == PF_OP_TRANSPOSE && x.dtype == src.nodes[x.in[0]].dtype && n.dtype == x.dtype && src.nodes[x.in[0]].shape.size() >= 2 &&
+                    src.nodes[x.in[0]].op != PF_OP_INPUT) {
+                    // transposed twice: the value itself (an output slot of its own if the user asked for one)
+                    map[i] = map[x.in[0]];
+                    if (n.is_output) out.nodes[map[i]].is_output = true;
+                    continue;
+                }
                 const bool computed = x.op != PF_OP_INPUT && x.op != PF_OP_CONST;
                 if (computed && x.op != PF_OP_TRANSPOSE && worth_sinking(v)) {
                     const Ref r = transposed(v, true);
