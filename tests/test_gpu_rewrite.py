@@ -1,0 +1,90 @@
+"""GPU parity for transposes of computed values.
+
+The planner pushes a transpose of an elementwise value down to the operands (the consumer's
+kernel recomputes the value in its own orientation; operands with a last or second-to-last
+extent of 1 change orientation without moving data).  The oracle executes the graph as written,
+transposes included, so these cases check the rewrite against the definition.
+"""
+import numpy as np
+import pytest
+import torch
+
+from tests.harness import Runner, check_against_oracle, oracle_outputs
+from workloads import configs, rng
+from workloads.irtext import Builder
+
+pytestmark = pytest.mark.gpu
+
+
+def _workload(name, build, shapes, dtype, positive=()):
+    g = Builder()
+    ins = [g.input(dtype, s) for s in shapes]
+    outs = build(g, ins)
+    for o in outs:
+        g.output(o)
+    data = []
+    for k, s in enumerate(shapes):
+        x = rng.normal(90 + k, 0, int(np.prod(s))).reshape(s)
+        if k in positive:
+            x = np.abs(x) + 0.5
+        data.append(rng.store(x, dtype))
+    w = configs.Workload(name, g.text(), data, [dtype] * len(shapes), [tuple(s) for s in shapes], [dtype] * len(outs),
+                         [()] * len(outs))
+    refs = oracle_outputs(w)
+    w.output_shapes = [r.shape for r in refs]
+    return w.finish(), refs
+
+
+def _softmax_then_transpose(g, ins):
+    x, wgt = ins
+    m = g.op("max", [x], g_dt(g))
+    e = g.op("exp", [g.op("sub", [x, m], g_dt(g))], g_dt(g))
+    p = g.op("div", [e, g.op("sum", [e], g_dt(g))], g_dt(g))
+    return [g.op("mul", [g.op("transpose", [p], g_dt(g)), wgt], g_dt(g))]
+
+
+def g_dt(g):
+    return g.dtype
+
+
+CASES = [
+    # (name, builder, input shapes, indices of inputs kept positive, expected kernels)
+    ("unary chain", lambda g, i: [g.op("tanh", [g.op("transpose", [g.op("exp", [i[0]], g.dtype)], g.dtype)], g.dtype)],
+     [(70, 133)], (), 1),
+    ("weights and per-row scale change orientation for free",
+     lambda g, i: [g.op("gelu", [g.op("transpose", [g.op("mul", [g.op("add", [i[0], i[1]], g.dtype), i[2]], g.dtype)], g.dtype)], g.dtype)],
+     [(96, 200), (200,), (96, 1)], (), 1),
+    ("two full operands", lambda g, i: [g.op("sub", [g.op("transpose", [g.op("div", [i[0], i[1]], g.dtype)], g.dtype), i[2]], g.dtype)],
+     [(133, 64), (133, 64), (64, 133)], (1,), 1),
+    ("needed in both orientations",
+     lambda g, i: (lambda e: [e, g.op("tanh", [g.op("transpose", [e], g.dtype)], g.dtype)])(g.op("exp", [i[0]], g.dtype)),
+     [(3, 50, 72)], (), 2),
+    ("batched, scalar constant inside the cone",
+     lambda g, i: [g.op("add", [g.op("transpose", [g.op("mul", [g.op("sigmoid", [i[0]], g.dtype), g.const(1.5, g.dtype)], g.dtype)], g.dtype), i[1]], g.dtype)],
+     [(4, 33, 80), (80, 1)], (), 1),
+    ("softmax, then transposed and scaled: only the row statistics cross kernels", _softmax_then_transpose, [(64, 96), (96, 1)], (), 2),
+    ("transposed twice", lambda g, i: [g.op("exp", [g.op("transpose", [g.op("transpose", [g.op("tanh", [i[0]], g.dtype)], g.dtype)], g.dtype)], g.dtype)],
+     [(40, 56)], (), 1),
+    ("a reduction behind the recomputed value",
+     lambda g, i: (lambda h: [g.op("div", [h, g.op("sum", [h], g.dtype)], g.dtype)])(
+         g.op("transpose", [g.op("exp", [g.op("mul", [i[0], g.const(0.1, g.dtype)], g.dtype)], g.dtype)], g.dtype)),
+     [(48, 100)], (), 2),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("name,build,shapes,positive,kernels", CASES)
+def test_transposes_of_computed_values_match_the_oracle(name, build, shapes, positive, kernels, dtype):
+    def build_typed(g, ins):
+        g.dtype = dtype
+        return build(g, ins)
+    w, refs = _workload(name, build_typed, shapes, dtype, positive)
+    r = Runner(w)
+    assert r.info["n_kernels"] == kernels, (name, [gi["template"] for gi in r.exe.groups()])
+    outs = r.run()
+    torch.cuda.synchronize()
+    check_against_oracle(w, outs, refs=refs, what=name)
+    u = Runner(w, fuse=False, intermediates_f32=True)          # op by op: every transpose is a kernel of its own
+    uo = u.run()
+    torch.cuda.synchronize()
+    check_against_oracle(w, uo, refs=refs, what=name + " unfused")
