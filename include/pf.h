@@ -197,7 +197,10 @@ typedef struct {
 } pf_jit_stats;
 pf_status pf_jit_stats_get(pf_jit_stats* h_out);
 
-/* Runs the compiled subgraph once.  d_inputs / d_outputs follow the order of
+/* Thread safety: a pf_exec may be shared by several host threads (its lazy module load is guarded);
+ * each call in flight needs its own workspace.  pf_graph objects are not synchronised.
+ *
+ * Runs the compiled subgraph once.  d_inputs / d_outputs follow the order of
  * the graph's `in` declarations and pf_graph_output calls.  d_workspace must
  * hold workspace_bytes (256-byte aligned) and is private to this call while it
  * is in flight.  Enqueues n_kernels launches on `stream` (a hipStream_t; NULL

@@ -208,6 +208,10 @@ pf_status pf_compile(const pf_graph* g, const pf_options* h_opt, pf_exec** e) {
                 const int user = opt.fuse ? work.nodes[id].orig : id;
                 if (user >= 0) grp.user_nodes.push_back(user);
             }
+            size_t n_args = grp.operands.size() + 2;
+            for (auto& st : grp.stores) n_args += 1 + st.also_outputs.size();
+            if (n_args > (size_t)pf::kMaxKernelArgs)
+                pf::fail(PF_E_COMPILE, "a fused group would take %zu kernel arguments (limit %d)", n_args, pf::kMaxKernelArgs);
             pf::generate_source(work, opt, grp, idx++);
             if (grp.scratch_bytes) {     // partial results of a split reduction live at the end of the workspace
                 const uint64_t at = (ex->plan.workspace_bytes + 255) / 256 * 256;

@@ -1,6 +1,8 @@
 // A compiled subgraph: the plan, its code objects and (once loaded) the
 // device modules.
 #pragma once
+#include <mutex>
+
 #include "pf_internal.h"
 
 struct pf_exec {
@@ -8,6 +10,7 @@ struct pf_exec {
     pf_options opt;
     int n_inputs = 0, n_outputs = 0;
     std::vector<uint64_t> input_bytes, output_bytes;
+    std::mutex load_mu;             // guards the lazy module load (several threads may share one pf_exec)
     bool loaded = false;
     std::vector<void*> modules;     // hipModule_t
     std::vector<void*> functions;   // hipFunction_t

@@ -151,6 +151,9 @@ struct Group {
     uint64_t bytes_read = 0, bytes_written = 0;
 };
 
+// pointer arguments of one kernel (operands + stores) plus the outer extent and the scratch pointer
+constexpr int kMaxKernelArgs = 160;
+
 struct Plan {
     std::vector<Group> groups;
     uint64_t workspace_bytes = 0;

@@ -117,6 +117,7 @@ void jit_stats(pf_jit_stats* out) {
 }
 
 void exec_load(pf_exec& e) {
+    std::lock_guard<std::mutex> lk(e.load_mu);
     if (e.loaded) return;
     e.modules.assign(e.plan.groups.size(), nullptr);
     e.functions.assign(e.plan.groups.size(), nullptr);
@@ -154,8 +155,8 @@ void exec_run(pf_exec& e, const void* const* d_inputs, void* const* d_outputs, v
     exec_load(e);
     for (size_t i = 0; i < e.plan.groups.size(); ++i) {
         Group& grp = e.plan.groups[i];
-        void* ptrs[160];
-        void* args[160];
+        void* ptrs[kMaxKernelArgs];
+        void* args[kMaxKernelArgs];
         int n = 0;
         for (auto& o : grp.operands) {
             const void* p = o.graph_input >= 0    ? d_inputs[o.graph_input]
