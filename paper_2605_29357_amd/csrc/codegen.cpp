@@ -1030,7 +1030,14 @@ struct Emit {
         const int64_t C = grp.domain[rd - 1], R = grp.domain[rd - 2];
         int64_t L = 1;
         for (int k = 0; k < rd - 2; ++k) L *= grp.domain[k];
-        const int64_t tr = (R + 63) / 64, tc = (C + 63) / 64;
+        // Tile edge: 64 (16 elements per lane: long contiguous runs on both sides), or 32 (4 elements per
+        // lane) while 64-wide tiles would leave the chip short of waves: a small problem is bound by the
+        // chain of instructions each wave runs on its own, and four times as many waves with a quarter
+        // of the work each cut that chain (heavy epilogues on 1.5 M elements: 21 us -> 7 us measured).
+        int64_t t64 = L * ((R + 63) / 64) * ((C + 63) / 64);
+        const int TS = t64 < 2048 ? 32 : 64;
+        const int TXN = TS / 4, TYN = 256 / TXN, NI = TS / TYN, EPL = NI * 4;    // lanes along a row, rows per pass, passes, elements per lane
+        const int64_t tr = (R + TS - 1) / TS, tc = (C + TS - 1) / TS;
         grp.block = 256;
         // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Runs of G consecutive
         // tiles go to the same XCD, so tiles that share cache lines (rows whose length is no multiple
@@ -1043,17 +1050,18 @@ struct Emit {
         const int64_t rounds = (tiles + 8 * G - 1) / (8 * G);
         grp.grid = xcd_remap ? rounds * 8 * G : tiles;
         grp.vec = 4;
-        grp.chunks_per_lane = 4;
+        grp.chunks_per_lane = NI;
         grp.lanes_per_row = 0;
         int n_t = 0;
         for (auto& o : grp.operands) n_t += o.transposed ? 1 : 0;
         RU = 1;
-        NN = 16;
+        NN = EPL;
 
         signature();
         line(strf("    constexpr %s C = %lld, R = %lld, TR = %lld, TC = %lld;", idx_t(), (long long)C, (long long)R, (long long)tr,
                   (long long)tc));
-        line(strf("    __shared__ float tile[%d][64][65];", std::max(n_t, 1)));
+        line(strf("    constexpr int TS = %d, TXN = %d, TYN = %d, NI = %d;", TS, TXN, TYN, NI));
+        line(strf("    __shared__ float tile[%d][TS][TS + 1];", std::max(n_t, 1)));
         if (xcd_remap) {
             line(strf("    const %s slot = blockIdx.x / 8;", idx_t()));
             line(strf("    const %s b = ((slot / %d) * 8 + blockIdx.x %% 8) * %d + slot %% %d;", idx_t(), G, G, G));
@@ -1062,8 +1070,8 @@ struct Emit {
             line(strf("    const %s b = blockIdx.x;", idx_t()));
         }
         line(strf("    const %s tcol = b %% TC, trow = (b / TC) %% TR, lead = b / (TC * TR);", idx_t()));
-        line(strf("    const %s r0 = trow * 64, c0 = tcol * 64;", idx_t()));
-        line("    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;");
+        line(strf("    const %s r0 = trow * TS, c0 = tcol * TS;", idx_t()));
+        line("    const int tx = threadIdx.x % TXN, ty = threadIdx.x / TXN;");
         emit_lead_decomposition("lead", rd - 2);
         // stage transposed operands through LDS: memory is [.., C, R] with R contiguous
         int ti = 0;
@@ -1072,8 +1080,8 @@ struct Emit {
             if (!o.transposed) continue;
             std::string base = lead_offset_n(o, rd - 2);
             const bool vec_ok = (R % 4 == 0) && lead_strides_multiple_of(o, 4, rd - 2);
-            line("    _Pragma(\"unroll\") for (int i = 0; i < 4; ++i) {");
-            line(strf("        const %s cc = c0 + ty + 16 * i, rr = r0 + tx * 4;", idx_t()));
+            line("    _Pragma(\"unroll\") for (int i = 0; i < NI; ++i) {");
+            line(strf("        const %s cc = c0 + ty + TYN * i, rr = r0 + tx * 4;", idx_t()));
             line("        float t4[4] = {0.0f, 0.0f, 0.0f, 0.0f};");
             if (vec_ok) {
                 line(strf("        if (cc < C && rr < R) pf_ld<4, false>(p%zu + %s + cc * R + rr, t4);", oi, base.c_str()));
@@ -1083,7 +1091,7 @@ struct Emit {
                 line(strf("        else if (cc < C) { _Pragma(\"unroll\") for (int j = 0; j < 4; ++j) if (rr + j < R) t4[j] = pf_ld1(p%zu + %s + cc * R + rr + j); }",
                           oi, base.c_str()));
             }
-            line(strf("        _Pragma(\"unroll\") for (int j = 0; j < 4; ++j) tile[%d][ty + 16 * i][tx * 4 + j] = t4[j];", ti));
+            line(strf("        _Pragma(\"unroll\") for (int j = 0; j < 4; ++j) tile[%d][ty + TYN * i][tx * 4 + j] = t4[j];", ti));
             line("    }");
             ++ti;
         }
@@ -1091,10 +1099,10 @@ struct Emit {
         ti = 0;
         for (size_t oi = 0; oi < grp.operands.size(); ++oi) {
             const Operand& o = grp.operands[oi];
-            line(strf("    float x%zu[16];", oi));
+            line(strf("    float x%zu[%d];", oi, EPL));
             if (o.transposed) {
-                line("    _Pragma(\"unroll\") for (int i = 0; i < 4; ++i)");
-                line(strf("        _Pragma(\"unroll\") for (int j = 0; j < 4; ++j) x%zu[i * 4 + j] = tile[%d][tx * 4 + j][ty + 16 * i];", oi, ti));
+                line("    _Pragma(\"unroll\") for (int i = 0; i < NI; ++i)");
+                line(strf("        _Pragma(\"unroll\") for (int j = 0; j < 4; ++j) x%zu[i * 4 + j] = tile[%d][tx * 4 + j][ty + TYN * i];", oi, ti));
                 ++ti;
                 continue;
             }
@@ -1102,8 +1110,8 @@ struct Emit {
             const int64_t sr = o.stride[rd - 2], sc = o.stride[rd - 1];
             const bool vec_ok = sc == 1 && (C % 4 == 0) && (sr % 4 == 0) && lead_strides_multiple_of(o, 4, rd - 2) && !o.mapped(rd - 1) &&
                                 o.const_offset % 4 == 0;
-            line("    _Pragma(\"unroll\") for (int i = 0; i < 4; ++i) {");
-            line(strf("        const %s rr = r0 + ty + 16 * i, cc = c0 + tx * 4;", idx_t()));
+            line("    _Pragma(\"unroll\") for (int i = 0; i < NI; ++i) {");
+            line(strf("        const %s rr = r0 + ty + TYN * i, cc = c0 + tx * 4;", idx_t()));
             line(strf("        const %s rc = rr < R ? rr : R - 1;", idx_t()));
             if (vec_ok) {
                 line(strf("        if (cc < C) pf_ld<4, false>(p%zu + %s + %s * %lld + cc, &x%zu[i * 4]);", oi, base.c_str(),
@@ -1122,14 +1130,14 @@ struct Emit {
             }
             line("    }");
         }
-        for (int id : grp.nodes) emit_elementwise(id, 16);
+        for (int id : grp.nodes) emit_elementwise(id, EPL);
         int sp = 0;
         const bool st_vec = C % 4 == 0;
         for (auto& st : grp.stores) {
             int cnt = 1 + (int)st.also_outputs.size();
             for (int c = 0; c < cnt; ++c, ++sp) {
-                line("    _Pragma(\"unroll\") for (int i = 0; i < 4; ++i) {");
-                line(strf("        const %s rr = r0 + ty + 16 * i, cc = c0 + tx * 4;", idx_t()));
+                line("    _Pragma(\"unroll\") for (int i = 0; i < NI; ++i) {");
+                line(strf("        const %s rr = r0 + ty + TYN * i, cc = c0 + tx * 4;", idx_t()));
                 line(strf("        const %s o = (lead * R + rr) * C + cc;", idx_t()));
                 if (st_vec) line(strf("        if (rr < R && cc < C) pf_st<4, false>(q%d + o, &v%d[i * 4]);", sp, st.node));
                 else {
