@@ -436,14 +436,19 @@ __global__ void __launch_bounds__(kSeedBlock) score_stage_kernel(pf::PairBatch b
         case PF_F16 * 4 + PF_F16: seed_sample<PF_F16, PF_F16>(pr, k, acc); break;
         default: break;          // fp64 references are not screened: no seed needed
     }
-    // errors are >= 0 and never NaN, so their bit patterns order like the values
-    __shared__ unsigned long long s_max[2];
-    if (threadIdx.x < 2) s_max[threadIdx.x] = 0;
+    // every lane has a value here, so waves reduce by shuffles (LDS atomics of 64 lanes on one address
+    // would be served one lane at a time) and one lane folds the 16 wave results
+    __shared__ double s_abs[kSeedBlock / 64], s_rel[kSeedBlock / 64];
+    const double wa = wave_max(acc.max_abs), wr = wave_max(acc.max_rel);
+    if ((threadIdx.x & 63) == 0) { s_abs[threadIdx.x >> 6] = wa; s_rel[threadIdx.x >> 6] = wr; }
     __syncthreads();
-    if (acc.max_abs > 0.0) atomicMax(&s_max[0], (unsigned long long)__double_as_longlong(acc.max_abs));
-    if (acc.max_rel > 0.0) atomicMax(&s_max[1], (unsigned long long)__double_as_longlong(acc.max_rel));
-    __syncthreads();
-    if (threadIdx.x < 2) seeds[((size_t)p * kSeedParts + part) * 2 + threadIdx.x] = __longlong_as_double((long long)s_max[threadIdx.x]);
+    if (threadIdx.x < 2) {
+        const double* w = threadIdx.x == 0 ? s_abs : s_rel;
+        double m = w[0];
+#pragma unroll
+        for (int k = 1; k < kSeedBlock / 64; ++k) m = fmax(m, w[k]);
+        seeds[((size_t)p * kSeedParts + part) * 2 + threadIdx.x] = m;
+    }
 }
 
 // The seed of a pair: the largest of its kSeedParts partial maxima (uniform loads, a few dozen instructions per wave).
