@@ -341,9 +341,15 @@ def reuse_table(torch, pf, Runner, alloc_outputs, stream):
     return table
 
 
+def configs_tol(dt):
+    from workloads import configs
+    return (configs.RTOL[dt], configs.ATOL[dt])
+
+
 def cfg5_table(torch, pf, Runner, alloc_outputs, stream):
     """The 256 random fusible DAGs: fused and op-by-op device time each (median of 12 runs after 3 warm-ups; inputs
-    are resident, one buffer set), kernel counts, algorithmic and planned bytes."""
+    are resident, one buffer set), kernel counts, algorithmic and planned bytes; then every output of every fused
+    run is scored against its op-by-op counterpart in ONE batched scoring call."""
     from paper_2605_29357_amd.torch_util import TORCH_DT, HipEvent
     from workloads import dags
 
@@ -356,20 +362,45 @@ def cfg5_table(torch, pf, Runner, alloc_outputs, stream):
         torch.cuda.synchronize()
         return float(np.median([a.elapsed_us(b) for a, b in evs]))
 
-    rows = []
+    rows, kept, pairs = [], [], []
     for k in range(dags.N_DAGS):
         w = dags.cfg5(k, with_inputs=False)
         f = Runner(w, fuse=True, upload=False)
         u = Runner(w, fuse=False, intermediates_f32=False, upload=False)
         f.d_in = u.d_in = [(torch.rand(tuple(s), device="cuda") + 0.5).to(TORCH_DT[dt]) for dt, s in zip(w.input_dtypes, w.input_shapes)]
-        outs = alloc_outputs(w, poison=False)
+        outs, uouts = alloc_outputs(w, poison=False), alloc_outputs(w, poison=False)
         rows.append({"dag": w.name, "bytes": w.algorithmic_bytes, "planned_bytes": f.info["planned_bytes"],
-                     "fused_us": med_time(f, outs), "unfused_us": med_time(u, outs), "fused_kernels": f.info["n_kernels"],
+                     "fused_us": med_time(f, outs), "unfused_us": med_time(u, uouts), "fused_kernels": f.info["n_kernels"],
                      "unfused_kernels": u.info["n_kernels"], "templates": [g["template"] for g in f.exe.groups()]})
-        del f, u, outs
+        # every output of the fused run against the op-by-op one: the pairs of one batched scoring call
+        for o, uo, dt in zip(outs, uouts, w.output_dtypes):
+            p = pf.Pair()
+            p.d_cand, p.d_ref, p.n = o.data_ptr(), uo.data_ptr(), o.numel()
+            p.cand_dtype = p.ref_dtype = pf.DTYPES[dt]
+            p.rtol, p.atol, p.equal_nan = configs_tol(dt) + (0,)
+            pairs.append(p)
+        kept.append((outs, uouts))
+        del f, u
+    res = torch.zeros(len(pairs) * ctypes.sizeof(pf.ScoreResult), dtype=torch.uint8, device="cuda")
+    sws = torch.empty(max(pf.score_workspace_bytes(len(pairs)), 256), dtype=torch.uint8, device="cuda")
+    ts = []
+    for i in range(8):
+        a, b = HipEvent(), HipEvent()
+        a.record(stream)
+        pf.score(pairs, res.data_ptr(), sws.data_ptr(), sws.numel(), stream.cuda_stream)
+        b.record(stream)
+        torch.cuda.synchronize()
+        ts.append(a.elapsed_us(b))
+    raw = res.cpu().numpy().tobytes()
+    results = [pf.ScoreResult.from_buffer_copy(raw, i * ctypes.sizeof(pf.ScoreResult)) for i in range(len(pairs))]
+    pair_bytes = sum(2 * p.n * (4 if p.cand_dtype == pf.DTYPES["f32"] else 2) for p in pairs)
+    scoring = {"pairs": len(pairs), "bytes": pair_bytes, "us": float(np.median(ts[2:])),
+               "GBps": pair_bytes / float(np.median(ts[2:])) / 1e3, "pairs_allclose": int(sum(r.allclose for r in results)),
+               "elements": int(sum(p.n for p in pairs))}
+    del kept
     tf, tu = sum(r["fused_us"] for r in rows), sum(r["unfused_us"] for r in rows)
     big = [r for r in rows if r["bytes"] >= 16e6 and r["fused_kernels"] == 1]
-    return {"dags": rows,
+    return {"dags": rows, "scoring": scoring,
             "summary": {"fused_us_total": tf, "unfused_us_total": tu, "speedup_total": tu / tf,
                         "geomean_speedup": float(np.exp(np.mean([np.log(r["unfused_us"] / r["fused_us"]) for r in rows]))),
                         "fused_kernels": sum(r["fused_kernels"] for r in rows), "unfused_kernels": sum(r["unfused_kernels"] for r in rows),

@@ -35,13 +35,15 @@ inline bool score_combo_supported(int cd, int rd) {
 constexpr int kScoreSlots = 64;   // partial result slots per pair
 constexpr int kScoreSeedParts = 16;   // sampled maxima per pair (two doubles each), folded by every reader
 
-// up to kBatch descriptors passed by value to the upload kernel
-constexpr int kPairBatch = 24;
+// up to kPairBatch descriptors passed by value to the staging kernel (kernel arguments are limited to 4 KB)
+constexpr int kPairBatch = 48;
 struct PairBatch {
     PairDev pairs[kPairBatch];
     unsigned long long start[kPairBatch + 1];   // first block of each pair (+ total when last)
     int first, count, last, pad_;
 };
+
+static_assert(sizeof(PairBatch) + 64 <= 4096, "a batch of descriptors and the other kernel arguments must fit in 4 KB");
 
 // tolerances of every ladder level, per candidate dtype (indexed by pf_dtype; the f64 row is unused)
 struct LadderTable {
