@@ -593,7 +593,14 @@ __device__ __forceinline__ void ladder_one(typename Elem<CD>::raw ra, typename E
     for (int k = 0; k < PF_LADDER_LEVELS; ++k) cnt[k] += !(fin & (d <= __dadd_rn(at[k], __dmul_rn(rt[k], ab))));
 }
 
-template <int CD, int RD>
+// FAST: both tolerances grow with the level (checked on the host), so the bound atol_k + rtol_k |b|,
+// rounded like the oracle rounds it, grows with k too (rounding is monotone): an element that passes
+// level k passes every later one.  The levels are therefore walked in order, in fp32, against bounds
+// pulled 2e-6 inwards (d <= bound: certainly passes; three vector instructions per element and level,
+// the table in scalar registers), and a wave stops at the first level all of its elements pass, after
+// one level for identical buffers.  An element within 4e-6 of a bound at some level (neither
+// "certainly passes" nor "certainly fails"), or with a NaN or an infinity, is recounted exactly in fp64.
+template <int CD, int RD, bool FAST>
 __global__ void __launch_bounds__(kBlock) ladder_kernel(const pf::PairDev* pairs, const unsigned long long* block_start, int n_pairs,
                                                         pf::LadderTable table, pf_ladder_result* slots, unsigned long long block_offset) {
     int lo = 0, hi = n_pairs;
@@ -611,13 +618,82 @@ __global__ void __launch_bounds__(kBlock) ladder_kernel(const pf::PairDev* pairs
 #pragma unroll
     for (int k = 0; k < PF_LADDER_LEVELS; ++k) cnt[k] = 0;
     const unsigned long long nvec = (end - begin) / 8;
-    for (unsigned long long v = threadIdx.x; v < nvec; v += kBlock) {
-        typename Elem<CD>::raw ra[8];
-        typename Elem<RD>::raw rb[8];
-        Elem<CD>::load8(pr.cand, begin + v * 8, ra);
-        Elem<RD>::load8(pr.ref, begin + v * 8, rb);
+    if (FAST && RD != PF_F64) {
+        constexpr int L = PF_LADDER_LEVELS;
+        float rlo[L], alo[L];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) ladder_one<CD, RD>(ra[j], rb[j], pr.equal_nan, rt, at, cnt);
+        for (int k = 0; k < L; ++k) {
+            rlo[k] = (float)(rt[k] * (1.0 - 2e-6));
+            alo[k] = (float)(at[k] * (1.0 - 2e-6));
+        }
+        // the next vector is on its way while the current one is walked
+        Vec8<CD> na;
+        Vec8<RD> nb;
+        if (threadIdx.x < nvec) {
+            na.load(pr.cand, begin + (unsigned long long)threadIdx.x * 8);
+            nb.load(pr.ref, begin + (unsigned long long)threadIdx.x * 8);
+        }
+        for (unsigned long long it = 0; it * kBlock < nvec; ++it) {
+            const unsigned long long v = it * kBlock + threadIdx.x;
+            const bool live = v < nvec;
+            const Vec8<CD> va = na;
+            const Vec8<RD> vb = nb;
+            if (v + kBlock < nvec) {
+                na.load(pr.cand, begin + (v + kBlock) * 8);
+                nb.load(pr.ref, begin + (v + kBlock) * 8);
+            }
+            // four elements at a time: their differences, references and scaled differences stay in registers
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                float d[4], ab[4], u[4];
+                bool redo[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float a = va.f32(half * 4 + j), b = vb.f32(half * 4 + j);
+                    d[j] = fabsf(a - b);
+                    ab[j] = fabsf(b);
+                    // NaN, infinite difference or infinite reference: exact path only (and nothing counted here)
+                    redo[j] = live & !((d[j] < __builtin_inff()) & (ab[j] < __builtin_inff()));
+                    if (redo[j] | !live) { d[j] = 0.0f; ab[j] = 0.0f; }
+                    u[j] = d[j] * (1.0f - 4.1e-6f);    // d > bound >= u: the outward bound (2e-6 the other way) may still hold d
+                }
+                int levels = 0;                         // levels walked by this wave
+#pragma unroll
+                for (int k = 0; k < L; ++k) {
+                    bool any_fail = false;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float bound = __builtin_fmaf(rlo[k], ab[j], alo[k]);
+                        const bool fail = d[j] > bound;
+                        cnt[k] += fail;
+                        redo[j] |= fail & (u[j] <= bound);
+                        any_fail |= fail;
+                    }
+                    levels = k + 1;
+                    if (!__any(any_fail)) break;
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    if (!__any(redo[j])) continue;
+                    if (redo[j]) {
+                        // take back what the walk counted for this element, count it exactly
+#pragma unroll
+                        for (int k = 0; k < L; ++k)
+                            if (k < levels) cnt[k] -= d[j] > __builtin_fmaf(rlo[k], ab[j], alo[k]);
+                        ladder_one<CD, RD>(va.raw(half * 4 + j), vb.raw(half * 4 + j), pr.equal_nan, rt, at, cnt);
+                    }
+                }
+            }
+        }
+    } else {
+        for (unsigned long long v = threadIdx.x; v < nvec; v += kBlock) {
+            typename Elem<CD>::raw ra[8];
+            typename Elem<RD>::raw rb[8];
+            Elem<CD>::load8(pr.cand, begin + v * 8, ra);
+            Elem<RD>::load8(pr.ref, begin + v * 8, rb);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) ladder_one<CD, RD>(ra[j], rb[j], pr.equal_nan, rt, at, cnt);
+        }
     }
     for (unsigned long long i = begin + nvec * 8 + threadIdx.x; i < end; i += kBlock)
         ladder_one<CD, RD>(Elem<CD>::load1(pr.cand, i), Elem<RD>::load1(pr.ref, i), pr.equal_nan, rt, at, cnt);
@@ -700,10 +776,24 @@ hipError_t launch_ladder(const PairDev* d_pairs, const unsigned long long* d_blo
                          const LadderTable& table, pf_ladder_result* d_results, pf_ladder_result* d_slots, hipStream_t stream) {
     const int nbs = (n_pairs * kSlots + kBlock - 1) / kBlock;
     hipLaunchKernelGGL(ladder_init_kernel, dim3(nbs), dim3(kBlock), 0, stream, n_pairs, d_slots);
+    // the screened kernel needs tolerances that grow with the level and that fp32 represents comfortably
+    bool fast[4];
+    for (int dt = 0; dt < 4; ++dt) {
+        fast[dt] = true;
+        for (int k = 0; k < PF_LADDER_LEVELS; ++k) {
+            if (!(table.rtol[dt][k] >= 1e-30 && table.atol[dt][k] >= 1e-30 && table.rtol[dt][k] <= 1e30 && table.atol[dt][k] <= 1e30)) fast[dt] = false;
+            if (k > 0 && !(table.rtol[dt][k] >= table.rtol[dt][k - 1] && table.atol[dt][k] >= table.atol[dt][k - 1])) fast[dt] = false;
+        }
+    }
 #define PF_LAUNCH(CD, RD)                                                                                                    \
-    if (ranges.count[CD][RD])                                                                                                \
-        hipLaunchKernelGGL((ladder_kernel<CD, RD>), dim3((unsigned)ranges.count[CD][RD]), dim3(kBlock), 0, stream, d_pairs,    \
-                           d_block_start, n_pairs, table, d_slots, ranges.first[CD][RD]);
+    if (ranges.count[CD][RD]) {                                                                                              \
+        if (fast[CD])                                                                                                        \
+            hipLaunchKernelGGL((ladder_kernel<CD, RD, true>), dim3((unsigned)ranges.count[CD][RD]), dim3(kBlock), 0, stream,   \
+                               d_pairs, d_block_start, n_pairs, table, d_slots, ranges.first[CD][RD]);                       \
+        else                                                                                                                 \
+            hipLaunchKernelGGL((ladder_kernel<CD, RD, false>), dim3((unsigned)ranges.count[CD][RD]), dim3(kBlock), 0, stream,  \
+                               d_pairs, d_block_start, n_pairs, table, d_slots, ranges.first[CD][RD]);                       \
+    }
     PF_LAUNCH(PF_F32, PF_F32)
     PF_LAUNCH(PF_F32, PF_BF16)
     PF_LAUNCH(PF_F32, PF_F64)
