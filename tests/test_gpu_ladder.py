@@ -48,3 +48,32 @@ def test_ladder_counts_match_the_oracle():
         assert g[0] == w[0] and g[1] == w[1], (n, cd, rd, g, w)
     # the counts really do differ between levels
     assert len(set(wants[6][1])) > 5
+
+
+@pytest.mark.parametrize("cd,rd", [("f32", "f32"), ("bf16", "f32"), ("f32", "bf16"), ("f16", "f32")])
+def test_ladder_elements_at_the_edge_of_a_level_are_counted_exactly(cd, rd):
+    """Differences placed within a few ulp (and within a few 1e-6) of atol_k + rtol_k |b| for every level:
+    what a screen in fp32 cannot settle has to come out of the exact path like the oracle's count."""
+    from oracle.score import score_pair
+    g = np.random.default_rng(7)
+    n_per = 3000
+    refs, cands = [], []
+    for t in metric.LADDER:
+        rt, at = metric.tolerance(cd, t)
+        b = g.normal(size=n_per) * 10.0 ** g.uniform(-3, 3, n_per)
+        if rd == "bf16":       # the reference as it will be stored, so that the bound below is the one the scorer sees
+            b = (rng.round_to_bf16_bits(b).astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+        else:
+            b = b.astype(np.float32).astype(np.float64)
+        bound = at + rt * np.abs(b)
+        eps = g.choice([-4e-6, -2e-6, -3e-7, -6e-8, 0.0, 6e-8, 3e-7, 2e-6, 4e-6], n_per)
+        a = b + g.choice([-1.0, 1.0], n_per) * bound * (1.0 + eps)
+        refs.append(b)
+        cands.append(a)
+    ref64, cand64 = np.concatenate(refs), np.concatenate(cands)
+    store = {"f32": lambda x: x.astype(np.float32), "bf16": rng.round_to_bf16_bits, "f16": rng.round_to_f16_bits}
+    c, r = store[cd](cand64), store[rd](ref64)
+    want = [score_pair(c, cd, r, rd, *metric.tolerance(cd, t), False)["n_viol"] for t in metric.LADDER]
+    got = ladder_on_gpu([(to_device(c, cd), cd, to_device(r, rd), rd, False)])[0]
+    assert got[0] == c.size and got[1] == want, (got, want)
+    assert 0 < want[-1] < want[0] < c.size
