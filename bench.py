@@ -244,7 +244,58 @@ def per_config_table(torch, pf, configs, Runner, alloc_outputs, stream, w3, fuse
     # the paper's Case 1 at its D96 route (roll + slice + add + LayerNorm, two outputs, bf16)
     table["case1_roll_slice_add_layernorm_D96"] = entry(configs.roll_slice_add_layernorm(), 40)
     table["case2_masked_mean_pooling"] = entry(configs.masked_mean_pooling(), 6)   # 6 x 101 MB
+    # launch-bound steps: op-by-op and fused execution, each followed by scoring, enqueued one call at a time and
+    # replayed from a captured HIP graph of 16 steps (wall time per step, host included)
+    for name, w in (("cfg1_add_layernorm", configs.cfg1_add_layernorm()), ("cfg2_masked_softmax", configs.cfg2_masked_softmax())):
+        table[name]["step_wall_us"] = graph_replay_step(torch, pf, configs, Runner, alloc_outputs, w)
     return table
+
+
+def graph_replay_step(torch, pf, configs, Runner, alloc_outputs, w, steps=16, reps=30):
+    """Wall-clock microseconds per (execute + score) step: eager calls against replays of a captured graph."""
+    dt = w.output_dtypes[0]
+    out = {}
+    ref = Runner(w, fuse=False, intermediates_f32=True).run()
+    for label, fuse in (("fused", True), ("op_by_op", False)):
+        r = Runner(w, fuse=fuse, intermediates_f32=False)
+        outs = alloc_outputs(w, poison=False)
+        p = pf.Pair()
+        p.d_cand, p.d_ref, p.n = outs[0].data_ptr(), ref[0].data_ptr(), outs[0].numel()
+        p.cand_dtype = p.ref_dtype = pf.DTYPES[dt]
+        p.rtol, p.atol, p.equal_nan = configs.RTOL[dt], configs.ATOL[dt], 0
+        res = torch.zeros(ctypes.sizeof(pf.ScoreResult), dtype=torch.uint8, device="cuda")
+        sws = torch.empty(max(pf.score_workspace_bytes(1), 256), dtype=torch.uint8, device="cuda")
+        side = torch.cuda.Stream()
+
+        def one(stream):
+            r.run(outs, stream=stream)
+            pf.score([p], res.data_ptr(), sws.data_ptr(), sws.numel(), stream.cuda_stream)
+
+        with torch.cuda.stream(side):
+            for _ in range(3):
+                one(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for _ in range(steps):
+                one(side)
+        times = {"eager": [], "graph": []}
+        for _ in range(reps):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            with torch.cuda.stream(side):
+                for _ in range(steps):
+                    one(side)
+            torch.cuda.synchronize()
+            times["eager"].append((time.perf_counter() - t0) * 1e6 / steps)
+            t0 = time.perf_counter()
+            graph.replay()
+            torch.cuda.synchronize()
+            times["graph"].append((time.perf_counter() - t0) * 1e6 / steps)
+        out[label] = {"kernels_per_step": r.info["n_kernels"] + 3, "eager_us": float(np.median(times["eager"])),
+                      "graph_us": float(np.median(times["graph"]))}
+        del graph
+    return out
 
 
 def _rotating(torch, r, w, alloc_outputs, min_bytes=600e6, max_sets=48):

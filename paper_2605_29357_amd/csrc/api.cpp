@@ -359,25 +359,27 @@ size_t staged_head_bytes(int n_pairs) {
 }
 
 // with_seeds: the single-level scorer, whose staging kernel also clears the slots and samples the seeds
+void check_pair(const pf_pair& p, int i) {
+    if (p.cand_dtype != PF_F32 && p.cand_dtype != PF_BF16 && p.cand_dtype != PF_F16)
+        pf::fail(PF_E_INVALID, "pair %d: candidate dtype must be f32, bf16 or f16", i);
+    if (!pf::score_combo_supported(p.cand_dtype, p.ref_dtype))
+        pf::fail(PF_E_INVALID, "pair %d: unsupported dtype combination (candidate %d, reference %d)", i, p.cand_dtype, p.ref_dtype);
+    if (p.n && (!p.d_cand || !p.d_ref)) pf::fail(PF_E_INVALID, "pair %d: NULL buffer", i);
+    if (((uintptr_t)p.d_cand | (uintptr_t)p.d_ref) & 15) pf::fail(PF_E_INVALID, "pair %d: buffers must be 16-byte aligned", i);
+    if (!(p.rtol >= 0.0) || !(p.atol >= 0.0)) pf::fail(PF_E_INVALID, "pair %d: tolerances must be >= 0", i);
+}
+
 // the seed parts of the single-level scorer follow its slots
 double* score_seeds(char* d_rest, int n_pairs) { return (double*)(d_rest + (size_t)n_pairs * pf::kScoreSlots * sizeof(pf_score_result)); }
 
-StagedPairs stage_pairs(const pf_pair* h_pairs, int n_pairs, void* d_workspace, void* stream, bool with_seeds) {
+StagedPairs stage_pairs(const pf_pair* h_pairs, int n_pairs, void* d_workspace, void* stream, bool with_seeds,
+                        const int* caller_index = nullptr) {
     StagedPairs sp;
     const size_t pairs_bytes = ((size_t)n_pairs * sizeof(pf::PairDev) + 255) / 256 * 256;
     sp.d_pairs = (pf::PairDev*)d_workspace;
     sp.d_start = (unsigned long long*)((char*)d_workspace + pairs_bytes);
     sp.d_rest = (char*)d_workspace + staged_head_bytes(n_pairs);
-    for (int i = 0; i < n_pairs; ++i) {
-        const pf_pair& p = h_pairs[i];
-        if (p.cand_dtype != PF_F32 && p.cand_dtype != PF_BF16 && p.cand_dtype != PF_F16)
-            pf::fail(PF_E_INVALID, "pair %d: candidate dtype must be f32, bf16 or f16", i);
-        if (!pf::score_combo_supported(p.cand_dtype, p.ref_dtype))
-            pf::fail(PF_E_INVALID, "pair %d: unsupported dtype combination (candidate %d, reference %d)", i, p.cand_dtype, p.ref_dtype);
-        if (p.n && (!p.d_cand || !p.d_ref)) pf::fail(PF_E_INVALID, "pair %d: NULL buffer", i);
-        if (((uintptr_t)p.d_cand | (uintptr_t)p.d_ref) & 15) pf::fail(PF_E_INVALID, "pair %d: buffers must be 16-byte aligned", i);
-        if (!(p.rtol >= 0.0) || !(p.atol >= 0.0)) pf::fail(PF_E_INVALID, "pair %d: tolerances must be >= 0", i);
-    }
+    for (int i = 0; i < n_pairs; ++i) check_pair(h_pairs[i], caller_index ? caller_index[i] : i);
     std::vector<int> order(n_pairs);
     for (int i = 0; i < n_pairs; ++i) order[i] = i;
     auto combo = [&](int i) { return h_pairs[i].cand_dtype * 4 + h_pairs[i].ref_dtype; };
@@ -400,7 +402,7 @@ StagedPairs stage_pairs(const pf_pair* h_pairs, int n_pairs, void* d_workspace, 
             b.pairs[k].rtol = p.rtol;
             b.pairs[k].atol = p.atol;
             b.pairs[k].equal_nan = p.equal_nan;
-            b.pairs[k].orig = order[first + k];
+            b.pairs[k].orig = caller_index ? caller_index[order[first + k]] : order[first + k];
             b.start[k] = total;
             const unsigned long long chunk = pf::score_chunk_elems(p.n);
             b.pairs[k].chunk = chunk;
@@ -437,10 +439,52 @@ pf_status pf_score(const pf_pair* h_pairs, int n_pairs, pf_score_result* d_resul
     return guarded([&] {
         if (n_pairs == 0) return;
         check_score_args(h_pairs, n_pairs, d_results, d_workspace, workspace_bytes, pf_score_workspace_bytes(n_pairs));
-        StagedPairs sp = stage_pairs(h_pairs, n_pairs, d_workspace, stream, true);
-        hipError_t err = pf::launch_score(sp.d_pairs, sp.d_start, n_pairs, sp.ranges, d_results, (pf_score_result*)sp.d_rest,
-                                          score_seeds(sp.d_rest, n_pairs), (hipStream_t)stream);
-        if (err != hipSuccess) pf::fail(PF_E_RUNTIME, "score launch failed: %s", hipGetErrorString(err));
+        // Small pairs take one workgroup each and a single launch per dtype combination; the others go
+        // through staging, the block-per-chunk kernels and the final fold.
+        for (int i = 0; i < n_pairs; ++i) check_pair(h_pairs[i], i);      // nothing is enqueued for an invalid batch
+        std::vector<pf_pair> big;
+        std::vector<int> big_index;
+        std::vector<int> small[4][4];
+        const unsigned long long small_max = pf::score_small_pair_elems();
+        for (int i = 0; i < n_pairs; ++i) {
+            const pf_pair& p = h_pairs[i];
+            const bool dt_ok = p.cand_dtype >= 0 && p.cand_dtype <= PF_F16 && p.ref_dtype >= 0 && p.ref_dtype <= PF_F16;
+            if (dt_ok && p.n <= small_max && pf::score_combo_supported(p.cand_dtype, p.ref_dtype)) small[p.cand_dtype][p.ref_dtype].push_back(i);
+            else {
+                big.push_back(p);
+                big_index.push_back(i);
+            }
+        }
+        if (!big.empty()) {
+            StagedPairs sp = stage_pairs(big.data(), (int)big.size(), d_workspace, stream, true, big_index.data());
+            hipError_t err = pf::launch_score(sp.d_pairs, sp.d_start, (int)big.size(), sp.ranges, d_results, (pf_score_result*)sp.d_rest,
+                                              score_seeds(sp.d_rest, (int)big.size()), (hipStream_t)stream);
+            if (err != hipSuccess) pf::fail(PF_E_RUNTIME, "score launch failed: %s", hipGetErrorString(err));
+        }
+        for (int cd = 0; cd < 4; ++cd)
+            for (int rd = 0; rd < 4; ++rd) {
+                const std::vector<int>& idx = small[cd][rd];
+                for (size_t first = 0; first < idx.size(); first += pf::kPairBatch) {
+                    pf::PairBatch b;
+                    memset(&b, 0, sizeof b);
+                    b.count = (int)std::min<size_t>(pf::kPairBatch, idx.size() - first);
+                    for (int k = 0; k < b.count; ++k) {
+                        const pf_pair& p = h_pairs[idx[first + k]];
+                        b.pairs[k].cand = p.d_cand;
+                        b.pairs[k].ref = p.d_ref;
+                        b.pairs[k].n = p.n;
+                        b.pairs[k].cand_dtype = p.cand_dtype;
+                        b.pairs[k].ref_dtype = p.ref_dtype;
+                        b.pairs[k].rtol = p.rtol;
+                        b.pairs[k].atol = p.atol;
+                        b.pairs[k].equal_nan = p.equal_nan;
+                        b.pairs[k].orig = idx[first + k];
+                        b.pairs[k].chunk = pf::score_chunk_elems(p.n);
+                    }
+                    hipError_t err = pf::launch_score_small(b, cd, rd, d_results, (hipStream_t)stream);
+                    if (err != hipSuccess) pf::fail(PF_E_RUNTIME, "score launch failed: %s", hipGetErrorString(err));
+                }
+            }
     });
 }
 

@@ -156,7 +156,8 @@ template <int CD, int RD>
 __device__ __forceinline__ void score_chunk(const pf::PairDev& pr, unsigned long long begin, unsigned long long end, Acc& acc) {
     // vectors of 8 elements, lanes interleaved so that a wave reads contiguous memory
     const unsigned long long nvec = (end - begin) / 8;
-    for (unsigned long long v = threadIdx.x; v < nvec; v += kBlock) {
+    const unsigned int nthr = blockDim.x;          // 256 in the main kernel, 1024 in the one-workgroup-per-pair kernel
+    for (unsigned long long v = threadIdx.x; v < nvec; v += nthr) {
         typename Elem<CD>::raw ra[8];
         typename Elem<RD>::raw rb[8];
         Elem<CD>::load8(pr.cand, begin + v * 8, ra);
@@ -164,7 +165,7 @@ __device__ __forceinline__ void score_chunk(const pf::PairDev& pr, unsigned long
 #pragma unroll
         for (int j = 0; j < 8; ++j) score_one<CD, RD>(ra[j], rb[j], pr, acc);
     }
-    for (unsigned long long i = begin + nvec * 8 + threadIdx.x; i < end; i += kBlock)
+    for (unsigned long long i = begin + nvec * 8 + threadIdx.x; i < end; i += nthr)
         score_one<CD, RD>(Elem<CD>::load1(pr.cand, i), Elem<RD>::load1(pr.ref, i), pr, acc);
 }
 
@@ -255,7 +256,8 @@ __device__ __forceinline__ void score_chunk_fast(const pf::PairDev& pr, unsigned
     refresh();
     unsigned int xor_acc = 0;
     const unsigned long long nvec = (end - begin) / 8;
-    const unsigned long long iters = (nvec + kBlock - 1) / kBlock;
+    const unsigned int nthr = blockDim.x;
+    const unsigned long long iters = (nvec + nthr - 1) / nthr;
     // the next vector is already on its way while the current one is screened (two vectors ahead
     // cost registers, hence resident waves, and measured 7% slower)
     Vec8<CD> na;
@@ -265,13 +267,13 @@ __device__ __forceinline__ void score_chunk_fast(const pf::PairDev& pr, unsigned
         nb.load(pr.ref, begin + (unsigned long long)threadIdx.x * 8);
     }
     for (unsigned long long it = 0; it < iters; ++it) {
-        const unsigned long long v = it * kBlock + threadIdx.x;
+        const unsigned long long v = it * nthr + threadIdx.x;
         const bool live = v < nvec;
         const Vec8<CD> va = na;
         const Vec8<RD> vb = nb;
-        if (v + kBlock < nvec) {
-            na.load(pr.cand, begin + (v + kBlock) * 8);
-            nb.load(pr.ref, begin + (v + kBlock) * 8);
+        if (v + nthr < nvec) {
+            na.load(pr.cand, begin + (v + nthr) * 8);
+            nb.load(pr.ref, begin + (v + nthr) * 8);
         }
         unsigned int fmask = 0;          // bit j: element j needs the exact path
         unsigned int nv = 0;
@@ -354,7 +356,7 @@ __device__ __forceinline__ void score_chunk_fast(const pf::PairDev& pr, unsigned
         }
     }
     if (CD == RD) acc.bitdiff += xor_acc ? 1u : 0u;
-    for (unsigned long long i = begin + nvec * 8 + threadIdx.x; i < end; i += kBlock) {
+    for (unsigned long long i = begin + nvec * 8 + threadIdx.x; i < end; i += nthr) {
         const typename Elem<CD>::raw ea = Elem<CD>::load1(pr.cand, i);
         const typename Elem<RD>::raw eb = Elem<RD>::load1(pr.ref, i);
         if (CD == RD) acc.bitdiff += ea != eb;
@@ -465,6 +467,42 @@ __device__ __forceinline__ void load_seed(const double* __restrict__ seeds, int 
     }
 }
 
+// Block reduction; true on the one thread that holds the block's totals afterwards.  On the screened path
+// a lane has something to report only if it went through the exact path, so few lanes do: they fold
+// their values into LDS with atomics (one round trip) instead of every wave walking a chain of ~100
+// dependent cross-lane shuffles, which used to make up a third of a wave's lifetime.  Waves in which many
+// lanes report reduce by shuffles first.
+template <int CD, int RD>
+__device__ __forceinline__ bool block_fold(Acc& acc, double& ma, double& mr, unsigned long long* t /* [6] */) {
+    if (RD == PF_F64) acc.max_rel = fmax(acc.max_rel, __ddiv_rn(acc.keep_d, acc.keep_b));   // only score_one defers a division
+    __shared__ unsigned long long s_red[8];      // max_abs bits, max_rel bits, six counts
+    const int lane = threadIdx.x & 63;
+    if (threadIdx.x < 8) s_red[threadIdx.x] = 0;
+    __syncthreads();
+    double wa = acc.max_abs, wr = acc.max_rel;
+    unsigned long long c[6] = {acc.n_viol, acc.bitdiff, acc.nan_c, acc.nan_r, acc.inf_c, acc.inf_r};
+    if (CD == RD) c[1] = (__any(acc.bitdiff != 0) && lane == 0) ? 1u : 0u;      // only "any difference" matters
+    const bool mine = (wa > 0.0) | (wr > 0.0) | ((c[0] | c[2] | c[3] | c[4] | c[5]) != 0);
+    if (__popcll(__ballot(mine)) > 16) {
+        wa = wave_max(wa); wr = wave_max(wr);
+#pragma unroll
+        for (int k = 0; k < 6; ++k) if (k != 1) c[k] = wave_sum(c[k]);
+        if (lane != 0) { wa = 0.0; wr = 0.0; c[0] = c[2] = c[3] = c[4] = c[5] = 0; }
+    }
+    // errors are >= 0 and never NaN, so their bit patterns order like the values
+    if (wa > 0.0) atomicMax(&s_red[0], (unsigned long long)__double_as_longlong(wa));
+    if (wr > 0.0) atomicMax(&s_red[1], (unsigned long long)__double_as_longlong(wr));
+#pragma unroll
+    for (int k = 0; k < 6; ++k) if (c[k]) atomicAdd(&s_red[2 + k], c[k]);
+    __syncthreads();
+    if (threadIdx.x != 0) return false;
+    ma = __longlong_as_double((long long)s_red[0]);
+    mr = __longlong_as_double((long long)s_red[1]);
+#pragma unroll
+    for (int k = 0; k < 6; ++k) t[k] = s_red[2 + k];
+    return true;
+}
+
 // One instantiation per (candidate dtype, reference dtype): the host orders the
 // pairs by dtype combination, so each instantiation owns a contiguous range of
 // blocks and is register-allocated for its own path only.
@@ -491,36 +529,9 @@ __global__ void __launch_bounds__(kBlock) score_kernel(const pf::PairDev* __rest
         load_seed(seeds, lo, seed_abs, seed_rel);
         score_chunk_fast<CD, RD>(pr, begin, end, acc, seed_abs, seed_rel);
     }
-    if (RD == PF_F64) acc.max_rel = fmax(acc.max_rel, __ddiv_rn(acc.keep_d, acc.keep_b));   // only score_one defers a division
-    // Block reduction.  On the screened path a lane has something to report only if it went through
-    // the exact path, so few lanes do: they fold their values into LDS with atomics (one round trip)
-    // instead of every wave walking a chain of ~100 dependent cross-lane shuffles, which used to make
-    // up a third of a wave's lifetime.  Waves in which many lanes report reduce by shuffles first.
-    __shared__ unsigned long long s_red[8];      // max_abs bits, max_rel bits, six counts
-    const int lane = threadIdx.x & 63;
-    if (threadIdx.x < 8) s_red[threadIdx.x] = 0;
-    __syncthreads();
-    double wa = acc.max_abs, wr = acc.max_rel;
-    unsigned long long c[6] = {acc.n_viol, acc.bitdiff, acc.nan_c, acc.nan_r, acc.inf_c, acc.inf_r};
-    if (CD == RD) c[1] = (__any(acc.bitdiff != 0) && lane == 0) ? 1u : 0u;      // only "any difference" matters
-    const bool mine = (wa > 0.0) | (wr > 0.0) | ((c[0] | c[2] | c[3] | c[4] | c[5]) != 0);
-    if (__popcll(__ballot(mine)) > 16) {
-        wa = wave_max(wa); wr = wave_max(wr);
-#pragma unroll
-        for (int k = 0; k < 6; ++k) if (k != 1) c[k] = wave_sum(c[k]);
-        if (lane != 0) { wa = 0.0; wr = 0.0; c[0] = c[2] = c[3] = c[4] = c[5] = 0; }
-    }
-    // errors are >= 0 and never NaN, so their bit patterns order like the values
-    if (wa > 0.0) atomicMax(&s_red[0], (unsigned long long)__double_as_longlong(wa));
-    if (wr > 0.0) atomicMax(&s_red[1], (unsigned long long)__double_as_longlong(wr));
-#pragma unroll
-    for (int k = 0; k < 6; ++k) if (c[k]) atomicAdd(&s_red[2 + k], c[k]);
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const double ma = __longlong_as_double((long long)s_red[0]), mr = __longlong_as_double((long long)s_red[1]);
-        unsigned long long t[6];
-#pragma unroll
-        for (int k = 0; k < 6; ++k) t[k] = s_red[2 + k];
+    double ma, mr;
+    unsigned long long t[6];
+    if (block_fold<CD, RD>(acc, ma, mr, t)) {
         // one of kSlots partial results of this pair; the final kernel folds them
         pf_score_result* r = my_slot;
         // nothing at the end of a workgroup waits for memory: no value is read back
@@ -532,6 +543,33 @@ __global__ void __launch_bounds__(kBlock) score_kernel(const pf::PairDev* __rest
         if (t[3]) atomicAdd((unsigned long long*)&r->nan_ref, t[3]);
         if (t[4]) atomicAdd((unsigned long long*)&r->inf_cand, t[4]);
         if (t[5]) atomicAdd((unsigned long long*)&r->inf_ref, t[5]);
+    }
+}
+
+// Pairs of at most kSmallPair elements: one workgroup of 1024 lanes scores the whole pair and writes
+// its result, in a single launch for up to kPairBatch pairs (descriptors arrive as kernel arguments).
+// No slots, no seeds, no second kernel: such a pair costs one kernel (~4 us) instead of three, which
+// is what a launch-bound evaluation of small subgraphs is made of.
+constexpr int kSmallBlock = 1024;
+constexpr unsigned long long kSmallPair = 8192;     // one vector of eight elements per lane
+template <int CD, int RD>
+__global__ void __launch_bounds__(kSmallBlock) score_small_kernel(pf::PairBatch batch, pf_score_result* res) {
+    if ((int)blockIdx.x >= batch.count) return;
+    const pf::PairDev pr = batch.pairs[blockIdx.x];
+    Acc acc;
+    // at most eight elements per lane: evaluating each one exactly is cheaper than screening from a zero threshold
+    score_chunk<CD, RD>(pr, 0, pr.n, acc);
+    acc.max_rel = fmax(acc.max_rel, __ddiv_rn(acc.keep_d, acc.keep_b));      // the division score_one defers
+    double ma, mr;
+    unsigned long long t[6];
+    if (block_fold<CD, RD>(acc, ma, mr, t)) {
+        pf_score_result r;
+        r.n = pr.n;
+        r.max_abs = ma; r.max_rel = mr; r.n_viol = t[0]; r.reserved_ = t[1];
+        r.nan_cand = t[2]; r.nan_ref = t[3]; r.inf_cand = t[4]; r.inf_ref = t[5];
+        r.allclose = t[0] == 0 ? 1u : 0u;
+        r.bit_identical = (CD == RD && t[1] == 0) ? 1u : 0u;
+        res[pr.orig] = r;
     }
 }
 
@@ -748,6 +786,26 @@ hipError_t launch_score_stage(const PairBatch& batch, PairDev* d_pairs, unsigned
                               double* d_seeds, hipStream_t stream) {
     hipLaunchKernelGGL(score_stage_kernel, dim3(batch.count * kSeedParts), dim3(kSeedBlock), 0, stream, batch, d_pairs, d_block_start,
                        d_slots, d_seeds);
+    return hipGetLastError();
+}
+
+unsigned long long score_small_pair_elems() { return kSmallPair; }
+
+hipError_t launch_score_small(const PairBatch& batch, int cd, int rd, pf_score_result* d_results, hipStream_t stream) {
+#define PF_SMALL(CD, RD)                                                                                                     \
+    if (cd == CD && rd == RD)                                                                                                \
+        hipLaunchKernelGGL((score_small_kernel<CD, RD>), dim3(batch.count), dim3(kSmallBlock), 0, stream, batch, d_results);
+    PF_SMALL(PF_F32, PF_F32)
+    PF_SMALL(PF_F32, PF_BF16)
+    PF_SMALL(PF_F32, PF_F64)
+    PF_SMALL(PF_BF16, PF_F32)
+    PF_SMALL(PF_BF16, PF_BF16)
+    PF_SMALL(PF_BF16, PF_F64)
+    PF_SMALL(PF_F32, PF_F16)
+    PF_SMALL(PF_F16, PF_F32)
+    PF_SMALL(PF_F16, PF_F16)
+    PF_SMALL(PF_F16, PF_F64)
+#undef PF_SMALL
     return hipGetLastError();
 }
 

@@ -60,6 +60,9 @@ hipError_t launch_score_stage(const PairBatch& batch, PairDev* d_pairs, unsigned
                               double* d_seeds, hipStream_t stream);
 hipError_t launch_score(const PairDev* d_pairs, const unsigned long long* d_block_start, int n_pairs, const ScoreRanges& ranges,
                         pf_score_result* d_results, pf_score_result* d_slots, const double* d_seeds, hipStream_t stream);
+// pairs of at most score_small_pair_elems() elements: one workgroup per pair, results written directly
+unsigned long long score_small_pair_elems();
+hipError_t launch_score_small(const PairBatch& batch, int cd, int rd, pf_score_result* d_results, hipStream_t stream);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
 
 }  // namespace pf
