@@ -372,8 +372,13 @@ void check_pair(const pf_pair& p, int i) {
 // the seed parts of the single-level scorer follow its slots
 double* score_seeds(char* d_rest, int n_pairs) { return (double*)(d_rest + (size_t)n_pairs * pf::kScoreSlots * sizeof(pf_score_result)); }
 
-StagedPairs stage_pairs(const pf_pair* h_pairs, int n_pairs, void* d_workspace, void* stream, bool with_seeds,
-                        const int* caller_index = nullptr) {
+// mode 0: descriptors uploaded (the ladder); 1: uploaded, slots cleared, seeds sampled (the scorer);
+// 2: nothing launched, the single batch is handed back to the caller (a scoring call of few mid-size pairs)
+StagedPairs stage_pairs(const pf_pair* h_pairs, int n_pairs, void* d_workspace, void* stream, int mode,
+                        const int* caller_index = nullptr, pf::PairBatch* direct = nullptr) {
+    // the chunk follows the whole call: what counts is how many workgroups the call has, not each pair
+    unsigned long long call_elems = 0;
+    for (int i = 0; i < n_pairs; ++i) call_elems += h_pairs[i].n;
     StagedPairs sp;
     const size_t pairs_bytes = ((size_t)n_pairs * sizeof(pf::PairDev) + 255) / 256 * 256;
     sp.d_pairs = (pf::PairDev*)d_workspace;
@@ -404,7 +409,9 @@ StagedPairs stage_pairs(const pf_pair* h_pairs, int n_pairs, void* d_workspace, 
             b.pairs[k].equal_nan = p.equal_nan;
             b.pairs[k].orig = caller_index ? caller_index[order[first + k]] : order[first + k];
             b.start[k] = total;
-            const unsigned long long chunk = pf::score_chunk_elems(p.n);
+            // unstaged calls are latency-bound: as many workgroups as the pair has slots, one vector per lane or more
+            unsigned long long chunk = pf::score_chunk_elems(call_elems);
+            if (mode == 2) chunk = std::max<unsigned long long>(2048, ((p.n + pf::kScoreSlots - 1) / pf::kScoreSlots + 2047) / 2048 * 2048);
             b.pairs[k].chunk = chunk;
             const unsigned long long nb = (p.n + chunk - 1) / chunk;
             if (sp.ranges.count[p.cand_dtype][p.ref_dtype] == 0) sp.ranges.first[p.cand_dtype][p.ref_dtype] = total;
@@ -413,9 +420,13 @@ StagedPairs stage_pairs(const pf_pair* h_pairs, int n_pairs, void* d_workspace, 
         }
         b.start[b.count] = total;
         if (total >= (1ull << 31)) pf::fail(PF_E_INVALID, "too many elements for one scoring call");
-        hipError_t err = with_seeds ? pf::launch_score_stage(b, sp.d_pairs, sp.d_start, (pf_score_result*)sp.d_rest,
-                                                             score_seeds(sp.d_rest, n_pairs), (hipStream_t)stream)
-                                    : pf::launch_score_upload(b, sp.d_pairs, sp.d_start, (hipStream_t)stream);
+        if (mode == 2) {
+            *direct = b;
+            continue;
+        }
+        hipError_t err = mode == 1 ? pf::launch_score_stage(b, sp.d_pairs, sp.d_start, (pf_score_result*)sp.d_rest,
+                                                            score_seeds(sp.d_rest, n_pairs), (hipStream_t)stream)
+                                   : pf::launch_score_upload(b, sp.d_pairs, sp.d_start, (hipStream_t)stream);
         if (err != hipSuccess) pf::fail(PF_E_RUNTIME, "descriptor upload failed: %s", hipGetErrorString(err));
     }
     return sp;
@@ -455,8 +466,19 @@ pf_status pf_score(const pf_pair* h_pairs, int n_pairs, pf_score_result* d_resul
                 big_index.push_back(i);
             }
         }
-        if (!big.empty()) {
-            StagedPairs sp = stage_pairs(big.data(), (int)big.size(), d_workspace, stream, true, big_index.data());
+        // Few pairs of at most 64 chunks each need no staging launch: their descriptors travel as kernel
+        // arguments, every workgroup stores its partial result in a slot of its own and the fold reads
+        // only the slots that were written (two launches per call instead of three).
+        bool direct_ok = !big.empty() && (int)big.size() <= pf::kPairBatch;
+        for (auto& p : big)
+            if (p.n > (uint64_t)pf::kScoreSlots * 8192) direct_ok = false;       // above half a million elements the seeded path wins
+        if (direct_ok) {
+            pf::PairBatch b;
+            StagedPairs sp = stage_pairs(big.data(), (int)big.size(), d_workspace, stream, 2, big_index.data(), &b);
+            hipError_t err = pf::launch_score_direct(b, sp.ranges, d_results, (pf_score_result*)sp.d_rest, (hipStream_t)stream);
+            if (err != hipSuccess) pf::fail(PF_E_RUNTIME, "score launch failed: %s", hipGetErrorString(err));
+        } else if (!big.empty()) {
+            StagedPairs sp = stage_pairs(big.data(), (int)big.size(), d_workspace, stream, 1, big_index.data());
             hipError_t err = pf::launch_score(sp.d_pairs, sp.d_start, (int)big.size(), sp.ranges, d_results, (pf_score_result*)sp.d_rest,
                                               score_seeds(sp.d_rest, (int)big.size()), (hipStream_t)stream);
             if (err != hipSuccess) pf::fail(PF_E_RUNTIME, "score launch failed: %s", hipGetErrorString(err));
@@ -504,7 +526,7 @@ pf_status pf_score_ladder(const pf_pair* h_pairs, int n_pairs, pf_ladder_result*
     return guarded([&] {
         if (n_pairs == 0) return;
         check_score_args(h_pairs, n_pairs, d_results, d_workspace, workspace_bytes, pf_score_ladder_workspace_bytes(n_pairs));
-        StagedPairs sp = stage_pairs(h_pairs, n_pairs, d_workspace, stream, false);
+        StagedPairs sp = stage_pairs(h_pairs, n_pairs, d_workspace, stream, 0);
         pf::LadderTable table;
         memset(&table, 0, sizeof table);
         for (int dt : {(int)PF_F32, (int)PF_BF16, (int)PF_F16})

@@ -573,6 +573,77 @@ __global__ void __launch_bounds__(kSmallBlock) score_small_kernel(pf::PairBatch 
     }
 }
 
+// The same walk for a call of few mid-size pairs (at most kPairBatch pairs of at most kSlots chunks):
+// descriptors and block prefix are kernel arguments, there are no seeds (a lane's thresholds start from
+// zero and rise with its own records) and each workgroup stores its totals in a slot of its own.
+template <int CD, int RD>
+__global__ void __launch_bounds__(kBlock) score_direct_kernel(pf::PairBatch batch, pf_score_result* slots, unsigned long long block_offset) {
+    const unsigned long long bid = block_offset + blockIdx.x;
+    int lo = 0, hi = batch.count;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (batch.start[mid] <= bid) lo = mid; else hi = mid;
+    }
+    const pf::PairDev pr = batch.pairs[lo];
+    const unsigned long long begin = (bid - batch.start[lo]) * pr.chunk;
+    const unsigned long long end = begin + pr.chunk < pr.n ? begin + pr.chunk : pr.n;
+    Acc acc;
+    double seed_abs = 0.0, seed_rel = 0.0;
+    if (RD == PF_F64) {
+        score_chunk<CD, RD>(pr, begin, end, acc);
+    } else {
+        // the workgroup seeds itself: every lane evaluates one element of the chunk exactly (a run of 256
+        // consecutive elements in its middle), the largest errors become everybody's starting thresholds
+        __shared__ double s_seed[2][kBlock / 64];
+        Acc sample;
+        const unsigned long long i = begin + (end - begin) / 2 + threadIdx.x;
+        if (i < end) score_exact<CD, RD>(Elem<CD>::load1(pr.cand, i), Elem<RD>::load1(pr.ref, i), pr, sample);
+        const double wa = wave_max(sample.max_abs), wr = wave_max(sample.max_rel);
+        if ((threadIdx.x & 63) == 0) { s_seed[0][threadIdx.x >> 6] = wa; s_seed[1][threadIdx.x >> 6] = wr; }
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < kBlock / 64; ++w) { seed_abs = fmax(seed_abs, s_seed[0][w]); seed_rel = fmax(seed_rel, s_seed[1][w]); }
+        score_chunk_fast<CD, RD>(pr, begin, end, acc, seed_abs, seed_rel);
+    }
+    double ma, mr;
+    unsigned long long t[6];
+    if (block_fold<CD, RD>(acc, ma, mr, t)) {
+        // the seeds are errors of elements of this chunk (the walk lets elements that tie them pass unrecorded)
+        ma = fmax(ma, seed_abs);
+        mr = fmax(mr, seed_rel);
+        pf_score_result r;
+        r.n = end - begin;
+        r.max_abs = ma; r.max_rel = mr; r.n_viol = t[0]; r.reserved_ = t[1];
+        r.nan_cand = t[2]; r.nan_ref = t[3]; r.inf_cand = t[4]; r.inf_ref = t[5];
+        r.allclose = 0; r.bit_identical = 0;
+        slots[(size_t)lo * kSlots + (bid - batch.start[lo])] = r;
+    }
+}
+
+// One wave per pair: lane k folds the slot of chunk k, if the pair has that many chunks.
+__global__ void __launch_bounds__(64) score_direct_final_kernel(pf::PairBatch batch, pf_score_result* res, const pf_score_result* slots) {
+    const int p = blockIdx.x;
+    if (p >= batch.count) return;
+    const unsigned long long nb = batch.start[p + 1] - batch.start[p];
+    pf_score_result s;
+    s.max_abs = 0.0; s.max_rel = 0.0; s.n = 0; s.n_viol = 0; s.nan_cand = s.nan_ref = s.inf_cand = s.inf_ref = 0; s.reserved_ = 0;
+    if (threadIdx.x < nb) s = slots[(size_t)p * kSlots + threadIdx.x];
+    const double ma = wave_max(s.max_abs), mr = wave_max(s.max_rel);
+    const unsigned long long nv = wave_sum(s.n_viol), bd = wave_sum(s.reserved_);
+    const unsigned long long nc = wave_sum(s.nan_cand), nr = wave_sum(s.nan_ref);
+    const unsigned long long ic = wave_sum(s.inf_cand), ir = wave_sum(s.inf_ref);
+    if (threadIdx.x == 0) {
+        const pf::PairDev pr = batch.pairs[p];
+        pf_score_result r;
+        r.n = pr.n;
+        r.max_abs = ma; r.max_rel = mr; r.n_viol = nv; r.reserved_ = bd;
+        r.nan_cand = nc; r.nan_ref = nr; r.inf_cand = ic; r.inf_ref = ir;
+        r.allclose = nv == 0 ? 1u : 0u;
+        r.bit_identical = (pr.cand_dtype == pr.ref_dtype && bd == 0) ? 1u : 0u;
+        res[pr.orig] = r;
+    }
+}
+
 // One wave per pair: lane k folds slot k (kSlots == 64), then a wave reduction.
 __global__ void __launch_bounds__(64) score_final_kernel(const pf::PairDev* pairs, int n_pairs, pf_score_result* res,
                                                          const pf_score_result* slots, const double* seeds) {
@@ -774,8 +845,16 @@ __global__ void __launch_bounds__(256) copy_kernel(u32x4* __restrict__ dst, cons
 
 namespace pf {
 
-// Elements per workgroup (four times longer chunks for large pairs measured 4-6% slower).
-unsigned long long score_chunk_elems(unsigned long long n) { (void)n; return kChunk; }
+// Elements per workgroup, from the elements of the whole call: 16384 for large calls (four times longer
+// chunks measured 4-6% slower), fewer while that would leave the call with under 2048 workgroups, down to
+// one vector per lane: a workgroup walks its chunk one vector at a time, and a call of a few million
+// elements is bound by that latency (2 M elements: 18 us -> 15 us).
+unsigned long long score_chunk_elems(unsigned long long n) {
+    const unsigned long long step = (unsigned long long)kBlock * 8;
+    unsigned long long c = (n / 2048 + step - 1) / step * step;
+    if (c < step) c = step;
+    return c < kChunk ? c : kChunk;
+}
 
 hipError_t launch_score_upload(const PairBatch& batch, PairDev* d_pairs, unsigned long long* d_block_start, hipStream_t stream) {
     hipLaunchKernelGGL(score_upload_kernel, dim3(1), dim3(64), 0, stream, batch, d_pairs, d_block_start);
@@ -790,6 +869,27 @@ hipError_t launch_score_stage(const PairBatch& batch, PairDev* d_pairs, unsigned
 }
 
 unsigned long long score_small_pair_elems() { return kSmallPair; }
+
+hipError_t launch_score_direct(const PairBatch& batch, const ScoreRanges& ranges, pf_score_result* d_results, pf_score_result* d_slots,
+                               hipStream_t stream) {
+#define PF_LAUNCH(CD, RD)                                                                                                  \
+    if (ranges.count[CD][RD])                                                                                              \
+        hipLaunchKernelGGL((score_direct_kernel<CD, RD>), dim3((unsigned)ranges.count[CD][RD]), dim3(kBlock), 0, stream,     \
+                           batch, d_slots, ranges.first[CD][RD]);
+    PF_LAUNCH(PF_F32, PF_F32)
+    PF_LAUNCH(PF_F32, PF_BF16)
+    PF_LAUNCH(PF_F32, PF_F64)
+    PF_LAUNCH(PF_BF16, PF_F32)
+    PF_LAUNCH(PF_BF16, PF_BF16)
+    PF_LAUNCH(PF_BF16, PF_F64)
+    PF_LAUNCH(PF_F32, PF_F16)
+    PF_LAUNCH(PF_F16, PF_F32)
+    PF_LAUNCH(PF_F16, PF_F16)
+    PF_LAUNCH(PF_F16, PF_F64)
+#undef PF_LAUNCH
+    hipLaunchKernelGGL(score_direct_final_kernel, dim3(batch.count), dim3(64), 0, stream, batch, d_results, d_slots);
+    return hipGetLastError();
+}
 
 hipError_t launch_score_small(const PairBatch& batch, int cd, int rd, pf_score_result* d_results, hipStream_t stream) {
 #define PF_SMALL(CD, RD)                                                                                                     \

@@ -63,6 +63,9 @@ hipError_t launch_score(const PairDev* d_pairs, const unsigned long long* d_bloc
 // pairs of at most score_small_pair_elems() elements: one workgroup per pair, results written directly
 unsigned long long score_small_pair_elems();
 hipError_t launch_score_small(const PairBatch& batch, int cd, int rd, pf_score_result* d_results, hipStream_t stream);
+// at most kPairBatch pairs of at most kScoreSlots chunks each, descriptors as kernel arguments: main kernels + fold
+hipError_t launch_score_direct(const PairBatch& batch, const ScoreRanges& ranges, pf_score_result* d_results, pf_score_result* d_slots,
+                               hipStream_t stream);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
 
 }  // namespace pf
