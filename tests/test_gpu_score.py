@@ -152,3 +152,30 @@ def test_elements_on_the_tolerance_boundary_and_extreme_magnitudes(cd, rd):
         got = score_on_gpu(specs)
     for i, (g, w) in enumerate(zip(got, wants)):
         assert g == w, (i, g, w)
+
+
+@pytest.mark.parametrize("n_pairs", [1, 3, 48, 49])
+def test_every_route_through_the_scorer_gives_the_oracle_result(n_pairs):
+    """One workgroup per pair (up to 8192 elements), the unstaged route (a call of at most 48 pairs of up to
+    524288 elements) and the staged route, alone and mixed in one call, at the sizes where the routes change."""
+    sizes = [8192, 8193, 70001, 524288, 524289, 2048, 1, 300000, 16385, 600000]
+    combos = [("f32", "f32"), ("bf16", "bf16"), ("bf16", "f32"), ("f32", "f64"), ("f32", "bf16")]
+    specs, wants = [], []
+    for k in range(n_pairs):
+        n = sizes[k % len(sizes)] if n_pairs <= 3 else [8192, 8193, 40000, 2048, 100, 524288][k % 6]
+        cd, rd = combos[k % len(combos)]
+        rtol, atol = [(1e-5, 1e-5), (2e-2, 1e-5), (0.0, 0.0)][k % 3]
+        c, r = _pair(n, cd, rd, 900 + k, max(rtol, 1e-6), max(atol, 1e-7))
+        specs.append((to_device(c, cd), cd, to_device(r, rd), rd, rtol, atol, bool(k & 1)))
+        wants.append(oracle_score_dict(c, cd, r, rd, rtol, atol, bool(k & 1)))
+    with np.errstate(all="ignore"):
+        got = score_on_gpu(specs)
+    for k, (g, w) in enumerate(zip(got, wants)):
+        assert g == w, (k, specs[k][1], specs[k][3], specs[k][0].numel(), g, w)
+    if n_pairs == 3:
+        # the same three pairs with a large fourth one: everything beyond 8192 elements takes the staged route
+        c, r = _pair(600000, "f32", "f32", 77, 1e-5, 1e-5)
+        more = specs + [(to_device(c, "f32"), "f32", to_device(r, "f32"), "f32", 1e-5, 1e-5, False)]
+        with np.errstate(all="ignore"):
+            again = score_on_gpu(more)
+        assert again[:3] == wants and again[3] == oracle_score_dict(c, "f32", r, "f32", 1e-5, 1e-5, False)
