@@ -42,3 +42,29 @@ def test_random_dags(first):
             want = oracle_score_dict(to_host_bits(o, dt), dt, to_host_bits(u, dt), dt, configs.RTOL[dt], configs.ATOL[dt])
             assert g == want, (w.name, g, want)
         del fused, unfused, outs, uouts
+
+
+def test_random_dags_drawn_from_another_seed():
+    """Structures the committed workload never contains: the same generator with another seed, every draw the
+    oracle certifies as well conditioned (the rule the committed workload was certified with), fused, against
+    the oracle."""
+    import importlib.util
+    import os
+    spec = importlib.util.spec_from_file_location(
+        "make_cfg5_attempts", os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "make_cfg5_attempts.py"))
+    cert = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(cert)
+    checked = 0
+    for k in range(0, dags.N_DAGS, 3):
+        w = dags.draw_dag(k, 0, seed=101, max_rows=40)
+        try:
+            cert.check(w)
+        except cert.Rejected:
+            continue
+        print("seed 101 dag", k, w.name, flush=True)
+        refs = oracle_outputs(w)
+        outs = Runner(w).run()
+        torch.cuda.synchronize()
+        check_against_oracle(w, outs, refs=refs, what="seed 101 dag %d" % k)
+        checked += 1
+    assert checked >= 70
