@@ -1033,9 +1033,14 @@ struct Emit {
         // Tile edge: 64 (16 elements per lane: long contiguous runs on both sides), or 32 (4 elements per
         // lane) while 64-wide tiles would leave the chip short of waves: a small problem is bound by the
         // chain of instructions each wave runs on its own, and four times as many waves with a quarter
-        // of the work each cut that chain (heavy epilogues on 1.5 M elements: 21 us -> 7 us measured).
+        // of the work each cut that chain (heavy epilogues on 1.5 M elements: 21 us -> 16 us measured).
         int64_t t64 = L * ((R + 63) / 64) * ((C + 63) / 64);
-        const int TS = t64 < 2048 ? 32 : 64;
+        int n_compute = 0;
+        for (int id : grp.nodes) n_compute += g.nodes[id].op != PF_OP_TRANSPOSE;
+        // plain transposes of 20 MB and more run 5-25% faster with 64-wide tiles; with an epilogue of several
+        // operators the shorter instruction chain per wave still wins at four times that size
+        const int64_t few_tiles = n_compute <= 2 ? 2048 : n_compute <= 6 ? 4096 : 8192;
+        const int TS = t64 < few_tiles ? 32 : 64;
         const int TXN = TS / 4, TYN = 256 / TXN, NI = TS / TYN, EPL = NI * 4;    // lanes along a row, rows per pass, passes, elements per lane
         const int64_t tr = (R + TS - 1) / TS, tc = (C + TS - 1) / TS;
         grp.block = 256;
