@@ -1037,11 +1037,21 @@ struct Emit {
         int64_t t64 = L * ((R + 63) / 64) * ((C + 63) / 64);
         int n_compute = 0;
         for (int id : grp.nodes) n_compute += g.nodes[id].op != PF_OP_TRANSPOSE;
-        // plain transposes of 20 MB and more run 5-25% faster with 64-wide tiles; with an epilogue of several
+        // plain transposes of 5 MB and more run up to 25% faster with 64-wide tiles; with an epilogue of several
         // operators the shorter instruction chain per wave still wins at four times that size
-        const int64_t few_tiles = n_compute <= 2 ? 2048 : n_compute <= 6 ? 4096 : 8192;
+        const int64_t few_tiles = n_compute <= 1 ? 512 : n_compute <= 3 ? 2048 : n_compute <= 6 ? 4096 : 8192;
         const int TS = t64 < few_tiles ? 32 : 64;
-        const int TXN = TS / 4, TYN = 256 / TXN, NI = TS / TYN, EPL = NI * 4;    // lanes along a row, rows per pass, passes, elements per lane
+        // 16-byte accesses on both sides: four fp32 elements per lane and row, eight when every tensor of the
+        // group holds 16-bit elements (64-wide tiles only: a 32-wide tile of eight-element vectors has no
+        // whole pass of 256 lanes); 8192 x 8192 bf16 went from 4.4 to 4.7 TB/s
+        int min_item = 4;
+        for (auto& o : grp.operands) min_item = std::min(min_item, itemsize(o.dtype));
+        for (auto& st : grp.stores) min_item = std::min(min_item, itemsize(st.dtype));
+        bool all_16bit = min_item == 2;
+        for (auto& o : grp.operands) if (numel(o.shape) > 1 && itemsize(o.dtype) != 2 && o.stride[rd - 1] != 0) all_16bit = false;
+        for (auto& st : grp.stores) if (itemsize(st.dtype) != 2) all_16bit = false;
+        const int VW = (TS == 64 && all_16bit) ? 8 : 4;
+        const int TXN = TS / VW, TYN = 256 / TXN, NI = TS / TYN, EPL = NI * VW;  // lanes along a row, rows per pass, passes, elements per lane
         const int64_t tr = (R + TS - 1) / TS, tc = (C + TS - 1) / TS;
         grp.block = 256;
         // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Runs of G consecutive
@@ -1054,7 +1064,7 @@ struct Emit {
         const bool xcd_remap = tiles >= 64 && G > 1;
         const int64_t rounds = (tiles + 8 * G - 1) / (8 * G);
         grp.grid = xcd_remap ? rounds * 8 * G : tiles;
-        grp.vec = 4;
+        grp.vec = VW;
         grp.chunks_per_lane = NI;
         grp.lanes_per_row = 0;
         int n_t = 0;
@@ -1065,7 +1075,7 @@ struct Emit {
         signature();
         line(strf("    constexpr %s C = %lld, R = %lld, TR = %lld, TC = %lld;", idx_t(), (long long)C, (long long)R, (long long)tr,
                   (long long)tc));
-        line(strf("    constexpr int TS = %d, TXN = %d, TYN = %d, NI = %d;", TS, TXN, TYN, NI));
+        line(strf("    constexpr int TS = %d, TXN = %d, TYN = %d, NI = %d, VW = %d;", TS, TXN, TYN, NI, VW));
         line(strf("    __shared__ float tile[%d][TS][TS + 1];", std::max(n_t, 1)));
         if (xcd_remap) {
             line(strf("    const %s slot = blockIdx.x / 8;", idx_t()));
@@ -1084,19 +1094,20 @@ struct Emit {
             const Operand& o = grp.operands[oi];
             if (!o.transposed) continue;
             std::string base = lead_offset_n(o, rd - 2);
-            const bool vec_ok = (R % 4 == 0) && lead_strides_multiple_of(o, 4, rd - 2);
+            const bool vec_ok = (R % VW == 0) && lead_strides_multiple_of(o, VW, rd - 2);
             line("    _Pragma(\"unroll\") for (int i = 0; i < NI; ++i) {");
-            line(strf("        const %s cc = c0 + ty + TYN * i, rr = r0 + tx * 4;", idx_t()));
-            line("        float t4[4] = {0.0f, 0.0f, 0.0f, 0.0f};");
+            line(strf("        const %s cc = c0 + ty + TYN * i, rr = r0 + tx * VW;", idx_t()));
+            line("        float t4[VW];");
+            line("        _Pragma(\"unroll\") for (int j = 0; j < VW; ++j) t4[j] = 0.0f;");
             if (vec_ok) {
-                line(strf("        if (cc < C && rr < R) pf_ld<4, false>(p%zu + %s + cc * R + rr, t4);", oi, base.c_str()));
+                line(strf("        if (cc < C && rr < R) pf_ld<VW, false>(p%zu + %s + cc * R + rr, t4);", oi, base.c_str()));
             } else {
                 // rows of a length that is no multiple of four: full vectors at element alignment, scalars at the row end
-                line(strf("        if (cc < C && rr + 4 <= R) pf_ld<4, false, true>(p%zu + %s + cc * R + rr, t4);", oi, base.c_str()));
-                line(strf("        else if (cc < C) { _Pragma(\"unroll\") for (int j = 0; j < 4; ++j) if (rr + j < R) t4[j] = pf_ld1(p%zu + %s + cc * R + rr + j); }",
+                line(strf("        if (cc < C && rr + VW <= R) pf_ld<VW, false, true>(p%zu + %s + cc * R + rr, t4);", oi, base.c_str()));
+                line(strf("        else if (cc < C) { _Pragma(\"unroll\") for (int j = 0; j < VW; ++j) if (rr + j < R) t4[j] = pf_ld1(p%zu + %s + cc * R + rr + j); }",
                           oi, base.c_str()));
             }
-            line(strf("        _Pragma(\"unroll\") for (int j = 0; j < 4; ++j) tile[%d][ty + TYN * i][tx * 4 + j] = t4[j];", ti));
+            line(strf("        _Pragma(\"unroll\") for (int j = 0; j < VW; ++j) tile[%d][ty + TYN * i][tx * VW + j] = t4[j];", ti));
             line("    }");
             ++ti;
         }
@@ -1107,29 +1118,29 @@ struct Emit {
             line(strf("    float x%zu[%d];", oi, EPL));
             if (o.transposed) {
                 line("    _Pragma(\"unroll\") for (int i = 0; i < NI; ++i)");
-                line(strf("        _Pragma(\"unroll\") for (int j = 0; j < 4; ++j) x%zu[i * 4 + j] = tile[%d][tx * 4 + j][ty + TYN * i];", oi, ti));
+                line(strf("        _Pragma(\"unroll\") for (int j = 0; j < VW; ++j) x%zu[i * VW + j] = tile[%d][tx * VW + j][ty + TYN * i];", oi, ti));
                 ++ti;
                 continue;
             }
             std::string base = lead_offset_n(o, rd - 2);
             const int64_t sr = o.stride[rd - 2], sc = o.stride[rd - 1];
-            const bool vec_ok = sc == 1 && (C % 4 == 0) && (sr % 4 == 0) && lead_strides_multiple_of(o, 4, rd - 2) && !o.mapped(rd - 1) &&
-                                o.const_offset % 4 == 0;
+            const bool vec_ok = sc == 1 && (C % VW == 0) && (sr % VW == 0) && lead_strides_multiple_of(o, VW, rd - 2) && !o.mapped(rd - 1) &&
+                                o.const_offset % VW == 0;
             line("    _Pragma(\"unroll\") for (int i = 0; i < NI; ++i) {");
-            line(strf("        const %s rr = r0 + ty + TYN * i, cc = c0 + tx * 4;", idx_t()));
+            line(strf("        const %s rr = r0 + ty + TYN * i, cc = c0 + tx * VW;", idx_t()));
             line(strf("        const %s rc = rr < R ? rr : R - 1;", idx_t()));
             if (vec_ok) {
-                line(strf("        if (cc < C) pf_ld<4, false>(p%zu + %s + %s * %lld + cc, &x%zu[i * 4]);", oi, base.c_str(),
+                line(strf("        if (cc < C) pf_ld<VW, false>(p%zu + %s + %s * %lld + cc, &x%zu[i * VW]);", oi, base.c_str(),
                           mapexpr(o, rd - 2, "rc").c_str(), (long long)sr, oi));
-                line(strf("        else { _Pragma(\"unroll\") for (int j = 0; j < 4; ++j) x%zu[i * 4 + j] = 0.0f; }", oi));
+                line(strf("        else { _Pragma(\"unroll\") for (int j = 0; j < VW; ++j) x%zu[i * VW + j] = 0.0f; }", oi));
             } else {
                 const bool ua_ok = sc == 1 && !o.mapped(rd - 1);     // contiguous along the row, merely not 16-byte aligned
                 if (ua_ok)
-                    line(strf("        if (cc + 4 <= C) pf_ld<4, false, true>(p%zu + %s + %s * %lld + cc, &x%zu[i * 4]); else", oi, base.c_str(),
+                    line(strf("        if (cc + VW <= C) pf_ld<VW, false, true>(p%zu + %s + %s * %lld + cc, &x%zu[i * VW]); else", oi, base.c_str(),
                               mapexpr(o, rd - 2, "rc").c_str(), (long long)sr, oi));
-                line("        _Pragma(\"unroll\") for (int j = 0; j < 4; ++j) {");
+                line("        _Pragma(\"unroll\") for (int j = 0; j < VW; ++j) {");
                 line(strf("            const %s cj = cc + j < C ? cc + j : C - 1;", idx_t()));
-                line(strf("            x%zu[i * 4 + j] = pf_ld1(p%zu + %s + %s * %lld + %s * %lld);", oi, oi, base.c_str(),
+                line(strf("            x%zu[i * VW + j] = pf_ld1(p%zu + %s + %s * %lld + %s * %lld);", oi, oi, base.c_str(),
                           mapexpr(o, rd - 2, "rc").c_str(), (long long)sr, mapexpr(o, rd - 1, "cj").c_str(), (long long)sc));
                 line("        }");
             }
@@ -1137,17 +1148,17 @@ struct Emit {
         }
         for (int id : grp.nodes) emit_elementwise(id, EPL);
         int sp = 0;
-        const bool st_vec = C % 4 == 0;
+        const bool st_vec = C % VW == 0;
         for (auto& st : grp.stores) {
             int cnt = 1 + (int)st.also_outputs.size();
             for (int c = 0; c < cnt; ++c, ++sp) {
                 line("    _Pragma(\"unroll\") for (int i = 0; i < NI; ++i) {");
-                line(strf("        const %s rr = r0 + ty + TYN * i, cc = c0 + tx * 4;", idx_t()));
+                line(strf("        const %s rr = r0 + ty + TYN * i, cc = c0 + tx * VW;", idx_t()));
                 line(strf("        const %s o = (lead * R + rr) * C + cc;", idx_t()));
-                if (st_vec) line(strf("        if (rr < R && cc < C) pf_st<4, false>(q%d + o, &v%d[i * 4]);", sp, st.node));
+                if (st_vec) line(strf("        if (rr < R && cc < C) pf_st<VW, false>(q%d + o, &v%d[i * VW]);", sp, st.node));
                 else {
-                    line(strf("        if (rr < R && cc + 4 <= C) pf_st<4, false, true>(q%d + o, &v%d[i * 4]);", sp, st.node));
-                    line(strf("        else if (rr < R) { _Pragma(\"unroll\") for (int j = 0; j < 4; ++j) if (cc + j < C) pf_st1(q%d + o + j, v%d[i * 4 + j]); }",
+                    line(strf("        if (rr < R && cc + VW <= C) pf_st<VW, false, true>(q%d + o, &v%d[i * VW]);", sp, st.node));
+                    line(strf("        else if (rr < R) { _Pragma(\"unroll\") for (int j = 0; j < VW; ++j) if (cc + j < C) pf_st1(q%d + o + j, v%d[i * VW + j]); }",
                               sp, st.node));
                 }
                 line("    }");

@@ -88,3 +88,26 @@ def test_transposes_of_computed_values_match_the_oracle(name, build, shapes, pos
     uo = u.run()
     torch.cuda.synchronize()
     check_against_oracle(w, uo, refs=refs, what=name + " unfused")
+
+
+@pytest.mark.parametrize("dtype,shape", [("bf16", (4096, 4096)), ("f16", (2, 3000, 2056)), ("bf16", (4100, 4099)), ("bf16", (3, 2999, 3001)),
+                                         ("f32", (4096, 4096))])
+def test_large_transposes_with_an_epilogue(dtype, shape):
+    """64-wide tiles (eight-element vectors when every tensor of the group holds 16-bit elements), whole and
+    ragged extents; pure data movement must be bit-exact."""
+    t_shape = tuple(shape[:-2]) + (shape[-1], shape[-2])
+
+    def build(g, ins):
+        g.dtype = dtype
+        t = g.op("transpose", [ins[0]], dtype)
+        return [t, g.op("mul", [g.op("add", [t, ins[1]], dtype), ins[2]], dtype)]
+    w, refs = _workload("large transpose", build, [shape, t_shape, (t_shape[-1],)], dtype)
+    r = Runner(w)
+    assert r.info["n_kernels"] == 1 and r.exe.group_info(0)["template"] == "tile"
+    assert "TS = 64" in r.exe.source(0) and ("VW = 8" in r.exe.source(0)) == (dtype != "f32")
+    outs = r.run()
+    torch.cuda.synchronize()
+    from tests.harness import to_host_bits
+    moved = to_host_bits(outs[0], dtype)
+    np.testing.assert_array_equal(moved, np.swapaxes(w.inputs[0], -1, -2))      # the bits themselves
+    check_against_oracle(w, outs, refs=refs, what="large transpose %s %s" % (dtype, shape))
