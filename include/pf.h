@@ -208,6 +208,15 @@ pf_status pf_jit_stats_get(pf_jit_stats* h_out);
 pf_status pf_execute(pf_exec* e, const void* const* d_inputs, int n_in, void* const* d_outputs, int n_out,
                      void* d_workspace, size_t workspace_bytes, void* stream);
 
+/* Runs a compiled subgraph at another outermost extent than the one it was compiled for (a smaller
+ * batch: the last member of a task instance, Sec. 3.1, need not be compiled at all).  Every tensor that
+ * carries the outermost dim of the kernel's domain is taken to have outer_extent there; tensors that
+ * broadcast along it are unchanged.  Only for subgraphs that are one kernel of the elementwise or row
+ * templates without scratch, 1 <= outer_extent <= the compiled extent (the index width and the tiling
+ * were chosen for that one); otherwise PF_E_INVALID and nothing is enqueued. */
+pf_status pf_execute_outer(pf_exec* e, int64_t outer_extent, const void* const* d_inputs, int n_in, void* const* d_outputs,
+                           int n_out, void* stream);
+
 /* As pf_execute, with two caller-owned hipEvent_t handles (either may be NULL):
  * start_event is recorded when the first kernel begins executing and
  * stop_event when the last kernel has finished, so that

@@ -122,6 +122,7 @@ def lib():
         "pf_exec_group_info": [vp, C.c_int, C.POINTER(_GroupInfo)],
         "pf_exec_source": [vp, C.c_int, C.c_char_p, sz, C.POINTER(sz)],
         "pf_exec_kernel_name": [vp, C.c_int, C.c_char_p, sz, C.POINTER(sz)],
+        "pf_execute_outer": [vp, C.c_int64, C.POINTER(C.c_void_p), C.c_int, C.POINTER(C.c_void_p), C.c_int, vp],
         "pf_jit_stats_get": [C.POINTER(_JitStats)],
         "pf_execute": [vp, C.POINTER(vp), C.c_int, C.POINTER(vp), C.c_int, vp, sz, vp],
         "pf_execute_timed": [vp, C.POINTER(vp), C.c_int, C.POINTER(vp), C.c_int, vp, sz, vp, vp, vp],
@@ -275,6 +276,12 @@ class Exec:
         buf = C.create_string_buffer(need.value)
         _check(lib().pf_exec_source(self._h, i, buf, need.value, C.byref(need)))
         return buf.value.decode()
+
+    def execute_outer(self, outer_extent, input_ptrs, output_ptrs, stream=0):
+        """As execute, at another (smaller) outermost extent than the compiled one; one-kernel subgraphs only."""
+        ins = (C.c_void_p * len(input_ptrs))(*input_ptrs)
+        outs = (C.c_void_p * len(output_ptrs))(*output_ptrs)
+        _check(lib().pf_execute_outer(self._h, int(outer_extent), ins, len(input_ptrs), outs, len(output_ptrs), C.c_void_p(stream)))
 
     def kernel_name(self, i):
         need = C.c_size_t()

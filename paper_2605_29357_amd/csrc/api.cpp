@@ -331,6 +331,26 @@ pf_status pf_execute(pf_exec* e, const void* const* d_inputs, int n_in, void* co
     });
 }
 
+pf_status pf_execute_outer(pf_exec* e, int64_t outer_extent, const void* const* d_inputs, int n_in, void* const* d_outputs, int n_out,
+                           void* stream) {
+    return guarded([&] {
+        need(e, "e");
+        if (e->plan.groups.size() != 1 || e->plan.workspace_bytes != 0)
+            pf::fail(PF_E_INVALID, "another outermost extent needs a subgraph that is one kernel without scratch");
+        const pf::Group& grp = e->plan.groups[0];
+        if (grp.rt_per_block <= 0 || grp.domain.size() < 2)
+            pf::fail(PF_E_INVALID, "this kernel is specialised for its outermost extent (template %d)", (int)grp.tmpl);
+        for (auto& o : grp.operands)
+            if (o.mapped(0)) pf::fail(PF_E_INVALID, "an operand is rolled or sliced along the outermost dim");
+        check_execute_args(e, d_inputs, n_in, d_outputs, n_out, nullptr, 0);
+        if (outer_extent < 1 || outer_extent > grp.domain[0])
+            pf::fail(PF_E_INVALID, "outermost extent %lld outside 1 .. %lld (the compiled one)", (long long)outer_extent, (long long)grp.domain[0]);
+        if ((outer_extent * grp.rt_rows_per_outer) % grp.rt_row_multiple)
+            pf::fail(PF_E_INVALID, "this kernel needs a multiple of %lld rows", (long long)grp.rt_row_multiple);
+        pf::exec_run(*e, d_inputs, d_outputs, nullptr, stream, nullptr, nullptr, outer_extent);
+    });
+}
+
 pf_status pf_execute_timed(pf_exec* e, const void* const* d_inputs, int n_in, void* const* d_outputs, int n_out,
                            void* d_workspace, size_t workspace_bytes, void* stream, void* start_event, void* stop_event) {
     return guarded([&] {

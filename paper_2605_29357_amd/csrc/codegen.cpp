@@ -259,6 +259,11 @@ struct Emit {
         const int64_t row_groups = (R + RU - 1) / RU;
         grp.block = block;
         grp.grid = (row_groups + teams - 1) / teams;
+        if (rd >= 2) {
+            grp.rt_per_outer = grp.rt_rows_per_outer = inner_rows();
+            grp.rt_per_block = (int64_t)RU * teams;
+            grp.rt_row_multiple = groups_exact ? RU : 1;      // a kernel compiled for whole row groups has no partial-group code
+        }
         grp.lanes_per_row = T;
         grp.vec = vec;
         grp.chunks_per_lane = (int)K;
@@ -437,6 +442,10 @@ struct Emit {
         hoisted.clear();
         grp.block = T;
         grp.grid = R;
+        if (rd >= 2) {
+            grp.rt_per_outer = grp.rt_rows_per_outer = inner_rows();
+            grp.rt_per_block = 1;
+        }
         grp.lanes_per_row = T;
         grp.vec = vec;
         grp.chunks_per_lane = (int)(((C + vec - 1) / vec + T - 1) / T);
@@ -935,6 +944,11 @@ struct Emit {
         const int64_t nvec = (N + vec - 1) / vec;
         grp.block = block;
         grp.grid = (nvec + (int64_t)block * U - 1) / ((int64_t)block * U);
+        if (rd >= 2 && !straddle) {                           // whole vectors per row: no tail code to depend on the element count
+            grp.rt_per_outer = inner_rows() * C;
+            grp.rt_per_block = (int64_t)vec * block * U;
+            grp.rt_rows_per_outer = inner_rows();
+        }
         grp.vec = vec;
         grp.chunks_per_lane = U;
         grp.lanes_per_row = 0;

@@ -21,5 +21,5 @@ namespace pf {
 void exec_load(pf_exec& e);
 void exec_unload(pf_exec& e);
 void exec_run(pf_exec& e, const void* const* d_inputs, void* const* d_outputs, void* d_ws, void* stream, void* start_event,
-              void* stop_event);
+              void* stop_event, int64_t outer_override = 0);
 }  // namespace pf

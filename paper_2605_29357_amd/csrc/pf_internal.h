@@ -134,6 +134,9 @@ struct Group {
     // the same module combines them
     bool outer_runtime = false;     // the kernel takes the outermost domain extent as its last scalar argument
     int64_t outer_extent = 0;
+    // running at another outermost extent than the compiled one: grid = ceil(outer * rt_per_outer / rt_per_block),
+    // allowed when rt_per_block > 0 and outer * rt_rows_per_outer is a multiple of rt_row_multiple
+    int64_t rt_per_outer = 0, rt_per_block = 0, rt_rows_per_outer = 1, rt_row_multiple = 1;
     uint64_t scratch_bytes = 0;
     int64_t scratch_offset = -1;
     std::string kernel2_name;

@@ -151,7 +151,7 @@ void exec_unload(pf_exec& e) {
 }
 
 void exec_run(pf_exec& e, const void* const* d_inputs, void* const* d_outputs, void* d_ws, void* stream, void* start_event,
-              void* stop_event) {
+              void* stop_event, int64_t outer_override) {
     exec_load(e);
     for (size_t i = 0; i < e.plan.groups.size(); ++i) {
         Group& grp = e.plan.groups[i];
@@ -169,7 +169,8 @@ void exec_run(pf_exec& e, const void* const* d_inputs, void* const* d_outputs, v
             for (int k : s.also_outputs) ptrs[n++] = d_outputs[k];
         }
         for (int k = 0; k < n; ++k) args[k] = &ptrs[k];
-        long long outer = grp.outer_extent;
+        long long outer = outer_override > 0 ? outer_override : grp.outer_extent;
+        const int64_t grid1 = outer_override > 0 ? (outer * grp.rt_per_outer + grp.rt_per_block - 1) / grp.rt_per_block : grp.grid;
         if (grp.outer_runtime) args[n++] = &outer;
         if (grp.scratch_bytes) {
             ptrs[n] = (char*)d_ws + grp.scratch_offset;
@@ -190,7 +191,7 @@ void exec_run(pf_exec& e, const void* const* d_inputs, void* const* d_outputs, v
             if (b && r == hipSuccess) (void)hipEventRecord(b, (hipStream_t)stream);
             return r;
         };
-        hipError_t err = launch(e.functions[i], grp.grid, grp.block, ev0, two ? nullptr : ev1);
+        hipError_t err = launch(e.functions[i], grid1, grp.block, ev0, two ? nullptr : ev1);
         if (err == hipSuccess && two) err = launch(e.functions2[i], grp.grid2, grp.block2, nullptr, ev1);
         if (err != hipSuccess) fail(PF_E_RUNTIME, "launch of %s failed: %s", grp.kernel_name.c_str(), hipGetErrorString(err));
     }

@@ -8,7 +8,8 @@ import pytest
 import torch
 
 import paper_2605_29357_amd as pf
-from tests.harness import Runner, check_against_oracle
+from tests.harness import Runner, check_against_oracle, to_device
+from paper_2605_29357_amd.torch_util import alloc_outputs
 from workloads import configs, sweeps
 
 pytestmark = pytest.mark.gpu
@@ -77,3 +78,25 @@ def test_members_that_share_one_code_object_match_the_oracle(name, make, outers)
         torch.cuda.synchronize()
         check_against_oracle(w, outs, what="%s, outer extent %d" % (name, r))
     assert len(names) == 1, names
+
+
+@pytest.mark.parametrize("name,make,compiled,others", [
+    ("flat", lambda r: configs.cfg3_bias_gelu_gate(rows=r, cols=264), 300, (1, 37, 299)),
+    ("layernorm rows", lambda r: configs.cfg1_add_layernorm(rows=r, cols=768), 200, (1, 7, 64)),
+    ("layernorm, several rows in flight", lambda r: configs.cfg1_add_layernorm(rows=r, cols=96), 1 << 16, (4, 1000, 65532)),
+    ("softmax batch", lambda r: configs.cfg2_masked_softmax(heads=r, seq=133), 5, (2, 3)),
+    ("rmsnorm + rope batch", lambda r: configs.cfg4_rmsnorm_rope(r, 64, 4, 128), 5, (2, 4)),
+    ("layernorm rows streamed", lambda r: configs.cfg1_add_layernorm(rows=r, cols=70001), 3, (2,)),
+])
+def test_one_compiled_kernel_runs_smaller_outer_extents(name, make, compiled, others):
+    """pf_execute_outer: the kernel compiled for the largest member runs the smaller ones as they come
+    (their inputs are other data of the smaller shape), and still runs its own extent afterwards."""
+    big = Runner(make(compiled))
+    assert big.info["n_kernels"] == 1
+    for r in others + (compiled,):
+        w = make(r)
+        d_in = [to_device(a, dt) for a, dt in zip(w.inputs, w.input_dtypes)]
+        outs = alloc_outputs(w)
+        big.exe.execute_outer(r, [t.data_ptr() for t in d_in], [t.data_ptr() for t in outs], torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        check_against_oracle(w, outs, what="%s: compiled for %d, run at %d" % (name, compiled, r))

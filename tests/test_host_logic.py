@@ -311,3 +311,33 @@ def test_members_that_differ_in_the_outermost_extent_share_one_code_object():
     b = Builder()
     b.output(b.op("gelu", [b.input("f32", (1000,))], "f32"))
     assert "pf_d0" not in pf.Exec(b.text()).source(0)
+
+
+def test_execute_at_another_outer_extent_is_refused_where_the_kernel_is_specialised():
+    # argument checks run before anything is enqueued, so they need no GPU
+    e = pf.Exec(configs.cfg3_bias_gelu_gate(rows=64, cols=256).text)
+    for bad in (0, 65, -3):
+        with pytest.raises(pf.PfError) as err:
+            e.execute_outer(bad, [16, 16, 16], [16])
+        assert err.value.status == pf.PF_E_INVALID and "outermost extent" in str(err.value)
+    # a transposing kernel, a two-kernel plan and a rank-1 problem keep every extent literal
+    g = Builder()
+    x = g.input("f32", (64, 96))
+    g.output(g.op("exp", [g.op("transpose", [x], "f32")], "f32"))
+    with pytest.raises(pf.PfError) as err:
+        pf.Exec(g.text()).execute_outer(32, [16], [16])
+    assert "specialised" in str(err.value)
+    g = Builder()
+    x = g.input("f32", (64, 96))
+    s = g.op("sum", [x], "f32", keepdim=0)
+    g.output(g.op("exp", [s], "f32"))
+    with pytest.raises(pf.PfError) as err:
+        pf.Exec(g.text()).execute_outer(32, [16], [16])
+    assert err.value.status == pf.PF_E_INVALID
+    # a LayerNorm kernel compiled for whole groups of rows wants a multiple of them
+    e = pf.Exec(configs.cfg1_add_layernorm(rows=1 << 16, cols=96).text)
+    assert e.group_info(0)["template"] == "row_resident"
+    if "RU = 1," not in e.source(0):
+        with pytest.raises(pf.PfError) as err:
+            e.execute_outer(1001, [16, 16, 16, 16], [16])
+        assert "multiple" in str(err.value)
