@@ -45,6 +45,8 @@ def parse():
     ap.add_argument("--sets", type=int, default=2, help="distinct buffer sets rotated through (cold cache)")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the main line: the ten-shape task instances, shape-aware tiling against a static one")
+    ap.add_argument("--score-sizes", action="store_true",
+                    help="time the scorer and the tolerance ladder on one pair of 1 k ... 90 M elements (bf16 and f32)")
     ap.add_argument("--cfg5", action="store_true",
                     help="instead of the main line: fused against op-by-op time of each of the 256 random DAGs")
     return ap.parse_args()
@@ -73,6 +75,9 @@ def main():
     if args.sweep:
         print(json.dumps({"sweep": sweep_table(torch, pf, Runner, alloc_outputs, stream),
                           "outer_extent_reuse": reuse_table(torch, pf, Runner, alloc_outputs, stream)}))
+        return
+    if args.score_sizes:
+        print(json.dumps({"score_sizes": score_sizes_table(torch, pf, stream)}))
         return
     if args.cfg5:
         print(json.dumps({"cfg5": cfg5_table(torch, pf, Runner, alloc_outputs, stream)}))
@@ -390,6 +395,40 @@ def reuse_table(torch, pf, Runner, alloc_outputs, stream):
             del f, ins, outs
         table[fam] = {"members": rows, "code_objects": len({r["kernel"] for r in rows})}
     return table
+
+
+def score_sizes_table(torch, pf, stream):
+    """One (candidate, reference) pair per call, candidate = reference with 1e-3 relative noise: device time from
+    just before the call's first kernel to just after its last (events on the stream; median of 30 calls after 10)."""
+    from paper_2605_29357_amd.torch_util import HipEvent
+    rows = []
+    for n in (1024, 8192, 8193, 65536, 131072, 131073, 1 << 21, 1 << 24, 8192 * 11008):
+        for dt, tdt in (("bf16", torch.bfloat16), ("f32", torch.float32)):
+            x = torch.randn(n, device="cuda").to(tdt)
+            y = (x.float() * (1 + 1e-3 * torch.randn(n, device="cuda"))).to(tdt)
+            p = pf.Pair()
+            p.d_cand, p.d_ref, p.n = y.data_ptr(), x.data_ptr(), n
+            p.cand_dtype = p.ref_dtype = pf.DTYPES[dt]
+            p.rtol, p.atol, p.equal_nan = 2e-2, 1e-5, 0
+            res = torch.zeros(max(ctypes.sizeof(pf.ScoreResult), ctypes.sizeof(pf.LadderResult)), dtype=torch.uint8, device="cuda")
+            ws = torch.empty(max(pf.score_workspace_bytes(1), pf.score_ladder_workspace_bytes(1), 256), dtype=torch.uint8, device="cuda")
+            row = {"elements": n, "dtype": dt, "bytes": 2 * n * x.element_size(),
+                   "route": "one workgroup" if n <= 8192 else "unstaged" if n <= 131072 else "staged"}
+            for label, call in (("score_us", pf.score), ("ladder_us", pf.score_ladder)):
+                ts = []
+                for _ in range(40):
+                    a, b = HipEvent(), HipEvent()
+                    a.record(stream)
+                    call([p], res.data_ptr(), ws.data_ptr(), ws.numel(), stream.cuda_stream)
+                    b.record(stream)
+                    torch.cuda.synchronize()
+                    ts.append(a.elapsed_us(b))
+                row[label] = float(np.median(ts[10:]))
+            row["score_GBps"] = row["bytes"] / row["score_us"] / 1e3
+            row["ladder_GBps"] = row["bytes"] / row["ladder_us"] / 1e3
+            rows.append(row)
+            del x, y
+    return rows
 
 
 def configs_tol(dt):

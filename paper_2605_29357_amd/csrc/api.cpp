@@ -491,7 +491,7 @@ pf_status pf_score(const pf_pair* h_pairs, int n_pairs, pf_score_result* d_resul
         // only the slots that were written (two launches per call instead of three).
         bool direct_ok = !big.empty() && (int)big.size() <= pf::kPairBatch;
         for (auto& p : big)
-            if (p.n > (uint64_t)pf::kScoreSlots * 8192) direct_ok = false;       // above half a million elements the seeded path wins
+            if (p.n > (uint64_t)pf::kScoreSlots * 2048) direct_ok = false;       // 131072 elements: beyond, the staged route is as fast or faster
         if (direct_ok) {
             pf::PairBatch b;
             StagedPairs sp = stage_pairs(big.data(), (int)big.size(), d_workspace, stream, 2, big_index.data(), &b);

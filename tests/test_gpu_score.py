@@ -157,12 +157,12 @@ def test_elements_on_the_tolerance_boundary_and_extreme_magnitudes(cd, rd):
 @pytest.mark.parametrize("n_pairs", [1, 3, 48, 49])
 def test_every_route_through_the_scorer_gives_the_oracle_result(n_pairs):
     """One workgroup per pair (up to 8192 elements), the unstaged route (a call of at most 48 pairs of up to
-    524288 elements) and the staged route, alone and mixed in one call, at the sizes where the routes change."""
-    sizes = [8192, 8193, 70001, 524288, 524289, 2048, 1, 300000, 16385, 600000]
+    131072 elements) and the staged route, alone and mixed in one call, at the sizes where the routes change."""
+    sizes = [8192, 8193, 70001, 131072, 131073, 2048, 1, 300000, 16385, 600000]
     combos = [("f32", "f32"), ("bf16", "bf16"), ("bf16", "f32"), ("f32", "f64"), ("f32", "bf16")]
     specs, wants = [], []
     for k in range(n_pairs):
-        n = sizes[k % len(sizes)] if n_pairs <= 3 else [8192, 8193, 40000, 2048, 100, 524288][k % 6]
+        n = sizes[k % len(sizes)] if n_pairs <= 3 else [8192, 8193, 40000, 2048, 100, 131072][k % 6]
         cd, rd = combos[k % len(combos)]
         rtol, atol = [(1e-5, 1e-5), (2e-2, 1e-5), (0.0, 0.0)][k % 3]
         c, r = _pair(n, cd, rd, 900 + k, max(rtol, 1e-6), max(atol, 1e-7))
