@@ -446,7 +446,7 @@ StagedPairs stage_pairs(const pf_pair* h_pairs, int n_pairs, void* d_workspace, 
         }
         hipError_t err = mode == 1 ? pf::launch_score_stage(b, sp.d_pairs, sp.d_start, (pf_score_result*)sp.d_rest,
                                                             score_seeds(sp.d_rest, n_pairs), (hipStream_t)stream)
-                                   : pf::launch_score_upload(b, sp.d_pairs, sp.d_start, (hipStream_t)stream);
+                                   : pf::launch_ladder_stage(b, sp.d_pairs, sp.d_start, (pf_ladder_result*)sp.d_rest, (hipStream_t)stream);
         if (err != hipSuccess) pf::fail(PF_E_RUNTIME, "descriptor upload failed: %s", hipGetErrorString(err));
     }
     return sp;
@@ -546,14 +546,50 @@ pf_status pf_score_ladder(const pf_pair* h_pairs, int n_pairs, pf_ladder_result*
     return guarded([&] {
         if (n_pairs == 0) return;
         check_score_args(h_pairs, n_pairs, d_results, d_workspace, workspace_bytes, pf_score_ladder_workspace_bytes(n_pairs));
-        StagedPairs sp = stage_pairs(h_pairs, n_pairs, d_workspace, stream, 0);
+        for (int i = 0; i < n_pairs; ++i) check_pair(h_pairs[i], i);
         pf::LadderTable table;
         memset(&table, 0, sizeof table);
         for (int dt : {(int)PF_F32, (int)PF_BF16, (int)PF_F16})
             for (int k = 0; k < PF_LADDER_LEVELS; ++k) pf::tolerance_at((pf_dtype)dt, k - (PF_LADDER_LEVELS - 1), &table.rtol[dt][k], &table.atol[dt][k]);
-        hipError_t err = pf::launch_ladder(sp.d_pairs, sp.d_start, n_pairs, sp.ranges, table, d_results, (pf_ladder_result*)sp.d_rest,
-                                           (hipStream_t)stream);
-        if (err != hipSuccess) pf::fail(PF_E_RUNTIME, "ladder launch failed: %s", hipGetErrorString(err));
+        // small pairs: one workgroup each, one launch per dtype combination; the others: staging, chunk kernels, fold
+        std::vector<pf_pair> big;
+        std::vector<int> big_index;
+        std::vector<int> small[4][4];
+        for (int i = 0; i < n_pairs; ++i) {
+            const pf_pair& p = h_pairs[i];
+            if (p.n <= pf::score_small_pair_elems()) small[p.cand_dtype][p.ref_dtype].push_back(i);
+            else {
+                big.push_back(p);
+                big_index.push_back(i);
+            }
+        }
+        if (!big.empty()) {
+            StagedPairs sp = stage_pairs(big.data(), (int)big.size(), d_workspace, stream, 0, big_index.data());
+            hipError_t err = pf::launch_ladder(sp.d_pairs, sp.d_start, (int)big.size(), sp.ranges, table, d_results,
+                                               (pf_ladder_result*)sp.d_rest, (hipStream_t)stream);
+            if (err != hipSuccess) pf::fail(PF_E_RUNTIME, "ladder launch failed: %s", hipGetErrorString(err));
+        }
+        for (int cd = 0; cd < 4; ++cd)
+            for (int rd = 0; rd < 4; ++rd) {
+                const std::vector<int>& idx = small[cd][rd];
+                for (size_t first = 0; first < idx.size(); first += pf::kPairBatch) {
+                    pf::PairBatch b;
+                    memset(&b, 0, sizeof b);
+                    b.count = (int)std::min<size_t>(pf::kPairBatch, idx.size() - first);
+                    for (int k = 0; k < b.count; ++k) {
+                        const pf_pair& p = h_pairs[idx[first + k]];
+                        b.pairs[k].cand = p.d_cand;
+                        b.pairs[k].ref = p.d_ref;
+                        b.pairs[k].n = p.n;
+                        b.pairs[k].cand_dtype = p.cand_dtype;
+                        b.pairs[k].ref_dtype = p.ref_dtype;
+                        b.pairs[k].equal_nan = p.equal_nan;
+                        b.pairs[k].orig = idx[first + k];
+                    }
+                    hipError_t err = pf::launch_ladder_small(b, cd, rd, table, d_results, (hipStream_t)stream);
+                    if (err != hipSuccess) pf::fail(PF_E_RUNTIME, "ladder launch failed: %s", hipGetErrorString(err));
+                }
+            }
     });
 }
 

@@ -375,17 +375,8 @@ __device__ __forceinline__ double wave_max(double v) {
     return v;
 }
 
-// Descriptors travel as kernel arguments (copied at launch), so the host array
-// can be released as soon as the call returns and no host-to-device copy has
-// to be ordered against the stream.
-__global__ void __launch_bounds__(64) score_upload_kernel(pf::PairBatch batch, pf::PairDev* pairs, unsigned long long* block_start) {
-    const int i = threadIdx.x;
-    if (i < batch.count) {
-        pairs[batch.first + i] = batch.pairs[i];
-        block_start[batch.first + i] = batch.start[i];
-    }
-    if (i == 0 && batch.last) block_start[batch.first + batch.count] = batch.start[batch.count];
-}
+// Descriptors travel as kernel arguments (copied at launch), so the host array can be released as soon
+// as the call returns and no host-to-device copy has to be ordered against the stream.
 
 // Stages a batch of pairs and seeds their maxima, in one launch.  The cheap screen of the main
 // kernel passes an element only when it cannot raise a running maximum, so a wave that starts from
@@ -673,14 +664,60 @@ __global__ void __launch_bounds__(64) score_final_kernel(const pf::PairDev* pair
 // (fp64, same arithmetic as the single-level scorer).  Both tolerances grow with
 // k, so the levels an element fails form a prefix; each level is nevertheless
 // tested on its own, which keeps the kernel free of any assumption on rounding.
-__global__ void __launch_bounds__(kBlock) ladder_init_kernel(int n_pairs, pf_ladder_result* slots) {
-    const int p = blockIdx.x * blockDim.x + threadIdx.x;
-    if (p < n_pairs * kSlots) {
+template <int CD, int RD>
+__device__ __forceinline__ void ladder_one(typename Elem<CD>::raw ra, typename Elem<RD>::raw rb, int equal_nan, const double* rt,
+                                           const double* at, unsigned int* cnt);
+
+// One workgroup per pair of the batch: writes the descriptor and the block prefix (kernel arguments) and
+// clears the pair's slots, in a single launch.
+__global__ void __launch_bounds__(kBlock) ladder_stage_kernel(pf::PairBatch batch, pf::PairDev* pairs, unsigned long long* block_start,
+                                                              pf_ladder_result* slots) {
+    const int local = blockIdx.x;
+    if (local >= batch.count) return;
+    const int p = batch.first + local;
+    if (threadIdx.x == 0) {
+        pairs[p] = batch.pairs[local];
+        block_start[p] = batch.start[local];
+        if (batch.last && local == batch.count - 1) block_start[p + 1] = batch.start[batch.count];
+    }
+    for (int k = threadIdx.x; k < kSlots; k += kBlock) {
         pf_ladder_result z;
         z.n = 0;
 #pragma unroll
-        for (int k = 0; k < PF_LADDER_LEVELS; ++k) z.n_viol[k] = 0;
-        slots[p] = z;
+        for (int l = 0; l < PF_LADDER_LEVELS; ++l) z.n_viol[l] = 0;
+        slots[(size_t)p * kSlots + k] = z;
+    }
+}
+
+// Pairs of at most kSmallPair elements: one workgroup of 1024 lanes counts the whole pair exactly and writes
+// its result; a single launch for up to kPairBatch pairs (see score_small_kernel).
+template <int CD, int RD>
+__global__ void __launch_bounds__(1024) ladder_small_kernel(pf::PairBatch batch, pf::LadderRow row, pf_ladder_result* res) {
+    if ((int)blockIdx.x >= batch.count) return;
+    const pf::PairDev pr = batch.pairs[blockIdx.x];
+    unsigned int cnt[PF_LADDER_LEVELS];
+#pragma unroll
+    for (int k = 0; k < PF_LADDER_LEVELS; ++k) cnt[k] = 0;
+    for (unsigned long long i = threadIdx.x; i < pr.n; i += blockDim.x)
+        ladder_one<CD, RD>(Elem<CD>::load1(pr.cand, i), Elem<RD>::load1(pr.ref, i), pr.equal_nan, row.rtol, row.atol, cnt);
+    __shared__ unsigned long long s_cnt[1024 / 64][PF_LADDER_LEVELS];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+#pragma unroll
+    for (int k = 0; k < PF_LADDER_LEVELS; ++k) {
+        const unsigned long long w = wave_sum((unsigned long long)cnt[k]);
+        if (lane == 0) s_cnt[wave][k] = w;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        pf_ladder_result r;
+        r.n = pr.n;
+#pragma unroll
+        for (int k = 0; k < PF_LADDER_LEVELS; ++k) {
+            unsigned long long t = 0;
+            for (int w = 0; w < 1024 / 64; ++w) t += s_cnt[w][k];
+            r.n_viol[k] = t;
+        }
+        res[pr.orig] = r;
     }
 }
 
@@ -856,11 +893,6 @@ unsigned long long score_chunk_elems(unsigned long long n) {
     return c < kChunk ? c : kChunk;
 }
 
-hipError_t launch_score_upload(const PairBatch& batch, PairDev* d_pairs, unsigned long long* d_block_start, hipStream_t stream) {
-    hipLaunchKernelGGL(score_upload_kernel, dim3(1), dim3(64), 0, stream, batch, d_pairs, d_block_start);
-    return hipGetLastError();
-}
-
 hipError_t launch_score_stage(const PairBatch& batch, PairDev* d_pairs, unsigned long long* d_block_start, pf_score_result* d_slots,
                               double* d_seeds, hipStream_t stream) {
     hipLaunchKernelGGL(score_stage_kernel, dim3(batch.count * kSeedParts), dim3(kSeedBlock), 0, stream, batch, d_pairs, d_block_start,
@@ -930,10 +962,38 @@ hipError_t launch_score(const PairDev* d_pairs, const unsigned long long* d_bloc
     return hipGetLastError();
 }
 
+hipError_t launch_ladder_stage(const PairBatch& batch, PairDev* d_pairs, unsigned long long* d_block_start, pf_ladder_result* d_slots,
+                               hipStream_t stream) {
+    hipLaunchKernelGGL(ladder_stage_kernel, dim3(batch.count), dim3(kBlock), 0, stream, batch, d_pairs, d_block_start, d_slots);
+    return hipGetLastError();
+}
+
+hipError_t launch_ladder_small(const PairBatch& batch, int cd, int rd, const LadderTable& table, pf_ladder_result* d_results,
+                               hipStream_t stream) {
+    LadderRow row;
+    for (int k = 0; k < PF_LADDER_LEVELS; ++k) {
+        row.rtol[k] = table.rtol[cd][k];
+        row.atol[k] = table.atol[cd][k];
+    }
+#define PF_SMALL(CD, RD)                                                                                                     \
+    if (cd == CD && rd == RD)                                                                                                \
+        hipLaunchKernelGGL((ladder_small_kernel<CD, RD>), dim3(batch.count), dim3(1024), 0, stream, batch, row, d_results);
+    PF_SMALL(PF_F32, PF_F32)
+    PF_SMALL(PF_F32, PF_BF16)
+    PF_SMALL(PF_F32, PF_F64)
+    PF_SMALL(PF_BF16, PF_F32)
+    PF_SMALL(PF_BF16, PF_BF16)
+    PF_SMALL(PF_BF16, PF_F64)
+    PF_SMALL(PF_F32, PF_F16)
+    PF_SMALL(PF_F16, PF_F32)
+    PF_SMALL(PF_F16, PF_F16)
+    PF_SMALL(PF_F16, PF_F64)
+#undef PF_SMALL
+    return hipGetLastError();
+}
+
 hipError_t launch_ladder(const PairDev* d_pairs, const unsigned long long* d_block_start, int n_pairs, const ScoreRanges& ranges,
                          const LadderTable& table, pf_ladder_result* d_results, pf_ladder_result* d_slots, hipStream_t stream) {
-    const int nbs = (n_pairs * kSlots + kBlock - 1) / kBlock;
-    hipLaunchKernelGGL(ladder_init_kernel, dim3(nbs), dim3(kBlock), 0, stream, n_pairs, d_slots);
     // the screened kernel needs tolerances that grow with the level and that fp32 represents comfortably
     bool fast[4];
     for (int dt = 0; dt < 4; ++dt) {

@@ -51,10 +51,20 @@ struct LadderTable {
     double atol[4][PF_LADDER_LEVELS];
 };
 
+// the tolerances of one candidate dtype (what a one-workgroup-per-pair ladder launch carries besides its batch)
+struct LadderRow {
+    double rtol[PF_LADDER_LEVELS];
+    double atol[PF_LADDER_LEVELS];
+};
+static_assert(sizeof(PairBatch) + sizeof(LadderRow) + 64 <= 4096, "batch + tolerances must fit the kernel arguments");
+
 unsigned long long score_chunk_elems(unsigned long long n);
+hipError_t launch_ladder_stage(const PairBatch& batch, PairDev* d_pairs, unsigned long long* d_block_start, pf_ladder_result* d_slots,
+                               hipStream_t stream);
+hipError_t launch_ladder_small(const PairBatch& batch, int cd, int rd, const LadderTable& table, pf_ladder_result* d_results,
+                               hipStream_t stream);
 hipError_t launch_ladder(const PairDev* d_pairs, const unsigned long long* d_block_start, int n_pairs, const ScoreRanges& ranges,
                          const LadderTable& table, pf_ladder_result* d_results, pf_ladder_result* d_slots, hipStream_t stream);
-hipError_t launch_score_upload(const PairBatch& batch, PairDev* d_pairs, unsigned long long* d_block_start, hipStream_t stream);
 // descriptor upload, slot clearing and seeding of one batch in a single launch (the single-level scorer)
 hipError_t launch_score_stage(const PairBatch& batch, PairDev* d_pairs, unsigned long long* d_block_start, pf_score_result* d_slots,
                               double* d_seeds, hipStream_t stream);
