@@ -170,7 +170,9 @@ typedef struct {
 
 typedef struct {
     pf_template tmpl;
-    int      n_nodes;            /* operator nodes computed by this kernel                */
+    int      n_nodes;            /* operator nodes computed by this kernel, in the caller's numbering: a value
+                                    behind a transpose may be recomputed in the reader's kernel (then it shows
+                                    in both, or only there), transposes that cancel show nowhere */
     int      nodes[64];
     int64_t  rows, cols;         /* iteration domain: product of leading dims, last dim   */
     int      block_threads;
