@@ -66,7 +66,8 @@ def main():
         sys.exit(2)
     import torch
     import paper_2605_29357_amd as pf
-    from paper_2605_29357_amd.torch_util import HipEvent, Runner, alloc_outputs, to_host_bits
+    from paper_2605_29357_amd.hip_events import HipEvent
+    from tests.device import Runner, alloc_outputs, to_host_bits
     from workloads import configs
 
     assert torch.cuda.is_available(), "no GPU"
@@ -179,7 +180,7 @@ def main():
 def time_runner(torch, runner, stream, in_sets, out_sets, warmup=20, trials=100, max_rounds=3):
     """Paper protocol: 20 warmup, 100 timed trials, median; re-run while IQR > 20% of the median.
     Times are device times from the start of the first kernel to the end of the last."""
-    from paper_2605_29357_amd.torch_util import HipEvent
+    from paper_2605_29357_amd.hip_events import HipEvent
     n = len(in_sets)
     med = iqr = None
     for _ in range(max_rounds):
@@ -361,7 +362,7 @@ def reuse_table(torch, pf, Runner, alloc_outputs, stream):
     pf_compile (a JIT compilation or a cache hit) and the fused kernel's device time."""
     import time
     import types
-    from paper_2605_29357_amd.torch_util import TORCH_DT
+    from tests.device import TORCH_DT
     from workloads import configs
     fams = {
         "bias_gelu_gate": (configs.cfg3_bias_gelu_gate(rows=8, cols=11008), lambda r: [(r, 11008), (11008,), (r, 11008)], (1024, 2048, 4096, 8192)),
@@ -400,7 +401,7 @@ def reuse_table(torch, pf, Runner, alloc_outputs, stream):
 def score_sizes_table(torch, pf, stream):
     """One (candidate, reference) pair per call, candidate = reference with 1e-3 relative noise: device time from
     just before the call's first kernel to just after its last (events on the stream; median of 30 calls after 10)."""
-    from paper_2605_29357_amd.torch_util import HipEvent
+    from paper_2605_29357_amd.hip_events import HipEvent
     rows = []
     for n in (1024, 8192, 8193, 65536, 131072, 131073, 1 << 21, 1 << 24, 8192 * 11008):
         for dt, tdt in (("bf16", torch.bfloat16), ("f32", torch.float32)):
@@ -440,7 +441,8 @@ def cfg5_table(torch, pf, Runner, alloc_outputs, stream):
     """The 256 random fusible DAGs: fused and op-by-op device time each (median of 12 runs after 3 warm-ups; inputs
     are resident, one buffer set), kernel counts, algorithmic and planned bytes; then every output of every fused
     run is scored against its op-by-op counterpart in ONE batched scoring call."""
-    from paper_2605_29357_amd.torch_util import TORCH_DT, HipEvent
+    from paper_2605_29357_amd.hip_events import HipEvent
+    from tests.device import TORCH_DT
     from workloads import dags
 
     def med_time(r, outs, n=12):

@@ -263,6 +263,18 @@ size_t pf_score_workspace_bytes(int n_pairs);
 pf_status pf_score(const pf_pair* h_pairs, int n_pairs, pf_score_result* d_results,
                    void* d_workspace, size_t workspace_bytes, void* stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): pf_score with the library's own scratch in place of a workspace
+ * argument.  The scratch is an array of 1.5 MiB inside the library's code object; each GPU the
+ * library runs on holds one copy until the process ends.  At most PF_SCORE_STATIC_MAX_PAIRS pairs per
+ * call (more is PF_E_INVALID and nothing is enqueued); results, arguments and error behaviour are
+ * those of pf_score.  The call allocates and frees no device memory and does not synchronise; the
+ * first call on a device looks the array's address up there.  All calls on one GPU share that
+ * GPU's array: each call clears what it needs first, and two calls whose kernels may overlap on
+ * one GPU (different streams, or threads without ordering) race - order them on one stream. */
+#define PF_SCORE_STATIC_MAX_PAIRS 256
+pf_status pf_score_static(const pf_pair* h_pairs, int n_pairs, pf_score_result* d_results, void* stream);
+
 /* ---- tolerance ladder and error-aware speedup scores (Sec. 3.4, App. D-F) ---- */
 
 #define PF_LADDER_LEVELS 11   /* tolerance indices t = -10 .. 0 */

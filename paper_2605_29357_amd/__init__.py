@@ -127,6 +127,7 @@ def lib():
         "pf_execute": [vp, C.POINTER(vp), C.c_int, C.POINTER(vp), C.c_int, vp, sz, vp],
         "pf_execute_timed": [vp, C.POINTER(vp), C.c_int, C.POINTER(vp), C.c_int, vp, sz, vp, vp, vp],
         "pf_score": [C.POINTER(Pair), C.c_int, vp, vp, sz, vp],
+        "pf_score_static": [C.POINTER(Pair), C.c_int, vp, vp],
         "pf_copy_bytes": [vp, vp, sz, vp],
         "pf_score_ladder": [C.POINTER(Pair), C.c_int, vp, vp, sz, vp],
         "pf_tolerance": [C.c_int, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)],
@@ -312,6 +313,15 @@ def score(pairs, results_ptr, workspace_ptr, workspace_bytes, stream=0):
     arr = (Pair * max(len(pairs), 1))(*pairs)
     _check(lib().pf_score(arr, len(pairs), C.c_void_p(results_ptr), C.c_void_p(workspace_ptr), workspace_bytes,
                           C.c_void_p(stream)))
+
+
+SCORE_STATIC_MAX_PAIRS = 256
+
+
+def score_static(pairs, results_ptr, stream=0):
+    """As score, with the library's own scratch array as the workspace (no device allocation anywhere)."""
+    arr = (Pair * max(len(pairs), 1))(*pairs)
+    _check(lib().pf_score_static(arr, len(pairs), C.c_void_p(results_ptr), C.c_void_p(stream)))
 
 
 def copy_bytes(dst_ptr, src_ptr, nbytes, stream=0):

@@ -213,6 +213,9 @@ pf_status pf_compile(const pf_graph* g, const pf_options* h_opt, pf_exec** e) {
             if (n_args > (size_t)pf::kMaxKernelArgs)
                 pf::fail(PF_E_COMPILE, "a fused group would take %zu kernel arguments (limit %d)", n_args, pf::kMaxKernelArgs);
             pf::generate_source(work, opt, grp, idx++);
+            if (grp.grid > 0x7fffffffLL || grp.grid2 > 0x7fffffffLL)
+                pf::fail(PF_E_COMPILE, "kernel %s would need %lld workgroups; a launch holds at most 2^31 - 1", grp.kernel_name.c_str(),
+                         (long long)std::max(grp.grid, grp.grid2));
             if (grp.scratch_bytes) {     // partial results of a split reduction live at the end of the workspace
                 const uint64_t at = (ex->plan.workspace_bytes + 255) / 256 * 256;
                 grp.scratch_offset = (int64_t)at;
@@ -465,9 +468,9 @@ void check_score_args(const void* h_pairs, int n_pairs, const void* d_results, v
 
 extern "C" {
 
-pf_status pf_score(const pf_pair* h_pairs, int n_pairs, pf_score_result* d_results, void* d_workspace, size_t workspace_bytes,
-                   void* stream) {
-    return guarded([&] {
+static void score_impl(const pf_pair* h_pairs, int n_pairs, pf_score_result* d_results, void* d_workspace, size_t workspace_bytes,
+                       void* stream) {
+    {
         if (n_pairs == 0) return;
         check_score_args(h_pairs, n_pairs, d_results, d_workspace, workspace_bytes, pf_score_workspace_bytes(n_pairs));
         // Small pairs take one workgroup each and a single launch per dtype combination; the others go
@@ -527,6 +530,28 @@ pf_status pf_score(const pf_pair* h_pairs, int n_pairs, pf_score_result* d_resul
                     if (err != hipSuccess) pf::fail(PF_E_RUNTIME, "score launch failed: %s", hipGetErrorString(err));
                 }
             }
+    }
+}
+
+pf_status pf_score(const pf_pair* h_pairs, int n_pairs, pf_score_result* d_results, void* d_workspace, size_t workspace_bytes,
+                   void* stream) {
+    return guarded([&] { score_impl(h_pairs, n_pairs, d_results, d_workspace, workspace_bytes, stream); });
+}
+
+pf_status pf_score_static(const pf_pair* h_pairs, int n_pairs, pf_score_result* d_results, void* stream) {
+    return guarded([&] {
+        if (n_pairs < 0) pf::fail(PF_E_INVALID, "n_pairs < 0");
+        if (n_pairs > PF_SCORE_STATIC_MAX_PAIRS)
+            pf::fail(PF_E_INVALID, "pf_score_static takes at most %d pairs per call (%d given); use pf_score with a workspace", PF_SCORE_STATIC_MAX_PAIRS,
+                     n_pairs);
+        if (n_pairs == 0) return;
+        void* d_scratch = nullptr;
+        size_t bytes = 0;
+        hipError_t err = pf::static_scratch(&d_scratch, &bytes);
+        if (err != hipSuccess) pf::fail(PF_E_RUNTIME, "address of the library's scratch array: %s", hipGetErrorString(err));
+        if (pf_score_workspace_bytes(n_pairs) > bytes)
+            pf::fail(PF_E_INVALID, "internal: %d pairs need %zu bytes of scratch, the library holds %zu", n_pairs, pf_score_workspace_bytes(n_pairs), bytes);
+        score_impl(h_pairs, n_pairs, d_results, d_scratch, bytes, stream);
     });
 }
 

@@ -1054,7 +1054,13 @@ struct Emit {
         // plain transposes of 5 MB and more run up to 25% faster with 64-wide tiles; with an epilogue of several
         // operators the shorter instruction chain per wave still wins at four times that size
         const int64_t few_tiles = n_compute <= 1 ? 512 : n_compute <= 3 ? 2048 : n_compute <= 6 ? 4096 : 8192;
-        const int TS = t64 < few_tiles ? 32 : 64;
+        int n_t = 0;
+        for (auto& o : grp.operands) n_t += o.transposed ? 1 : 0;
+        // every transposed operand is staged through a padded LDS tile of its own; a workgroup may declare 64 KB
+        auto lds_bytes = [&](int ts) { return (int64_t)std::max(n_t, 1) * ts * (ts + 1) * 4; };
+        const int TS = (t64 < few_tiles || lds_bytes(64) > 64 * 1024) ? 32 : 64;
+        if (lds_bytes(TS) > 64 * 1024)
+            fail(PF_E_COMPILE, "a tiled group with %d transposed operands needs %lld bytes of LDS", n_t, (long long)lds_bytes(TS));
         // 16-byte accesses on both sides: four fp32 elements per lane and row, eight when every tensor of the
         // group holds 16-bit elements (64-wide tiles only: a 32-wide tile of eight-element vectors has no
         // whole pass of 256 lanes); 8192 x 8192 bf16 went from 4.4 to 4.7 TB/s
@@ -1081,8 +1087,6 @@ struct Emit {
         grp.vec = VW;
         grp.chunks_per_lane = NI;
         grp.lanes_per_row = 0;
-        int n_t = 0;
-        for (auto& o : grp.operands) n_t += o.transposed ? 1 : 0;
         RU = 1;
         NN = EPL;
 

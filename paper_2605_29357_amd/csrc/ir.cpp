@@ -199,6 +199,14 @@ int graph_add_node(pf_graph& g, pf_op op, const std::vector<int>& in,
     } else {
         n.shape = g.nodes[in[0]].shape;
     }
+    // the same size limit as for inputs (a broadcast can grow far beyond its operands); the product is
+    // formed step by step so that it cannot wrap around first
+    int64_t count = 1;
+    for (int64_t d : n.shape) {
+        if (count >= (int64_t(1) << 40) / d + 1) fail(PF_E_COMPILE, "%%%d: result tensor too large", id);
+        count *= d;
+    }
+    if (count >= (int64_t(1) << 40)) fail(PF_E_COMPILE, "%%%d: result tensor too large", id);
     g.nodes.push_back(n);
     return id;
 }

@@ -61,6 +61,7 @@ struct Builder {
         std::vector<int> kinds;                 // per member: 2 full, 1 row-uniform, 3 column-uniform
         bool has_rowuni = false;
         bool has_view = false;                  // a member is, or reads through, a roll / slice
+        std::vector<int> t_sources;             // tensors read through a swap of their last two dims (one LDS tile each)
         Shape epilogue;                         // COL_REDUCE: canonical shape of the column-uniform members
     };
     std::vector<int> kind_of;                   // per node, kind inside its group
@@ -107,10 +108,29 @@ struct Builder {
         return false;
     }
 
+    // tensors node n reads in the other orientation
+    std::vector<int> transposed_reads(const Node& n) const {
+        std::vector<int> t;
+        if (n.op == PF_OP_TRANSPOSE) t.push_back(n.in[0]);
+        for (size_t k = 0; k < n.in.size(); ++k)
+            if (n.reads_alias(k)) t.push_back(n.in[k]);
+        return t;
+    }
+
+    // A tiled kernel stages every transposed operand through an LDS tile of its own (4,224 bytes at the
+    // narrow tile edge): twelve of them fit the 64 KB a workgroup may declare.
+    static constexpr size_t kMaxTransposedOperands = 12;
+
     bool can_join(int id, int gi) const {
         const Node& n = g.nodes[id];
         const G& grp = groups[gi];
         if (grp.nodes.size() >= 60) return false;
+        {
+            size_t extra = 0;
+            for (int p : transposed_reads(n))
+                if (std::find(grp.t_sources.begin(), grp.t_sources.end(), p) == grp.t_sources.end()) ++extra;
+            if (extra && grp.t_sources.size() + extra > kMaxTransposedOperands) return false;
+        }
         for (int p : n.in)
             if (group_of[p] == gi && !usable_in_kernel(p)) return false;
         for (size_t k = 0; k < n.in.size(); ++k)               // read in the other orientation: from memory only
@@ -179,6 +199,8 @@ struct Builder {
         G& grp = groups[gi];
         grp.nodes.push_back(id);
         group_of[id] = gi;
+        for (int p : transposed_reads(n))
+            if (std::find(grp.t_sources.begin(), grp.t_sources.end(), p) == grp.t_sources.end()) grp.t_sources.push_back(p);
         int k = 2;
         if (is_col_reduction(n)) {
             if (grp.tmpl != PF_T_COL_REDUCE) grp.epilogue = canon(n.shape);

@@ -10,6 +10,8 @@
 // the result does not depend on how the elements are spread over lanes.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "pf.h"
 #include "score_dev.h"
 
@@ -1025,6 +1027,39 @@ hipError_t launch_ladder(const PairDev* d_pairs, const unsigned long long* d_blo
 #undef PF_LAUNCH
     hipLaunchKernelGGL(ladder_final_kernel, dim3(n_pairs), dim3(64), 0, stream, d_pairs, n_pairs, d_results, d_slots);
     return hipGetLastError();
+}
+
+// ---- scratch that lives in the code object ----
+// Callers that cannot allocate device memory (code under graph capture, tight serving loops, harnesses
+// that forbid hipMalloc) score through pf_score_static, whose workspace is this array.  Every GPU
+// holds its own copy at its own address, so the address is looked up once per device, with that
+// device current, and only that pointer ever reaches a kernel or a runtime call: the array's name in
+// host code is a stand-in, not a device address.
+}  // namespace pf
+
+static __device__ __align__(256) unsigned char scratch[PF_STATIC_SCRATCH_BYTES];
+
+namespace pf {
+
+hipError_t static_scratch(void** d_ptr, size_t* bytes) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void* per_device[kMaxDevices];          // zero-initialised: not looked up yet
+    int dev = -1;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess) return err;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lk(mu);
+    if (!per_device[dev]) {
+        void* p = nullptr;
+        err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (err != hipSuccess) return err;
+        if (!p) return hipErrorInvalidSymbol;
+        per_device[dev] = p;
+    }
+    *d_ptr = per_device[dev];
+    *bytes = PF_STATIC_SCRATCH_BYTES;
+    return hipSuccess;
 }
 
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream) {

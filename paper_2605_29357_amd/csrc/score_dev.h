@@ -78,4 +78,9 @@ hipError_t launch_score_direct(const PairBatch& batch, const ScoreRanges& ranges
                                hipStream_t stream);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
 
+// The workspace of pf_score_static: an array inside the library's code object.  Looks its address up
+// on the current device the first time it is asked for there; never allocates.
+#define PF_STATIC_SCRATCH_BYTES (1536 * 1024)
+hipError_t static_scratch(void** d_ptr, size_t* bytes);
+
 }  // namespace pf

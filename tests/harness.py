@@ -4,8 +4,8 @@ import numpy as np
 
 from oracle import dag as oracle_dag
 from oracle import score as oracle_score
-from paper_2605_29357_amd.torch_util import (Runner, alloc_outputs, score_on_gpu, to_device,  # noqa: F401
-                                             to_host_bits)
+from tests.device import (Runner, alloc_outputs, check_all_guards, score_on_gpu, to_device,  # noqa: F401
+                          to_host_bits)
 from workloads import configs
 
 
@@ -14,6 +14,7 @@ def oracle_outputs(w):
 
 def check_against_oracle(w, outs, refs=None, rtol=None, atol=None, what=""):
     """Element-by-element |gpu - oracle| <= atol + rtol*|oracle| in fp64; NaN positions must agree."""
+    check_all_guards()          # nothing was written outside an output or the workspace
     refs = refs if refs is not None else oracle_outputs(w)
     assert len(outs) == len(refs)
     worst = 0.0

@@ -12,7 +12,7 @@ import torch
 import paper_2605_29357_amd as pf
 from oracle import metric
 from oracle.score import score_pair
-from paper_2605_29357_amd.torch_util import ladder_on_gpu
+from tests.device import ladder_on_gpu
 from tests.harness import (Runner, check_against_oracle, oracle_outputs, oracle_score_dict, score_on_gpu, to_device,
                            to_host_bits)
 from workloads import configs, dags, rng

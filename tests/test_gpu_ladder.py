@@ -4,7 +4,7 @@ import pytest
 import torch
 
 from oracle import metric
-from paper_2605_29357_amd.torch_util import ladder_on_gpu, to_device
+from tests.device import ladder_on_gpu, to_device
 from workloads import rng
 
 pytestmark = pytest.mark.gpu

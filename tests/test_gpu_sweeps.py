@@ -9,7 +9,7 @@ import torch
 
 import paper_2605_29357_amd as pf
 from tests.harness import Runner, check_against_oracle, to_device
-from paper_2605_29357_amd.torch_util import alloc_outputs
+from tests.device import alloc_outputs
 from workloads import configs, sweeps
 
 pytestmark = pytest.mark.gpu

@@ -341,3 +341,79 @@ def test_execute_at_another_outer_extent_is_refused_where_the_kernel_is_speciali
         with pytest.raises(pf.PfError) as err:
             e.execute_outer(1001, [16, 16, 16, 16], [16])
         assert "multiple" in str(err.value)
+
+
+def test_many_transposed_operands_stay_within_the_lds_a_workgroup_may_declare():
+    # every transposed operand is staged through an LDS tile of its own; the planner stops a tiled group
+    # before the tiles outgrow 64 KB and the template narrows its tiles when it has to
+    import re
+    g = Builder()
+    acc = None
+    for _ in range(14):
+        t = g.op("transpose", [g.input("f32", (4096, 4096))], "f32")
+        acc = t if acc is None else g.op("add", [acc, t], "f32")
+    g.output(acc)
+    e = pf.Exec(g.text())
+    assert e.info()["n_kernels"] >= 2                      # 14 tiles do not fit one kernel
+    for k, gi in enumerate(e.groups()):
+        if gi["template"] != "tile":
+            continue
+        m = re.search(r"__shared__ float tile\[(\d+)\]\[TS\]\[TS \+ 1\]", e.source(k))
+        ts = int(re.search(r"constexpr int TS = (\d+)", e.source(k)).group(1))
+        assert m and int(m.group(1)) * ts * (ts + 1) * 4 <= 64 * 1024, (k, m.group(1), ts)
+
+
+def test_tensors_of_2_to_the_30_elements_and_more_are_indexed_with_64_bits():
+    b = Builder()
+    x = b.input("bf16", (1 << 15, 1 << 15))
+    b.output(b.op("gelu", [x], "bf16"))
+    src = pf.Exec(b.text()).source(0)
+    assert "const long long e0" in src and "unsigned e0" not in src
+    small = Builder()
+    small.output(small.op("gelu", [small.input("bf16", (1 << 14, 1 << 15))], "bf16"))
+    assert "const unsigned e0" in pf.Exec(small.text()).source(0)
+    w = configs.cfg2_masked_softmax(heads=2, seq=512)
+    wide = pf.Graph(w.text).variant([(4100, 512, 512), (512, 512)])
+    assert "long long grp_raw" in pf.Exec(wide).source(0)
+
+
+def test_results_too_large_to_index_or_to_launch_are_compile_errors():
+    # a broadcast grows far beyond its operands: the result obeys the same size limit as an input
+    b = Builder()
+    y = b.op("add", [b.input("f32", (1000000, 1000000, 1)), b.input("f32", (1, 1000000))], "f32")
+    with pytest.raises(pf.PfError) as err:
+        b.output(y)
+        pf.Exec(b.text())
+    assert err.value.status == pf.PF_E_COMPILE and "too large" in str(err.value)
+    # the largest tensors the size limit admits still fit a launch (the library refuses a grid it cannot count)
+    b = Builder()
+    b.output(b.op("exp", [b.input("bf16", (1 << 20, 1 << 19))], "bf16"))
+    assert 0 < pf.Exec(b.text()).group_info(0)["grid_blocks"] < 2 ** 31
+
+
+def test_cached_code_objects_are_tied_to_the_compiler_and_the_target(tmp_path, monkeypatch):
+    import glob
+    monkeypatch.setenv("PF_CACHE_DIR", str(tmp_path))
+    b = Builder()
+    b.output(b.op("tanh", [b.op("exp", [b.input("f32", (37, 53))], "f32")], "f32"))     # a kernel nothing else compiles
+    s0 = pf.jit_stats()
+    pf.Exec(b.text())
+    s1 = pf.jit_stats()
+    assert s1["compiled"] == s0["compiled"] + 1
+    files = glob.glob(str(tmp_path / "*.pfk"))
+    assert len(files) == 1
+    blob = open(files[0], "rb").read()
+    assert blob[:8] == b"PFCACHE2" and b"gfx950" in blob[24:64] and b"hiprtc" in blob[24:64]
+    # the same file under another compiler version is not this compiler's object: it must not be loaded
+    tlen = int.from_bytes(blob[8:16], "little")
+    forged = bytearray(blob)
+    forged[24:24 + tlen] = bytes(blob[24:24 + tlen]).replace(b"hiprtc", b"hiprtC")
+    open(files[0], "wb").write(bytes(forged))
+    import subprocess, sys
+    code = ("import os,sys; sys.path.insert(0, %r); import paper_2605_29357_amd as pf; pf.Exec(%r); s = pf.jit_stats(); "
+            "print(s['compiled'], s['disk_hits'])") % (ROOT, b.text())
+    out = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, env=dict(os.environ, PF_CACHE_DIR=str(tmp_path)))
+    assert out.stdout.split() == ["1", "0"], out.stdout + out.stderr
+    # and once rewritten by this compiler it is a hit for the next process
+    out = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, env=dict(os.environ, PF_CACHE_DIR=str(tmp_path)))
+    assert out.stdout.split() == ["0", "1"], out.stdout + out.stderr
