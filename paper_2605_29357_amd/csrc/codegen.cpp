@@ -319,15 +319,12 @@ struct Emit {
             const bool nt = numel(o.shape) * itemsize(o.dtype) >= (int64_t(1) << 22);
             line(strf("    float x%zu[%d];", oi, reps * N));
             line(strf("    _Pragma(\"unroll\") for (int u = 0; u < %d; ++u) _Pragma(\"unroll\") for (int k = 0; k < K; ++k) {", reps));
-            line(strf("        const %s c0 = (%s)(k * T + lane) * VEC;", idx_t(), idx_t()));
+            emit_chunk_start(ragged);
             if (last_mapped(o)) {     // rolled / sliced along the row: gather element by element
                 line(strf("        _Pragma(\"unroll\") for (int j = 0; j < VEC; ++j) x%zu[u * N + k * VEC + j] = (c0 + j < C) ? pf_ld1(p%zu + %s + %s * %lld) : 0.0f;",
                           oi, oi, base.c_str(), mapexpr(o, rd - 1, "(c0 + j)").c_str(), (long long)o.stride[rd - 1]));
             } else if (ragged) {
-                line(strf("        if (c0 + VEC <= C) pf_ld<VEC, %s, true>(p%zu + %s + c0, &x%zu[u * N + k * VEC]);", nt ? "true" : "false", oi,
-                          base.c_str(), oi));
-                line(strf("        else { _Pragma(\"unroll\") for (int j = 0; j < VEC; ++j) x%zu[u * N + k * VEC + j] = (c0 + j < C) ? pf_ld1(p%zu + %s + c0 + j) : 0.0f; }",
-                          oi, oi, base.c_str()));
+                line(strf("        pf_ld<VEC, %s, true>(p%zu + %s + c0, &x%zu[u * N + k * VEC]);", nt ? "true" : "false", oi, base.c_str(), oi));
             } else if (mask) {
                 line(strf("        if (c0 < C) pf_ld<VEC, %s>(p%zu + %s + c0, &x%zu[u * N + k * VEC]);", nt ? "true" : "false", oi,
                           base.c_str(), oi));
@@ -348,10 +345,10 @@ struct Emit {
             const int src = n.in[0];
             auto valid_open = [&]() {
                 line("    _Pragma(\"unroll\") for (int u = 0; u < RU; ++u) _Pragma(\"unroll\") for (int k = 0; k < K; ++k) {");
-                line(strf("        const %s c0 = (%s)(k * T + lane) * VEC;", idx_t(), idx_t()));
+                emit_chunk_start(ragged);
                 line("        _Pragma(\"unroll\") for (int jj = 0; jj < VEC; ++jj) {");
                 line("            const int j = k * VEC + jj;");
-                line(strf("            if (%s) {", ragged ? "c0 + jj < C" : mask ? "c0 < C" : "true"));
+                line(strf("            if (%s) {", ragged ? "jj >= skip" : mask ? "c0 < C" : "true"));
             };
             auto valid_close = [&]() { line("            }"); line("        }"); line("    }"); };
             std::string xj = ref(id, src, "j");
@@ -409,12 +406,11 @@ struct Emit {
                 } else {
                     const bool nt = numel(st.shape) * itemsize(st.dtype) >= (int64_t(1) << 22);
                     line("    _Pragma(\"unroll\") for (int u = 0; u < RU; ++u) _Pragma(\"unroll\") for (int k = 0; k < K; ++k) {");
-                    line(strf("        const %s c0 = (%s)(k * T + lane) * VEC;", idx_t(), idx_t()));
+                    emit_chunk_start(ragged);
                     if (ragged) {
-                        line(strf("        if (row_ok[u] && c0 + VEC <= C) pf_st<VEC, %s, true>(q%d + row[u] * C + c0, &v%d[u * N + k * VEC]);",
+                        // the shifted last chunk stores the elements it shares with the chunk before a second time, with the same values
+                        line(strf("        if (row_ok[u] && c0n < C) pf_st<VEC, %s, true>(q%d + row[u] * C + c0, &v%d[u * N + k * VEC]);",
                                   nt ? "true" : "false", q, st.node));
-                        line(strf("        else if (row_ok[u]) { _Pragma(\"unroll\") for (int j = 0; j < VEC; ++j) if (c0 + j < C) pf_st1(q%d + row[u] * C + c0 + j, v%d[u * N + k * VEC + j]); }",
-                                  q, st.node));
                     } else
                     line(strf("        if (row_ok[u]%s) pf_st<VEC, %s>(q%d + row[u] * C + c0, &v%d[u * N + k * VEC]);", mask ? " && c0 < C" : "",
                               nt ? "true" : "false", q, st.node));
@@ -423,6 +419,21 @@ struct Emit {
             }
         }
         line("}");
+    }
+
+    // Where a lane's chunk k starts in its row.  Rows whose length is no multiple of the vector end in a partial
+    // chunk; that chunk is moved back so that it ends with the row: every access stays a full vector inside the
+    // row, and the `skip` elements it shares with the chunk before it are left out of reductions (they are
+    // computed twice, with identical results, and stored twice).  A chunk that lies wholly past the row
+    // (c0n >= C) reads the same last vector and contributes nothing.
+    void emit_chunk_start(bool ragged) {
+        if (!ragged) {
+            line(strf("        const %s c0 = (%s)(k * T + lane) * VEC;", idx_t(), idx_t()));
+            return;
+        }
+        line(strf("        const %s c0n = (%s)(k * T + lane) * VEC;", idx_t(), idx_t()));
+        line(strf("        const %s c0 = c0n + VEC <= C ? c0n : C - VEC;", idx_t()));
+        line("        const int skip = (int)(c0n - c0); (void)skip;");
     }
 
     // ================================================================ ROW_LOOP

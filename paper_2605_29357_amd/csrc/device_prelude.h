@@ -190,18 +190,50 @@ PF_DEV void pf_st1(u16* p, float v) { *p = pf_f2bf(v); }
 PF_DEV void pf_st1(float* p, float v) { *p = v; }
 
 // ---- scalar math ----
+PF_DEV float pf_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
 #if PF_PRECISE
-PF_DEV float pf_div(float a, float b) { return a / b; }
-PF_DEV float pf_exp(float x) { return expf(x); }
-PF_DEV float pf_tanh(float x) { return tanhf(x); }
-PF_DEV float pf_sigmoid(float x) { return 1.0f / (1.0f + expf(-x)); }
+// fp32 graphs: every operator stays within about two ulp of the exact result, built from the hardware's
+// one-ulp estimates (v_rcp_f32, v_exp_f32) instead of the correctly rounded library routines, which cost
+// two to three times the instructions and would make these kernels bound by the vector ALU.
+//
+// a / b = a * (1/b): one ulp from the reciprocal, half an ulp from the product.  The reciprocal estimate
+// flushes subnormal results and inputs, so divisors outside [2^-126, 2^126) take the correctly rounded
+// division, as do quotients that come out non-finite (the division defines what 0/0, x/0, inf/inf are).
+PF_DEV float pf_div(float a, float b) {
+    const float q = a * pf_rcp(b);
+    const bool plain = (((pf_f2bits(b) & 0x7f800000u) - 0x00800000u) < 0x7e000000u) & (__builtin_fabsf(q) < __builtin_inff());
+    if (__builtin_expect(!plain, 0)) return a / b;
+    return q;
+}
+// e^x = 2^(x log2 e): the product x log2 e is carried as two floats (its rounding error alone would cost
+// |x| * 1e-7 of relative accuracy) and the low part enters as a first-order correction.
+PF_DEV float pf_exp(float x) {
+    const float L = 1.4426950216293335f, Llo = 1.9259629911e-8f;      // log2 e = L + Llo
+    const float y = x * L;
+    const float ylo = __builtin_fmaf(x, Llo, __builtin_fmaf(x, L, -y));
+    const float p = __builtin_amdgcn_exp2f(y);
+    const float r = __builtin_fmaf(p, ylo * 0.6931471806f, p);
+    return (r == r) ? r : p;       // x infinite or the result out of range: the correction is inf - inf, p is the answer
+}
+// tanh: an odd polynomial where 1 - 2 / (1 + e^2x) would cancel (|x| < 0.625, 0.8 ulp), the exponential form beyond
+PF_DEV float pf_tanh(float x) {
+    const float ax = __builtin_fabsf(x), u = x * x;
+    float q = __builtin_fmaf(u, -0.005691985599696636f, 0.020626291632652283f);
+    q = __builtin_fmaf(q, u, -0.05373531952500343f);
+    q = __builtin_fmaf(q, u, 0.13331381976604462f);
+    q = __builtin_fmaf(q, u, -0.3333328068256378f);
+    const float small = __builtin_fmaf(x * u, q, x);
+    const float t = __builtin_amdgcn_exp2f(ax * -2.8853900817779268f);      // e^(-2|x|) <= 0.29: its rounding hardly shows
+    const float big = __builtin_copysignf((1.0f - t) * pf_rcp(1.0f + t), x);
+    return ax < 0.625f ? small : big;                                       // NaN compares false and leaves through `big`
+}
+PF_DEV float pf_sigmoid(float x) { return pf_rcp(1.0f + pf_exp(-x)); }
 PF_DEV float pf_gelu_tanh(float x) {
     // 0.5 x (1 + tanh u) = x / (1 + exp(-2u)), u = sqrt(2/pi) (x + 0.044715 x^3)
-    float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
-    return x / (1.0f + expf(-2.0f * u));
+    const float u = 0.7978845608028654f * __builtin_fmaf(0.044715f * x, x * x, x);
+    return x * pf_rcp(1.0f + pf_exp(-2.0f * u));
 }
 #else
-PF_DEV float pf_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
 PF_DEV float pf_div(float a, float b) { return a * pf_rcp(b); }
 PF_DEV float pf_exp(float x) { return __builtin_amdgcn_exp2f(x * 1.4426950408889634f); }
 PF_DEV float pf_tanh(float x) { return 1.0f - 2.0f * pf_rcp(1.0f + __builtin_amdgcn_exp2f(x * 2.8853900817779268f)); }
