@@ -412,10 +412,15 @@ def score_sizes_table(torch, pf, stream):
             p.cand_dtype = p.ref_dtype = pf.DTYPES[dt]
             p.rtol, p.atol, p.equal_nan = 2e-2, 1e-5, 0
             res = torch.zeros(max(ctypes.sizeof(pf.ScoreResult), ctypes.sizeof(pf.LadderResult)), dtype=torch.uint8, device="cuda")
-            ws = torch.empty(max(pf.score_workspace_bytes(1), pf.score_ladder_workspace_bytes(1), 256), dtype=torch.uint8, device="cuda")
+            res2 = torch.zeros(ctypes.sizeof(pf.LadderResult), dtype=torch.uint8, device="cuda")
+            ws = torch.empty(max(pf.score_all_workspace_bytes(1), 256), dtype=torch.uint8, device="cuda")
             row = {"elements": n, "dtype": dt, "bytes": 2 * n * x.element_size(),
-                   "route": "one workgroup" if n <= 8192 else "unstaged" if n <= 131072 else "staged"}
-            for label, call in (("score_us", pf.score), ("ladder_us", pf.score_ladder)):
+                   "route": "one workgroup, one launch" if n <= 8192 else "staging launch + walking launch"}
+
+            def both(pairs, r, w, wn, st):
+                pf.score_all(pairs, r, res2.data_ptr(), w, wn, st)
+
+            for label, call in (("score_us", pf.score), ("ladder_us", pf.score_ladder), ("both_us", both)):
                 ts = []
                 for _ in range(40):
                     a, b = HipEvent(), HipEvent()
@@ -427,6 +432,7 @@ def score_sizes_table(torch, pf, stream):
                 row[label] = float(np.median(ts[10:]))
             row["score_GBps"] = row["bytes"] / row["score_us"] / 1e3
             row["ladder_GBps"] = row["bytes"] / row["ladder_us"] / 1e3
+            row["both_GBps"] = row["bytes"] / row["both_us"] / 1e3
             rows.append(row)
             del x, y
     return rows

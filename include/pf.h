@@ -254,7 +254,9 @@ typedef struct {
     uint64_t reserved_;      /* internal progress counter; ignore              */
 } pf_score_result;
 
-/* Bytes of device scratch pf_score needs for n_pairs pairs. */
+/* Bytes of device scratch pf_score needs for n_pairs pairs (about 5.5 KB per pair).  A workspace
+ * needs no initialisation, holds nothing of value after the call, and is private to the call while
+ * it runs. */
 size_t pf_score_workspace_bytes(int n_pairs);
 
 /* Scores n_pairs pairs in one pass over their elements.  h_pairs is read
@@ -295,6 +297,14 @@ typedef struct {
 size_t    pf_score_ladder_workspace_bytes(int n_pairs);
 pf_status pf_score_ladder(const pf_pair* h_pairs, int n_pairs, pf_ladder_result* d_results,
                           void* d_workspace, size_t workspace_bytes, void* stream);
+
+/* Both results from a single read of every pair: what the evaluation of Sec. 3.4 needs per output (the
+ * verdict of Eq. 1 at all eleven numerical tolerance levels for ES_t / AS, and the error maxima and counts
+ * at the pair's own rtol / atol).  d_score_results and d_ladder_results receive n_pairs structs each;
+ * arguments, workspace (pf_score_all_workspace_bytes) and error behaviour as for pf_score. */
+size_t    pf_score_all_workspace_bytes(int n_pairs);
+pf_status pf_score_all(const pf_pair* h_pairs, int n_pairs, pf_score_result* d_score_results, pf_ladder_result* d_ladder_results,
+                       void* d_workspace, size_t workspace_bytes, void* stream);
 
 /* One evaluated subgraph: measured speedup over the reference execution, how it
  * failed if it did (0: ran; 2: compilation, 3: runtime failure; an accuracy

@@ -128,6 +128,7 @@ def lib():
         "pf_execute_timed": [vp, C.POINTER(vp), C.c_int, C.POINTER(vp), C.c_int, vp, sz, vp, vp, vp],
         "pf_score": [C.POINTER(Pair), C.c_int, vp, vp, sz, vp],
         "pf_score_static": [C.POINTER(Pair), C.c_int, vp, vp],
+        "pf_score_all": [C.POINTER(Pair), C.c_int, vp, vp, vp, sz, vp],
         "pf_copy_bytes": [vp, vp, sz, vp],
         "pf_score_ladder": [C.POINTER(Pair), C.c_int, vp, vp, sz, vp],
         "pf_tolerance": [C.c_int, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)],
@@ -148,6 +149,8 @@ def lib():
     L.pf_score_workspace_bytes.restype = sz
     L.pf_score_ladder_workspace_bytes.argtypes = [C.c_int]
     L.pf_score_ladder_workspace_bytes.restype = sz
+    L.pf_score_all_workspace_bytes.argtypes = [C.c_int]
+    L.pf_score_all_workspace_bytes.restype = sz
     L.pf_last_error.restype = C.c_char_p
     L.pf_version.restype = C.c_char_p
     _lib_handle = L
@@ -351,6 +354,17 @@ def score_ladder(pairs, results_ptr, workspace_ptr, workspace_bytes, stream=0):
     arr = (Pair * max(len(pairs), 1))(*pairs)
     _check(lib().pf_score_ladder(arr, len(pairs), C.c_void_p(results_ptr), C.c_void_p(workspace_ptr), workspace_bytes,
                                  C.c_void_p(stream)))
+
+
+def score_all_workspace_bytes(n_pairs):
+    return lib().pf_score_all_workspace_bytes(n_pairs)
+
+
+def score_all(pairs, score_results_ptr, ladder_results_ptr, workspace_ptr, workspace_bytes, stream=0):
+    """Both results from one read of every pair: len(pairs) ScoreResult and len(pairs) LadderResult structs."""
+    arr = (Pair * max(len(pairs), 1))(*pairs)
+    _check(lib().pf_score_all(arr, len(pairs), C.c_void_p(score_results_ptr), C.c_void_p(ladder_results_ptr),
+                              C.c_void_p(workspace_ptr), workspace_bytes, C.c_void_p(stream)))
 
 
 def _cases(cases):

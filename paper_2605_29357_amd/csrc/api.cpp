@@ -366,22 +366,6 @@ pf_status pf_execute_timed(pf_exec* e, const void* const* d_inputs, int n_in, vo
 
 namespace {
 
-// Validates the pairs, orders them by dtype combination (each combination then
-// owns a contiguous block range) and uploads descriptors + block prefix into the
-// head of the workspace.  Returns where the per-pair scratch after them begins.
-struct StagedPairs {
-    pf::PairDev* d_pairs;
-    unsigned long long* d_start;
-    char* d_rest;
-    pf::ScoreRanges ranges;
-};
-
-size_t staged_head_bytes(int n_pairs) {
-    size_t b = ((size_t)n_pairs * sizeof(pf::PairDev) + 255) / 256 * 256;
-    return b + (((size_t)n_pairs + 1) * sizeof(unsigned long long) + 255) / 256 * 256;
-}
-
-// with_seeds: the single-level scorer, whose staging kernel also clears the slots and samples the seeds
 void check_pair(const pf_pair& p, int i) {
     if (p.cand_dtype != PF_F32 && p.cand_dtype != PF_BF16 && p.cand_dtype != PF_F16)
         pf::fail(PF_E_INVALID, "pair %d: candidate dtype must be f32, bf16 or f16", i);
@@ -392,150 +376,166 @@ void check_pair(const pf_pair& p, int i) {
     if (!(p.rtol >= 0.0) || !(p.atol >= 0.0)) pf::fail(PF_E_INVALID, "pair %d: tolerances must be >= 0", i);
 }
 
-// the seed parts of the single-level scorer follow its slots
-double* score_seeds(char* d_rest, int n_pairs) { return (double*)(d_rest + (size_t)n_pairs * pf::kScoreSlots * sizeof(pf_score_result)); }
-
-// mode 0: descriptors uploaded (the ladder); 1: uploaded, slots cleared, seeds sampled (the scorer);
-// 2: nothing launched, the single batch is handed back to the caller (a scoring call of few mid-size pairs)
-StagedPairs stage_pairs(const pf_pair* h_pairs, int n_pairs, void* d_workspace, void* stream, int mode,
-                        const int* caller_index = nullptr, pf::PairBatch* direct = nullptr) {
-    // the chunk follows the whole call: what counts is how many workgroups the call has, not each pair
-    unsigned long long call_elems = 0;
-    for (int i = 0; i < n_pairs; ++i) call_elems += h_pairs[i].n;
-    StagedPairs sp;
-    const size_t pairs_bytes = ((size_t)n_pairs * sizeof(pf::PairDev) + 255) / 256 * 256;
-    sp.d_pairs = (pf::PairDev*)d_workspace;
-    sp.d_start = (unsigned long long*)((char*)d_workspace + pairs_bytes);
-    sp.d_rest = (char*)d_workspace + staged_head_bytes(n_pairs);
-    for (int i = 0; i < n_pairs; ++i) check_pair(h_pairs[i], caller_index ? caller_index[i] : i);
-    std::vector<int> order(n_pairs);
-    for (int i = 0; i < n_pairs; ++i) order[i] = i;
-    auto combo = [&](int i) { return h_pairs[i].cand_dtype * 4 + h_pairs[i].ref_dtype; };
-    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return combo(a) < combo(b); });
-    memset(&sp.ranges, 0, sizeof sp.ranges);
-    unsigned long long total = 0;
-    for (int first = 0; first < n_pairs; first += pf::kPairBatch) {
-        pf::PairBatch b;
-        memset(&b, 0, sizeof b);
-        b.first = first;
-        b.count = n_pairs - first < pf::kPairBatch ? n_pairs - first : pf::kPairBatch;
-        b.last = first + b.count == n_pairs;
-        for (int k = 0; k < b.count; ++k) {
-            const pf_pair& p = h_pairs[order[first + k]];
-            b.pairs[k].cand = p.d_cand;
-            b.pairs[k].ref = p.d_ref;
-            b.pairs[k].n = p.n;
-            b.pairs[k].cand_dtype = p.cand_dtype;
-            b.pairs[k].ref_dtype = p.ref_dtype;
-            b.pairs[k].rtol = p.rtol;
-            b.pairs[k].atol = p.atol;
-            b.pairs[k].equal_nan = p.equal_nan;
-            b.pairs[k].orig = caller_index ? caller_index[order[first + k]] : order[first + k];
-            b.start[k] = total;
-            // unstaged calls are latency-bound: as many workgroups as the pair has slots, one vector per lane or more
-            unsigned long long chunk = pf::score_chunk_elems(call_elems);
-            if (mode == 2) chunk = std::max<unsigned long long>(2048, ((p.n + pf::kScoreSlots - 1) / pf::kScoreSlots + 2047) / 2048 * 2048);
-            b.pairs[k].chunk = chunk;
-            const unsigned long long nb = (p.n + chunk - 1) / chunk;
-            if (sp.ranges.count[p.cand_dtype][p.ref_dtype] == 0) sp.ranges.first[p.cand_dtype][p.ref_dtype] = total;
-            sp.ranges.count[p.cand_dtype][p.ref_dtype] += nb;
-            total += nb;
-        }
-        b.start[b.count] = total;
-        if (total >= (1ull << 31)) pf::fail(PF_E_INVALID, "too many elements for one scoring call");
-        if (mode == 2) {
-            *direct = b;
-            continue;
-        }
-        hipError_t err = mode == 1 ? pf::launch_score_stage(b, sp.d_pairs, sp.d_start, (pf_score_result*)sp.d_rest,
-                                                            score_seeds(sp.d_rest, n_pairs), (hipStream_t)stream)
-                                   : pf::launch_ladder_stage(b, sp.d_pairs, sp.d_start, (pf_ladder_result*)sp.d_rest, (hipStream_t)stream);
-        if (err != hipSuccess) pf::fail(PF_E_RUNTIME, "descriptor upload failed: %s", hipGetErrorString(err));
-    }
-    return sp;
+pf::PairDev descriptor(const pf_pair& p, int orig, unsigned long long chunk) {
+    pf::PairDev d;
+    memset(&d, 0, sizeof d);
+    d.cand = p.d_cand;
+    d.ref = p.d_ref;
+    d.n = p.n;
+    d.cand_dtype = p.cand_dtype;
+    d.ref_dtype = p.ref_dtype;
+    d.rtol = p.rtol;
+    d.atol = p.atol;
+    d.equal_nan = p.equal_nan;
+    d.orig = orig;
+    d.chunk = chunk;
+    return d;
 }
 
-void check_score_args(const void* h_pairs, int n_pairs, const void* d_results, void* d_workspace, size_t have, size_t want) {
+// Workspace: descriptors, workgroup prefix, tickets and seeds of the pairs, then 64 partial-result slots per pair
+// for each result wanted.  Every part is written by the staging launch before it is read: a workspace needs
+// no initialisation.
+struct WsLayout {
+    size_t pairs, start, tickets, seeds, sslots, lslots, total;
+};
+WsLayout ws_layout(int n_pairs, bool score, bool ladder) {
+    const size_t n = n_pairs < 0 ? 0 : (size_t)n_pairs;
+    auto up = [](size_t b) { return (b + 255) / 256 * 256; };
+    WsLayout w;
+    size_t at = 0;
+    w.pairs = at; at += up(n * sizeof(pf::PairDev));
+    w.start = at; at += up((n + 1) * sizeof(unsigned long long));
+    w.tickets = at; at += up(n * (pf::kScoreSlots + 1) * sizeof(unsigned int));
+    w.seeds = at; at += up(n * pf::kScoreSeedParts * 2 * sizeof(double));
+    w.sslots = at; if (score) at += up(n * pf::kScoreSlots * sizeof(pf_score_result));
+    w.lslots = at; if (ladder) at += up(n * pf::kScoreSlots * sizeof(pf_ladder_result));
+    w.total = at;
+    return w;
+}
+
+// One pass over the pairs for either result or both (d_score / d_ladder: NULL = not wanted).
+void score_impl(const pf_pair* h_pairs, int n_pairs, pf_score_result* d_score, pf_ladder_result* d_ladder, void* d_workspace,
+                size_t workspace_bytes, void* stream) {
     if (n_pairs < 0) pf::fail(PF_E_INVALID, "n_pairs < 0");
+    if (n_pairs == 0) return;
     need(h_pairs, "h_pairs");
-    need(d_results, "d_results");
+    if (!d_score && !d_ladder) pf::fail(PF_E_INVALID, "d_results is NULL");
+    for (int i = 0; i < n_pairs; ++i) check_pair(h_pairs[i], i);      // nothing is enqueued for an invalid batch
     need(d_workspace, "d_workspace");
-    if (have < want) pf::fail(PF_E_RUNTIME, "score workspace too small (%zu < %zu bytes)", have, want);
+    const WsLayout lay = ws_layout(n_pairs, d_score != nullptr, d_ladder != nullptr);
+    if (workspace_bytes < lay.total) pf::fail(PF_E_RUNTIME, "score workspace too small (%zu < %zu bytes)", workspace_bytes, lay.total);
     if ((uintptr_t)d_workspace & 255) pf::fail(PF_E_INVALID, "workspace is not 256-byte aligned");
+    const hipStream_t hs = (hipStream_t)stream;
+    pf::LadderTable table;
+    memset(&table, 0, sizeof table);
+    for (int dt : {(int)PF_F32, (int)PF_BF16, (int)PF_F16})
+        for (int k = 0; k < PF_LADDER_LEVELS; ++k) pf::tolerance_at((pf_dtype)dt, k - (PF_LADDER_LEVELS - 1), &table.rtol[dt][k], &table.atol[dt][k]);
+
+    // Small pairs take one workgroup each and a single launch per dtype combination; the others are staged
+    // (descriptors, cleared slots, seeds) and then walked by one launch per dtype combination.
+    std::vector<int> big, small[4][4];
+    const unsigned long long small_max = pf::score_small_pair_elems();
+    unsigned long long call_elems = 0;
+    for (int i = 0; i < n_pairs; ++i) {
+        const pf_pair& p = h_pairs[i];
+        if (p.n <= small_max) small[p.cand_dtype][p.ref_dtype].push_back(i);
+        else {
+            big.push_back(i);
+            call_elems += p.n;
+        }
+    }
+    if (!big.empty()) {
+        // ordered by dtype combination: each kernel instantiation then owns a contiguous range of workgroups
+        auto combo = [&](int i) { return h_pairs[i].cand_dtype * 4 + h_pairs[i].ref_dtype; };
+        std::stable_sort(big.begin(), big.end(), [&](int a, int b) { return combo(a) < combo(b); });
+        const int nb = (int)big.size();
+        const unsigned long long chunk = pf::score_chunk_elems(call_elems, d_ladder != nullptr);
+        unsigned long long call_chunks = 0;
+        for (int i : big) call_chunks += (h_pairs[i].n + chunk - 1) / chunk;
+        const unsigned long long target = pf::score_target_wgs(d_ladder != nullptr);
+        const unsigned long long chunks_per_wg = (call_chunks + target - 1) / target;
+        char* base = (char*)d_workspace;
+        pf::ScoreSpace sp;
+        sp.pairs = (pf::PairDev*)(base + lay.pairs);
+        sp.start = (unsigned long long*)(base + lay.start);
+        sp.tickets = (unsigned int*)(base + lay.tickets);
+        sp.seeds = (double*)(base + lay.seeds);
+        sp.sslots = d_score ? (pf_score_result*)(base + lay.sslots) : nullptr;
+        sp.lslots = d_ladder ? (pf_ladder_result*)(base + lay.lslots) : nullptr;
+        pf::ScoreRanges ranges;
+        memset(&ranges, 0, sizeof ranges);
+        unsigned long long total = 0;
+        pf::PairBatch b;
+        for (int first = 0; first < nb; first += pf::kPairBatch) {
+            memset(&b, 0, sizeof b);
+            b.first = first;
+            b.count = nb - first < pf::kPairBatch ? nb - first : pf::kPairBatch;
+            b.last = first + b.count == nb;
+            for (int k = 0; k < b.count; ++k) {
+                const pf_pair& p = h_pairs[big[first + k]];
+                b.pairs[k] = descriptor(p, big[first + k], chunk);
+                b.start[k] = total;
+                const unsigned long long nw = ((p.n + chunk - 1) / chunk + chunks_per_wg - 1) / chunks_per_wg;
+                b.pairs[k].wgs = nw;
+                if (ranges.count[p.cand_dtype][p.ref_dtype] == 0) ranges.first[p.cand_dtype][p.ref_dtype] = total;
+                ranges.count[p.cand_dtype][p.ref_dtype] += nw;
+                total += nw;
+            }
+            b.start[b.count] = total;
+            if (total >= (1ull << 31)) pf::fail(PF_E_INVALID, "internal: %llu workgroups", total);
+            hipError_t err = pf::launch_stage(b, sp, hs);
+            if (err != hipSuccess) pf::fail(PF_E_RUNTIME, "staging launch failed: %s", hipGetErrorString(err));
+        }
+        hipError_t err = pf::launch_pairs(sp, nb, ranges, table, d_score, d_ladder, hs);
+        if (err != hipSuccess) pf::fail(PF_E_RUNTIME, "score launch failed: %s", hipGetErrorString(err));
+    }
+    for (int cd = 0; cd < 4; ++cd)
+        for (int rd = 0; rd < 4; ++rd) {
+            const std::vector<int>& idx = small[cd][rd];
+            for (size_t first = 0; first < idx.size(); first += pf::kPairBatch) {
+                pf::PairBatch b;
+                memset(&b, 0, sizeof b);
+                b.count = (int)std::min<size_t>(pf::kPairBatch, idx.size() - first);
+                for (int k = 0; k < b.count; ++k) b.pairs[k] = descriptor(h_pairs[idx[first + k]], idx[first + k], 0);
+                hipError_t err = pf::launch_small(b, cd, rd, table, d_score, d_ladder, hs);
+                if (err != hipSuccess) pf::fail(PF_E_RUNTIME, "score launch failed: %s", hipGetErrorString(err));
+            }
+        }
 }
 
 }  // namespace
 
 extern "C" {
 
-static void score_impl(const pf_pair* h_pairs, int n_pairs, pf_score_result* d_results, void* d_workspace, size_t workspace_bytes,
-                       void* stream) {
-    {
-        if (n_pairs == 0) return;
-        check_score_args(h_pairs, n_pairs, d_results, d_workspace, workspace_bytes, pf_score_workspace_bytes(n_pairs));
-        // Small pairs take one workgroup each and a single launch per dtype combination; the others go
-        // through staging, the block-per-chunk kernels and the final fold.
-        for (int i = 0; i < n_pairs; ++i) check_pair(h_pairs[i], i);      // nothing is enqueued for an invalid batch
-        std::vector<pf_pair> big;
-        std::vector<int> big_index;
-        std::vector<int> small[4][4];
-        const unsigned long long small_max = pf::score_small_pair_elems();
-        for (int i = 0; i < n_pairs; ++i) {
-            const pf_pair& p = h_pairs[i];
-            const bool dt_ok = p.cand_dtype >= 0 && p.cand_dtype <= PF_F16 && p.ref_dtype >= 0 && p.ref_dtype <= PF_F16;
-            if (dt_ok && p.n <= small_max && pf::score_combo_supported(p.cand_dtype, p.ref_dtype)) small[p.cand_dtype][p.ref_dtype].push_back(i);
-            else {
-                big.push_back(p);
-                big_index.push_back(i);
-            }
-        }
-        // Few pairs of at most 64 chunks each need no staging launch: their descriptors travel as kernel
-        // arguments, every workgroup stores its partial result in a slot of its own and the fold reads
-        // only the slots that were written (two launches per call instead of three).
-        bool direct_ok = !big.empty() && (int)big.size() <= pf::kPairBatch;
-        for (auto& p : big)
-            if (p.n > (uint64_t)pf::kScoreSlots * 2048) direct_ok = false;       // 131072 elements: beyond, the staged route is as fast or faster
-        if (direct_ok) {
-            pf::PairBatch b;
-            StagedPairs sp = stage_pairs(big.data(), (int)big.size(), d_workspace, stream, 2, big_index.data(), &b);
-            hipError_t err = pf::launch_score_direct(b, sp.ranges, d_results, (pf_score_result*)sp.d_rest, (hipStream_t)stream);
-            if (err != hipSuccess) pf::fail(PF_E_RUNTIME, "score launch failed: %s", hipGetErrorString(err));
-        } else if (!big.empty()) {
-            StagedPairs sp = stage_pairs(big.data(), (int)big.size(), d_workspace, stream, 1, big_index.data());
-            hipError_t err = pf::launch_score(sp.d_pairs, sp.d_start, (int)big.size(), sp.ranges, d_results, (pf_score_result*)sp.d_rest,
-                                              score_seeds(sp.d_rest, (int)big.size()), (hipStream_t)stream);
-            if (err != hipSuccess) pf::fail(PF_E_RUNTIME, "score launch failed: %s", hipGetErrorString(err));
-        }
-        for (int cd = 0; cd < 4; ++cd)
-            for (int rd = 0; rd < 4; ++rd) {
-                const std::vector<int>& idx = small[cd][rd];
-                for (size_t first = 0; first < idx.size(); first += pf::kPairBatch) {
-                    pf::PairBatch b;
-                    memset(&b, 0, sizeof b);
-                    b.count = (int)std::min<size_t>(pf::kPairBatch, idx.size() - first);
-                    for (int k = 0; k < b.count; ++k) {
-                        const pf_pair& p = h_pairs[idx[first + k]];
-                        b.pairs[k].cand = p.d_cand;
-                        b.pairs[k].ref = p.d_ref;
-                        b.pairs[k].n = p.n;
-                        b.pairs[k].cand_dtype = p.cand_dtype;
-                        b.pairs[k].ref_dtype = p.ref_dtype;
-                        b.pairs[k].rtol = p.rtol;
-                        b.pairs[k].atol = p.atol;
-                        b.pairs[k].equal_nan = p.equal_nan;
-                        b.pairs[k].orig = idx[first + k];
-                        b.pairs[k].chunk = pf::score_chunk_elems(p.n);
-                    }
-                    hipError_t err = pf::launch_score_small(b, cd, rd, d_results, (hipStream_t)stream);
-                    if (err != hipSuccess) pf::fail(PF_E_RUNTIME, "score launch failed: %s", hipGetErrorString(err));
-                }
-            }
-    }
-}
+size_t pf_score_workspace_bytes(int n_pairs) { return ws_layout(n_pairs, true, false).total; }
+size_t pf_score_ladder_workspace_bytes(int n_pairs) { return ws_layout(n_pairs, false, true).total; }
+size_t pf_score_all_workspace_bytes(int n_pairs) { return ws_layout(n_pairs, true, true).total; }
 
 pf_status pf_score(const pf_pair* h_pairs, int n_pairs, pf_score_result* d_results, void* d_workspace, size_t workspace_bytes,
                    void* stream) {
-    return guarded([&] { score_impl(h_pairs, n_pairs, d_results, d_workspace, workspace_bytes, stream); });
+    return guarded([&] {
+        if (n_pairs > 0) need(d_results, "d_results");
+        score_impl(h_pairs, n_pairs, d_results, nullptr, d_workspace, workspace_bytes, stream);
+    });
+}
+
+pf_status pf_score_ladder(const pf_pair* h_pairs, int n_pairs, pf_ladder_result* d_results, void* d_workspace,
+                          size_t workspace_bytes, void* stream) {
+    return guarded([&] {
+        if (n_pairs > 0) need(d_results, "d_results");
+        score_impl(h_pairs, n_pairs, nullptr, d_results, d_workspace, workspace_bytes, stream);
+    });
+}
+
+pf_status pf_score_all(const pf_pair* h_pairs, int n_pairs, pf_score_result* d_score_results, pf_ladder_result* d_ladder_results,
+                       void* d_workspace, size_t workspace_bytes, void* stream) {
+    return guarded([&] {
+        if (n_pairs > 0) {
+            need(d_score_results, "d_score_results");
+            need(d_ladder_results, "d_ladder_results");
+        }
+        score_impl(h_pairs, n_pairs, d_score_results, d_ladder_results, d_workspace, workspace_bytes, stream);
+    });
 }
 
 pf_status pf_score_static(const pf_pair* h_pairs, int n_pairs, pf_score_result* d_results, void* stream) {
@@ -545,76 +545,14 @@ pf_status pf_score_static(const pf_pair* h_pairs, int n_pairs, pf_score_result* 
             pf::fail(PF_E_INVALID, "pf_score_static takes at most %d pairs per call (%d given); use pf_score with a workspace", PF_SCORE_STATIC_MAX_PAIRS,
                      n_pairs);
         if (n_pairs == 0) return;
+        need(d_results, "d_results");
         void* d_scratch = nullptr;
         size_t bytes = 0;
         hipError_t err = pf::static_scratch(&d_scratch, &bytes);
         if (err != hipSuccess) pf::fail(PF_E_RUNTIME, "address of the library's scratch array: %s", hipGetErrorString(err));
-        if (pf_score_workspace_bytes(n_pairs) > bytes)
-            pf::fail(PF_E_INVALID, "internal: %d pairs need %zu bytes of scratch, the library holds %zu", n_pairs, pf_score_workspace_bytes(n_pairs), bytes);
-        score_impl(h_pairs, n_pairs, d_results, d_scratch, bytes, stream);
-    });
-}
-
-size_t pf_score_workspace_bytes(int n_pairs) {
-    if (n_pairs < 0) n_pairs = 0;
-    return staged_head_bytes(n_pairs) + (size_t)n_pairs * pf::kScoreSlots * sizeof(pf_score_result) +
-           (size_t)n_pairs * pf::kScoreSeedParts * 2 * sizeof(double);
-}
-
-size_t pf_score_ladder_workspace_bytes(int n_pairs) {
-    if (n_pairs < 0) n_pairs = 0;
-    return staged_head_bytes(n_pairs) + (size_t)n_pairs * pf::kScoreSlots * sizeof(pf_ladder_result);
-}
-
-pf_status pf_score_ladder(const pf_pair* h_pairs, int n_pairs, pf_ladder_result* d_results, void* d_workspace,
-                          size_t workspace_bytes, void* stream) {
-    return guarded([&] {
-        if (n_pairs == 0) return;
-        check_score_args(h_pairs, n_pairs, d_results, d_workspace, workspace_bytes, pf_score_ladder_workspace_bytes(n_pairs));
-        for (int i = 0; i < n_pairs; ++i) check_pair(h_pairs[i], i);
-        pf::LadderTable table;
-        memset(&table, 0, sizeof table);
-        for (int dt : {(int)PF_F32, (int)PF_BF16, (int)PF_F16})
-            for (int k = 0; k < PF_LADDER_LEVELS; ++k) pf::tolerance_at((pf_dtype)dt, k - (PF_LADDER_LEVELS - 1), &table.rtol[dt][k], &table.atol[dt][k]);
-        // small pairs: one workgroup each, one launch per dtype combination; the others: staging, chunk kernels, fold
-        std::vector<pf_pair> big;
-        std::vector<int> big_index;
-        std::vector<int> small[4][4];
-        for (int i = 0; i < n_pairs; ++i) {
-            const pf_pair& p = h_pairs[i];
-            if (p.n <= pf::score_small_pair_elems()) small[p.cand_dtype][p.ref_dtype].push_back(i);
-            else {
-                big.push_back(p);
-                big_index.push_back(i);
-            }
-        }
-        if (!big.empty()) {
-            StagedPairs sp = stage_pairs(big.data(), (int)big.size(), d_workspace, stream, 0, big_index.data());
-            hipError_t err = pf::launch_ladder(sp.d_pairs, sp.d_start, (int)big.size(), sp.ranges, table, d_results,
-                                               (pf_ladder_result*)sp.d_rest, (hipStream_t)stream);
-            if (err != hipSuccess) pf::fail(PF_E_RUNTIME, "ladder launch failed: %s", hipGetErrorString(err));
-        }
-        for (int cd = 0; cd < 4; ++cd)
-            for (int rd = 0; rd < 4; ++rd) {
-                const std::vector<int>& idx = small[cd][rd];
-                for (size_t first = 0; first < idx.size(); first += pf::kPairBatch) {
-                    pf::PairBatch b;
-                    memset(&b, 0, sizeof b);
-                    b.count = (int)std::min<size_t>(pf::kPairBatch, idx.size() - first);
-                    for (int k = 0; k < b.count; ++k) {
-                        const pf_pair& p = h_pairs[idx[first + k]];
-                        b.pairs[k].cand = p.d_cand;
-                        b.pairs[k].ref = p.d_ref;
-                        b.pairs[k].n = p.n;
-                        b.pairs[k].cand_dtype = p.cand_dtype;
-                        b.pairs[k].ref_dtype = p.ref_dtype;
-                        b.pairs[k].equal_nan = p.equal_nan;
-                        b.pairs[k].orig = idx[first + k];
-                    }
-                    hipError_t err = pf::launch_ladder_small(b, cd, rd, table, d_results, (hipStream_t)stream);
-                    if (err != hipSuccess) pf::fail(PF_E_RUNTIME, "ladder launch failed: %s", hipGetErrorString(err));
-                }
-            }
+        const size_t want = ws_layout(n_pairs, true, false).total;
+        if (want > bytes) pf::fail(PF_E_INVALID, "internal: %d pairs need %zu bytes of scratch, the library holds %zu", n_pairs, want, bytes);
+        score_impl(h_pairs, n_pairs, d_results, nullptr, d_scratch, bytes, stream);
     });
 }
 

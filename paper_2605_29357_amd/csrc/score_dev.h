@@ -15,7 +15,8 @@ struct PairDev {
     double rtol, atol;
     int equal_nan;
     int orig;               // index of this pair in the caller's array
-    unsigned long long chunk;   // elements per workgroup
+    unsigned long long chunk;   // elements per chunk (a multiple of 2048)
+    unsigned long long wgs;     // workgroups of this pair: workgroup w walks chunks w, w + wgs, w + 2 wgs, ...
 };
 
 // blocks of each (candidate dtype, reference dtype) combination, indexed by pf_dtype: a contiguous range
@@ -32,18 +33,25 @@ inline bool score_combo_supported(int cd, int rd) {
     return true;
 }
 
-constexpr int kScoreSlots = 64;   // partial result slots per pair
+constexpr int kScoreSlots = 64;       // partial result slots per pair (spread the atomics of its workgroups)
 constexpr int kScoreSeedParts = 16;   // sampled maxima per pair (two doubles each), folded by every reader
-
-// up to kPairBatch descriptors passed by value to the staging kernel (kernel arguments are limited to 4 KB)
-constexpr int kPairBatch = 48;
-struct PairBatch {
-    PairDev pairs[kPairBatch];
-    unsigned long long start[kPairBatch + 1];   // first block of each pair (+ total when last)
-    int first, count, last, pad_;
+// Where the parts of a call's workspace lie (device pointers; sslots / lslots are NULL when that result is not wanted).
+struct ScoreSpace {
+    struct PairDev* pairs;            // [n_pairs] descriptors, ordered by dtype combination
+    unsigned long long* start;        // [n_pairs + 1] first workgroup of each pair
+    unsigned int* tickets;            // [n_pairs][1 + kScoreSlots] finished: slots of the pair, workgroups of each slot
+    double* seeds;                    // [n_pairs][kScoreSeedParts][2]
+    pf_score_result* sslots;          // [n_pairs][kScoreSlots]
+    pf_ladder_result* lslots;         // [n_pairs][kScoreSlots]
 };
 
-static_assert(sizeof(PairBatch) + 64 <= 4096, "a batch of descriptors and the other kernel arguments must fit in 4 KB");
+// up to kPairBatch descriptors passed by value to a kernel (kernel arguments are limited to 4 KB)
+constexpr int kPairBatch = 42;
+struct PairBatch {
+    PairDev pairs[kPairBatch];
+    unsigned long long start[kPairBatch + 1];   // first workgroup of each pair (+ total when last)
+    int first, count, last, pad_;
+};
 
 // tolerances of every ladder level, per candidate dtype (indexed by pf_dtype; the f64 row is unused)
 struct LadderTable {
@@ -56,26 +64,20 @@ struct LadderRow {
     double rtol[PF_LADDER_LEVELS];
     double atol[PF_LADDER_LEVELS];
 };
-static_assert(sizeof(PairBatch) + sizeof(LadderRow) + 64 <= 4096, "batch + tolerances must fit the kernel arguments");
 
-unsigned long long score_chunk_elems(unsigned long long n);
-hipError_t launch_ladder_stage(const PairBatch& batch, PairDev* d_pairs, unsigned long long* d_block_start, pf_ladder_result* d_slots,
-                               hipStream_t stream);
-hipError_t launch_ladder_small(const PairBatch& batch, int cd, int rd, const LadderTable& table, pf_ladder_result* d_results,
-                               hipStream_t stream);
-hipError_t launch_ladder(const PairDev* d_pairs, const unsigned long long* d_block_start, int n_pairs, const ScoreRanges& ranges,
-                         const LadderTable& table, pf_ladder_result* d_results, pf_ladder_result* d_slots, hipStream_t stream);
-// descriptor upload, slot clearing and seeding of one batch in a single launch (the single-level scorer)
-hipError_t launch_score_stage(const PairBatch& batch, PairDev* d_pairs, unsigned long long* d_block_start, pf_score_result* d_slots,
-                              double* d_seeds, hipStream_t stream);
-hipError_t launch_score(const PairDev* d_pairs, const unsigned long long* d_block_start, int n_pairs, const ScoreRanges& ranges,
-                        pf_score_result* d_results, pf_score_result* d_slots, const double* d_seeds, hipStream_t stream);
+static_assert(sizeof(PairBatch) + sizeof(LadderRow) + 128 <= 4096, "a batch of descriptors, the tolerances and the other kernel arguments must fit in 4 KB");
+
+unsigned long long score_chunk_elems(unsigned long long call_elems, bool ladder);
+unsigned long long score_target_wgs(bool ladder);
 // pairs of at most score_small_pair_elems() elements: one workgroup per pair, results written directly
 unsigned long long score_small_pair_elems();
-hipError_t launch_score_small(const PairBatch& batch, int cd, int rd, pf_score_result* d_results, hipStream_t stream);
-// at most kPairBatch pairs of at most kScoreSlots chunks each, descriptors as kernel arguments: main kernels + fold
-hipError_t launch_score_direct(const PairBatch& batch, const ScoreRanges& ranges, pf_score_result* d_results, pf_score_result* d_slots,
-                               hipStream_t stream);
+// descriptors, cleared slots and tickets, and seeds of one batch of pairs, in one launch
+hipError_t launch_stage(const PairBatch& batch, const ScoreSpace& sp, hipStream_t stream);
+// the walking kernels (one launch per dtype combination present); d_sres / d_lres: either may be NULL
+hipError_t launch_pairs(const ScoreSpace& sp, int n_pairs, const ScoreRanges& ranges, const LadderTable& table, pf_score_result* d_sres,
+                        pf_ladder_result* d_lres, hipStream_t stream);
+hipError_t launch_small(const PairBatch& batch, int cd, int rd, const LadderTable& table, pf_score_result* d_sres, pf_ladder_result* d_lres,
+                        hipStream_t stream);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
 
 // The workspace of pf_score_static: an array inside the library's code object.  Looks its address up

@@ -171,3 +171,18 @@ def ladder_on_gpu(pairs_spec, stream=None):
     s.synchronize()
     check_all_guards()
     return [(lr.n, list(lr.n_viol)) for lr in read_structs(res, pf.LadderResult, n)]
+
+
+def score_all_on_gpu(pairs_spec, stream=None):
+    """Both results from one pass (pf_score_all): pairs_spec as for score_on_gpu.  Returns (score dicts, ladder tuples)."""
+    n = len(pairs_spec)
+    pairs = make_pairs(pairs_spec)
+    sres, _s = guarded_bytes(max(n, 1) * ctypes.sizeof(pf.ScoreResult), fill=0xEE)
+    lres, _l = guarded_bytes(max(n, 1) * ctypes.sizeof(pf.LadderResult), fill=0xEE)
+    ws, _w = guarded_bytes(max(pf.score_all_workspace_bytes(n), 256), fill=255)
+    s = stream if stream is not None else torch.cuda.current_stream()
+    pf.score_all(pairs, sres.data_ptr(), lres.data_ptr(), ws.data_ptr(), ws.numel(), s.cuda_stream)
+    s.synchronize()
+    check_all_guards()
+    return ([r.as_dict() for r in read_structs(sres, pf.ScoreResult, n)],
+            [(lr.n, list(lr.n_viol)) for lr in read_structs(lres, pf.LadderResult, n)])

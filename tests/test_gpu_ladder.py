@@ -4,7 +4,7 @@ import pytest
 import torch
 
 from oracle import metric
-from tests.device import ladder_on_gpu, to_device
+from tests.device import ladder_on_gpu, score_all_on_gpu, to_device
 from workloads import rng
 
 pytestmark = pytest.mark.gpu
@@ -77,3 +77,32 @@ def test_ladder_elements_at_the_edge_of_a_level_are_counted_exactly(cd, rd):
     got = ladder_on_gpu([(to_device(c, cd), cd, to_device(r, rd), rd, False)])[0]
     assert got[0] == c.size and got[1] == want, (got, want)
     assert 0 < want[-1] < want[0] < c.size
+
+
+def test_one_pass_gives_both_results_and_each_equals_the_oracle():
+    """pf_score_all: the single-level result and the eleven ladder counts from one read of every pair, on every
+    route (one workgroup per pair, chunks with descriptors by value, chunks with staged descriptors)."""
+    from oracle.score import score_pair
+    sizes = [0, 5, 8192, 8193, 70001, 300007, 1 << 20, 2500017]
+    combos = [("f32", "f32"), ("bf16", "bf16"), ("bf16", "f32"), ("f32", "f64"), ("f16", "f16"), ("f32", "bf16")]
+    store = {"f32": lambda x: x.astype(np.float32), "bf16": rng.round_to_bf16_bits, "f16": rng.round_to_f16_bits,
+             "f64": lambda x: x.astype(np.float64)}
+    for n_pairs in (len(sizes), 60):
+        specs, want_s, want_l = [], [], []
+        for k in range(n_pairs):
+            n = sizes[k % len(sizes)] if n_pairs == len(sizes) else [9000, 100, 40000, 8192, 131073][k % 5]
+            cd, rd = combos[k % len(combos)]
+            c64, r64 = _noisy(n, "f64", "f64", 700 + k)
+            c, r = store[cd](c64), store[rd](r64)
+            rtol, atol = [(1e-5, 1e-5), (2e-2, 1e-5), (0.0, 0.0)][k % 3]
+            en = bool(k & 1)
+            dc = to_device(c, cd) if n else torch.empty(0, device="cuda")
+            dr = to_device(r, rd) if n else torch.empty(0, device="cuda")
+            specs.append((dc, cd, dr, rd, rtol, atol, en))
+            with np.errstate(all="ignore"):
+                want_s.append(score_pair(c, cd, r, rd, rtol, atol, en))
+                want_l.append((n, [score_pair(c, cd, r, rd, *metric.tolerance(cd, t), en)["n_viol"] for t in metric.LADDER]))
+        got_s, got_l = score_all_on_gpu(specs)
+        for k in range(n_pairs):
+            assert got_s[k] == want_s[k], (n_pairs, k, specs[k][1], specs[k][3], got_s[k], want_s[k])
+            assert got_l[k][0] == want_l[k][0] and got_l[k][1] == want_l[k][1], (n_pairs, k, specs[k][1], specs[k][3], got_l[k], want_l[k])
