@@ -199,8 +199,38 @@ pf_status pf_compile(const pf_graph* g, const pf_options* h_opt, pf_exec** e) {
         ex->opt = opt;
         // fused plans work on a rewritten copy (transposes of computed values pushed down to the operands)
         pf_graph work;
-        if (opt.fuse) pf::sink_transposes(*g, opt, work);
-        else work = *g;
+        if (opt.fuse) {
+            // Reductions that could run in their sources' orientation instead of behind a transpose: plan with and
+            // without each and keep what the traffic model prefers (bytes moved, plus what a kernel costs at least
+            // expressed in bytes: about 4 us at the copy rate).
+            const std::vector<int> sites = pf::column_reduction_sites(*g, opt);
+            auto cost_of = [&](const std::vector<int>& chosen) {
+                pf_graph w;
+                pf::Plan p;
+                pf::sink_transposes(*g, opt, chosen, w);
+                pf::make_plan(w, opt, p);
+                return pf::plan_cost(p);
+            };
+            std::vector<int> best;
+            if (!sites.empty()) {
+                uint64_t best_cost = cost_of(best);
+                const uint64_t all_cost = cost_of(sites);
+                if (all_cost < best_cost) { best = sites; best_cost = all_cost; }
+                // one site at a time, from whichever end is ahead
+                for (int s : sites) {
+                    std::vector<int> trial = best;
+                    auto it = std::find(trial.begin(), trial.end(), s);
+                    if (it == trial.end()) trial.push_back(s);
+                    else trial.erase(it);
+                    std::sort(trial.begin(), trial.end());
+                    const uint64_t c = cost_of(trial);
+                    if (c < best_cost) { best = trial; best_cost = c; }
+                }
+            }
+            pf::sink_transposes(*g, opt, best, work);
+        } else {
+            work = *g;
+        }
         pf::make_plan(work, opt, ex->plan);
         int idx = 0;
         for (auto& grp : ex->plan.groups) {

@@ -708,7 +708,11 @@ struct Emit {
             grp.scratch_bytes = (uint64_t)blocks * n_red * W * (precise ? 8 : 4);
             grp.kernel2_name = grp.kernel_name + "_fin";
             grp.grid2 = tiles;
-            grp.block2 = W < 64 ? 64 : W;
+            // the combining kernel: W columns x KP lanes along the partial results (all powers of two)
+            int KP = 1;
+            while (KP * 2 <= SP && W * KP * 2 <= 1024) KP <<= 1;
+            while (W * KP < 64) KP <<= 1;
+            grp.block2 = W * KP;
         }
         // operands that do not change along S are loaded once
         hoisted.clear();
@@ -911,21 +915,37 @@ struct Emit {
         signature(strf("const %s* __restrict__ scratch", acc));
         grp.kernel_name = name1;
         grp.block = block1;
-        line(strf("    constexpr int W = %d, SP = %d, NRED = %d, BLOCK = %d;", W, SP, n_red, grp.block2));
+        line(strf("    constexpr int W = %d, SP = %d, NRED = %d, BLOCK = %d, KP = BLOCK / W;", W, SP, n_red, grp.block2));
         line(strf("    constexpr %s DD = %lld, CT = %lld;", idx_t(), (long long)DD, (long long)CT));
         line(strf("    const %s tile = blockIdx.x, ct = tile %% CT, lead = tile / CT;", idx_t()));
         emit_lead_decomposition("lead", nlead);
-        line("    for (int c = threadIdx.x; c < W; c += BLOCK) {");
-        line(strf("        %s fin[NRED];", acc));
+        // lane (kk, c) folds partial results kk, kk + KP, ... of column c; LDS then folds the KP lanes of a column
+        line(strf("    __shared__ %s red[NRED][KP][W];", acc));
+        line("    {");
+        line("        const int c = threadIdx.x % W, kk = threadIdx.x / W;");
         for (int id : grp.nodes) {
             const Node& n = g.nodes[id];
             if (!is_reduction(n.op)) continue;
             const int sl = slot_of.at(id);
             const std::string at = strf("scratch[(((%s)tile * SP + k) * NRED + %d) * W + c]", idx_t(), sl);
             if (n.op == PF_OP_MAX)
-                line(strf("        { float t = -__builtin_inff(); for (int k = 0; k < SP; ++k) t = pf_max_nan(t, (float)%s); fin[%d] = t; }", at.c_str(), sl));
+                line(strf("        { float t = -__builtin_inff(); _Pragma(\"unroll 4\") for (int k = kk; k < SP; k += KP) t = pf_max_nan(t, (float)%s); red[%d][kk][c] = t; }",
+                          at.c_str(), sl));
             else
-                line(strf("        { %s t = 0; for (int k = 0; k < SP; ++k) t += %s; fin[%d] = t; }", acc, at.c_str(), sl));
+                line(strf("        { %s t = 0; _Pragma(\"unroll 4\") for (int k = kk; k < SP; k += KP) t += %s; red[%d][kk][c] = t; }", acc, at.c_str(), sl));
+        }
+        line("    }");
+        line("    __syncthreads();");
+        line("    for (int c = threadIdx.x; c < W; c += BLOCK) {");
+        line(strf("        %s fin[NRED];", acc));
+        for (int id : grp.nodes) {
+            const Node& n = g.nodes[id];
+            if (!is_reduction(n.op)) continue;
+            const int sl = slot_of.at(id);
+            if (n.op == PF_OP_MAX)
+                line(strf("        { float t = (float)red[%d][0][c]; for (int q = 1; q < KP; ++q) t = pf_max_nan(t, (float)red[%d][q][c]); fin[%d] = t; }", sl, sl, sl));
+            else
+                line(strf("        { %s t = red[%d][0][c]; for (int q = 1; q < KP; ++q) t += red[%d][q][c]; fin[%d] = t; }", acc, sl, sl, sl));
         }
         emit_epilogue([](int sl) { return strf("fin[%d]", sl); });
         line("    }");

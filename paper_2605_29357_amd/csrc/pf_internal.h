@@ -57,6 +57,7 @@ struct Node {
     int orig = -1;                 // the user's node this one computes (a value recomputed in the other orientation keeps it)
     std::vector<char> alias_t;     // per operand: read through a swap of its last two dims that moves no data
     bool reads_alias(size_t k) const { return k < alias_t.size() && alias_t[k]; }
+    bool col_prologue = false;     // computed for a column reduction in its sources' orientation: belongs in that reduction's kernel
 };
 
 }  // namespace pf
@@ -164,9 +165,16 @@ struct Plan {
 };
 
 void make_plan(const pf_graph& g, const pf_options& opt, Plan& plan);
+// What a plan costs under the traffic model: bytes moved, plus for each kernel what a launch costs at least,
+// expressed in bytes (about 4 us at the rate of a plain copy).
+constexpr uint64_t kLaunchCostBytes = 24u << 20;
+uint64_t plan_cost(const Plan& plan);
 
 // ---- rewrite.cpp ----
-void sink_transposes(const pf_graph& g, const pf_options& opt, pf_graph& out);
+// `sites`: reductions over the last dim (caller's node ids, from column_reduction_sites) to run as reductions
+// over dim -2 of their operand's cone, evaluated in the orientation its sources have in memory
+void sink_transposes(const pf_graph& g, const pf_options& opt, const std::vector<int>& sites, pf_graph& out);
+std::vector<int> column_reduction_sites(const pf_graph& g, const pf_options& opt);
 
 // ---- codegen.cpp ----
 void generate_source(const pf_graph& g, const pf_options& opt, Group& grp, int index);

@@ -15,9 +15,10 @@
 //     elementwise nodes on the reduced ("column-uniform") shape.
 // Boundaries fall where the domain changes (a transpose of a value computed in
 // the same kernel, a broadcast that grows the shape) and where a reduction
-// would have to join a tiled group.  Groups are numbered in execution order;
-// a node only ever joins a group at or after the groups of all its producers,
-// so the group graph is acyclic by construction.
+// would have to join a tiled group.  A node may join any group that does not
+// come to depend on itself that way (the groups its operands live in must not
+// need anything the group computes); the groups are put in execution order at
+// the end.
 #include <algorithm>
 #include <cstring>
 
@@ -66,6 +67,42 @@ struct Builder {
     };
     std::vector<int> kind_of;                   // per node, kind inside its group
     std::vector<G> groups;
+    std::vector<std::vector<int>> needs;        // per group: the groups it reads values from
+    bool join_earlier = true;                   // a node may join the group of any operand, not only the latest of them
+
+    // does group a need, directly or through others, something group b computes?
+    bool depends(int a, int b) const {
+        std::vector<int> todo = {a};
+        std::vector<char> seen(groups.size(), 0);
+        while (!todo.empty()) {
+            const int x = todo.back();
+            todo.pop_back();
+            if (x == b) return true;
+            if (seen[x]) continue;
+            seen[x] = 1;
+            for (int y : needs[x]) todo.push_back(y);
+        }
+        return false;
+    }
+    // groups node id reads from (through a view: the group of the tensor it finally reads)
+    std::vector<int> producer_groups(int id) const {
+        std::vector<int> r;
+        auto add = [&](int p) {
+            if (group_of[p] >= 0 && std::find(r.begin(), r.end(), group_of[p]) == r.end()) r.push_back(group_of[p]);
+        };
+        for (int p : g.nodes[id].in) {
+            add(p);
+            if (is_view(g.nodes[p].op)) add(root_of(p));
+        }
+        if (is_view(g.nodes[id].op)) add(root_of(id));
+        return r;
+    }
+    // would the groups still have an execution order with node id in group gi?
+    bool keeps_order(int id, int gi) const {
+        for (int gp : producer_groups(id))
+            if (gp != gi && depends(gp, gi)) return false;
+        return true;
+    }
 
     Builder(const pf_graph& gr, const pf_options& o) : g(gr), opt(o) {
         group_of.assign(g.nodes.size(), -1);
@@ -125,6 +162,7 @@ struct Builder {
         const Node& n = g.nodes[id];
         const G& grp = groups[gi];
         if (grp.nodes.size() >= 60) return false;
+        if (!keeps_order(id, gi)) return false;
         {
             size_t extra = 0;
             for (int p : transposed_reads(n))
@@ -133,6 +171,8 @@ struct Builder {
         }
         for (int p : n.in)
             if (group_of[p] == gi && !usable_in_kernel(p)) return false;
+        // the prologue of a column reduction stays where that reduction can follow it
+        if (n.col_prologue && ((grp.tmpl != PF_T_EW_FLAT && grp.tmpl != PF_T_COL_REDUCE) || grp.has_rowuni || grp.has_view)) return false;
         for (size_t k = 0; k < n.in.size(); ++k)               // read in the other orientation: from memory only
             if (n.reads_alias(k) && group_of[n.in[k]] == gi) return false;
         if (is_col_reduction(n)) {
@@ -170,6 +210,8 @@ struct Builder {
         }
         if (is_reduction(n.op)) {
             if (grp.tmpl == PF_T_TILE) return false;
+            for (int m : grp.nodes)
+                if (g.nodes[m].col_prologue) return false;
             const Node& x = g.nodes[n.in[0]];
             return canon(x.shape) == grp.domain && !grp.domain.empty();
         }
@@ -179,7 +221,7 @@ struct Builder {
             // the node's own shape is the domain
             return true;
         }
-        if (k == 1) return grp.tmpl == PF_T_ROW_RESIDENT || grp.tmpl == PF_T_ROW_LOOP;
+        if (k == 1) return grp.tmpl == PF_T_ROW_RESIDENT || grp.tmpl == PF_T_ROW_LOOP;   // (never holds prologue nodes: see above)
         return false;
     }
 
@@ -197,6 +239,8 @@ struct Builder {
     void join(int id, int gi) {
         const Node& n = g.nodes[id];
         G& grp = groups[gi];
+        for (int gp : producer_groups(id))
+            if (gp != gi && std::find(needs[gi].begin(), needs[gi].end(), gp) == needs[gi].end()) needs[gi].push_back(gp);
         grp.nodes.push_back(id);
         group_of[id] = gi;
         for (int p : transposed_reads(n))
@@ -230,6 +274,7 @@ struct Builder {
         else if (is_reduction(n.op)) grp.domain = canon(g.nodes[n.in[0]].shape);
         else grp.domain = canon(n.shape);
         groups.push_back(grp);
+        needs.emplace_back();
         join(id, (int)groups.size() - 1);
     }
 
@@ -241,23 +286,56 @@ struct Builder {
                 seed((int)i);
                 continue;
             }
-            int cand = -1;
-            for (int p : n.in) {
-                cand = std::max(cand, group_of[p]);
-                if (is_view(g.nodes[p].op)) cand = std::max(cand, group_of[root_of(p)]);
-            }
-            if (is_view(n.op)) cand = std::max(cand, group_of[root_of((int)i)]);
-            int last = (int)groups.size() - 1;
+            // first choice: the latest group an operand lives in; then the other operands' groups (a group may come
+            // to run after one numbered higher, as long as no cycle arises); then any later group, preferring one
+            // that already reads an operand of this node, which saves its bytes (not for a transpose: it is pure
+            // data movement and belongs with its readers, which come next)
+            std::vector<int> from = producer_groups((int)i);
+            std::sort(from.begin(), from.end(), [](int a, int b) { return a > b; });
+            const int cand = from.empty() ? -1 : from[0];
+            const int last = (int)groups.size() - 1;
             int pick = -1;
-            if (cand >= 0 && can_join((int)i, cand)) pick = cand;
-            // otherwise any later group will do; one that already reads an operand of this node saves its bytes
-            // (not for a transpose: it is pure data movement and belongs with its readers, which come next)
+            for (size_t k = 0; k < (join_earlier ? from.size() : std::min<size_t>(from.size(), 1)) && pick < 0; ++k)
+                if (can_join((int)i, from[k])) pick = from[k];
             for (int gi = last; gi > cand && pick < 0 && n.op != PF_OP_TRANSPOSE; --gi)
                 if (shares_operand((int)i, gi) && can_join((int)i, gi)) pick = gi;
             if (pick < 0 && last > cand && can_join((int)i, last)) pick = last;
             if (pick >= 0) join((int)i, pick);
             else seed((int)i);
         }
+        put_in_execution_order();
+    }
+
+    // renumbers the groups so that each comes after the groups it reads from (lowest old number first among the ready ones)
+    void put_in_execution_order() {
+        const int n = (int)groups.size();
+        std::vector<int> order, pos(n, -1);
+        std::vector<char> done(n, 0);
+        while ((int)order.size() < n) {
+            int pick = -1;
+            for (int gi = 0; gi < n && pick < 0; ++gi) {
+                if (done[gi]) continue;
+                bool ready = true;
+                for (int y : needs[gi]) ready &= done[y] != 0;
+                if (ready) pick = gi;
+            }
+            if (pick < 0) fail(PF_E_COMPILE, "internal: kernel groups depend on each other in a cycle");
+            done[pick] = 1;
+            pos[pick] = (int)order.size();
+            order.push_back(pick);
+        }
+        std::vector<G> sorted;
+        std::vector<std::vector<int>> sorted_needs;
+        for (int gi : order) {
+            sorted.push_back(groups[gi]);
+            std::vector<int> nd;
+            for (int y : needs[gi]) nd.push_back(pos[y]);
+            sorted_needs.push_back(nd);
+        }
+        groups.swap(sorted);
+        needs.swap(sorted_needs);
+        for (int& go : group_of)
+            if (go >= 0) go = pos[go];
     }
 };
 
@@ -265,11 +343,11 @@ uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
 
 }  // namespace
 
-void make_plan(const pf_graph& g, const pf_options& opt, Plan& plan) {
-    if (g.outputs.empty()) fail(PF_E_COMPILE, "graph has no outputs");
-    for (int o : g.outputs)
-        if (g.nodes[o].op == PF_OP_INPUT) fail(PF_E_COMPILE, "output %%%d is a graph input; nothing to compute", o);
+namespace {
+
+void plan_with(const pf_graph& g, const pf_options& opt, bool join_earlier, Plan& plan) {
     Builder b(g, opt);
+    b.join_earlier = join_earlier;
     b.run();
 
     const size_t nn = g.nodes.size();
@@ -457,7 +535,7 @@ void make_plan(const pf_graph& g, const pf_options& opt, Plan& plan) {
                 const int p = n.in[k];
                 if (g.nodes[p].op == PF_OP_CONST) continue;
                 bool inside = b.group_of[p] == (int)gi && b.usable_in_kernel(p);
-                if (n.op == PF_OP_TRANSPOSE || n.reads_alias(k)) add_operand(p, true);
+                if (n.op == PF_OP_TRANSPOSE || n.reads_alias(k)) add_operand(p, true, epilogue_node && n.op != PF_OP_TRANSPOSE);
                 else if (inside) continue;
                 else if (is_view(g.nodes[p].op)) add_view_operand(p);
                 else add_operand(p, false, epilogue_node);
@@ -500,13 +578,22 @@ void make_plan(const pf_graph& g, const pf_options& opt, Plan& plan) {
                 grp.stores.push_back(s);
                 mem_dtype[id] = n.dtype;
             }
-            // a second, full-precision copy when later kernels need the value and
-            // the output buffer would round it
-            const bool need_ws = outside_use && (!n.is_output || (opt.intermediates_f32 && n.dtype != PF_F32));
+            // Later kernels read a value in fp32 (a second copy beside a 16-bit output: averaging the rounded values of
+            // an output instead fails the tolerance where the average nearly cancels), unless every reader is a
+            // transpose that is a graph output of this node's own 16-bit dtype: rounding before or after the move gives
+            // the same bits.
+            bool only_moved = n.dtype != PF_F32 && n.dtype != PF_F64;
+            for (int c : b.consumers[id]) {
+                const Node& cn = g.nodes[c];
+                if (b.group_of[c] == (int)gi && b.usable_in_kernel(id) && cn.op != PF_OP_TRANSPOSE && !is_view(cn.op)) continue;   // reads it in-kernel
+                // (a transpose that is a graph output and nothing else: no arithmetic ever sees the moved value)
+                if (cn.op != PF_OP_TRANSPOSE || cn.dtype != n.dtype || !cn.is_output || !b.consumers[c].empty()) only_moved = false;
+            }
+            const bool need_ws = outside_use && (!n.is_output || (opt.intermediates_f32 && n.dtype != PF_F32 && !only_moved));
             if (need_ws) {
                 Store s;
                 s.node = id;
-                s.dtype = opt.intermediates_f32 ? PF_F32 : n.dtype;
+                s.dtype = (opt.intermediates_f32 && !only_moved) ? PF_F32 : n.dtype;
                 s.shape = n.shape;
                 s.row_scalar = row_scalar;
                 s.col_uniform = col_uniform;
@@ -524,6 +611,27 @@ void make_plan(const pf_graph& g, const pf_options& opt, Plan& plan) {
         plan.groups.push_back(std::move(grp));
     }
     plan.workspace_bytes = ws;
+}
+
+}  // namespace
+
+uint64_t plan_cost(const Plan& plan) {
+    uint64_t c = 0;
+    for (auto& grp : plan.groups) c += grp.bytes_read + grp.bytes_written + kLaunchCostBytes;
+    return c;
+}
+
+void make_plan(const pf_graph& g, const pf_options& opt, Plan& plan) {
+    if (g.outputs.empty()) fail(PF_E_COMPILE, "graph has no outputs");
+    for (int o : g.outputs)
+        if (g.nodes[o].op == PF_OP_INPUT) fail(PF_E_COMPILE, "output %%%d is a graph input; nothing to compute", o);
+    // The grouping is greedy, so neither way of choosing a node's group is always ahead: letting it join the group
+    // of any of its operands saves a kernel or a round trip in most graphs and costs one in a few.  Plan both ways.
+    plan_with(g, opt, true, plan);
+    if (!opt.fuse) return;
+    Plan other;
+    plan_with(g, opt, false, other);
+    if (plan_cost(other) < plan_cost(plan)) plan = std::move(other);
 }
 
 }  // namespace pf

@@ -11,6 +11,14 @@
 // LDS transpose like any transposed input.  A value needed in both orientations is
 // computed in both: recomputation costs arithmetic, the round trip costs HBM traffic.
 //
+// The same identity serves reductions: a reduction over the last dim of a value that only exists
+// transposed (an elementwise cone over transposed tensors) is a reduction over the second-to-last
+// dim of the cone evaluated in the tensors' own orientation, which a column-reduction kernel reads
+// straight from memory.  The result has the same linear order either way ([.., R, 1] against
+// [.., 1, R]), so its readers take it as it lies.  Whether that pays depends on what else needs the
+// transposed value, so the caller chooses the reductions to treat this way ("sites") by planning
+// both ways.
+//
 // The rewrite clones the elementwise cone above such a transpose, bounded by what
 // the recomputation reads compared with what the round trip would move, and drops
 // nodes nothing observes any more.  Every node of the rewritten graph remembers the
@@ -43,8 +51,12 @@ struct Sinker {
     pf_graph out;
     std::vector<int> map;              // old id -> new id of the same value
     std::map<int, int> tnode;          // old id -> new id of a node holding its transposed value
+    std::set<int> sites;               // reductions (old ids) to run as column reductions in their sources' orientation
+    std::set<int> standin;             // old ids whose new node has the last two dims swapped (same linear order)
+    bool in_site = false;              // cloning the cone of a column-reduction site
 
-    Sinker(const pf_graph& g, const pf_options& o) : src(g), opt(o), map(g.nodes.size(), -1) {}
+    Sinker(const pf_graph& g, const pf_options& o, const std::vector<int>& chosen = {})
+        : src(g), opt(o), map(g.nodes.size(), -1), sites(chosen.begin(), chosen.end()) {}
 
     int push(const Node& n) {
         out.nodes.push_back(n);
@@ -93,11 +105,56 @@ struct Sinker {
         return n_nodes <= 24 && n_full <= 3 && bytes <= saved;
     }
 
+    // Is transpose(x) computable without moving data: every full-size leaf of x's elementwise cone is itself a
+    // transpose (read plainly in the other orientation) and everything else is a constant or changes orientation
+    // in place?  n_t counts the transposes that disappear.
+    void free_cone(int x, std::set<int>& seen, int& n_nodes, int& n_t, bool& ok) const {
+        if (!seen.insert(x).second) return;
+        const Node& n = src.nodes[x];
+        if (n.op == PF_OP_CONST || n.shape.empty()) return;
+        if (n.op == PF_OP_TRANSPOSE && src.nodes[n.in[0]].shape.size() >= 2) {
+            if (!moves_no_data(n.shape)) ++n_t;
+            return;
+        }
+        if (moves_no_data(n.shape)) return;
+        if (sinkable_op(n.op) && n.shape.size() >= 2) {
+            ++n_nodes;
+            for (int p : n.in) free_cone(p, seen, n_nodes, n_t, ok);
+            return;
+        }
+        ok = false;
+    }
+
+    // May reduction i (over the last dim) run as a reduction over dim -2 of its operand's transposed cone?
+    bool site_possible(int i, const std::vector<std::vector<int>>& consumers) const {
+        const Node& n = src.nodes[i];
+        if (!is_reduction(n.op) || n.red_dim != -1) return false;
+        const Node& x = src.nodes[n.in[0]];
+        if (x.shape.size() < 2 || moves_no_data(x.shape)) return false;
+        std::set<int> seen;
+        int n_nodes = 0, n_t = 0;
+        bool ok = true;
+        free_cone(n.in[0], seen, n_nodes, n_t, ok);
+        if (!ok || n_t < 1 || n_nodes > 24) return false;
+        return readers_take_it_as_it_lies(i, consumers);
+    }
+
+    // Readers take such a result as it lies, and only elementwise ones are taught to; per-row arithmetic on it
+    // comes to lie the same way, so its readers are asked in turn.
+    bool readers_take_it_as_it_lies(int i, const std::vector<std::vector<int>>& consumers) const {
+        for (int c : consumers[i]) {
+            const Node& cn = src.nodes[c];
+            if (!sinkable_op(cn.op)) return false;
+            if (cn.shape.size() >= 2 && moves_no_data(cn.shape) && !readers_take_it_as_it_lies(c, consumers)) return false;
+        }
+        return true;
+    }
+
     Ref transposed(int x, bool top) {
         const Node& n = src.nodes[x];
         if (n.op == PF_OP_CONST || n.shape.empty()) return {map[x], false};
         if (n.op == PF_OP_TRANSPOSE && src.nodes[n.in[0]].shape.size() >= 2) return {map[n.in[0]], false};
-        if (moves_no_data(n.shape)) return {map[x], true};
+        if (moves_no_data(n.shape)) return {map[x], standin.count(x) == 0};      // a stand-in already lies the other way
         auto it = tnode.find(x);
         if (it != tnode.end()) return {it->second, false};
         int id;
@@ -105,6 +162,7 @@ struct Sinker {
             Node c = n;
             c.is_output = false;
             c.orig = x;
+            c.col_prologue = in_site;
             c.shape = swapped(n.shape);
             c.alias_t.assign(n.in.size(), 0);
             for (size_t k = 0; k < n.in.size(); ++k) {
@@ -151,9 +209,48 @@ struct Sinker {
                     continue;
                 }
             }
+            if (sites.count((int)i)) {
+                // reduce(x, last dim) = reduce(transpose(x), dim -2), with transpose(x) computed from x's sources as they lie
+                in_site = true;
+                const Ref r = transposed(n.in[0], false);
+                in_site = false;
+                Node c = n;
+                c.orig = (int)i;
+                c.in = {r.id};
+                c.alias_t.assign(1, r.alias ? 1 : 0);
+                c.red_dim = -2;
+                if (n.keepdim) {
+                    c.shape = swapped(n.shape);
+                    standin.insert((int)i);
+                }
+                map[i] = push(c);
+                continue;
+            }
             Node c = n;
             c.orig = (int)i;
-            for (size_t k = 0; k < c.in.size(); ++k) c.in[k] = map[c.in[k]];
+            bool reads_standin = false;
+            for (int p : n.in) reads_standin |= standin.count(p) != 0;
+            if (reads_standin && sinkable_op(n.op) && n.shape.size() >= 2 && moves_no_data(n.shape)) {
+                // arithmetic on such a result alone (one value per row, like the result): computed the way the result
+                // lies, so that it can finish in the reduction's kernel; it becomes a stand-in itself
+                c.shape = swapped(n.shape);
+                c.alias_t.assign(n.in.size(), 0);
+                for (size_t k = 0; k < n.in.size(); ++k) {
+                    const Node& pn = src.nodes[n.in[k]];
+                    c.alias_t[k] = (standin.count(n.in[k]) || pn.op == PF_OP_CONST || pn.shape.empty()) ? 0 : 1;
+                    c.in[k] = map[n.in[k]];
+                }
+                standin.insert((int)i);
+                map[i] = push(c);
+                continue;
+            }
+            for (size_t k = 0; k < c.in.size(); ++k) {
+                if (standin.count(c.in[k])) {          // same linear order, the last two dims named the other way round
+                    c.alias_t.resize(c.in.size(), 0);
+                    c.alias_t[k] = 1;
+                }
+                c.in[k] = map[c.in[k]];
+            }
             map[i] = push(c);
         }
         for (int i : src.inputs) out.inputs.push_back(map[i]);
@@ -185,11 +282,22 @@ struct Sinker {
 
 }  // namespace
 
-void sink_transposes(const pf_graph& g, const pf_options& opt, pf_graph& out) {
-    Sinker s(g, opt);
+void sink_transposes(const pf_graph& g, const pf_options& opt, const std::vector<int>& sites, pf_graph& out) {
+    Sinker s(g, opt, sites);
     s.run();
     s.prune();
     out = s.out;
+}
+
+std::vector<int> column_reduction_sites(const pf_graph& g, const pf_options& opt) {
+    Sinker s(g, opt);
+    std::vector<std::vector<int>> consumers(g.nodes.size());
+    for (size_t i = 0; i < g.nodes.size(); ++i)
+        for (int p : g.nodes[i].in) consumers[p].push_back((int)i);
+    std::vector<int> sites;
+    for (size_t i = 0; i < g.nodes.size(); ++i)
+        if (s.site_possible((int)i, consumers)) sites.push_back((int)i);
+    return sites;
 }
 
 }  // namespace pf

@@ -69,6 +69,7 @@ def _run_both(w, refs, kernels=None, template=None):
     uo = u.run()
     torch.cuda.synchronize()
     check_against_oracle(w, uo, refs=refs, what=w.name + " unfused")
+    return r
 
 
 @pytest.mark.parametrize("op", ["sum", "mean", "max", "var"])

@@ -150,10 +150,12 @@ def test_prefix_kernel_count_is_monotone_with_plateaus_inside_groups():
     s = g.op("sum", [h], "f32")
     y = g.op("div", [h, s], "f32")
     g.output(y)
+    # ... and the row sum of the transposed value is a column sum of tanh(exp(x)) in x's own orientation: no full-size
+    # value crosses kernels (x is read twice, y written once, the 96 sums go through memory)
     ex = pf.Exec(g.text())
-    assert [gi["template"] for gi in ex.groups()] == ["tile", "row_resident"]
-    assert [gi["nodes"] for gi in ex.groups()] == [[t, h], [s, y]]
-    assert ex.info()["planned_bytes"] == 64 * 96 * 4 * 4               # x in, tanh out and in, y out
+    assert [gi["template"] for gi in ex.groups()] == ["col_reduce", "tile"]
+    assert [gi["nodes"] for gi in ex.groups()] == [[e, h, s], [t, h, y]]
+    assert ex.info()["planned_bytes"] == 64 * 96 * 4 * 3 + 2 * 96 * 4
     assert pf.Exec(g.text(), fuse=False).info()["n_kernels"] == 5
     # a per-row statistic changes orientation without moving data: only the statistic itself crosses kernels
     g = Builder()
