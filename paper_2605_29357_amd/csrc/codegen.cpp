@@ -156,19 +156,12 @@ struct Emit {
                               a1.c_str()));
             return;
         }
-        // fp32 graphs divide by reciprocal estimate; a lane that met a divisor the estimate cannot serve repeats
-        // the operator exactly (see pf_div_est)
-        const bool est = precise && n.op == PF_OP_DIV;
-        auto est_expr = [&](const std::string& j) { return strf("pf_div_est(%s, %s, bad%d)", ref(id, n.in[0], j).c_str(), ref(id, n.in[1], j).c_str(), id); };
-        if (est) line(strf("    bool bad%d = false;", id));
         if (k == 2) {
             line(strf("    float v%d[%d];", id, RU * N));
-            line(loops + strf(" v%d[%s] = %s;", id, slot("j").c_str(), est ? est_expr("j").c_str() : expr("j").c_str()));
-            if (est) line(strf("    if (__builtin_expect(bad%d, 0)) {", id) + loops.substr(3) + strf(" v%d[%s] = %s; }", id, slot("j").c_str(), expr("j").c_str()));
+            line(loops + strf(" v%d[%s] = %s;", id, slot("j").c_str(), expr("j").c_str()));
         } else {
             line(strf("    float s%d[%d];", id, RU));
-            line(strf("    _Pragma(\"unroll\") for (int u = 0; u < %d; ++u) s%d[u] = %s;", RU, id, est ? est_expr("0").c_str() : expr("0").c_str()));
-            if (est) line(strf("    if (__builtin_expect(bad%d, 0)) { _Pragma(\"unroll\") for (int u = 0; u < %d; ++u) s%d[u] = %s; }", id, RU, id, expr("0").c_str()));
+            line(strf("    _Pragma(\"unroll\") for (int u = 0; u < %d; ++u) s%d[u] = %s;", RU, id, expr("0").c_str()));
         }
     }
 

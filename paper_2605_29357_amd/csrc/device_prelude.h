@@ -196,17 +196,17 @@ PF_DEV float pf_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
 // one-ulp estimates (v_rcp_f32, v_exp_f32) instead of the correctly rounded library routines, which cost
 // two to three times the instructions and would make these kernels bound by the vector ALU.
 //
-// a / b = a * (1/b): one ulp from the reciprocal, half an ulp from the product; zero, infinite and NaN operands
-// come out as the division defines them.  The reciprocal estimate flushes subnormal inputs and results, so
-// for a subnormal divisor or one of 2^126 and more the estimate is wrong: `bad` records that (zero, infinite
-// and NaN divisors are flagged with them, which costs nothing but the rare detour), and the caller then repeats
-// the operator with the correctly rounded division -- one test per operator and lane, not one per element,
-// so that the estimates of a lane's elements are scheduled together.
-PF_DEV float pf_div_est(float a, float b, bool& bad) {
-    bad |= ((pf_f2bits(b) & 0x7fffffffu) - 0x00800000u) >= 0x7e000000u;
-    return a * pf_rcp(b);
+// a / b = a * (1/b): one ulp from the reciprocal, half an ulp from the product.  The reciprocal estimate
+// flushes subnormal results and inputs, so divisors outside [2^-126, 2^126) take the correctly rounded
+// division, as do quotients that come out non-finite (the division defines what 0/0, x/0, inf/inf are).
+// (One test per element: collecting the tests of a lane's elements into a single branch per operator measured
+// 2-5 us slower on the subgraphs with several divisions.)
+PF_DEV float pf_div(float a, float b) {
+    const float q = a * pf_rcp(b);
+    const bool plain = (((pf_f2bits(b) & 0x7f800000u) - 0x00800000u) < 0x7e000000u) & (__builtin_fabsf(q) < __builtin_inff());
+    if (__builtin_expect(!plain, 0)) return a / b;
+    return q;
 }
-PF_DEV float pf_div(float a, float b) { return a / b; }
 // e^x = 2^(x log2 e): the product x log2 e is carried as two floats (its rounding error alone would cost
 // |x| * 1e-7 of relative accuracy) and the low part enters as a first-order correction.
 PF_DEV float pf_exp(float x) {

@@ -69,6 +69,7 @@ struct Builder {
     std::vector<G> groups;
     std::vector<std::vector<int>> needs;        // per group: the groups it reads values from
     bool join_earlier = true;                   // a node may join the group of any operand, not only the latest of them
+    bool prologue_apart = true;                 // the prologue of a column reduction avoids flat groups a row reduction may want
 
     // does group a need, directly or through others, something group b computes?
     bool depends(int a, int b) const {
@@ -172,7 +173,18 @@ struct Builder {
         for (int p : n.in)
             if (group_of[p] == gi && !usable_in_kernel(p)) return false;
         // the prologue of a column reduction stays where that reduction can follow it
-        if (n.col_prologue && ((grp.tmpl != PF_T_EW_FLAT && grp.tmpl != PF_T_COL_REDUCE) || grp.has_rowuni || grp.has_view)) return false;
+        if (n.col_prologue) {
+            if ((grp.tmpl != PF_T_EW_FLAT && grp.tmpl != PF_T_COL_REDUCE) || grp.has_rowuni || grp.has_view) return false;
+            // ... and does not take a flat group of other nodes away from a row reduction over the same domain
+            // that is still to come (it could not follow them into a column-reduction kernel)
+            bool others = false;
+            for (int m : grp.nodes) others |= !g.nodes[m].col_prologue && !is_col_reduction(g.nodes[m]);
+            if (others && prologue_apart && grp.tmpl != PF_T_COL_REDUCE)
+                for (size_t r = (size_t)id + 1; r < g.nodes.size(); ++r) {
+                    const Node& rn = g.nodes[r];
+                    if (is_reduction(rn.op) && rn.red_dim == -1 && canon(g.nodes[rn.in[0]].shape) == grp.domain) return false;
+                }
+        }
         for (size_t k = 0; k < n.in.size(); ++k)               // read in the other orientation: from memory only
             if (n.reads_alias(k) && group_of[n.in[k]] == gi) return false;
         if (is_col_reduction(n)) {
@@ -300,6 +312,14 @@ struct Builder {
             for (int gi = last; gi > cand && pick < 0 && n.op != PF_OP_TRANSPOSE; --gi)
                 if (shares_operand((int)i, gi) && can_join((int)i, gi)) pick = gi;
             if (pick < 0 && last > cand && can_join((int)i, last)) pick = last;
+            // still none: any group of the node's own domain that takes it saves a launch (two unrelated row
+            // statistics of one tensor shape are one kernel); a transpose stays with its readers
+            if (pick < 0 && join_earlier && n.op != PF_OP_TRANSPOSE && !n.col_prologue) {
+                const Shape own = is_col_reduction(n) ? canon_min2(g.nodes[n.in[0]].shape)
+                                  : is_reduction(n.op) ? canon(g.nodes[n.in[0]].shape) : canon(n.shape);
+                for (int gi = last; gi >= 0 && pick < 0; --gi)
+                    if (groups[gi].domain == own && can_join((int)i, gi)) pick = gi;
+            }
             if (pick >= 0) join((int)i, pick);
             else seed((int)i);
         }
@@ -345,9 +365,10 @@ uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
 
 namespace {
 
-void plan_with(const pf_graph& g, const pf_options& opt, bool join_earlier, Plan& plan) {
+void plan_with(const pf_graph& g, const pf_options& opt, bool join_earlier, bool prologue_apart, Plan& plan) {
     Builder b(g, opt);
     b.join_earlier = join_earlier;
+    b.prologue_apart = prologue_apart;
     b.run();
 
     const size_t nn = g.nodes.size();
@@ -625,13 +646,19 @@ void make_plan(const pf_graph& g, const pf_options& opt, Plan& plan) {
     if (g.outputs.empty()) fail(PF_E_COMPILE, "graph has no outputs");
     for (int o : g.outputs)
         if (g.nodes[o].op == PF_OP_INPUT) fail(PF_E_COMPILE, "output %%%d is a graph input; nothing to compute", o);
-    // The grouping is greedy, so neither way of choosing a node's group is always ahead: letting it join the group
-    // of any of its operands saves a kernel or a round trip in most graphs and costs one in a few.  Plan both ways.
-    plan_with(g, opt, true, plan);
+    // The grouping is greedy, so no way of choosing a node's group is always ahead: letting it join the group of any
+    // of its operands saves a kernel or a round trip in most graphs and costs one in a few, and so does keeping the
+    // prologue of a column reduction out of flat groups.  Plan each way, keep the cheapest.
+    plan_with(g, opt, true, true, plan);
     if (!opt.fuse) return;
-    Plan other;
-    plan_with(g, opt, false, other);
-    if (plan_cost(other) < plan_cost(plan)) plan = std::move(other);
+    bool any_prologue = false;
+    for (auto& n : g.nodes) any_prologue |= n.col_prologue;
+    for (int policy = 1; policy < 4; ++policy) {
+        if ((policy & 2) && !any_prologue) continue;
+        Plan other;
+        plan_with(g, opt, !(policy & 1), !(policy & 2), other);
+        if (plan_cost(other) < plan_cost(plan)) plan = std::move(other);
+    }
 }
 
 }  // namespace pf

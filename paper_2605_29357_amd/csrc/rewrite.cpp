@@ -51,12 +51,18 @@ struct Sinker {
     pf_graph out;
     std::vector<int> map;              // old id -> new id of the same value
     std::map<int, int> tnode;          // old id -> new id of a node holding its transposed value
+    std::map<int, int> pnode;          // old id -> new id of a copy computed inside a column reduction's kernel
     std::set<int> sites;               // reductions (old ids) to run as column reductions in their sources' orientation
     std::set<int> standin;             // old ids whose new node has the last two dims swapped (same linear order)
     bool in_site = false;              // cloning the cone of a column-reduction site
 
+    std::vector<std::vector<int>> readers;   // per old node: the nodes that read it
+
     Sinker(const pf_graph& g, const pf_options& o, const std::vector<int>& chosen = {})
-        : src(g), opt(o), map(g.nodes.size(), -1), sites(chosen.begin(), chosen.end()) {}
+        : src(g), opt(o), map(g.nodes.size(), -1), sites(chosen.begin(), chosen.end()), readers(g.nodes.size()) {
+        for (size_t i = 0; i < g.nodes.size(); ++i)
+            for (int p : g.nodes[i].in) readers[p].push_back((int)i);
+    }
 
     int push(const Node& n) {
         out.nodes.push_back(n);
@@ -150,10 +156,39 @@ struct Sinker {
         return true;
     }
 
+    // Inside a column-reduction site a transposed leaf is read as it lies; if it is elementwise arithmetic on
+    // tensors in memory, the reduction's kernel computes it again from those instead of having another kernel
+    // write it out (a few levels deep at most: beyond that the value is taken from memory).
+    int recomputed(int y, int depth) {
+        const Node& n = src.nodes[y];
+        if (!sinkable_op(n.op) || n.shape.size() < 2 || moves_no_data(n.shape) || depth >= 6) return map[y];
+        // a value some kernel computes in this orientation anyway (an output, or read by more than transposes) is
+        // taken from there: that kernel may well be this one
+        bool elsewhere = n.is_output;
+        for (int c : readers[y]) elsewhere |= src.nodes[c].op != PF_OP_TRANSPOSE && depth == 0;
+        if (elsewhere) return map[y];
+        auto it = pnode.find(y);
+        if (it != pnode.end()) return it->second;
+        Node c = n;
+        c.is_output = false;
+        c.orig = y;
+        c.col_prologue = true;
+        for (size_t k = 0; k < n.in.size(); ++k) {
+            c.in[k] = recomputed(n.in[k], depth + 1);
+            if (standin.count(n.in[k])) {
+                c.alias_t.resize(n.in.size(), 0);
+                c.alias_t[k] = 1;
+            }
+        }
+        const int id = push(c);
+        pnode[y] = id;
+        return id;
+    }
+
     Ref transposed(int x, bool top) {
         const Node& n = src.nodes[x];
         if (n.op == PF_OP_CONST || n.shape.empty()) return {map[x], false};
-        if (n.op == PF_OP_TRANSPOSE && src.nodes[n.in[0]].shape.size() >= 2) return {map[n.in[0]], false};
+        if (n.op == PF_OP_TRANSPOSE && src.nodes[n.in[0]].shape.size() >= 2) return {in_site ? recomputed(n.in[0], 0) : map[n.in[0]], false};
         if (moves_no_data(n.shape)) return {map[x], standin.count(x) == 0};      // a stand-in already lies the other way
         auto it = tnode.find(x);
         if (it != tnode.end()) return {it->second, false};
