@@ -47,6 +47,8 @@ def parse():
                     help="instead of the main line: the ten-shape task instances, shape-aware tiling against a static one")
     ap.add_argument("--score-sizes", action="store_true",
                     help="time the scorer and the tolerance ladder on one pair of 1 k ... 90 M elements (bf16 and f32)")
+    ap.add_argument("--dags", type=str, default="",
+                    help="with --cfg5: only these DAG numbers (comma separated), e.g. for a run under rocprofv3")
     ap.add_argument("--cfg5", action="store_true",
                     help="instead of the main line: fused against op-by-op time of each of the 256 random DAGs")
     return ap.parse_args()
@@ -81,7 +83,8 @@ def main():
         print(json.dumps({"score_sizes": score_sizes_table(torch, pf, stream)}))
         return
     if args.cfg5:
-        print(json.dumps({"cfg5": cfg5_table(torch, pf, Runner, alloc_outputs, stream)}))
+        only = [int(k) for k in args.dags.split(",") if k.strip()] or None
+        print(json.dumps({"cfg5": cfg5_table(torch, pf, Runner, alloc_outputs, stream, only)}))
         return
 
     # ---------------------------------------------------------------- workload
@@ -151,7 +154,11 @@ def main():
     kname = src[src.index('extern "C" __global__'):].split("(")[1].split()[-1]
     roofline = {"bound": "hbm", "kernel": kname + " (bias + tanh-GELU gate, bf16 [8192,11008])",
                 "achieved": w.algorithmic_bytes / (kernel_us * 1e-6) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "traffic": MEASURED_TRAFFIC_BYTES.get(kname), "avg_us": kernel_us, "median_us": stats(k_us)[0],
+                "traffic": MEASURED_TRAFFIC_BYTES.get(kname),
+                "traffic_source": ("stored: FETCH_SIZE + WRITE_SIZE of this kernel from profiles/bench_cfg3_hbm_traffic_pmc.md, "
+                                   "not collected in this run") if kname in MEASURED_TRAFFIC_BYTES else
+                                  "none: the kernel has changed since the counters in profiles/bench_cfg3_hbm_traffic_pmc.md were taken",
+                "avg_us": kernel_us, "median_us": stats(k_us)[0],
                 "algorithmic_bytes": w.algorithmic_bytes, "grid": gi["grid_blocks"], "block": gi["block_threads"]}
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
 
@@ -166,6 +173,21 @@ def main():
            "roofline": roofline,
            "score": {"avg_us": score_us, "GBps": score_bytes / (score_us * 1e-6) / 1e9, "bytes": score_bytes,
                      "allclose": sr.allclose, "max_abs": sr.max_abs, "n_viol": sr.n_viol}}
+
+    # the tolerance ladder and both results in one pass, on the same pair (outside the timed steps)
+    lres = torch.zeros(ctypes.sizeof(pf.LadderResult), dtype=torch.uint8, device="cuda")
+    aws = torch.empty(max(pf.score_all_workspace_bytes(1), 256), dtype=torch.uint8, device="cuda")
+    for label, call in (("ladder_us", lambda p: pf.score_ladder(p, lres.data_ptr(), aws.data_ptr(), aws.numel(), stream.cuda_stream)),
+                        ("both_us", lambda p: pf.score_all(p, res.data_ptr(), lres.data_ptr(), aws.data_ptr(), aws.numel(), stream.cuda_stream))):
+        ts = []
+        for i in range(12):
+            a, b = HipEvent(), HipEvent()
+            a.record(stream)
+            call(pairs[i % nsets])
+            b.record(stream)
+            torch.cuda.synchronize()
+            ts.append(a.elapsed_us(b))
+        out["score"][label] = float(np.median(ts[4:]))
 
     # --------------------------------------------- per-config table (paper protocol)
     if not args.no_extra:
@@ -219,6 +241,23 @@ def per_config_table(torch, pf, configs, Runner, alloc_outputs, stream, w3, fuse
     table["copy_256MiB"] = {"us": med, "iqr_us": iqr, "GBps": 2 * nbytes / (med * 1e-6) / 1e9}
     del src, dsts
 
+    def copy_same_bytes(total, sets):
+        """A plain copy moving `total` bytes (half read, half written), cold: the ceiling for a kernel of that size."""
+        half = max(total // 2 // 16 * 16, 16)
+        srcs = [torch.empty(half, dtype=torch.uint8, device="cuda").random_(0, 255) for _ in range(sets)]
+        dsts = [torch.empty(half, dtype=torch.uint8, device="cuda") for _ in range(sets)]
+        from paper_2605_29357_amd.hip_events import HipEvent
+        ts = []
+        for i in range(60):
+            a, b = HipEvent(), HipEvent()
+            a.record(stream)
+            pf.copy_bytes(dsts[i % sets].data_ptr(), srcs[i % sets].data_ptr(), half, stream.cuda_stream)
+            b.record(stream)
+            if i >= 10:
+                ts.append((a, b))
+        torch.cuda.synchronize()
+        return stats([a.elapsed_us(b) for a, b in ts])[0]
+
     def entry(w, sets):
         f = Runner(w, fuse=True)
         u = Runner(w, fuse=False, intermediates_f32=False)
@@ -228,10 +267,14 @@ def per_config_table(torch, pf, configs, Runner, alloc_outputs, stream, w3, fuse
         um, ui = time_runner(torch, u, stream, ins, outs)
         # warm: one buffer set, so repeat runs may be served from the Infinity Cache
         wm, wi = time_runner(torch, f, stream, ins[:1], outs[:1])
+        unfused_kernels = u.info["n_kernels"]
+        del u
+        cp = copy_same_bytes(w.algorithmic_bytes, sets)
         return {"bytes": w.algorithmic_bytes, "fused_us": fm, "fused_iqr_us": fi, "fused_kernels": f.info["n_kernels"],
+                "copy_same_bytes_us": cp, "pct_of_copy": 100 * cp / fm,
                 "fused_GBps": w.algorithmic_bytes / (fm * 1e-6) / 1e9,
                 "fused_pct_peak": 100 * w.algorithmic_bytes / (fm * 1e-6) / 1e9 / HBM_PEAK_GBS,
-                "fused_warm_us": wm, "unfused_us": um, "unfused_iqr_us": ui, "unfused_kernels": u.info["n_kernels"],
+                "fused_warm_us": wm, "unfused_us": um, "unfused_iqr_us": ui, "unfused_kernels": unfused_kernels,
                 "speedup_vs_unfused": um / fm}
 
     # cfg3 reuses the buffers of the main loop
@@ -443,11 +486,12 @@ def configs_tol(dt):
     return (configs.RTOL[dt], configs.ATOL[dt])
 
 
-# Vector-ALU issue slots one element costs per operator, in units of one wave instruction at the rate of a
-# compare / convert / fp64 operation (16 lanes per SIMD and clock: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz =
-# 39.3e12 such lane-operations per second for the chip; fp32 add / mul / fma and simple integer operations issue
-# at twice that rate and count 0.5, transcendental instructions at half of it and count 2).  Counted from the
-# instruction sequences the kernels use for each operator; measured rates in profiles/valu_instruction_rates.md.
+# Vector-ALU issue slots one element costs per operator, in units of one wave instruction at half the fp32 FMA
+# rate.  The chip's published fp32 vector peak, 157.3 TFLOP/s = 78.6e12 FMA lane-operations per second, is 32 lanes
+# per SIMD and clock (256 CUs x 4 SIMDs x 2.4 GHz); compares, selects, conversions and fp64 operations issue at
+# 16 lanes per clock (the unit: 39.3e12 lane-operations per second), transcendental instructions at 8.  So
+# fp32 add / mul / fma and simple integer operations count 0.5, the 16-lane class 1, v_rcp / v_exp 2.  Counted from
+# the instruction sequences the kernels use for each operator.
 ALU_UNITS = {"add": 0.5, "sub": 0.5, "mul": 0.5, "div": 6.5, "exp": 6.5, "tanh": 13.5, "sigmoid": 9.5, "gelu": 11.0, "rsqrt": 2.0,
              "maximum": 3.0, "minimum": 3.0, "rot_pairs": 0.5, "transpose": 2.0, "sum": 1.5, "mean": 1.5, "max": 3.0, "var": 4.0,
              "roll": 0.0, "slice": 0.0}
@@ -478,7 +522,7 @@ def alu_bound_us(pf, exe, graph, dtype):
     return total
 
 
-def cfg5_table(torch, pf, Runner, alloc_outputs, stream):
+def cfg5_table(torch, pf, Runner, alloc_outputs, stream, only=None):
     """The 256 random fusible DAGs on their seeded inputs: fused and op-by-op device time each (median of 30 runs
     after 5 warm-ups; HIP events attached to the dispatches).  Cold: the runs rotate through enough copies of the
     DAG's buffers that more than 512 MB is touched between two uses of the same copy (the Infinity Cache holds
@@ -502,9 +546,18 @@ def cfg5_table(torch, pf, Runner, alloc_outputs, stream):
         torch.cuda.synchronize()
         return float(np.median([a.elapsed_us(b) for a, b in evs]))
 
+    if only is not None:
+        # a plain copy of known size (256 MiB in, 256 MiB out): scales the hardware byte counters when a few DAGs
+        # are run under a counter-collecting profiler
+        cp_src = torch.empty(1 << 28, dtype=torch.uint8, device="cuda").random_(0, 255)
+        cp_dst = torch.empty(1 << 28, dtype=torch.uint8, device="cuda")
+        for _ in range(3):
+            pf.copy_bytes(cp_dst.data_ptr(), cp_src.data_ptr(), 1 << 28, stream.cuda_stream)
+        torch.cuda.synchronize()
+        del cp_src, cp_dst
     rows, kept, pairs = [], [], []
     t_start = time.perf_counter()
-    for k in range(dags.N_DAGS):
+    for k in (only if only is not None else range(dags.N_DAGS)):
         w = dags.cfg5(k)                                     # seeded inputs, as certified with the oracle
         dt = w.meta["dtype"]
         f = Runner(w, fuse=True, guard=False)
