@@ -573,6 +573,25 @@ def cfg5_table(torch, pf, Runner, alloc_outputs, stream, only=None):
         unfused = med_time(u, ins, outs if nsets > 1 else [uouts])
         u.d_in = ins[0]
         u.run(uouts, stream)
+        # what a plain copy of the same byte volume takes, cold (half read, half written): the practical ceiling
+        # for a kernel of this size, measured for the DAGs the 16 MB summary is about
+        copy_us = None
+        if w.algorithmic_bytes >= 16e6:
+            half = w.algorithmic_bytes // 2 // 16 * 16
+            csets = int(max(2, min(48, 600e6 // (2 * half) + 1)))
+            srcs = [torch.empty(half, dtype=torch.uint8, device="cuda").random_(0, 255) for _ in range(csets)]
+            dsts = [torch.empty(half, dtype=torch.uint8, device="cuda") for _ in range(csets)]
+            ts = []
+            for i in range(35):
+                a, b = HipEvent(), HipEvent()
+                a.record(stream)
+                pf.copy_bytes(dsts[i % csets].data_ptr(), srcs[i % csets].data_ptr(), half, stream.cuda_stream)
+                b.record(stream)
+                if i >= 5:
+                    ts.append((a, b))
+            torch.cuda.synchronize()
+            copy_us = float(np.median([a.elapsed_us(b) for a, b in ts]))
+            del srcs, dsts
         g = f.exe.graph
         hbm_us = w.algorithmic_bytes / (HBM_PEAK_GBS * 1e3)
         alu_us = alu_bound_us(pf, f.exe, g, dt)
@@ -580,6 +599,7 @@ def cfg5_table(torch, pf, Runner, alloc_outputs, stream, only=None):
                      "cold": bool(cold_ok), "fused_us": fused_cold, "fused_warm_us": fused_warm, "unfused_us": unfused,
                      "fused_kernels": f.info["n_kernels"], "unfused_kernels": u.info["n_kernels"],
                      "templates": [gi["template"] for gi in f.exe.groups()], "hbm_bound_us": hbm_us, "alu_bound_us": alu_us,
+                     "copy_same_bytes_us": copy_us, "pct_of_copy": 100 * copy_us / fused_cold if copy_us else None,
                      "binds": "alu" if alu_us > hbm_us else "hbm", "pct_of_hbm_peak": 100 * hbm_us / fused_cold,
                      "pct_of_bound": 100 * max(hbm_us, alu_us) / fused_cold})
         # every output of the fused run against the op-by-op one: the pairs of one batched scoring call
@@ -623,6 +643,9 @@ def cfg5_table(torch, pf, Runner, alloc_outputs, stream, only=None):
                         "their_median_pct_of_hbm_peak_cold": float(np.median([r["pct_of_hbm_peak"] for r in big])) if big else None,
                         "their_min_pct_of_hbm_peak_cold": float(min(r["pct_of_hbm_peak"] for r in big)) if big else None,
                         "their_median_pct_of_bound_cold": float(np.median([r["pct_of_bound"] for r in big])) if big else None,
+                        "their_median_pct_of_equal_bytes_copy": float(np.median([r["pct_of_copy"] for r in big])) if big else None,
+                        "their_min_pct_of_equal_bytes_copy": float(min(r["pct_of_copy"] for r in big)) if big else None,
+                        "median_pct_of_hbm_peak_of_those_copies": float(np.median([100 * r["hbm_bound_us"] / r["copy_same_bytes_us"] for r in big])) if big else None,
                         "alu_bound_among_them": int(sum(r["binds"] == "alu" for r in big)),
                         "median_planned_over_algorithmic_3plus_kernels":
                             float(np.median([r["planned_bytes"] / r["bytes"] for r in multi])) if multi else None}}

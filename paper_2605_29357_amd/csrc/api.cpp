@@ -426,7 +426,7 @@ pf::PairDev descriptor(const pf_pair& p, int orig, unsigned long long chunk) {
 // for each result wanted.  Every part is written by the staging launch before it is read: a workspace needs
 // no initialisation.
 struct WsLayout {
-    size_t pairs, start, tickets, seeds, sslots, lslots, total;
+    size_t pairs, start, wg_pair, tickets, seeds, sslots, lslots, total;
 };
 WsLayout ws_layout(int n_pairs, bool score, bool ladder) {
     const size_t n = n_pairs < 0 ? 0 : (size_t)n_pairs;
@@ -435,6 +435,7 @@ WsLayout ws_layout(int n_pairs, bool score, bool ladder) {
     size_t at = 0;
     w.pairs = at; at += up(n * sizeof(pf::PairDev));
     w.start = at; at += up((n + 1) * sizeof(unsigned long long));
+    w.wg_pair = at; at += up((n + pf::kScoreMaxTargetWGs) * sizeof(int));      // a call has at most target + n workgroups      // a call has at most target + n workgroups
     w.tickets = at; at += up(n * (pf::kScoreSlots + 1) * sizeof(unsigned int));
     w.seeds = at; at += up(n * pf::kScoreSeedParts * 2 * sizeof(double));
     w.sslots = at; if (score) at += up(n * pf::kScoreSlots * sizeof(pf_score_result));
@@ -482,12 +483,13 @@ void score_impl(const pf_pair* h_pairs, int n_pairs, pf_score_result* d_score, p
         const unsigned long long chunk = pf::score_chunk_elems(call_elems, d_ladder != nullptr);
         unsigned long long call_chunks = 0;
         for (int i : big) call_chunks += (h_pairs[i].n + chunk - 1) / chunk;
-        const unsigned long long target = pf::score_target_wgs(d_ladder != nullptr);
+        const unsigned long long target = pf::score_target_wgs(d_ladder != nullptr, nb);
         const unsigned long long chunks_per_wg = (call_chunks + target - 1) / target;
         char* base = (char*)d_workspace;
         pf::ScoreSpace sp;
         sp.pairs = (pf::PairDev*)(base + lay.pairs);
         sp.start = (unsigned long long*)(base + lay.start);
+        sp.wg_pair = (int*)(base + lay.wg_pair);
         sp.tickets = (unsigned int*)(base + lay.tickets);
         sp.seeds = (double*)(base + lay.seeds);
         sp.sslots = d_score ? (pf_score_result*)(base + lay.sslots) : nullptr;
@@ -512,7 +514,7 @@ void score_impl(const pf_pair* h_pairs, int n_pairs, pf_score_result* d_score, p
                 total += nw;
             }
             b.start[b.count] = total;
-            if (total >= (1ull << 31)) pf::fail(PF_E_INVALID, "internal: %llu workgroups", total);
+            if (total > pf::kScoreMaxTargetWGs + (unsigned long long)n_pairs) pf::fail(PF_E_INVALID, "internal: %llu workgroups", total);
             hipError_t err = pf::launch_stage(b, sp, hs);
             if (err != hipSuccess) pf::fail(PF_E_RUNTIME, "staging launch failed: %s", hipGetErrorString(err));
         }

@@ -669,6 +669,9 @@ __global__ void __launch_bounds__(kSeedBlock) stage_kernel(pf::PairBatch batch, 
     }
     const int k0 = part * kSeedBlock + threadIdx.x;
     if (k0 < kSlots + 1) sp.tickets[(size_t)p * (kSlots + 1) + k0] = 0;
+    // which pair each workgroup of the walking kernel belongs to (one load there instead of a search over the prefix)
+    for (unsigned long long w = (unsigned long long)k0; w < pr.wgs; w += (unsigned long long)kSeedParts * kSeedBlock)
+        sp.wg_pair[batch.start[local] + w] = p;
     if (sp.sslots)
         for (int k = k0; k < kSlots; k += kSeedParts * kSeedBlock) {
             pf_score_result z;
@@ -720,12 +723,7 @@ template <int CD, int RD, int MODE>
 __global__ void __launch_bounds__(kBlock) pair_kernel(pf::ScoreSpace sp, int n_pairs, pf::LadderRow row, int ladder_fast, pf_score_result* sres,
                                                       pf_ladder_result* lres, unsigned long long block_offset) {
     const unsigned long long bid = block_offset + blockIdx.x;
-    // which pair does this workgroup belong to: largest p with start[p] <= bid
-    int lo = 0, hi = n_pairs;
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (uniform_u64(sp.start + mid) <= bid) lo = mid; else hi = mid;
-    }
+    const int lo = __builtin_amdgcn_readfirstlane(sp.wg_pair[bid]);       // written by the staging launch
     const pf::PairDev pr = uniform_pair(sp.pairs + lo);
     const unsigned long long wg = bid - uniform_u64(sp.start + lo);          // this workgroup among the pr.wgs of its pair
     Acc acc;
@@ -917,13 +915,19 @@ void launch_small_mode(const pf::PairBatch& batch, int cd, int rd, const pf::Lad
 namespace pf {
 
 // Elements per chunk and workgroups per call.  A call is walked by at most about score_target_wgs() workgroups
-// (and at least one per pair); beyond that a workgroup walks several chunks, round robin.  Measured on 90 M
-// bf16 elements: the single-level kernel (5 workgroups resident per compute unit) is fastest with one round of
-// resident workgroups, 1280, and chunks of 8192 or 4096 elements; the ladder kernels, with fewer resident waves and more
-// arithmetic per element, with 3072 workgroups and chunks of 16384.  Smaller calls get smaller chunks, so that
-// they still spread over the chip, down to one vector per lane (a call of a few million elements is bound by
-// the latency of walking a chunk one vector at a time).
-unsigned long long score_target_wgs(bool ladder) { return ladder ? 3072 : 1280; }
+// (and at least one per pair); beyond that a workgroup walks several chunks, round robin.  Measured on one pair
+// of 90 M bf16 elements: the single-level kernel (5 workgroups resident per compute unit) is fastest with one
+// round of resident workgroups, 1280, and chunks of 8192 or 4096 elements; the ladder kernels, with fewer resident
+// waves and more arithmetic per element, with 3072 workgroups and chunks of 16384.  A call of many pairs of
+// different sizes and dtypes needs more, shorter-lived workgroups to even out (780 pairs, 5 GB: 1800 us with
+// 1280 workgroups, 1275 us with 10240, no better beyond), so the target grows with the number of pairs.
+// Smaller calls get smaller chunks, so that they still spread over the chip, down to one vector per lane (a call
+// of a few million elements is bound by the latency of walking a chunk one vector at a time).
+unsigned long long score_target_wgs(bool ladder, int n_pairs) {
+    const unsigned long long k = n_pairs < 1 ? 1 : (unsigned long long)n_pairs;
+    const unsigned long long t = ladder ? 3072 * (k < 4 ? k : 4) : 1280 * (k < 8 ? k : 8);
+    return t < kScoreMaxTargetWGs ? t : kScoreMaxTargetWGs;
+}
 unsigned long long score_chunk_elems(unsigned long long n, bool ladder) {
     unsigned long long c = (n / 2048 + kStep - 1) / kStep * kStep;
     if (c < kStep) c = kStep;

@@ -34,11 +34,13 @@ inline bool score_combo_supported(int cd, int rd) {
 }
 
 constexpr int kScoreSlots = 64;       // partial result slots per pair (spread the atomics of its workgroups)
+constexpr unsigned long long kScoreMaxTargetWGs = 12288;  // score_target_wgs() never asks for more
 constexpr int kScoreSeedParts = 16;   // sampled maxima per pair (two doubles each), folded by every reader
 // Where the parts of a call's workspace lie (device pointers; sslots / lslots are NULL when that result is not wanted).
 struct ScoreSpace {
     struct PairDev* pairs;            // [n_pairs] descriptors, ordered by dtype combination
     unsigned long long* start;        // [n_pairs + 1] first workgroup of each pair
+    int* wg_pair;                     // [workgroups of the call] the pair each workgroup of the walking kernel works on
     unsigned int* tickets;            // [n_pairs][1 + kScoreSlots] finished: slots of the pair, workgroups of each slot
     double* seeds;                    // [n_pairs][kScoreSeedParts][2]
     pf_score_result* sslots;          // [n_pairs][kScoreSlots]
@@ -68,7 +70,7 @@ struct LadderRow {
 static_assert(sizeof(PairBatch) + sizeof(LadderRow) + 128 <= 4096, "a batch of descriptors, the tolerances and the other kernel arguments must fit in 4 KB");
 
 unsigned long long score_chunk_elems(unsigned long long call_elems, bool ladder);
-unsigned long long score_target_wgs(bool ladder);
+unsigned long long score_target_wgs(bool ladder, int n_pairs);
 // pairs of at most score_small_pair_elems() elements: one workgroup per pair, results written directly
 unsigned long long score_small_pair_elems();
 // descriptors, cleared slots and tickets, and seeds of one batch of pairs, in one launch
