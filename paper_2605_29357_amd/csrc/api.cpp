@@ -518,7 +518,7 @@ void score_impl(const pf_pair* h_pairs, int n_pairs, pf_score_result* d_score, p
             hipError_t err = pf::launch_stage(b, sp, hs);
             if (err != hipSuccess) pf::fail(PF_E_RUNTIME, "staging launch failed: %s", hipGetErrorString(err));
         }
-        hipError_t err = pf::launch_pairs(sp, nb, ranges, table, d_score, d_ladder, hs);
+        hipError_t err = pf::launch_pairs(sp, ranges, table, d_score, d_ladder, hs);
         if (err != hipSuccess) pf::fail(PF_E_RUNTIME, "score launch failed: %s", hipGetErrorString(err));
     }
     for (int cd = 0; cd < 4; ++cd)

@@ -720,7 +720,7 @@ __global__ void __launch_bounds__(kSeedBlock) stage_kernel(pf::PairBatch batch, 
 // own path only.  A workgroup walks its chunks, folds its totals into a slot of its pair and takes a ticket; the
 // last one of the pair to do so folds the slots.
 template <int CD, int RD, int MODE>
-__global__ void __launch_bounds__(kBlock) pair_kernel(pf::ScoreSpace sp, int n_pairs, pf::LadderRow row, int ladder_fast, pf_score_result* sres,
+__global__ void __launch_bounds__(kBlock) pair_kernel(pf::ScoreSpace sp, pf::LadderRow row, int ladder_fast, pf_score_result* sres,
                                                       pf_ladder_result* lres, unsigned long long block_offset) {
     const unsigned long long bid = block_offset + blockIdx.x;
     const int lo = __builtin_amdgcn_readfirstlane(sp.wg_pair[bid]);       // written by the staging launch
@@ -869,14 +869,14 @@ __global__ void __launch_bounds__(256) copy_kernel(u32x4* __restrict__ dst, cons
 }
 
 template <int MODE>
-void launch_pairs_mode(const pf::ScoreSpace& sp, int n_pairs, const pf::ScoreRanges& ranges, const pf::LadderTable& table, const bool* fast,
+void launch_pairs_mode(const pf::ScoreSpace& sp, const pf::ScoreRanges& ranges, const pf::LadderTable& table, const bool* fast,
                        pf_score_result* sres, pf_ladder_result* lres, hipStream_t stream) {
 #define PF_LAUNCH(CD, RD)                                                                                                      \
     if (ranges.count[CD][RD]) {                                                                                                \
         pf::LadderRow row;                                                                                                     \
         for (int k = 0; k < L; ++k) { row.rtol[k] = table.rtol[CD][k]; row.atol[k] = table.atol[CD][k]; }                      \
         hipLaunchKernelGGL((pair_kernel<CD, RD, MODE>), dim3((unsigned)ranges.count[CD][RD]), dim3(kBlock), 0, stream, sp,      \
-                           n_pairs, row, (int)fast[CD], sres, lres, ranges.first[CD][RD]);                                     \
+                           row, (int)fast[CD], sres, lres, ranges.first[CD][RD]);                                              \
     }
     PF_LAUNCH(PF_F32, PF_F32)
     PF_LAUNCH(PF_F32, PF_BF16)
@@ -953,13 +953,13 @@ static void ladder_fast_flags(const LadderTable& table, bool* fast) {
     }
 }
 
-hipError_t launch_pairs(const ScoreSpace& sp, int n_pairs, const ScoreRanges& ranges, const LadderTable& table, pf_score_result* d_sres,
+hipError_t launch_pairs(const ScoreSpace& sp, const ScoreRanges& ranges, const LadderTable& table, pf_score_result* d_sres,
                         pf_ladder_result* d_lres, hipStream_t stream) {
     bool fast[4];
     ladder_fast_flags(table, fast);
-    if (d_sres && d_lres) launch_pairs_mode<kScore | kLadder>(sp, n_pairs, ranges, table, fast, d_sres, d_lres, stream);
-    else if (d_sres) launch_pairs_mode<kScore>(sp, n_pairs, ranges, table, fast, d_sres, d_lres, stream);
-    else launch_pairs_mode<kLadder>(sp, n_pairs, ranges, table, fast, d_sres, d_lres, stream);
+    if (d_sres && d_lres) launch_pairs_mode<kScore | kLadder>(sp, ranges, table, fast, d_sres, d_lres, stream);
+    else if (d_sres) launch_pairs_mode<kScore>(sp, ranges, table, fast, d_sres, d_lres, stream);
+    else launch_pairs_mode<kLadder>(sp, ranges, table, fast, d_sres, d_lres, stream);
     return hipGetLastError();
 }
 

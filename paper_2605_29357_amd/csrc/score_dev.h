@@ -76,7 +76,7 @@ unsigned long long score_small_pair_elems();
 // descriptors, cleared slots and tickets, and seeds of one batch of pairs, in one launch
 hipError_t launch_stage(const PairBatch& batch, const ScoreSpace& sp, hipStream_t stream);
 // the walking kernels (one launch per dtype combination present); d_sres / d_lres: either may be NULL
-hipError_t launch_pairs(const ScoreSpace& sp, int n_pairs, const ScoreRanges& ranges, const LadderTable& table, pf_score_result* d_sres,
+hipError_t launch_pairs(const ScoreSpace& sp, const ScoreRanges& ranges, const LadderTable& table, pf_score_result* d_sres,
                         pf_ladder_result* d_lres, hipStream_t stream);
 hipError_t launch_small(const PairBatch& batch, int cd, int rd, const LadderTable& table, pf_score_result* d_sres, pf_ladder_result* d_lres,
                         hipStream_t stream);
