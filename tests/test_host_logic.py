@@ -419,3 +419,69 @@ def test_cached_code_objects_are_tied_to_the_compiler_and_the_target(tmp_path, m
     # and once rewritten by this compiler it is a hit for the next process
     out = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, env=dict(os.environ, PF_CACHE_DIR=str(tmp_path)))
     assert out.stdout.split() == ["0", "1"], out.stdout + out.stderr
+
+
+def _plan(build, shapes, dtypes):
+    g = Builder()
+    ins = [g.input(dt, sh) for sh, dt in zip(shapes, dtypes)]
+    for o in build(g, ins):
+        g.output(o)
+    e = pf.Exec(g.text())
+    return e, [gi["template"] for gi in e.groups()], e.info()
+
+
+def test_a_reader_of_a_moved_reduction_joins_the_tile_kernel_that_computes_its_other_operand():
+    # y = x * max(x) with x = w / transpose(a): the row maximum of the transposed value is a column maximum in a's own
+    # orientation; the product then joins the tile kernel that computes x, although that group was opened
+    # before the reduction's (the groups are put in execution order afterwards), so x never crosses memory
+    R, C = 96, 200
+
+    def build(g, ins):
+        a, wgt = ins                                        # [C, R], [C]
+        x = g.op("div", [wgt, g.op("transpose", [a], "f32")], "f32")      # [R, C]
+        return [g.op("mul", [x, g.op("max", [x], "f32")], "f32")]
+
+    e, tmpl, info = _plan(build, [(C, R), (C,)], ["f32"] * 2)
+    assert tmpl == ["col_reduce", "tile"]
+    assert info["planned_bytes"] == 4 * (2 * (R * C + C) + R * C + 2 * R)        # a and w twice, y once, the maxima out and in
+    assert info["workspace_bytes"] <= 256 * ((4 * R + 255) // 256)
+
+
+def test_unrelated_statistics_of_one_tensor_shape_share_a_kernel():
+    # sum(a), a transposed output in between, then max(b) - a: the two row statistics have no operand in common when
+    # the second is placed, and still run in one row kernel
+    R, C = 300, 96
+
+    def build(g, ins):
+        a, b = ins
+        s = g.op("sum", [a], "f32")
+        t = g.op("transpose", [g.op("div", [a, b], "f32")], "f32")
+        m = g.op("sub", [a, g.op("max", [b], "f32")], "f32")
+        return [s, t, m]
+
+    e, tmpl, info = _plan(build, [(R, C), (R, C)], ["f32"] * 2)
+    assert sorted(tmpl) == ["row_resident", "tile"] and info["n_kernels"] == 2
+
+
+def test_a_16_bit_value_that_is_only_moved_crosses_kernels_in_16_bits():
+    # y = tanh(a) * mean(a) lives in a row kernel; its only reader is a transpose that is a bf16 graph output, so the
+    # scratch copy is bf16 (rounding before or after the move gives the same bits) instead of fp32
+    R, C = 512, 384
+
+    def build(g, ins):
+        a, b, c, d = ins
+        y = g.op("mul", [g.op("mul", [g.op("mul", [g.op("tanh", [a], "bf16"), g.op("mean", [a], "bf16")], "bf16"), b], "bf16"), c], "bf16")
+        return [g.op("transpose", [g.op("mul", [y, d], "bf16")], "bf16"), g.op("max", [a], "bf16")]
+
+    e, tmpl, info = _plan(build, [(R, C)] * 4, ["bf16"] * 4)
+    assert tmpl == ["row_resident", "tile"]
+    assert info["workspace_bytes"] == 2 * R * C
+    # ... but a value that later arithmetic reads stays in fp32
+    def build2(g, ins):
+        a, b, c, d = ins
+        y = g.op("mul", [g.op("mul", [g.op("mul", [g.op("tanh", [a], "bf16"), g.op("mean", [a], "bf16")], "bf16"), b], "bf16"), c], "bf16")
+        t = g.op("transpose", [g.op("mul", [y, d], "bf16")], "bf16")
+        return [g.op("sum", [t], "bf16"), g.op("max", [a], "bf16")]
+
+    e2, tmpl2, info2 = _plan(build2, [(R, C)] * 4, ["bf16"] * 4)
+    assert info2["workspace_bytes"] == 0 or info2["workspace_bytes"] >= 4 * R * C or "col_reduce" in tmpl2
