@@ -200,10 +200,10 @@ pf_status pf_compile(const pf_graph* g, const pf_options* h_opt, pf_exec** e) {
         // fused plans work on a rewritten copy (transposes of computed values pushed down to the operands)
         pf_graph work;
         if (opt.fuse) {
-            // Reductions that could run in their sources' orientation instead of behind a transpose: plan with and
-            // without each and keep what the traffic model prefers (bytes moved, plus what a kernel costs at least
+            // Reductions that could run in their sources' orientation instead of behind a transpose, and transposes whose
+            // kernel could take over the results of the kernel before it: plan with and without each and keep what the traffic model prefers (bytes moved, plus what a kernel costs at least
             // expressed in bytes: about 4 us at the copy rate).
-            const std::vector<int> sites = pf::column_reduction_sites(*g, opt);
+            const std::vector<int> sites = pf::rewrite_sites(*g, opt);
             auto cost_of = [&](const std::vector<int>& chosen) {
                 pf_graph w;
                 pf::Plan p;

@@ -1195,11 +1195,37 @@ struct Emit {
             }
             line("    }");
         }
-        for (int id : grp.nodes) emit_elementwise(id, EPL);
+        for (int id : grp.nodes)
+            if (plan_kind.at(id) != 4) emit_elementwise(id, EPL);
         int sp = 0;
         const bool st_vec = C % VW == 0;
         for (auto& st : grp.stores) {
             int cnt = 1 + (int)st.also_outputs.size();
+            if (st.tstore) {
+                // A result of the other orientation: memory is [.., C, R] with R contiguous.  The lanes' values go through
+                // the LDS tile the other way round from a transposed load: written as computed, read back transposed,
+                // stored coalesced along R.  (The tile is free by now: every staged operand sits in registers; the
+                // barriers keep the uses of the tile apart.)
+                const bool tv_ok = R % VW == 0;
+                line("    __syncthreads();");
+                line("    _Pragma(\"unroll\") for (int i = 0; i < NI; ++i)");
+                line(strf("        _Pragma(\"unroll\") for (int j = 0; j < VW; ++j) tile[0][tx * VW + j][ty + TYN * i] = v%d[i * VW + j];", st.value_node));
+                line("    __syncthreads();");
+                for (int c = 0; c < cnt; ++c, ++sp) {
+                    line("    _Pragma(\"unroll\") for (int i = 0; i < NI; ++i) {");
+                    line(strf("        const %s cc = c0 + ty + TYN * i, rr = r0 + tx * VW;", idx_t()));
+                    line("        float t4[VW];");
+                    line("        _Pragma(\"unroll\") for (int j = 0; j < VW; ++j) t4[j] = tile[0][ty + TYN * i][tx * VW + j];");
+                    line(strf("        const %s o = (lead * C + cc) * R + rr;", idx_t()));
+                    if (tv_ok) line(strf("        if (cc < C && rr < R) pf_st<VW, false>(q%d + o, t4);", sp));
+                    else {
+                        line(strf("        if (cc < C && rr + VW <= R) pf_st<VW, false, true>(q%d + o, t4);", sp));
+                        line(strf("        else if (cc < C) { _Pragma(\"unroll\") for (int j = 0; j < VW; ++j) if (rr + j < R) pf_st1(q%d + o + j, t4[j]); }", sp));
+                    }
+                    line("    }");
+                }
+                continue;
+            }
             for (int c = 0; c < cnt; ++c, ++sp) {
                 line("    _Pragma(\"unroll\") for (int i = 0; i < NI; ++i) {");
                 line(strf("        const %s rr = r0 + ty + TYN * i, cc = c0 + tx * VW;", idx_t()));
@@ -1391,9 +1417,12 @@ struct Emit {
         wide = maxel >= (int64_t(1) << 30);
         for (int o : g.outputs)
             if (g.nodes[o].dtype == PF_F32) precise = true;
+        for (auto& st : grp.stores)
+            if (st.tstore && grp.tmpl != PF_T_TILE) fail(PF_E_COMPILE, "internal: a transposed store outside a tiled group");
         if (grp.tmpl == PF_T_TILE) {
             bool any_t = false;
             for (auto& o : grp.operands) any_t |= o.transposed;
+            for (auto& st : grp.stores) any_t |= st.tstore;
             if (!any_t) grp.tmpl = PF_T_EW_FLAT;
         }
         // name: template + operators (+ a hash of the specialised source, added below), so

@@ -57,6 +57,7 @@ struct Node {
     int orig = -1;                 // the user's node this one computes (a value recomputed in the other orientation keeps it)
     std::vector<char> alias_t;     // per operand: read through a swap of its last two dims that moves no data
     bool reads_alias(size_t k) const { return k < alias_t.size() && alias_t[k]; }
+    bool store_t = false;          // a transpose whose operand is computed in its kernel and only written out: a transposed store
     bool col_prologue = false;     // computed for a column reduction in its sources' orientation: belongs in that reduction's kernel
 };
 
@@ -120,6 +121,8 @@ struct Store {
     int graph_output = -1;     // index into d_outputs, or
     int64_t ws_offset = -1;    // byte offset into the workspace
     std::vector<int> also_outputs;  // further graph-output slots receiving the same values
+    bool tstore = false;       // written through a swap of the last two dims (tile kernels: an LDS transpose on the store side)
+    int value_node = -1;       // the member whose registers are stored (-1: `node` itself)
 };
 
 struct Group {
@@ -171,10 +174,12 @@ constexpr uint64_t kLaunchCostBytes = 24u << 20;
 uint64_t plan_cost(const Plan& plan);
 
 // ---- rewrite.cpp ----
-// `sites`: reductions over the last dim (caller's node ids, from column_reduction_sites) to run as reductions
-// over dim -2 of their operand's cone, evaluated in the orientation its sources have in memory
+// `sites` (caller's node ids, from rewrite_sites): reductions over the last dim to run as reductions over dim -2
+// of their operand's cone, evaluated in the orientation its sources have in memory; and transposes of computed
+// values whose kernel is to take over what the value's own kernel computes besides (results of that orientation
+// are then written through a transposed store)
 void sink_transposes(const pf_graph& g, const pf_options& opt, const std::vector<int>& sites, pf_graph& out);
-std::vector<int> column_reduction_sites(const pf_graph& g, const pf_options& opt);
+std::vector<int> rewrite_sites(const pf_graph& g, const pf_options& opt);
 
 // ---- codegen.cpp ----
 void generate_source(const pf_graph& g, const pf_options& opt, Group& grp, int index);

@@ -59,7 +59,7 @@ struct Builder {
         pf_template tmpl;
         Shape domain;
         std::vector<int> nodes;
-        std::vector<int> kinds;                 // per member: 2 full, 1 row-uniform, 3 column-uniform
+        std::vector<int> kinds;                 // per member: 2 full, 1 row-uniform, 3 column-uniform, 4 stored through a transpose
         bool has_rowuni = false;
         bool has_view = false;                  // a member is, or reads through, a roll / slice
         std::vector<int> t_sources;             // tensors read through a swap of their last two dims (one LDS tile each)
@@ -167,11 +167,11 @@ struct Builder {
         {
             size_t extra = 0;
             for (int p : transposed_reads(n))
-                if (std::find(grp.t_sources.begin(), grp.t_sources.end(), p) == grp.t_sources.end()) ++extra;
+                if (group_of[p] != gi && std::find(grp.t_sources.begin(), grp.t_sources.end(), p) == grp.t_sources.end()) ++extra;
             if (extra && grp.t_sources.size() + extra > kMaxTransposedOperands) return false;
         }
         for (int p : n.in)
-            if (group_of[p] == gi && !usable_in_kernel(p)) return false;
+            if (group_of[p] == gi && (!usable_in_kernel(p) || kind_of[p] == 4)) return false;
         // the prologue of a column reduction stays where that reduction can follow it
         if (n.col_prologue) {
             if ((grp.tmpl != PF_T_EW_FLAT && grp.tmpl != PF_T_COL_REDUCE) || grp.has_rowuni || grp.has_view) return false;
@@ -214,8 +214,16 @@ struct Builder {
         }
         for (int p : n.in)                                    // a view operand is read from its root
             if (is_view(g.nodes[p].op) && group_of[p] != gi && group_of[root_of(p)] == gi) return false;
+        if (n.op == PF_OP_TRANSPOSE && group_of[n.in[0]] == gi) {
+            // The operand is computed in this kernel.  Only a result that is written out and read by nobody (the
+            // rewrite marks those) can leave through a transposed store; everything else needs the value in memory.
+            if (!n.store_t || !n.is_output || !consumers[id].empty()) return false;
+            if (grp.tmpl != PF_T_EW_FLAT && grp.tmpl != PF_T_TILE) return false;
+            if (grp.has_rowuni || grp.has_view || grp.domain.size() < 2) return false;
+            const Node& x = g.nodes[n.in[0]];
+            return kind_of[n.in[0]] == 2 && x.op != PF_OP_TRANSPOSE && !is_view(x.op) && canon(x.shape) == grp.domain;
+        }
         if (n.op == PF_OP_TRANSPOSE) {
-            if (group_of[n.in[0]] == gi) return false;          // operand must already be in memory
             if (grp.tmpl != PF_T_EW_FLAT && grp.tmpl != PF_T_TILE) return false;
             if (grp.has_rowuni) return false;
             return canon(n.shape) == grp.domain && grp.domain.size() >= 2;
@@ -255,8 +263,10 @@ struct Builder {
             if (gp != gi && std::find(needs[gi].begin(), needs[gi].end(), gp) == needs[gi].end()) needs[gi].push_back(gp);
         grp.nodes.push_back(id);
         group_of[id] = gi;
+        const bool store_side = n.op == PF_OP_TRANSPOSE && group_of[n.in[0]] == gi;
         for (int p : transposed_reads(n))
-            if (std::find(grp.t_sources.begin(), grp.t_sources.end(), p) == grp.t_sources.end()) grp.t_sources.push_back(p);
+            if (!(store_side && p == n.in[0]) && std::find(grp.t_sources.begin(), grp.t_sources.end(), p) == grp.t_sources.end())
+                grp.t_sources.push_back(p);
         int k = 2;
         if (is_col_reduction(n)) {
             if (grp.tmpl != PF_T_COL_REDUCE) grp.epilogue = canon(n.shape);
@@ -265,6 +275,9 @@ struct Builder {
         } else if (grp.tmpl == PF_T_COL_REDUCE) {
             for (int p : n.in)
                 if (group_of[p] == gi && kind_of[p] == 3) k = 3;
+        } else if (store_side) {
+            grp.tmpl = PF_T_TILE;
+            k = 4;
         } else {
             if (n.op == PF_OP_TRANSPOSE) grp.tmpl = PF_T_TILE;
             if (is_reduction(n.op)) grp.tmpl = PF_T_ROW_RESIDENT;
@@ -551,6 +564,7 @@ void plan_with(const pf_graph& g, const pf_options& opt, bool join_earlier, bool
                 add_view_operand(id);
                 continue;
             }
+            if (bg.kinds[m] == 4) continue;            // reads nothing: its operand sits in registers
             const bool epilogue_node = is_col && bg.kinds[m] == 3 && !is_reduction(n.op);
             for (size_t k = 0; k < n.in.size(); ++k) {
                 const int p = n.in[k];
@@ -567,6 +581,20 @@ void plan_with(const pf_graph& g, const pf_options& opt, bool join_earlier, bool
         for (size_t m = 0; m < bg.nodes.size(); ++m) {
             const int id = bg.nodes[m];
             const Node& n = g.nodes[id];
+            if (bg.kinds[m] == 4) {
+                Store s;
+                s.node = id;
+                s.value_node = n.in[0];
+                s.tstore = true;
+                s.dtype = n.dtype;
+                s.shape = n.shape;
+                s.graph_output = output_slot[id];
+                for (size_t k = 0; k < g.outputs.size(); ++k)
+                    if (g.outputs[k] == id && (int)k != output_slot[id]) s.also_outputs.push_back((int)k);
+                grp.stores.push_back(s);
+                mem_dtype[id] = n.dtype;
+                continue;
+            }
             bool outside_use = false;
             for (int c : b.consumers[id]) {
                 const pf_op cop = g.nodes[c].op;
@@ -575,7 +603,8 @@ void plan_with(const pf_graph& g, const pf_options& opt, bool join_earlier, bool
                     if (cop == PF_OP_TRANSPOSE) outside_use = true;
                     continue;
                 }
-                if (b.group_of[c] != (int)gi || !b.usable_in_kernel(id) || cop == PF_OP_TRANSPOSE || is_view(cop)) outside_use = true;
+                const bool stored_through = cop == PF_OP_TRANSPOSE && b.group_of[c] == (int)gi && b.kind_of[c] == 4;    // leaves from registers
+                if (b.group_of[c] != (int)gi || !b.usable_in_kernel(id) || (cop == PF_OP_TRANSPOSE && !stored_through) || is_view(cop)) outside_use = true;
                 for (size_t k = 0; k < g.nodes[c].in.size(); ++k)
                     if (g.nodes[c].in[k] == id && g.nodes[c].reads_alias(k)) outside_use = true;
             }

@@ -19,6 +19,12 @@
 // transposed value, so the caller chooses the reductions to treat this way ("sites") by planning
 // both ways.
 //
+// A third use: when a transpose of a computed value is not worth pushing down by itself (the value's kernel
+// computes other results from the same tensors, so they would be read twice), the transpose's kernel can
+// take over those results as well: it computes them in its own orientation from the tensors it stages
+// anyway and writes them through a transposed store.  The value's kernel then disappears.  These
+// transposes are sites of the caller's search, too.
+//
 // The rewrite clones the elementwise cone above such a transpose, bounded by what
 // the recomputation reads compared with what the round trip would move, and drops
 // nodes nothing observes any more.  Every node of the rewritten graph remembers the
@@ -55,6 +61,7 @@ struct Sinker {
     std::set<int> sites;               // reductions (old ids) to run as column reductions in their sources' orientation
     std::set<int> standin;             // old ids whose new node has the last two dims swapped (same linear order)
     bool in_site = false;              // cloning the cone of a column-reduction site
+    std::set<int> taken_over;          // outputs (old ids) a chosen transpose's kernel computes in its orientation and stores transposed
 
     std::vector<std::vector<int>> readers;   // per old node: the nodes that read it
 
@@ -62,6 +69,53 @@ struct Sinker {
         : src(g), opt(o), map(g.nodes.size(), -1), sites(chosen.begin(), chosen.end()), readers(g.nodes.size()) {
         for (size_t i = 0; i < g.nodes.size(); ++i)
             for (int p : g.nodes[i].in) readers[p].push_back((int)i);
+        for (int t : sites)
+            if (g.nodes[t].op == PF_OP_TRANSPOSE)
+                for (int y : outputs_to_take_over(t)) taken_over.insert(y);
+    }
+
+    // full-size tensors the elementwise cone of x reads from memory; false if the cone holds something that
+    // cannot be recomputed in the other orientation
+    bool cone_leaves(int x, std::set<int>& seen, std::set<int>& leaves, int& n_nodes) const {
+        if (!seen.insert(x).second) return true;
+        const Node& n = src.nodes[x];
+        if (n.op == PF_OP_CONST || n.shape.empty() || moves_no_data(n.shape)) return true;
+        if (sinkable_op(n.op) && n.shape.size() >= 2) {
+            ++n_nodes;
+            for (int p : n.in)
+                if (!cone_leaves(p, seen, leaves, n_nodes)) return false;
+            return true;
+        }
+        if (n.op == PF_OP_TRANSPOSE || is_view(n.op)) return false;
+        leaves.insert(x);
+        return true;
+    }
+
+    // A transpose t = transpose(v) of a computed elementwise value: the outputs of v's own orientation and shape that
+    // read some of what v's cone reads.  Empty if t is no such site.
+    std::vector<int> outputs_to_take_over(int t) const {
+        std::vector<int> ys;
+        const Node& tn = src.nodes[t];
+        if (tn.op != PF_OP_TRANSPOSE || tn.shape.size() < 2) return ys;
+        const int v = tn.in[0];
+        const Node& x = src.nodes[v];
+        if (!sinkable_op(x.op) || x.shape.size() < 2 || moves_no_data(x.shape)) return ys;
+        std::set<int> seen, leaves;
+        int n_nodes = 0;
+        if (!cone_leaves(v, seen, leaves, n_nodes) || n_nodes > 24 || leaves.empty() || leaves.size() > 8) return ys;
+        for (size_t y = 0; y < src.nodes.size(); ++y) {
+            const Node& yn = src.nodes[y];
+            if (!yn.is_output || !sinkable_op(yn.op) || yn.shape != x.shape) continue;      // (y may be v itself: needed both ways)
+            std::set<int> ys_seen, ys_leaves;
+            int yn_nodes = 0;
+            if (!cone_leaves((int)y, ys_seen, ys_leaves, yn_nodes) || yn_nodes > 24) continue;
+            // at least one tensor in common (its bytes are saved), and few enough staged tensors in all; whether
+            // the extra ones pay is the traffic model's call
+            size_t shared = 0;
+            for (int l : ys_leaves) shared += leaves.count(l);
+            if (shared >= 1 && leaves.size() + ys_leaves.size() - shared <= 8) ys.push_back((int)y);
+        }
+        return ys;
     }
 
     int push(const Node& n) {
@@ -233,8 +287,9 @@ struct Sinker {
                     continue;
                 }
                 const bool computed = x.op != PF_OP_INPUT && x.op != PF_OP_CONST;
-                if (computed && x.op != PF_OP_TRANSPOSE && worth_sinking(v)) {
-                    const Ref r = transposed(v, true);
+                const bool chosen = sites.count((int)i) && sinkable_op(x.op) && x.shape.size() >= 2 && !moves_no_data(x.shape);
+                if (computed && x.op != PF_OP_TRANSPOSE && (worth_sinking(v) || chosen)) {
+                    const Ref r = transposed(v, !chosen);
                     // the clone at the top of the cone stands for the transpose node itself
                     out.nodes[r.id].orig = (int)i;
                     out.nodes[r.id].dtype = n.dtype;
@@ -244,7 +299,22 @@ struct Sinker {
                     continue;
                 }
             }
-            if (sites.count((int)i)) {
+            if (taken_over.count((int)i)) {
+                // computed by the kernel of a chosen transpose, in that kernel's orientation, and written through a
+                // transposed store: y = transpose(transpose(y)) with the inner transpose pushed down to y's sources
+                const Ref r = transposed((int)i, false);
+                Node t;
+                t.op = PF_OP_TRANSPOSE;
+                t.dtype = n.dtype;
+                t.in = {r.id};
+                t.shape = n.shape;
+                t.orig = (int)i;
+                t.is_output = true;
+                t.store_t = true;
+                map[i] = push(t);
+                continue;
+            }
+            if (sites.count((int)i) && is_reduction(n.op)) {
                 // reduce(x, last dim) = reduce(transpose(x), dim -2), with transpose(x) computed from x's sources as they lie
                 in_site = true;
                 const Ref r = transposed(n.in[0], false);
@@ -324,14 +394,14 @@ void sink_transposes(const pf_graph& g, const pf_options& opt, const std::vector
     out = s.out;
 }
 
-std::vector<int> column_reduction_sites(const pf_graph& g, const pf_options& opt) {
+std::vector<int> rewrite_sites(const pf_graph& g, const pf_options& opt) {
     Sinker s(g, opt);
     std::vector<std::vector<int>> consumers(g.nodes.size());
     for (size_t i = 0; i < g.nodes.size(); ++i)
         for (int p : g.nodes[i].in) consumers[p].push_back((int)i);
     std::vector<int> sites;
     for (size_t i = 0; i < g.nodes.size(); ++i)
-        if (s.site_possible((int)i, consumers)) sites.push_back((int)i);
+        if (s.site_possible((int)i, consumers) || !s.outputs_to_take_over((int)i).empty()) sites.push_back((int)i);
     return sites;
 }
 

@@ -58,7 +58,15 @@ CASES = [
      [(133, 64), (133, 64), (64, 133)], (1,), 1),
     ("needed in both orientations",
      lambda g, i: (lambda e: [e, g.op("tanh", [g.op("transpose", [e], g.dtype)], g.dtype)])(g.op("exp", [i[0]], g.dtype)),
-     [(3, 50, 72)], (), 2),
+     [(3, 50, 72)], (), 1),          # one tile kernel computes it in the transposed orientation and stores it both ways
+    ("results of both orientations from the same tensor leave one tile kernel",
+     lambda g, i: (lambda e: [g.op("transpose", [g.op("add", [e, g.const(0.587, g.dtype)], g.dtype)], g.dtype), g.op("exp", [i[0]], g.dtype),
+                              g.op("transpose", [g.op("tanh", [e], g.dtype)], g.dtype)])(g.op("exp", [i[0]], g.dtype)),
+     [(133, 70)], (), 1),
+    ("a result of the other orientation that needs one more tensor is taken over as well",
+     lambda g, i: [g.op("div", [g.op("sub", [i[0], i[1]], g.dtype), i[1]], g.dtype),
+                   g.op("tanh", [g.op("transpose", [g.op("gelu", [g.op("rsqrt", [i[1]], g.dtype)], g.dtype, approx="tanh")], g.dtype)], g.dtype)],
+     [(5, 61, 96), (5, 61, 96)], (1,), 1),
     ("batched, scalar constant inside the cone",
      lambda g, i: [g.op("add", [g.op("transpose", [g.op("mul", [g.op("sigmoid", [i[0]], g.dtype), g.const(1.5, g.dtype)], g.dtype)], g.dtype), i[1]], g.dtype)],
      [(4, 33, 80), (80, 1)], (), 1),
@@ -88,6 +96,31 @@ def test_transposes_of_computed_values_match_the_oracle(name, build, shapes, pos
     uo = u.run()
     torch.cuda.synchronize()
     check_against_oracle(w, uo, refs=refs, what=name + " unfused")
+
+
+@pytest.mark.parametrize("dtype,shape", [("bf16", (4096, 4096)), ("bf16", (4100, 4099)), ("f32", (2, 1999, 2050)), ("f16", (3, 1000, 2056))])
+def test_large_tiles_store_results_of_both_orientations(dtype, shape):
+    """64-wide tiles with a store through the LDS transpose: x * w in x's own orientation and its transpose (plus an
+    epilogue) leave one kernel; whole and ragged extents, 16- and 32-bit elements."""
+    t_shape = tuple(shape[:-2]) + (shape[-1], shape[-2])
+
+    def build(g, ins):
+        g.dtype = dtype
+        y = g.op("mul", [ins[0], ins[1]], dtype)                                   # [.., R, C], stays an output in this orientation
+        return [y, g.op("add", [g.op("transpose", [y], dtype), ins[2]], dtype)]     # [.., C, R]
+    w, refs = _workload("both orientations", build, [shape, (shape[-1],), t_shape], dtype)
+    r = Runner(w)
+    assert r.info["n_kernels"] == 1 and r.exe.group_info(0)["template"] == "tile"
+    assert r.info["planned_bytes"] == w.algorithmic_bytes
+    if shape[-1] >= 4096:
+        assert "TS = 64" in r.exe.source(0)
+    outs = r.run()
+    torch.cuda.synchronize()
+    check_against_oracle(w, outs, refs=refs, what="both orientations %s %s" % (dtype, shape))
+    u = Runner(w, fuse=False, intermediates_f32=True)
+    uo = u.run()
+    torch.cuda.synchronize()
+    check_against_oracle(w, uo, refs=refs, what="both orientations unfused")
 
 
 @pytest.mark.parametrize("dtype,shape", [("bf16", (4096, 4096)), ("f16", (2, 3000, 2056)), ("bf16", (4100, 4099)), ("bf16", (3, 2999, 3001)),
