@@ -147,6 +147,7 @@ struct Group {
     int64_t grid2 = 0;
     int block2 = 0;
     std::vector<Store> stores;     // writes
+    int extra_launches = 0;        // plan-time estimate: a column reduction split over workgroups brings a combining kernel
     // launch configuration (filled by codegen)
     int block = 256;
     int64_t grid = 1;
@@ -168,8 +169,9 @@ struct Plan {
 };
 
 void make_plan(const pf_graph& g, const pf_options& opt, Plan& plan);
-// What a plan costs under the traffic model: bytes moved, plus for each kernel what a launch costs at least,
-// expressed in bytes (about 4 us at the rate of a plain copy).
+// What a plan costs under the traffic model: bytes moved (those of kernels that stage tensors through LDS transposes
+// weighted by how much slower such kernels run), plus for each kernel what a launch costs at least, expressed in
+// bytes (about 4 us at the rate of a plain copy).
 constexpr uint64_t kLaunchCostBytes = 24u << 20;
 uint64_t plan_cost(const Plan& plan);
 

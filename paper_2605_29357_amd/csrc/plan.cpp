@@ -655,6 +655,26 @@ void plan_with(const pf_graph& g, const pf_options& opt, bool join_earlier, bool
             }
         }
         if (grp.stores.empty()) continue;   // dead code: nothing observes this group
+        if (is_col) {
+            // will the kernel generator split the rows over workgroups (few column tiles, many rows)?  Then the
+            // group is two launches.  (The same test as in the column-reduction template, on the default tiling.)
+            int min_item = 4;
+            for (auto& o : grp.operands)
+                if (!o.coluni && o.stride[rd - 1] != 0) min_item = std::min(min_item, itemsize(o.dtype));
+            for (auto& st : grp.stores)
+                if (!st.col_uniform) min_item = std::min(min_item, itemsize(st.dtype));
+            const int64_t S = bg.domain[rd - 2], DD = bg.domain[rd - 1];
+            int64_t lead = 1;
+            for (int k = 0; k < rd - 2; ++k) lead *= bg.domain[k];
+            int vec = 16 / min_item;
+            while (vec > 1 && vec > DD) vec >>= 1;
+            const int64_t vcols = (DD + vec - 1) / vec;
+            int tx = 1;
+            while (tx < 16 && tx < vcols) tx <<= 1;
+            bool any_var = false;
+            for (int id : bg.nodes) any_var |= g.nodes[id].op == PF_OP_VAR;
+            if (lead * ((vcols + tx - 1) / tx) < 128 && S >= 8 * (1024 / tx) && !any_var) grp.extra_launches = 1;
+        }
         for (auto& o : grp.operands) grp.bytes_read += (uint64_t)numel(o.shape) * itemsize(o.dtype);
         for (auto& s : grp.stores)
             grp.bytes_written += (uint64_t)numel(s.shape) * itemsize(s.dtype) * (1 + s.also_outputs.size());
@@ -667,7 +687,16 @@ void plan_with(const pf_graph& g, const pf_options& opt, bool join_earlier, bool
 
 uint64_t plan_cost(const Plan& plan) {
     uint64_t c = 0;
-    for (auto& grp : plan.groups) c += grp.bytes_read + grp.bytes_written + kLaunchCostBytes;
+    for (auto& grp : plan.groups) {
+        // Bytes that cross an LDS transpose move slower than streamed ones, the more so the more tensors a tile
+        // kernel stages (measured on 100 - 200 MB kernels: one staged tensor 5.0 - 5.3 TB/s against 6.4 for a flat
+        // kernel, four 4.6 TB/s, eight 3.2 TB/s, where four and more no longer fit 64-wide tiles in 64 KB of LDS)
+        int staged = 0;
+        for (auto& o : grp.operands) staged += o.transposed ? 1 : 0;
+        for (auto& st : grp.stores) staged += st.tstore ? 1 : 0;
+        const double f = staged == 0 ? 1.0 : std::max(1.2, 0.8 + 0.15 * staged);
+        c += (uint64_t)((double)(grp.bytes_read + grp.bytes_written) * f) + kLaunchCostBytes * (uint64_t)(1 + grp.extra_launches);
+    }
     return c;
 }
 
