@@ -216,14 +216,17 @@ struct Emit {
             T <<= 1;
             K = (chunks + T - 1) / T;
         }
-        // Bandwidth regime (24 MB or more cross the kernel; smaller problems are latency-bound and lose 5-15%): with few long rows, more and lighter lanes keep
-        // more loads in flight; spread until the chip is filled twice, as long as no padding is added
-        // (556 x 4096 fp32 rows: 1024 lanes x 4 elements are 20% faster than 256 x 16).
-        if ((int64_t)(grp.bytes_read + grp.bytes_written) >= (int64_t(24) << 20))
-            while (K > 1 && T < 1024 && R * T < 256 * 64 * 32 && slots(T * 2) <= slots(T)) {
-                T <<= 1;
-                K = (chunks + T - 1) / T;
-            }
+        // (Spreading few long rows over still more, lighter lanes once tens of MB cross the kernel paid while the fp32
+        // operators were the library's: 556 x 4096 fp32 rows with three divisions, two tanh and an exp ran 20% faster
+        // with 1024 lanes x 4 elements than with 256 x 16.  With the estimate-based operators it is the other way
+        // round, 20.4 us against 13.4 us, so the rule is gone.)
+        // A workgroup of 1024 lanes leaves each lane 128 registers, one of 512 lanes 256: rows that fit 512 lanes with
+        // at most 32 elements per lane and value run there (96 rows of 11008 fp32 elements with eleven full-size
+        // operands and results spilled 28 registers at 1024 x 12 and ran in 18.6 us, 16.3 us at 512 x 24)
+        if (T == 1024 && (chunks + 511) / 512 <= per_lane_max) {
+            T = 512;
+            K = (chunks + T - 1) / T;
+        }
         if (opt.tune_row_lanes > 0) {
             T = opt.tune_row_lanes;
             if (T & (T - 1) || T > 1024) fail(PF_E_INVALID, "tune_row_lanes must be a power of two <= 1024");
