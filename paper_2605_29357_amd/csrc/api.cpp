@@ -197,27 +197,29 @@ pf_status pf_compile(const pf_graph* g, const pf_options* h_opt, pf_exec** e) {
             if (r) pf::fail(PF_E_INVALID, "pf_options.reserved must be zero");
         std::unique_ptr<pf_exec> ex(new pf_exec());
         ex->opt = opt;
-        // fused plans work on a rewritten copy (transposes of computed values pushed down to the operands)
-        pf_graph work;
+        // Fused plans work on a rewritten copy (transposes of computed values pushed down to the operands).  The
+        // rewrite has optional parts, its sites: reductions that could run in their sources' orientation instead of
+        // behind a transpose, and transposes whose kernel could take over the results of the kernel before it.  Plan
+        // with none, with all, and with each toggled in turn, and keep what the traffic model prefers.
+        std::vector<int> best;
         if (opt.fuse) {
-            // Reductions that could run in their sources' orientation instead of behind a transpose, and transposes whose
-            // kernel could take over the results of the kernel before it: plan with and without each and keep what the traffic model prefers (bytes moved, plus what a kernel costs at least
-            // expressed in bytes: about 4 us at the copy rate).
             const std::vector<int> sites = pf::rewrite_sites(*g, opt);
-            auto cost_of = [&](const std::vector<int>& chosen) {
-                pf_graph w;
-                pf::Plan p;
-                pf::sink_transposes(*g, opt, chosen, w);
-                pf::make_plan(w, opt, p);
-                return pf::plan_cost(p);
+            auto cost_of = [&](const std::vector<int>& chosen) -> uint64_t {
+                try {
+                    pf_graph w;
+                    pf::Plan p;
+                    pf::sink_transposes(*g, opt, chosen, w);
+                    pf::make_plan(w, opt, p);
+                    return pf::plan_cost(p);
+                } catch (const pf::Error&) {
+                    return ~uint64_t(0);        // this choice does not plan: any other is cheaper
+                }
             };
-            std::vector<int> best;
             if (!sites.empty()) {
                 uint64_t best_cost = cost_of(best);
                 const uint64_t all_cost = cost_of(sites);
                 if (all_cost < best_cost) { best = sites; best_cost = all_cost; }
-                // one site at a time, from whichever end is ahead
-                for (int s : sites) {
+                for (int s : sites) {              // one site at a time, from whichever end is ahead
                     std::vector<int> trial = best;
                     auto it = std::find(trial.begin(), trial.end(), s);
                     if (it == trial.end()) trial.push_back(s);
@@ -227,33 +229,43 @@ pf_status pf_compile(const pf_graph* g, const pf_options* h_opt, pf_exec** e) {
                     if (c < best_cost) { best = trial; best_cost = c; }
                 }
             }
-            pf::sink_transposes(*g, opt, best, work);
-        } else {
-            work = *g;
         }
-        pf::make_plan(work, opt, ex->plan);
-        int idx = 0;
-        for (auto& grp : ex->plan.groups) {
-            for (int id : grp.nodes) {
-                const int user = opt.fuse ? work.nodes[id].orig : id;
-                if (user >= 0) grp.user_nodes.push_back(user);
+        auto build = [&](const std::vector<int>& chosen) {
+            pf_graph work;
+            if (opt.fuse) pf::sink_transposes(*g, opt, chosen, work);
+            else work = *g;
+            ex->plan = pf::Plan();
+            pf::make_plan(work, opt, ex->plan);
+            int idx = 0;
+            for (auto& grp : ex->plan.groups) {
+                for (int id : grp.nodes) {
+                    const int user = opt.fuse ? work.nodes[id].orig : id;
+                    if (user >= 0) grp.user_nodes.push_back(user);
+                }
+                size_t n_args = grp.operands.size() + 2;
+                for (auto& st : grp.stores) n_args += 1 + st.also_outputs.size();
+                if (n_args > (size_t)pf::kMaxKernelArgs)
+                    pf::fail(PF_E_COMPILE, "a fused group would take %zu kernel arguments (limit %d)", n_args, pf::kMaxKernelArgs);
+                pf::generate_source(work, opt, grp, idx++);
+                if (grp.grid > 0x7fffffffLL || grp.grid2 > 0x7fffffffLL)
+                    pf::fail(PF_E_COMPILE, "kernel %s would need %lld workgroups; a launch holds at most 2^31 - 1", grp.kernel_name.c_str(),
+                             (long long)std::max(grp.grid, grp.grid2));
+                if (grp.scratch_bytes) {     // partial results of a split reduction live at the end of the workspace
+                    const uint64_t at = (ex->plan.workspace_bytes + 255) / 256 * 256;
+                    grp.scratch_offset = (int64_t)at;
+                    ex->plan.workspace_bytes = at + grp.scratch_bytes;
+                    grp.bytes_written += grp.scratch_bytes;
+                    grp.bytes_read += grp.scratch_bytes;
+                }
+                pf::jit_compile(grp);
             }
-            size_t n_args = grp.operands.size() + 2;
-            for (auto& st : grp.stores) n_args += 1 + st.also_outputs.size();
-            if (n_args > (size_t)pf::kMaxKernelArgs)
-                pf::fail(PF_E_COMPILE, "a fused group would take %zu kernel arguments (limit %d)", n_args, pf::kMaxKernelArgs);
-            pf::generate_source(work, opt, grp, idx++);
-            if (grp.grid > 0x7fffffffLL || grp.grid2 > 0x7fffffffLL)
-                pf::fail(PF_E_COMPILE, "kernel %s would need %lld workgroups; a launch holds at most 2^31 - 1", grp.kernel_name.c_str(),
-                         (long long)std::max(grp.grid, grp.grid2));
-            if (grp.scratch_bytes) {     // partial results of a split reduction live at the end of the workspace
-                const uint64_t at = (ex->plan.workspace_bytes + 255) / 256 * 256;
-                grp.scratch_offset = (int64_t)at;
-                ex->plan.workspace_bytes = at + grp.scratch_bytes;
-                grp.bytes_written += grp.scratch_bytes;
-                grp.bytes_read += grp.scratch_bytes;
-            }
-            pf::jit_compile(grp);
+        };
+        try {
+            build(best);
+        } catch (const pf::Error&) {
+            // a limit of the kernel generator (kernel arguments, LDS) that the plain rewrite may stay within
+            if (best.empty()) throw;
+            build({});
         }
         ex->n_inputs = (int)g->inputs.size();
         ex->n_outputs = (int)g->outputs.size();
