@@ -179,7 +179,8 @@ uint64_t plan_cost(const Plan& plan);
 // `sites` (caller's node ids, from rewrite_sites): reductions over the last dim to run as reductions over dim -2
 // of their operand's cone, evaluated in the orientation its sources have in memory; and transposes of computed
 // values whose kernel is to take over what the value's own kernel computes besides (results of that orientation
-// are then written through a transposed store)
+// are then written through a transposed store); and, listed as -(node + 1), transposes that only the caller reads, to
+// be written by the kernel that computes their operand
 void sink_transposes(const pf_graph& g, const pf_options& opt, const std::vector<int>& sites, pf_graph& out);
 std::vector<int> rewrite_sites(const pf_graph& g, const pf_options& opt);
 

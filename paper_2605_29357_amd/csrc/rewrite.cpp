@@ -70,7 +70,7 @@ struct Sinker {
         for (size_t i = 0; i < g.nodes.size(); ++i)
             for (int p : g.nodes[i].in) readers[p].push_back((int)i);
         for (int t : sites)
-            if (g.nodes[t].op == PF_OP_TRANSPOSE)
+            if (t >= 0 && g.nodes[t].op == PF_OP_TRANSPOSE)
                 for (int y : outputs_to_take_over(t)) taken_over.insert(y);
     }
 
@@ -89,6 +89,17 @@ struct Sinker {
         if (n.op == PF_OP_TRANSPOSE || is_view(n.op)) return false;
         leaves.insert(x);
         return true;
+    }
+
+    // A transpose that nothing reads but the caller, of a computed elementwise value: instead of recomputing the value in
+    // the other orientation (a kernel of its own unless other work of that orientation exists), the kernel that
+    // computes the value can write it out both ways.  Sites of this kind are listed as store_site(node).
+    static int store_site(int t) { return -(t + 1); }
+    bool store_through_possible(int t) const {
+        const Node& tn = src.nodes[t];
+        if (tn.op != PF_OP_TRANSPOSE || tn.shape.size() < 2 || !tn.is_output || !readers[t].empty()) return false;
+        const Node& x = src.nodes[tn.in[0]];
+        return sinkable_op(x.op) && x.shape.size() >= 2 && !moves_no_data(x.shape) && x.dtype == tn.dtype;
     }
 
     // A transpose t = transpose(v) of a computed elementwise value: the outputs of v's own orientation and shape that
@@ -287,6 +298,15 @@ struct Sinker {
                     continue;
                 }
                 const bool computed = x.op != PF_OP_INPUT && x.op != PF_OP_CONST;
+                if (sites.count(store_site((int)i)) && store_through_possible((int)i)) {
+                    // written by the kernel that computes the value, through that kernel's transposed store
+                    Node c = n;
+                    c.orig = (int)i;
+                    c.in = {map[v]};
+                    c.store_t = true;
+                    map[i] = push(c);
+                    continue;
+                }
                 const bool chosen = sites.count((int)i) && sinkable_op(x.op) && x.shape.size() >= 2 && !moves_no_data(x.shape);
                 if (computed && x.op != PF_OP_TRANSPOSE && (worth_sinking(v) || chosen)) {
                     const Ref r = transposed(v, !chosen);
@@ -402,6 +422,8 @@ std::vector<int> rewrite_sites(const pf_graph& g, const pf_options& opt) {
     std::vector<int> sites;
     for (size_t i = 0; i < g.nodes.size(); ++i)
         if (s.site_possible((int)i, consumers) || !s.outputs_to_take_over((int)i).empty()) sites.push_back((int)i);
+    for (size_t i = 0; i < g.nodes.size(); ++i)
+        if (s.store_through_possible((int)i)) sites.push_back(Sinker::store_site((int)i));
     return sites;
 }
 

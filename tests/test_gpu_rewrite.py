@@ -67,6 +67,10 @@ CASES = [
      lambda g, i: [g.op("div", [g.op("sub", [i[0], i[1]], g.dtype), i[1]], g.dtype),
                    g.op("tanh", [g.op("transpose", [g.op("gelu", [g.op("rsqrt", [i[1]], g.dtype)], g.dtype, approx="tanh")], g.dtype)], g.dtype)],
      [(5, 61, 96), (5, 61, 96)], (1,), 1),
+    ("a transpose only the caller reads is written by the kernel that computes its operand",
+     lambda g, i: (lambda v: [g.op("transpose", [g.op("tanh", [v], g.dtype)], g.dtype), g.op("add", [v, i[2]], g.dtype)])(
+         g.op("sub", [i[0], i[1]], g.dtype)),
+     [(3, 96, 259), (96, 1), (3, 96, 259)], (), 1),
     ("batched, scalar constant inside the cone",
      lambda g, i: [g.op("add", [g.op("transpose", [g.op("mul", [g.op("sigmoid", [i[0]], g.dtype), g.const(1.5, g.dtype)], g.dtype)], g.dtype), i[1]], g.dtype)],
      [(4, 33, 80), (80, 1)], (), 1),
