@@ -144,7 +144,8 @@ typedef struct {
     int tune_row_unroll;   /* row templates: rows in flight per team of lanes                     */
     int tune_flat_unroll;  /* ew_flat: 16-byte vectors per lane; tile: consecutive tiles per XCD  */
     int tune_col_block;    /* col_reduce: lanes per workgroup (power of two, 64..1024)             */
-    int reserved[2];       /* must be zero */
+    int tune_tile_edge;    /* tile: edge of the LDS tile, 32 or 64                                 */
+    int reserved[1];       /* must be zero */
 } pf_options;
 
 void pf_options_default(pf_options* h_opt);

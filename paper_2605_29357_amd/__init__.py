@@ -34,7 +34,7 @@ class _Attr(C.Structure):
 class _Options(C.Structure):
     _fields_ = [("fuse", C.c_int), ("intermediates_f32", C.c_int), ("tune_row_lanes", C.c_int),
                 ("tune_row_unroll", C.c_int), ("tune_flat_unroll", C.c_int), ("tune_col_block", C.c_int),
-                ("reserved", C.c_int * 2)]
+                ("tune_tile_edge", C.c_int), ("reserved", C.c_int * 1)]
 
 
 class _NodeInfo(C.Structure):

@@ -1092,7 +1092,11 @@ struct Emit {
         for (auto& o : grp.operands) n_t += o.transposed ? 1 : 0;
         // every transposed operand is staged through a padded LDS tile of its own; a workgroup may declare 64 KB
         auto lds_bytes = [&](int ts) { return (int64_t)std::max(n_t, 1) * ts * (ts + 1) * 4; };
-        const int TS = (t64 < few_tiles || lds_bytes(64) > 64 * 1024) ? 32 : 64;
+        int TS = (t64 < few_tiles || lds_bytes(64) > 64 * 1024) ? 32 : 64;
+        if (opt.tune_tile_edge > 0) {
+            if (opt.tune_tile_edge != 32 && opt.tune_tile_edge != 64) fail(PF_E_INVALID, "tune_tile_edge must be 32 or 64");
+            if (lds_bytes(opt.tune_tile_edge) <= 64 * 1024) TS = opt.tune_tile_edge;
+        }
         if (lds_bytes(TS) > 64 * 1024)
             fail(PF_E_COMPILE, "a tiled group with %d transposed operands needs %lld bytes of LDS", n_t, (long long)lds_bytes(TS));
         // 16-byte accesses on both sides: four fp32 elements per lane and row, eight when every tensor of the
