@@ -486,3 +486,15 @@ def test_a_16_bit_value_that_is_only_moved_crosses_kernels_in_16_bits():
 
     e2, tmpl2, info2 = _plan(build2, [(R, C)] * 4, ["bf16"] * 4)
     assert info2["workspace_bytes"] == 0 or info2["workspace_bytes"] >= 4 * R * C or "col_reduce" in tmpl2
+
+
+def test_the_tile_edge_can_be_overridden_for_experiments():
+    g = Builder()
+    x = g.input("f32", (300, 200))
+    g.output(g.op("exp", [g.op("transpose", [x], "f32")], "f32"))
+    auto = pf.Exec(g.text()).source(0)
+    assert "TS = 32" in auto                                     # a small problem: many small tiles
+    assert "TS = 64" in pf.Exec(g.text(), tune_tile_edge=64).source(0)
+    assert "TS = 32" in pf.Exec(g.text(), tune_tile_edge=32).source(0)
+    with pytest.raises(pf.PfError, match="tune_tile_edge"):
+        pf.Exec(g.text(), tune_tile_edge=48)
