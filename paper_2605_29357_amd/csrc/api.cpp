@@ -257,8 +257,38 @@ pf_status pf_compile(const pf_graph* g, const pf_options* h_opt, pf_exec** e) {
                     grp.bytes_written += grp.scratch_bytes;
                     grp.bytes_read += grp.scratch_bytes;
                 }
-                pf::jit_compile(grp);
             }
+            // One-workgroup kernels that touch nothing another kernel of the plan touches (they read graph inputs
+            // and write graph outputs nobody reads back) ride on another kernel instead of costing a launch.
+            if (opt.fuse) {
+                auto& groups = ex->plan.groups;
+                for (size_t r = 0; r < groups.size() && groups.size() > 1;) {
+                    const pf::Group& rider = groups[r];
+                    bool alone = rider.grid == 1;
+                    for (auto& o : rider.operands) alone &= o.graph_input >= 0;
+                    for (auto& st : rider.stores) alone &= st.graph_output >= 0 && st.ws_offset < 0;
+                    for (size_t j = 0; j < groups.size() && alone; ++j)
+                        if (j != r)
+                            for (auto& o : groups[j].operands)
+                                for (auto& st : rider.stores) alone &= o.node != st.node;
+                    bool attached = false;
+                    for (size_t h = 0; h < groups.size() && alone && !attached; ++h) {
+                        if (h == r) continue;
+                        size_t n_args = groups[h].operands.size() + rider.operands.size() + 2;
+                        for (auto& rd : groups[h].riders) {
+                            n_args += rd.operands.size();
+                            for (auto& st : rd.stores) n_args += 1 + st.also_outputs.size();
+                        }
+                        for (auto& st : groups[h].stores) n_args += 1 + st.also_outputs.size();
+                        for (auto& st : rider.stores) n_args += 1 + st.also_outputs.size();
+                        if (n_args > (size_t)pf::kMaxKernelArgs) continue;
+                        attached = pf::attach_rider(groups[h], rider);
+                    }
+                    if (attached) groups.erase(groups.begin() + (long)r);
+                    else ++r;
+                }
+            }
+            for (auto& grp : ex->plan.groups) pf::jit_compile(grp);
         };
         try {
             build(best);

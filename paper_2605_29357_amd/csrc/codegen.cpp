@@ -1475,6 +1475,7 @@ struct Emit {
         grp.kernel_name = nm;
         if (!grp.kernel2_name.empty()) grp.kernel2_name = nm + "_fin";
         grp.source = s;
+        grp.source_body_at = s.find(kDevicePrelude) + std::string(kDevicePrelude).size();      // the header line above it has just changed length
     }
 };
 
@@ -1483,6 +1484,98 @@ struct Emit {
 void generate_source(const pf_graph& g, const pf_options& opt, Group& grp, int index) {
     Emit e(g, opt, grp);
     e.run(index);
+}
+
+namespace {
+
+// p12 -> r0_p12, q3 -> r0_q3 (whole identifiers only)
+std::string rename_pointer_params(const std::string& text, const std::string& prefix) {
+    std::string out;
+    out.reserve(text.size() + 64);
+    auto ident = [](char c) { return (c >= 'a' && c <= 'z') || (c >= 'A' && c <= 'Z') || (c >= '0' && c <= '9') || c == '_'; };
+    for (size_t i = 0; i < text.size();) {
+        if ((text[i] == 'p' || text[i] == 'q') && (i == 0 || !ident(text[i - 1])) && i + 1 < text.size() && text[i + 1] >= '0' && text[i + 1] <= '9') {
+            size_t j = i + 1;
+            while (j < text.size() && text[j] >= '0' && text[j] <= '9') ++j;
+            if (j == text.size() || !ident(text[j])) {
+                out += prefix;
+                out.append(text, i, j - i);
+                i = j;
+                continue;
+            }
+        }
+        out += text[i++];
+    }
+    return out;
+}
+
+void replace_all(std::string& s, const std::string& what, const std::string& with) {
+    for (size_t at = 0; (at = s.find(what, at)) != std::string::npos; at += with.size()) s.replace(at, what.size(), with);
+}
+
+}  // namespace
+
+// A subgraph often has a small side computation (a chain on a weight vector, on per-row scalars) whose kernel is one
+// workgroup: a launch of its own costs ~4 us for microseconds of nothing.  Such a kernel rides on another kernel of
+// the plan instead: the host is launched with one workgroup more, and that workgroup runs the rider's code.  The
+// rider's kernel text becomes a device function in a namespace of its own (its pointer parameters renamed, its
+// workgroup index the constant 0); the host's kernel gets the rider's pointers after its own parameters and one
+// line at its top that sends workgroup number host.grid to the rider.
+bool attach_rider(Group& host, const Group& rider) {
+    if (rider.grid != 1 || !rider.kernel2_name.empty() || !host.kernel2_name.empty() || rider.scratch_bytes || !rider.riders.empty() || host.riders.size() >= 4) return false;
+    if (host.block != rider.block || host.source_body_at == 0 || rider.source_body_at == 0) return false;
+    // a tile kernel that stages several tensors has little LDS to spare for a rider's own
+    int staged = 0;
+    for (auto& o : host.operands) staged += o.transposed ? 1 : 0;
+    for (auto& st : host.stores) staged += st.tstore ? 1 : 0;
+    if (staged > 2) return false;
+    const std::string head = "extern \"C\" __global__ void __launch_bounds__(";
+    std::string rtext = rider.source.substr(rider.source_body_at);
+    const size_t rk = rtext.find(head);
+    if (rk == std::string::npos || rtext.find(head, rk + 1) != std::string::npos) return false;
+    const size_t rname_at = rtext.find(") ", rk + head.size());
+    const size_t rparen = rtext.find('(', rname_at + 2);
+    if (rname_at == std::string::npos || rparen == std::string::npos) return false;
+    const std::string tag = strf("r%zu_", host.riders.size()), space = strf("pf_rider%zu", host.riders.size());
+    rtext.replace(rk, rparen - rk, "__device__ __forceinline__ void pf_rider_kernel");
+    replace_all(rtext, "blockIdx.x", "0u");
+    rtext = rename_pointer_params(rtext, tag);
+
+    std::string htext = host.source.substr(host.source_body_at);
+    const size_t hk = htext.find(head);
+    if (hk == std::string::npos) return false;
+    const size_t hopen = htext.find('(', htext.find(") ", hk + head.size()) + 2);
+    const size_t hclose = htext.find(") {", hopen);
+    if (hopen == std::string::npos || hclose == std::string::npos) return false;
+    // the rider's pointers, as parameters of the host and as arguments of the call
+    std::string params, args;
+    auto add = [&](const std::string& type, const std::string& name) {
+        params += ", " + type + " " + name;
+        args += (args.empty() ? "" : ", ") + name;
+    };
+    auto tn = [](pf_dtype d) { return d == PF_BF16 ? "u16" : d == PF_F16 ? "f16" : "float"; };
+    for (size_t oi = 0; oi < rider.operands.size(); ++oi) add(strf("const %s* __restrict__", tn(rider.operands[oi].dtype)), strf("%sp%zu", tag.c_str(), oi));
+    int sp = 0;
+    for (auto& st : rider.stores)
+        for (size_t c = 0; c < 1 + st.also_outputs.size(); ++c, ++sp) add(strf("%s* __restrict__", tn(st.dtype)), strf("%sq%d", tag.c_str(), sp));
+    if (rider.outer_runtime) args += strf("%s(long long)%lld", args.empty() ? "" : ", ", (long long)rider.outer_extent);
+    std::string call = strf("\n    if (blockIdx.x == %lldu) { %s::pf_rider_kernel(%s); return; }", (long long)host.grid, space.c_str(), args.c_str());
+    htext.insert(hclose + 3, call);
+    htext.insert(hclose, params);
+    // (an earlier rider's parameters already follow the host's: this one's go after them, before the closing parenthesis)
+    host.source = host.source.substr(0, host.source_body_at) + "namespace " + space + " {\n" + rtext + "}  // namespace " + space + "\n" + htext;
+    Group::Rider rd;
+    rd.operands = rider.operands;
+    rd.stores = rider.stores;
+    host.riders.push_back(std::move(rd));
+    host.grid += 1;
+    host.rt_per_block = 0;                  // the rider's workgroup number is literal: no other outermost extent
+    host.bytes_read += rider.bytes_read;
+    host.bytes_written += rider.bytes_written;
+    host.nodes.insert(host.nodes.end(), rider.nodes.begin(), rider.nodes.end());
+    host.user_nodes.insert(host.user_nodes.end(), rider.user_nodes.begin(), rider.user_nodes.end());
+    host.node_kind.insert(host.node_kind.end(), rider.node_kind.begin(), rider.node_kind.end());
+    return true;
 }
 
 }  // namespace pf

@@ -153,6 +153,14 @@ struct Group {
     int64_t grid = 1;
     int lanes_per_row = 0;
     int vec = 1, chunks_per_lane = 1;
+    // A one-workgroup group that rides on this kernel as an extra workgroup (see attach_rider): its pointer
+    // arguments follow this group's own
+    struct Rider {
+        std::vector<Operand> operands;
+        std::vector<Store> stores;
+    };
+    std::vector<Rider> riders;     // in the order of their parameters in the kernel's signature
+    size_t source_body_at = 0;     // where the kernel text starts in `source`, after the common prelude
     std::string source;            // generated HIP
     std::string kernel_name;
     std::vector<char> code;        // code object
@@ -186,6 +194,9 @@ std::vector<int> rewrite_sites(const pf_graph& g, const pf_options& opt);
 
 // ---- codegen.cpp ----
 void generate_source(const pf_graph& g, const pf_options& opt, Group& grp, int index);
+// Lets the one-workgroup kernel of `rider` run as workgroup number host.grid of the host's kernel (both already
+// generated, same workgroup size, independent of each other).  False, and nothing changed, if they do not fit.
+bool attach_rider(Group& host, const Group& rider);
 
 // ---- runtime.cpp ----
 void jit_compile(Group& grp);

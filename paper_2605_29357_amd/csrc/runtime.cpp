@@ -244,6 +244,24 @@ void exec_run(pf_exec& e, const void* const* d_inputs, void* const* d_outputs, v
             args[n] = &ptrs[n];
             ++n;
         }
+        // the riders' pointers follow the host's own arguments, rider by rider: operands, then results
+        for (auto& rd : grp.riders) {
+            for (auto& o : rd.operands) {
+                ptrs[n] = (void*)d_inputs[o.graph_input];
+                args[n] = &ptrs[n];
+                ++n;
+            }
+            for (auto& st : rd.stores) {
+                ptrs[n] = d_outputs[st.graph_output];
+                args[n] = &ptrs[n];
+                ++n;
+                for (int k : st.also_outputs) {
+                    ptrs[n] = d_outputs[k];
+                    args[n] = &ptrs[n];
+                    ++n;
+                }
+            }
+        }
         // events, when given, bracket the kernels themselves (dispatch timestamps), not the
         // launch calls: the first kernel carries the start event, the last one the stop event
         const bool two = e.functions2[i] != nullptr;

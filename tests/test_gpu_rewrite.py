@@ -148,3 +148,29 @@ def test_large_transposes_with_an_epilogue(dtype, shape):
     moved = to_host_bits(outs[0], dtype)
     np.testing.assert_array_equal(moved, np.swapaxes(w.inputs[0], -1, -2))      # the bits themselves
     check_against_oracle(w, outs, refs=refs, what="large transpose %s %s" % (dtype, shape))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_small_side_computations_ride_on_another_kernel(dtype):
+    """A chain on a weight vector and one on per-row scalars would each be a one-workgroup kernel; independent of the
+    main kernel, they run as extra workgroups of it: one launch, four outputs."""
+    R, C = 300, 96
+
+    def build(g, ins):
+        g.dtype = dtype
+        x, wgt, per_row = ins                                                     # [R,C], [C], [R,1]
+        main = g.op("mul", [g.op("sub", [x, g.op("mean", [x], dtype)], dtype), wgt], dtype)
+        side_w = g.op("mul", [g.op("sigmoid", [wgt], dtype), g.const(2.0, dtype)], dtype)
+        side_sum = g.op("sum", [g.op("exp", [wgt], dtype)], dtype)
+        return [main, side_w, side_sum, g.op("tanh", [per_row], dtype)]
+    w, refs = _workload("riders", build, [(R, C), (C,), (R, 1)], dtype)
+    r = Runner(w)
+    assert r.info["n_kernels"] == 1 and "pf_rider1" in r.exe.source(0)
+    outs = r.run()
+    torch.cuda.synchronize()
+    check_against_oracle(w, outs, refs=refs, what="riders " + dtype)
+    u = Runner(w, fuse=False, intermediates_f32=True)
+    assert u.info["n_kernels"] == 8
+    uo = u.run()
+    torch.cuda.synchronize()
+    check_against_oracle(w, uo, refs=refs, what="riders unfused")

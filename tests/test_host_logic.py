@@ -498,3 +498,32 @@ def test_the_tile_edge_can_be_overridden_for_experiments():
     assert "TS = 32" in pf.Exec(g.text(), tune_tile_edge=32).source(0)
     with pytest.raises(pf.PfError, match="tune_tile_edge"):
         pf.Exec(g.text(), tune_tile_edge=48)
+
+
+def test_riders_keep_their_pointers_together_in_the_host_signature():
+    # two one-workgroup side computations ride on the main kernel: the launch passes, after the host's own arguments,
+    # each rider's operands and then its results, rider by rider - the signature must list them in that order
+    g = Builder()
+    x, wgt, per_row = g.input("f32", (300, 96)), g.input("f32", (96,)), g.input("f32", (300, 1))
+    g.output(g.op("mul", [g.op("sub", [x, g.op("mean", [x], "f32")], "f32"), wgt], "f32"))
+    g.output(g.op("mul", [g.op("sigmoid", [wgt], "f32"), g.const(2.0, "f32")], "f32"))
+    g.output(g.op("sum", [g.op("exp", [wgt], "f32")], "f32"))
+    g.output(g.op("tanh", [per_row], "f32"))
+    e = pf.Exec(g.text())
+    assert e.info()["n_kernels"] == 1
+    src = e.source(0)
+    sig = src[src.index('extern "C" __global__'):]
+    sig = sig[sig.index("(", sig.index(")") + 1) + 1:sig.index(") {")]          # past __launch_bounds__(256)
+    names = [p.split()[-1] for p in sig.split(",")]
+    own = [n for n in names if not n.startswith("r")]
+    riders = [n for n in names if n.startswith("r")]
+    assert names == own + riders and own[-1] == "pf_d0"
+    assert [n[0] for n in own[:-1]] == sorted(n[0] for n in own[:-1])              # p..., then q...
+    # rider by rider, operands before results
+    keys = [(int(n[1:n.index("_")]), n[n.index("_") + 1]) for n in riders]
+    assert keys == sorted(keys) and {k[0] for k in keys} == {0, 1}
+    assert sum(1 for k in keys if k[1] == "q") == 3 and len(own) - 1 == 2 + 1      # three side results; host: x, w in, one out
+    # the extra workgroups are dispatched before anything else happens
+    body = src[src.index(") {", src.index('extern "C" __global__')):]
+    assert body.index("pf_rider0::pf_rider_kernel") < body.index("constexpr int T")
+    assert "blockIdx.x == %du" % (e.group_info(0)["grid_blocks"] - 1) in body and "blockIdx.x == %du" % (e.group_info(0)["grid_blocks"] - 2) in body
