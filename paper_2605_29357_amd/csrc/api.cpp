@@ -258,34 +258,47 @@ pf_status pf_compile(const pf_graph* g, const pf_options* h_opt, pf_exec** e) {
                     grp.bytes_read += grp.scratch_bytes;
                 }
             }
-            // One-workgroup kernels that touch nothing another kernel of the plan touches (they read graph inputs
+            // Kernels of a few workgroups that touch nothing another kernel of the plan touches (they read graph inputs
             // and write graph outputs nobody reads back) ride on another kernel instead of costing a launch.
             if (opt.fuse) {
                 auto& groups = ex->plan.groups;
-                for (size_t r = 0; r < groups.size() && groups.size() > 1;) {
+                auto alone = [&](size_t r) {
                     const pf::Group& rider = groups[r];
-                    bool alone = rider.grid == 1;
-                    for (auto& o : rider.operands) alone &= o.graph_input >= 0;
-                    for (auto& st : rider.stores) alone &= st.graph_output >= 0 && st.ws_offset < 0;
-                    for (size_t j = 0; j < groups.size() && alone; ++j)
+                    bool ok = rider.grid >= 1 && rider.grid <= 64 && rider.riders.empty();
+                    for (auto& o : rider.operands) ok &= o.graph_input >= 0;
+                    for (auto& st : rider.stores) ok &= st.graph_output >= 0 && st.ws_offset < 0;
+                    for (size_t j = 0; j < groups.size() && ok; ++j)
                         if (j != r)
                             for (auto& o : groups[j].operands)
-                                for (auto& st : rider.stores) alone &= o.node != st.node;
-                    bool attached = false;
-                    for (size_t h = 0; h < groups.size() && alone && !attached; ++h) {
-                        if (h == r) continue;
-                        size_t n_args = groups[h].operands.size() + rider.operands.size() + 2;
-                        for (auto& rd : groups[h].riders) {
-                            n_args += rd.operands.size();
-                            for (auto& st : rd.stores) n_args += 1 + st.also_outputs.size();
+                                for (auto& st : rider.stores) ok &= o.node != st.node;
+                    return ok;
+                };
+                // the smallest such kernel first, onto the largest kernel that takes it
+                for (bool again = true; again && groups.size() > 1;) {
+                    again = false;
+                    std::vector<size_t> order(groups.size());
+                    for (size_t k = 0; k < order.size(); ++k) order[k] = k;
+                    std::stable_sort(order.begin(), order.end(), [&](size_t a, size_t b) { return groups[a].grid < groups[b].grid; });
+                    for (size_t r : order) {
+                        if (!alone(r)) continue;
+                        for (auto it = order.rbegin(); it != order.rend() && !again; ++it) {
+                            const size_t h = *it;
+                            if (h == r || groups[h].grid < groups[r].grid) continue;
+                            size_t n_args = groups[h].operands.size() + groups[r].operands.size() + 2;
+                            for (auto& st : groups[h].stores) n_args += 1 + st.also_outputs.size();
+                            for (auto& st : groups[r].stores) n_args += 1 + st.also_outputs.size();
+                            for (auto& rd : groups[h].riders) {
+                                n_args += rd.operands.size();
+                                for (auto& st : rd.stores) n_args += 1 + st.also_outputs.size();
+                            }
+                            if (n_args > (size_t)pf::kMaxKernelArgs) continue;
+                            again = pf::attach_rider(groups[h], groups[r]);
                         }
-                        for (auto& st : groups[h].stores) n_args += 1 + st.also_outputs.size();
-                        for (auto& st : rider.stores) n_args += 1 + st.also_outputs.size();
-                        if (n_args > (size_t)pf::kMaxKernelArgs) continue;
-                        attached = pf::attach_rider(groups[h], rider);
+                        if (again) {
+                            groups.erase(groups.begin() + (long)r);
+                            break;
+                        }
                     }
-                    if (attached) groups.erase(groups.begin() + (long)r);
-                    else ++r;
                 }
             }
             for (auto& grp : ex->plan.groups) pf::jit_compile(grp);

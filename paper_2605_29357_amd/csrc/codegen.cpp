@@ -1516,13 +1516,13 @@ void replace_all(std::string& s, const std::string& what, const std::string& wit
 }  // namespace
 
 // A subgraph often has a small side computation (a chain on a weight vector, on per-row scalars) whose kernel is one
-// workgroup: a launch of its own costs ~4 us for microseconds of nothing.  Such a kernel rides on another kernel of
-// the plan instead: the host is launched with one workgroup more, and that workgroup runs the rider's code.  The
+// workgroup or a few: a launch of its own costs ~4 us for microseconds of nothing.  Such a kernel rides on another kernel
+// of the plan instead: the host is launched with that many workgroups more, and those run the rider's code.  The
 // rider's kernel text becomes a device function in a namespace of its own (its pointer parameters renamed, its
-// workgroup index the constant 0); the host's kernel gets the rider's pointers after its own parameters and one
-// line at its top that sends workgroup number host.grid to the rider.
+// workgroup index counted from the host's grid); the host's kernel gets the rider's pointers after its own parameters
+// and one line at its top that sends the workgroups past its own grid to the rider.
 bool attach_rider(Group& host, const Group& rider) {
-    if (rider.grid != 1 || !rider.kernel2_name.empty() || !host.kernel2_name.empty() || rider.scratch_bytes || !rider.riders.empty() || host.riders.size() >= 4) return false;
+    if (rider.grid < 1 || rider.grid > 64 || !rider.kernel2_name.empty() || !host.kernel2_name.empty() || rider.scratch_bytes || !rider.riders.empty() || host.riders.size() >= 4) return false;
     if (host.block != rider.block || host.source_body_at == 0 || rider.source_body_at == 0) return false;
     // a tile kernel that stages several tensors has little LDS to spare for a rider's own
     int staged = 0;
@@ -1538,7 +1538,7 @@ bool attach_rider(Group& host, const Group& rider) {
     if (rname_at == std::string::npos || rparen == std::string::npos) return false;
     const std::string tag = strf("r%zu_", host.riders.size()), space = strf("pf_rider%zu", host.riders.size());
     rtext.replace(rk, rparen - rk, "__device__ __forceinline__ void pf_rider_kernel");
-    replace_all(rtext, "blockIdx.x", "0u");
+    replace_all(rtext, "blockIdx.x", strf("(blockIdx.x - %lldu)", (long long)host.grid));      // the rider's workgroups follow the host's
     rtext = rename_pointer_params(rtext, tag);
 
     std::string htext = host.source.substr(host.source_body_at);
@@ -1559,7 +1559,8 @@ bool attach_rider(Group& host, const Group& rider) {
     for (auto& st : rider.stores)
         for (size_t c = 0; c < 1 + st.also_outputs.size(); ++c, ++sp) add(strf("%s* __restrict__", tn(st.dtype)), strf("%sq%d", tag.c_str(), sp));
     if (rider.outer_runtime) args += strf("%s(long long)%lld", args.empty() ? "" : ", ", (long long)rider.outer_extent);
-    std::string call = strf("\n    if (blockIdx.x == %lldu) { %s::pf_rider_kernel(%s); return; }", (long long)host.grid, space.c_str(), args.c_str());
+    std::string call = strf("\n    if (blockIdx.x >= %lldu && blockIdx.x < %lldu) { %s::pf_rider_kernel(%s); return; }", (long long)host.grid,
+                            (long long)(host.grid + rider.grid), space.c_str(), args.c_str());
     htext.insert(hclose + 3, call);
     htext.insert(hclose, params);
     // (an earlier rider's parameters already follow the host's: this one's go after them, before the closing parenthesis)
@@ -1568,7 +1569,7 @@ bool attach_rider(Group& host, const Group& rider) {
     rd.operands = rider.operands;
     rd.stores = rider.stores;
     host.riders.push_back(std::move(rd));
-    host.grid += 1;
+    host.grid += rider.grid;
     host.rt_per_block = 0;                  // the rider's workgroup number is literal: no other outermost extent
     host.bytes_read += rider.bytes_read;
     host.bytes_written += rider.bytes_written;

@@ -153,8 +153,8 @@ struct Group {
     int64_t grid = 1;
     int lanes_per_row = 0;
     int vec = 1, chunks_per_lane = 1;
-    // A one-workgroup group that rides on this kernel as an extra workgroup (see attach_rider): its pointer
-    // arguments follow this group's own
+    // Small groups that ride on this kernel as extra workgroups (see attach_rider): their pointer arguments follow
+    // this group's own
     struct Rider {
         std::vector<Operand> operands;
         std::vector<Store> stores;
@@ -194,8 +194,8 @@ std::vector<int> rewrite_sites(const pf_graph& g, const pf_options& opt);
 
 // ---- codegen.cpp ----
 void generate_source(const pf_graph& g, const pf_options& opt, Group& grp, int index);
-// Lets the one-workgroup kernel of `rider` run as workgroup number host.grid of the host's kernel (both already
-// generated, same workgroup size, independent of each other).  False, and nothing changed, if they do not fit.
+// Lets the kernel of `rider` (at most 64 workgroups) run as the workgroups past host.grid of the host's kernel (both
+// already generated, same workgroup size, independent of each other).  False, and nothing changed, if they do not fit.
 bool attach_rider(Group& host, const Group& rider);
 
 // ---- runtime.cpp ----
