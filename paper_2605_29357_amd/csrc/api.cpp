@@ -264,7 +264,7 @@ pf_status pf_compile(const pf_graph* g, const pf_options* h_opt, pf_exec** e) {
                 auto& groups = ex->plan.groups;
                 auto alone = [&](size_t r) {
                     const pf::Group& rider = groups[r];
-                    bool ok = rider.grid >= 1 && rider.grid <= 64 && rider.riders.empty();
+                    bool ok = rider.grid >= 1 && rider.riders.empty();
                     for (auto& o : rider.operands) ok &= o.graph_input >= 0;
                     for (auto& st : rider.stores) ok &= st.graph_output >= 0 && st.ws_offset < 0;
                     for (size_t j = 0; j < groups.size() && ok; ++j)
