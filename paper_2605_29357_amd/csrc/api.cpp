@@ -6,6 +6,7 @@
 #include <cstring>
 #include <memory>
 #include <new>
+#include <set>
 
 #include "exec.h"
 #include "pf_internal.h"
@@ -258,32 +259,62 @@ pf_status pf_compile(const pf_graph* g, const pf_options* h_opt, pf_exec** e) {
                     grp.bytes_read += grp.scratch_bytes;
                 }
             }
-            // Kernels of a few workgroups that touch nothing another kernel of the plan touches (they read graph inputs
-            // and write graph outputs nobody reads back) ride on another kernel instead of costing a launch.
+            // Two kernels of a plan that do not depend on each other, directly or through others, need not be two
+            // launches: the smaller one rides on the other (attach_rider) wherever the merged kernel can stand in
+            // the execution order - after everything either of them reads, before everything that reads either.
             if (opt.fuse) {
                 auto& groups = ex->plan.groups;
-                auto alone = [&](size_t r) {
-                    const pf::Group& rider = groups[r];
-                    bool ok = rider.grid >= 1 && rider.riders.empty();
-                    for (auto& o : rider.operands) ok &= o.graph_input >= 0;
-                    for (auto& st : rider.stores) ok &= st.graph_output >= 0 && st.ws_offset < 0;
-                    for (size_t j = 0; j < groups.size() && ok; ++j)
-                        if (j != r)
-                            for (auto& o : groups[j].operands)
-                                for (auto& st : rider.stores) ok &= o.node != st.node;
-                    return ok;
+                struct Touch {
+                    std::set<int> reads, writes;       // nodes read from memory other kernels wrote; nodes written
                 };
-                // the smallest such kernel first, onto the largest kernel that takes it
+                auto touch_of = [&](const pf::Group& grp) {
+                    Touch t;
+                    auto add = [&](const std::vector<pf::Operand>& ops, const std::vector<pf::Store>& sts) {
+                        for (auto& o : ops)
+                            if (o.graph_input < 0) t.reads.insert(o.node);
+                        for (auto& st : sts) t.writes.insert(st.node);
+                    };
+                    add(grp.operands, grp.stores);
+                    for (auto& rd : grp.riders) add(rd.operands, rd.stores);
+                    return t;
+                };
+                auto needs = [](const Touch& b, const Touch& a) {          // does b read something a writes?
+                    for (int n : b.reads)
+                        if (a.writes.count(n)) return true;
+                    return false;
+                };
                 for (bool again = true; again && groups.size() > 1;) {
                     again = false;
-                    std::vector<size_t> order(groups.size());
-                    for (size_t k = 0; k < order.size(); ++k) order[k] = k;
+                    const size_t n = groups.size();
+                    std::vector<Touch> tch;
+                    for (auto& grp : groups) tch.push_back(touch_of(grp));
+                    // reach[b][a]: b needs a, directly or through others (the groups are in execution order)
+                    std::vector<std::vector<char>> reach(n, std::vector<char>(n, 0));
+                    for (size_t b = 0; b < n; ++b)
+                        for (size_t a = 0; a < b; ++a)
+                            if (needs(tch[b], tch[a])) {
+                                reach[b][a] = 1;
+                                for (size_t c = 0; c < a; ++c) reach[b][c] |= reach[a][c];
+                            }
+                    std::vector<size_t> order(n);
+                    for (size_t k = 0; k < n; ++k) order[k] = k;
                     std::stable_sort(order.begin(), order.end(), [&](size_t a, size_t b) { return groups[a].grid < groups[b].grid; });
-                    for (size_t r : order) {
-                        if (!alone(r)) continue;
+                    // the smallest kernel first, onto the largest kernel that takes it
+                    for (size_t oi = 0; oi < n && !again; ++oi) {
+                        const size_t r = order[oi];
+                        if (!groups[r].riders.empty()) continue;
                         for (auto it = order.rbegin(); it != order.rend() && !again; ++it) {
                             const size_t h = *it;
-                            if (h == r || groups[h].grid < groups[r].grid) continue;
+                            if (h == r || groups[h].grid < groups[r].grid || reach[r][h] || reach[h][r]) continue;
+                            // where may the merged kernel stand?  At the later of the two places if nothing in between
+                            // reads the earlier one; at the earlier if the later one reads nothing in between.
+                            const size_t lo = std::min(r, h), hi = std::max(r, h);
+                            bool at_hi = true, at_lo = true;
+                            for (size_t k = lo + 1; k < hi; ++k) {
+                                at_hi &= !reach[k][lo];
+                                at_lo &= !reach[hi][k];
+                            }
+                            if (!at_hi && !at_lo) continue;
                             size_t n_args = groups[h].operands.size() + groups[r].operands.size() + 2;
                             for (auto& st : groups[h].stores) n_args += 1 + st.also_outputs.size();
                             for (auto& st : groups[r].stores) n_args += 1 + st.also_outputs.size();
@@ -292,11 +323,17 @@ pf_status pf_compile(const pf_graph* g, const pf_options* h_opt, pf_exec** e) {
                                 for (auto& st : rd.stores) n_args += 1 + st.also_outputs.size();
                             }
                             if (n_args > (size_t)pf::kMaxKernelArgs) continue;
-                            again = pf::attach_rider(groups[h], groups[r]);
-                        }
-                        if (again) {
-                            groups.erase(groups.begin() + (long)r);
-                            break;
+                            if (!pf::attach_rider(groups[h], groups[r])) continue;
+                            again = true;
+                            pf::Group merged = std::move(groups[h]);
+                            const size_t place = at_hi ? hi : lo;
+                            // rebuild the order: everything but the two, with the merged kernel where it may stand
+                            std::vector<pf::Group> next;
+                            for (size_t k = 0; k < n; ++k) {
+                                if (k == place) next.push_back(std::move(merged));
+                                else if (k != r && k != h) next.push_back(std::move(groups[k]));
+                            }
+                            groups.swap(next);
                         }
                     }
                 }

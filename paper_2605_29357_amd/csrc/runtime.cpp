@@ -247,12 +247,14 @@ void exec_run(pf_exec& e, const void* const* d_inputs, void* const* d_outputs, v
         // the riders' pointers follow the host's own arguments, rider by rider: operands, then results
         for (auto& rd : grp.riders) {
             for (auto& o : rd.operands) {
-                ptrs[n] = (void*)d_inputs[o.graph_input];
+                ptrs[n] = o.graph_input >= 0 ? (void*)d_inputs[o.graph_input]
+                          : o.ws_offset >= 0 ? (void*)((char*)d_ws + o.ws_offset)
+                                             : (void*)d_outputs[o.graph_output];
                 args[n] = &ptrs[n];
                 ++n;
             }
             for (auto& st : rd.stores) {
-                ptrs[n] = d_outputs[st.graph_output];
+                ptrs[n] = st.graph_output >= 0 ? d_outputs[st.graph_output] : (void*)((char*)d_ws + st.ws_offset);
                 args[n] = &ptrs[n];
                 ++n;
                 for (int k : st.also_outputs) {
