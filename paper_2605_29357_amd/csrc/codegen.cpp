@@ -1522,18 +1522,23 @@ void replace_all(std::string& s, const std::string& what, const std::string& wit
 // workgroup index counted from the host's grid); the host's kernel gets the rider's pointers after its own parameters
 // and one line at its top that sends the workgroups past its own grid to the rider.
 bool attach_rider(Group& host, const Group& rider) {
-    // (a larger rider must be light on LDS, or every workgroup of the host would pay for it in occupancy, and must not
-    // move much: the launch it saves is worth ~4 us, while sharing one kernel's register and LDS budget with the host
-    // cost a 196 MB rider 1.5 us)
-    const bool light = (rider.tmpl == PF_T_EW_FLAT || rider.tmpl == PF_T_ROW_RESIDENT || rider.tmpl == PF_T_ROW_LOOP) &&
-                       rider.bytes_read + rider.bytes_written <= (uint64_t(48) << 20);
+    // (a larger rider must not move much: the launch it saves is worth ~4 us, while sharing one kernel's register and
+    // LDS budget with the host cost a 196 MB rider 1.5 us; and it must be light on LDS, or every workgroup of the host
+    // pays for it in occupancy: row and flat kernels are, a tile kernel is when host and rider together stage at most
+    // three tensors, a column reduction is not)
+    int rider_staged = 0;
+    for (auto& o : rider.operands) rider_staged += o.transposed ? 1 : 0;
+    for (auto& st : rider.stores) rider_staged += st.tstore ? 1 : 0;
+    int host_staged = 0;
+    for (auto& o : host.operands) host_staged += o.transposed ? 1 : 0;
+    for (auto& st : host.stores) host_staged += st.tstore ? 1 : 0;
+    const bool light = rider.bytes_read + rider.bytes_written <= (uint64_t(48) << 20) &&
+                       (rider.tmpl == PF_T_EW_FLAT || rider.tmpl == PF_T_ROW_RESIDENT || rider.tmpl == PF_T_ROW_LOOP ||
+                        (rider.tmpl == PF_T_TILE && rider_staged + host_staged <= 3));
     if (rider.grid < 1 || (rider.grid > 64 && !light) || !rider.kernel2_name.empty() || !host.kernel2_name.empty() || rider.scratch_bytes || !rider.riders.empty() || host.riders.size() >= 4) return false;
     if (host.block != rider.block || host.source_body_at == 0 || rider.source_body_at == 0) return false;
     // a tile kernel that stages several tensors has little LDS to spare for a rider's own
-    int staged = 0;
-    for (auto& o : host.operands) staged += o.transposed ? 1 : 0;
-    for (auto& st : host.stores) staged += st.tstore ? 1 : 0;
-    if (staged > 2) return false;
+    if (host_staged > 2) return false;
     const std::string head = "extern \"C\" __global__ void __launch_bounds__(";
     std::string rtext = rider.source.substr(rider.source_body_at);
     const size_t rk = rtext.find(head);
