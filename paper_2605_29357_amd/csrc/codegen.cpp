@@ -1532,7 +1532,7 @@ bool attach_rider(Group& host, const Group& rider) {
     int host_staged = 0;
     for (auto& o : host.operands) host_staged += o.transposed ? 1 : 0;
     for (auto& st : host.stores) host_staged += st.tstore ? 1 : 0;
-    const bool light = rider.bytes_read + rider.bytes_written <= (uint64_t(48) << 20) &&
+    const bool light = rider.bytes_read + rider.bytes_written <= (uint64_t(96) << 20) &&
                        (rider.tmpl == PF_T_EW_FLAT || rider.tmpl == PF_T_ROW_RESIDENT || rider.tmpl == PF_T_ROW_LOOP ||
                         (rider.tmpl == PF_T_TILE && rider_staged + host_staged <= 3));
     if (rider.grid < 1 || (rider.grid > 64 && !light) || !rider.kernel2_name.empty() || !host.kernel2_name.empty() || rider.scratch_bytes || !rider.riders.empty() || host.riders.size() >= 4) return false;
