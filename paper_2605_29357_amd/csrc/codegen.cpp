@@ -1575,6 +1575,15 @@ bool attach_rider(Group& host, const Group& rider) {
     htext.insert(hclose, params);
     // (an earlier rider's parameters already follow the host's: this one's go after them, before the closing parenthesis)
     host.source = host.source.substr(0, host.source_body_at) + "namespace " + space + " {\n" + rtext + "}  // namespace " + space + "\n" + htext;
+    // the kernel's name ends in a hash of its source: with a rider it is another kernel
+    {
+        unsigned long long h = 1469598103934665603ull;
+        for (unsigned char c : host.source) { h ^= c; h *= 1099511628211ull; }
+        const std::string old_name = host.kernel_name;
+        const std::string new_name = old_name.substr(0, old_name.rfind('_')) + strf("_%08x", (unsigned)(h ^ (h >> 32)));
+        replace_all(host.source, old_name, new_name);
+        host.kernel_name = new_name;
+    }
     Group::Rider rd;
     rd.operands = rider.operands;
     rd.stores = rider.stores;
