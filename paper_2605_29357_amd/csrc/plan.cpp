@@ -9,12 +9,14 @@
 //   - reductions over the last dim of a full value (their result is
 //     row-uniform and may be consumed inside the same kernel),
 //   - transposes of tensors that already sit in memory (read through a swap of
-//     the last two dims; the group then iterates in tiles),
+//     the last two dims; the group then iterates in tiles), and transposes the
+//     rewrite marks as results that only leave the kernel (a tiled group writes
+//     them through the same LDS transpose, on the store side),
 //   - reductions over the second-to-last dim of a full value (the pooling over
 //     the sequence dim of the paper's Case 2) followed by an epilogue of
 //     elementwise nodes on the reduced ("column-uniform") shape.
 // Boundaries fall where the domain changes (a transpose of a value computed in
-// the same kernel, a broadcast that grows the shape) and where a reduction
+// the same kernel that is read again, a broadcast that grows the shape) and where a reduction
 // would have to join a tiled group.  A node may join any group that does not
 // come to depend on itself that way (the groups its operands live in must not
 // need anything the group computes); the groups are put in execution order at
