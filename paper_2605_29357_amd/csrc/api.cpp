@@ -305,7 +305,9 @@ pf_status pf_compile(const pf_graph* g, const pf_options* h_opt, pf_exec** e) {
                         if (!groups[r].riders.empty()) continue;
                         for (auto it = order.rbegin(); it != order.rend() && !again; ++it) {
                             const size_t h = *it;
-                            if (h == r || groups[h].grid < groups[r].grid || reach[r][h] || reach[h][r]) continue;
+                            if (h == r || reach[r][h] || reach[h][r]) continue;
+                            // the host is the larger of the two, or the one with the larger workgroups
+                            if (groups[h].block < groups[r].block || (groups[h].block == groups[r].block && groups[h].grid < groups[r].grid)) continue;
                             // where may the merged kernel stand?  At the later of the two places if nothing in between
                             // reads the earlier one; at the earlier if the later one reads nothing in between.
                             const size_t lo = std::min(r, h), hi = std::max(r, h);

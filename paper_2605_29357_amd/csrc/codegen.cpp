@@ -1536,7 +1536,11 @@ bool attach_rider(Group& host, const Group& rider) {
                        (rider.tmpl == PF_T_EW_FLAT || rider.tmpl == PF_T_ROW_RESIDENT || rider.tmpl == PF_T_ROW_LOOP ||
                         (rider.tmpl == PF_T_TILE && rider_staged + host_staged <= 3));
     if (rider.grid < 1 || (rider.grid > 64 && !light) || !rider.kernel2_name.empty() || !host.kernel2_name.empty() || rider.scratch_bytes || !rider.riders.empty() || host.riders.size() >= 4) return false;
-    if (host.block != rider.block || host.source_body_at == 0 || rider.source_body_at == 0) return false;
+    if (host.source_body_at == 0 || rider.source_body_at == 0 || rider.block > host.block) return false;
+    // A rider written for fewer lanes than the host's workgroups have: the surplus waves of its workgroups leave at
+    // once (a barrier waits for the surviving waves of a workgroup only), which wastes their slots - small riders only.
+    const bool narrower = rider.block < host.block;
+    if (narrower && (rider.grid > 256 || rider.bytes_read + rider.bytes_written > (uint64_t(8) << 20))) return false;
     // a tile kernel that stages several tensors has little LDS to spare for a rider's own
     if (host_staged > 2) return false;
     const std::string head = "extern \"C\" __global__ void __launch_bounds__(";
@@ -1569,8 +1573,9 @@ bool attach_rider(Group& host, const Group& rider) {
     for (auto& st : rider.stores)
         for (size_t c = 0; c < 1 + st.also_outputs.size(); ++c, ++sp) add(strf("%s* __restrict__", tn(st.dtype)), strf("%sq%d", tag.c_str(), sp));
     if (rider.outer_runtime) args += strf("%s(long long)%lld", args.empty() ? "" : ", ", (long long)rider.outer_extent);
-    std::string call = strf("\n    if (blockIdx.x >= %lldu && blockIdx.x < %lldu) { %s::pf_rider_kernel(%s); return; }", (long long)host.grid,
-                            (long long)(host.grid + rider.grid), space.c_str(), args.c_str());
+    const std::string guard = narrower ? strf("if (threadIdx.x < %du) ", rider.block) : "";
+    std::string call = strf("\n    if (blockIdx.x >= %lldu && blockIdx.x < %lldu) { %s%s::pf_rider_kernel(%s); return; }", (long long)host.grid,
+                            (long long)(host.grid + rider.grid), guard.c_str(), space.c_str(), args.c_str());
     htext.insert(hclose + 3, call);
     htext.insert(hclose, params);
     // (an earlier rider's parameters already follow the host's: this one's go after them, before the closing parenthesis)

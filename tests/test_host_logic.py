@@ -269,12 +269,15 @@ def test_case_2_pooling_over_the_sequence_dim_is_one_column_reduction_kernel():
     m = b.op("mean", [x], "f32", dim=-2, keepdim=1)
     b.output(b.op("sub", [x, m], "f32"))
     assert [gi["template"] for gi in pf.Exec(b.text()).groups()] == ["col_reduce", "ew_flat"]
-    # reductions over different dims of the same tensor do not share a kernel
+    # reductions over different dims of the same tensor are different kernels (they need not be different launches:
+    # independent of each other, one rides on the other as an extra workgroup)
     b = Builder()
     x = b.input("f32", (8, 16))
     b.output(b.op("sum", [x], "f32", dim=-2))
     b.output(b.op("sum", [x], "f32"))
-    assert sorted(gi["template"] for gi in pf.Exec(b.text()).groups()) == ["col_reduce", "row_resident"]
+    both = pf.Exec(b.text())
+    assert both.info()["n_kernels"] == 1 and "pf_rider0" in both.source(0)
+    assert sorted(gi["template"] for gi in pf.Exec(b.text(), fuse=False).groups()) == ["col_reduce", "row_resident"]
 
 
 def test_fp16_tensors_parse_print_and_compile():
