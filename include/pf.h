@@ -163,9 +163,12 @@ typedef struct {
     uint64_t algorithmic_bytes;  /* external inputs once + outputs once                   */
     uint64_t workspace_bytes;    /* device scratch pf_execute needs (may be 0)            */
     uint64_t planned_bytes;      /* bytes the planned kernels read + write, incl. scratch */
-    int      n_groups;           /* fused groups; pf_exec_group_info / pf_exec_source index them.
-                                    A group is one kernel, except a column reduction over few column
-                                    tiles, which runs a partial and a combining kernel (n_kernels counts both) */
+    int      n_groups;           /* launches' worth of fused groups; pf_exec_group_info / pf_exec_source index
+                                    them.  A group is one kernel, except a column reduction over few column
+                                    tiles, which runs a partial and a combining kernel (n_kernels counts both).
+                                    Groups of a plan that do not depend on each other may share one kernel: the
+                                    smaller ones ride on the largest as extra workgroups and are reported with it
+                                    (its nodes, bytes and grid include theirs) */
     int      reserved_;
 } pf_plan_info;
 
